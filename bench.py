@@ -1,0 +1,151 @@
+#!/usr/bin/env python3
+"""Throughput of block-denoising decode on one MI355X (synthetic, random-init, batch 1).
+
+Workload = the headline configuration: Qwen2.5-VL-3B-shaped bf16 backbone, prefix of 1024 (768 synthetic
+visual embeddings + 256 random text ids), blocks of B=32 with a fixed schedule of 4 unmasks per step.
+One "step" of this benchmark is one whole block: the autoregressive seed, 8 denoising forwards with their
+LM-head/confidence/unmask, and the causal commit forward (9 weight passes, 32 tokens).  Inputs are resident
+in HBM before the timed region; the prefill is not timed.
+
+Prints ONE JSON line (see the keys below).  `roofline` prices the dominant kernel class (by time) against
+the 8 TB/s HBM peak using HIP events recorded around every launch in a second pass over the same steps;
+`cpu_baseline` times the CPU oracle on a bounded sample of the same workload on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8, help="blocks of 32 tokens to time (8 = 256 tokens)")
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--layers", type=int, default=36, help="debug only: fewer layers (result is then not the metric)")
+    ap.add_argument("--prefix", type=int, default=1024)
+    ap.add_argument("--block", type=int, default=32)
+    ap.add_argument("--fixed-k", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-pass", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is a single-GPU path (batch-1 decode); run with --gpus 1. "
+              "Independent requests per GPU are the multi-GPU form and need no communication.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2604_06832_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    B, K = args.block, args.fixed_k
+    shape = inputs.QWEN3B.with_layers(args.layers)
+    threads = min(16, os.cpu_count() or 8)
+
+    t0 = time.time()
+    w = inputs.make_weights(shape, 0, "bf16", threads=threads)
+    n_embed = args.prefix * 3 // 4
+    emb, ids = inputs.make_prompt(shape, n_embed, args.prefix - n_embed, seed=101)
+    print(f"[bench] weights generated in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
+    blocks = args.warmup + args.steps
+    ctx = binding.Context(shape, max_seq=args.prefix + (max(blocks, args.steps) + 1) * B, max_block=64)
+    t0 = time.time()
+    ctx.load_model(w)
+    print(f"[bench] weights uploaded in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+    d_emb = torch.from_numpy(emb).cuda()
+    d_ids = torch.from_numpy(ids).cuda()
+    tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    msk = torch.empty(B, dtype=torch.uint8, device="cuda")
+    n_den = -(-(B - 1) // K)                     # denoising forwards per block
+
+    def decode_block():
+        tok.fill_(shape.mask_token_id)
+        msk.fill_(1)
+        for _ in range(n_den):
+            ctx.bd_denoise_step(tok, msk, 0.9, K)
+        ctx.bd_commit_block(tok)
+
+    def run(n_blocks):
+        ctx.bd_prefill(d_emb, d_ids)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n_blocks):
+            decode_block()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t
+
+    run(args.warmup)                              # untimed warm-up blocks, then the prompt is prefilled afresh
+    elapsed = run(args.steps)
+    assert int(msk.sum().item()) == 0 and ctx.bd_cache_len() == args.prefix + args.steps * B
+    tokens = args.steps * B
+    forwards = args.steps * (n_den + 1)
+    ms_fwd = elapsed * 1e3 / forwards
+    # algorithmic bytes of the whole run: weights once per forward + cached K/V at each block's length
+    kv_pos_bytes = shape.n_layers * 2 * shape.kv_dim * 2
+    w_bytes = 2 * shape.weight_elements()
+    total_bytes = sum((n_den + 1) * (w_bytes + kv_pos_bytes * (args.prefix + b * B)) for b in range(args.steps))
+    step_frac = total_bytes / elapsed / 1e9 / HBM_PEAK_GBS
+
+    roofline = None
+    if not args.no_kernel_pass:
+        ctx.bd_k_profile(True)
+        run(args.steps)
+        prof = ctx.bd_k_profile_read()
+        ctx.bd_k_profile(False)
+        stream = {k: v for k, v in prof.items() if v[2] > 0 and v[1] > 0}
+        dom = max(stream, key=lambda k: stream[k][0])
+        ms, cnt, nbytes = stream[dom]
+        achieved = nbytes / (ms / cnt * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "avg_kernel_us": round(ms / cnt * 1e3, 2), "launches": cnt,
+                    "classes": {k: {"avg_us": round(v[0] / v[1] * 1e3, 2), "launches": v[1],
+                                    "GBps": round(v[2] / (v[0] / v[1] * 1e-3) / 1e9, 1) if v[2] else None}
+                                for k, v in prof.items() if v[1] > 0}}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle.bd_oracle import BlockDiffusionOracle
+        o = BlockDiffusionOracle(shape, w)
+        o.prefill(emb[:64], None)                  # a short prefix: K/V are <1% of a forward's bytes
+        t = np.full(B, shape.mask_token_id, np.int32)
+        m = np.ones(B, bool)
+        t1 = time.perf_counter()
+        n_f = 2
+        for _ in range(n_f):
+            o.denoise_step(t, m, 0.9, K)
+        dt = (time.perf_counter() - t1) / n_f
+        cpu = {"value": round(B / ((n_den + 1) * dt), 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+               "sample": f"{n_f} denoising forwards at B={B} (fp64 numpy oracle, prefix 64), {dt:.2f}s each, "
+                         f"extrapolated over the {n_den + 1}-forward block schedule"}
+
+    out = {
+        "metric": "decoded tokens/s at batch 1, 3B-shaped bf16, B=32; % HBM roofline per step",
+        "value": round(tokens / elapsed, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(elapsed * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"configs[1]: 3B-shaped bf16 ({shape.n_layers} layers), prefix {args.prefix} "
+                               f"({n_embed} visual embeddings + {args.prefix - n_embed} ids), B={B}, "
+                               f"fixed {K} unmasks/step, {tokens} tokens",
+                   "block": B, "fixed_k": K, "prefix": args.prefix, "forwards_per_block": n_den + 1},
+        "ms_per_forward": round(ms_fwd, 4), "hbm_roofline_frac_step": round(step_frac, 4),
+        "algorithmic_GB_per_forward": round(total_bytes / forwards / 1e9, 4),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

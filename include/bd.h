@@ -1,0 +1,139 @@
+/*
+ * bd.h - C ABI of the block-denoising decode library for MI355X (gfx950).
+ *
+ * The calls follow the paper's statement of block-diffusion decoding (Sec. 3.4 "Inference" and
+ * Alg. 1 of the appendix "Details of Speculative Decoding"): a causal prefill builds the KV cache;
+ * each block is seeded by one autoregressive prediction and then denoised step by step, every step
+ * being one decoder forward over the B block positions with the whole cached prefix visible and
+ * bidirectional attention inside the block, followed by a confidence-threshold unmask; a finished
+ * block is committed to the cache by a causal forward.
+ *
+ * Conventions
+ *   - Every function returns 0 (BD_OK) or a negative BD_E_* code; nothing aborts or throws.  On error
+ *     no output argument is written and the context state is unchanged.
+ *   - "dev" pointers are device memory owned by the caller (for instance PyTorch tensors); "host"
+ *     pointers are ordinary host memory.  The library never frees or keeps caller pointers beyond
+ *     the call, except that work enqueued on the stream reads/writes dev buffers asynchronously:
+ *     they must stay alive until the stream has run the call.
+ *   - All GPU work is enqueued on the hipStream_t given to bd_create (NULL = the default stream).
+ *     Calls return without synchronising unless stated.  A context is not thread-safe and belongs
+ *     to one stream and one device (the device current at bd_create).
+ *   - Token ids are int32.  The mask token id is fixed at creation (default vocab-1).
+ *   - The library owns the device copies of the weights (repacked into MFMA operand order), the KV
+ *     cache, the carry (prediction for the next uncached position) and all scratch memory.
+ */
+#ifndef BD_H_
+#define BD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bd_ctx bd_ctx;
+
+enum {
+  BD_OK = 0,
+  BD_E_ARG = -1,       /* null pointer, bad shape, B < 1 or B > max_block, unknown name ...      */
+  BD_E_STATE = -2,     /* call out of order: weights missing, decode before prefill ...           */
+  BD_E_CAPACITY = -3,  /* cache_len + B would exceed max_seq                                      */
+  BD_E_DTYPE = -4,     /* unsupported storage type for this tensor                                */
+  BD_E_HIP = -5        /* a HIP runtime call failed; bd_last_error() holds the text               */
+};
+
+enum { BD_F32 = 0, BD_BF16 = 1, BD_FP8_E4M3 = 2 };
+
+/* In-block attention mode of a forward (Alg. 1: draft mask / verify mask). */
+enum { BD_MODE_BIDIR = 0, BD_MODE_CAUSAL = 1 };
+
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+  float rope_theta;      /* rotary base, 1e6 in every configuration                                  */
+  float rms_eps;         /* RMSNorm epsilon, 1e-6                                                     */
+  int32_t max_seq;       /* KV-cache capacity in positions (committed context + one block)           */
+  int32_t max_block;     /* largest B of any call (<= 64)                                            */
+  int32_t mask_token_id; /* id embedded at masked positions; negative = vocab-1                       */
+  int32_t weight_dtype;  /* device storage of the seven decoder linears: BD_BF16 or BD_FP8_E4M3       */
+} bd_config;
+
+/* Shape limits: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads; hidden, ffn, vocab and the
+ * projection widths multiples of 16; hidden a multiple of 32. */
+int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out);
+void bd_destroy(bd_ctx* ctx);
+
+/* Upload one tensor.  name is one of "embed", "lm_head", "final_norm", "l<i>.attn_norm", "l<i>.wq",
+ * "l<i>.wk", "l<i>.wv", "l<i>.wo", "l<i>.ffn_norm", "l<i>.w_gate", "l<i>.w_up", "l<i>.w_down".
+ * host_ptr holds the row-major [out_features, in_features] matrix (or the gain vector) in `dtype`:
+ * BD_F32 (rounded to bf16 on device), BD_BF16 (raw bits) or, for the seven linears of a
+ * BD_FP8_E4M3 context, BD_FP8_E4M3 codes (OCP e4m3fn) with host_scales = one fp32 per output row.
+ * Gain vectors are BD_F32.  The call copies synchronously; the caller keeps ownership of host_ptr. */
+int bd_load_weight(bd_ctx* ctx, const char* name, const void* host_ptr, size_t bytes, int dtype,
+                   const float* host_scales);
+
+/* Alg. 1 prefill: causal forward over the prompt = n_embed continuous embeddings (dev fp32
+ * [n_embed, hidden], may be NULL when n_embed is 0) followed by n_ids token ids (dev int32).  Resets
+ * the cache, fills it with the prompt's K/V, sets the carry from the last prompt row.  The prompt is
+ * processed in chunks of at most max_block rows. */
+int bd_prefill(bd_ctx* ctx, const float* dev_embeds, int n_embed, const int32_t* dev_ids, int n_ids);
+
+/* One denoising step on the current block (Sec. 3.4; Alg. 1 draft step; "Decoding threshold").
+ *   dev_block_tokens [B] in/out, dev_mask [B] in/out (1 = still masked).
+ *   If mask[0] is set, position 0 first takes the carry's argmax (the autoregressive seed); this is
+ *   not counted against fixed_k.  If B > 1, one forward then runs over the block (mask id embedded at
+ *   masked positions, bidirectional in-block attention, cache untouched); the candidate and
+ *   confidence of position i >= 1 come from row i-1.  Revealed are the masked positions with
+ *   confidence > threshold, or the single most confident one if none clears it (ties: lowest
+ *   position); with fixed_k > 0 instead exactly min(fixed_k, remaining) most confident positions.
+ *   dev_n_unmasked (may be NULL): int32, number of positions revealed by this call (seed included).
+ *   dev_conf_out (may be NULL): fp32 [B], confidence of the candidate for every position (position 0:
+ *   the carry's). */
+int bd_denoise_step(bd_ctx* ctx, int32_t* dev_block_tokens, uint8_t* dev_mask, int B, float threshold,
+                    int fixed_k, int32_t* dev_n_unmasked, float* dev_conf_out);
+
+/* Commit a fully decoded block: causal forward over its B tokens, K/V of every layer appended to
+ * the cache, carry = prediction of the last row, cache_len += B.  The caller guarantees that no
+ * token equals the mask id (not checked: it would need a device synchronisation). */
+int bd_commit_block(bd_ctx* ctx, const int32_t* dev_block_tokens, int B);
+
+/* Alg. 1 verify + accept on B drafted ids: causal forward; dev_ar_pred[j] (may be NULL) = argmax of
+ * row j; *dev_n_accept (may be NULL) = length of the longest prefix of the draft in which draft[0]
+ * equals the carry's argmax and draft[j+1] equals ar_pred[j].  commit != 0 appends all B positions
+ * and moves the carry as bd_commit_block does (follow with bd_crop to drop rejected positions). */
+int bd_verify_block(bd_ctx* ctx, const int32_t* dev_draft, int B, int commit, int32_t* dev_ar_pred,
+                    int32_t* dev_n_accept);
+
+/* Alg. 1 Crop: forget cache positions >= new_len (0 <= new_len <= cache_len).  The carry becomes
+ * undefined: the next block must bring its own first token (mask[0] = 0). */
+int bd_crop(bd_ctx* ctx, int new_len);
+
+/* Committed context length, or a negative error. */
+int bd_cache_len(const bd_ctx* ctx);
+
+/* ---- inspection, used by the parity tests -------------------------------------------------------- */
+
+/* enable != 0: every later forward also stores its fp32 logits (costs vocab*B*4 bytes of writes). */
+int bd_debug_logits(bd_ctx* ctx, int enable);
+/* Copy the logits of the last forward: dev_out fp32 [rows, vocab], rows <= that forward's B. */
+int bd_read_logits(bd_ctx* ctx, float* dev_out, int rows);
+/* Unpack cache positions [pos0, pos0+count) of one layer to fp32 [count, n_kv_heads, head_dim]
+ * (post-rotary K, and V).  Positions up to cache_len + last B are readable. */
+int bd_read_kv(bd_ctx* ctx, int layer, int pos0, int count, float* dev_k_out, float* dev_v_out);
+/* The carry: argmax id and its softmax probability (each may be NULL). */
+int bd_read_carry(bd_ctx* ctx, int32_t* dev_cand, float* dev_conf);
+/* Candidate id and confidence of every row of the last forward (row i predicts position i+1). */
+int bd_read_rows(bd_ctx* ctx, int32_t* dev_cand, float* dev_conf, int rows);
+
+/* Algorithmic HBM bytes of one forward at the current cache length: every weight matrix once plus
+ * the cached K/V of all layers (what the roofline fraction is priced on). */
+int64_t bd_forward_bytes(const bd_ctx* ctx);
+
+const char* bd_strerror(int code);
+/* Text of the last BD_E_HIP failure of this process (static storage). */
+const char* bd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BD_H_ */

@@ -1,0 +1,245 @@
+"""Thin ctypes binding of libbd.so (include/bd.h, include/bd_kernels.h).
+
+Argument marshalling only: every step of the decode path runs inside the library's HIP kernels.
+PyTorch tensors are used as device buffers; their data pointers are handed over as plain pointers.
+There is no fallback: if the shared library is missing, importing `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbd.so")
+
+BD_OK, BD_E_ARG, BD_E_STATE, BD_E_CAPACITY, BD_E_DTYPE, BD_E_HIP = 0, -1, -2, -3, -4, -5
+BD_F32, BD_BF16, BD_FP8_E4M3 = 0, 1, 2
+BD_MODE_BIDIR, BD_MODE_CAUSAL = 0, 1
+
+# every symbol the two headers declare
+EXPORTS = [
+    "bd_create", "bd_destroy", "bd_load_weight", "bd_prefill", "bd_denoise_step", "bd_commit_block",
+    "bd_verify_block", "bd_crop", "bd_cache_len", "bd_debug_logits", "bd_read_logits", "bd_read_kv",
+    "bd_read_carry", "bd_read_rows", "bd_forward_bytes", "bd_strerror", "bd_last_error",
+    "bd_k_gemm", "bd_k_attention", "bd_k_profile", "bd_k_profile_read", "bd_k_class_count", "bd_k_class_name",
+    "bd_k_class_bytes",
+]
+
+
+class bd_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab")] + \
+               [("rope_theta", C.c_float), ("rms_eps", C.c_float)] + \
+               [(n, C.c_int32) for n in ("max_seq", "max_block", "mask_token_id", "weight_dtype")]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, f32 = C.c_void_p, C.c_int, C.c_float
+    L.bd_create.argtypes = [C.POINTER(bd_config), vp, C.POINTER(vp)]
+    L.bd_destroy.argtypes = [vp]
+    L.bd_destroy.restype = None
+    L.bd_load_weight.argtypes = [vp, C.c_char_p, vp, C.c_size_t, i32, vp]
+    L.bd_prefill.argtypes = [vp, vp, i32, vp, i32]
+    L.bd_denoise_step.argtypes = [vp, vp, vp, i32, f32, i32, vp, vp]
+    L.bd_commit_block.argtypes = [vp, vp, i32]
+    L.bd_verify_block.argtypes = [vp, vp, i32, i32, vp, vp]
+    L.bd_crop.argtypes = [vp, i32]
+    L.bd_cache_len.argtypes = [vp]
+    L.bd_debug_logits.argtypes = [vp, i32]
+    L.bd_read_logits.argtypes = [vp, vp, i32]
+    L.bd_read_kv.argtypes = [vp, i32, i32, i32, vp, vp]
+    L.bd_read_carry.argtypes = [vp, vp, vp]
+    L.bd_read_rows.argtypes = [vp, vp, vp, i32]
+    L.bd_forward_bytes.argtypes = [vp]
+    L.bd_forward_bytes.restype = C.c_int64
+    L.bd_strerror.argtypes = [i32]
+    L.bd_strerror.restype = C.c_char_p
+    L.bd_last_error.argtypes = []
+    L.bd_last_error.restype = C.c_char_p
+    L.bd_k_gemm.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32, C.POINTER(f32)]
+    L.bd_k_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, i32, C.POINTER(f32)]
+    L.bd_k_profile.argtypes = [vp, i32]
+    L.bd_k_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i32)]
+    L.bd_k_class_count.argtypes = []
+    L.bd_k_class_name.argtypes = [i32]
+    L.bd_k_class_name.restype = C.c_char_p
+    L.bd_k_class_bytes.argtypes = [vp, i32]
+    L.bd_k_class_bytes.restype = C.c_int64
+    _lib = L
+    return L
+
+
+class BdError(RuntimeError):
+    def __init__(self, code: int):
+        L = lib()
+        msg = L.bd_strerror(code).decode()
+        if code == BD_E_HIP:
+            msg += ": " + L.bd_last_error().decode()
+        super().__init__(f"bd error {code}: {msg}")
+        self.code = code
+
+
+def _check(code: int) -> int:
+    if code < 0:
+        raise BdError(code)
+    return code
+
+
+def _ptr(t) -> Optional[int]:
+    """Device pointer of a torch tensor (None passes NULL)."""
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous()
+    return t.data_ptr()
+
+
+class Context:
+    """One decode context = one bd_ctx.  Methods carry the names of the C calls they wrap."""
+
+    def __init__(self, shape, max_seq: int, max_block: int, weight_dtype: int = BD_BF16, stream=None):
+        import torch
+        self.shape = shape
+        cfg = bd_config(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
+                        shape.vocab, shape.rope_theta, shape.rms_eps, max_seq, max_block, shape.mask_token_id,
+                        weight_dtype)
+        self._stream = stream if stream is not None else torch.cuda.current_stream()
+        h = C.c_void_p()
+        _check(lib().bd_create(C.byref(cfg), C.c_void_p(self._stream.cuda_stream), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().bd_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    # -- weights ------------------------------------------------------------------------------------------
+    def bd_load_weight(self, name: str, arr: np.ndarray, scales: Optional[np.ndarray] = None):
+        arr = np.ascontiguousarray(arr)
+        dt = {np.dtype(np.float32): BD_F32, np.dtype(np.uint16): BD_BF16, np.dtype(np.uint8): BD_FP8_E4M3}[arr.dtype]
+        sp = None
+        if scales is not None:
+            scales = np.ascontiguousarray(scales, dtype=np.float32)
+            sp = scales.ctypes.data
+        _check(lib().bd_load_weight(self._h, name.encode(), arr.ctypes.data, arr.nbytes, dt, sp))
+
+    def load_model(self, weights: Dict[str, np.ndarray], as_bf16_bits: bool = True):
+        """Upload every tensor of an inputs.make_weights() dict (matrices as bf16 bit patterns when they are
+        already bf16-representable, else as fp32, which the library rounds)."""
+        from . import inputs
+        for name, w in weights.items():
+            if name.endswith(".scale"):
+                continue
+            if w.dtype == np.uint8:
+                self.bd_load_weight(name, w, weights[name + ".scale"])
+            elif w.ndim == 1 or not as_bf16_bits:
+                self.bd_load_weight(name, w.astype(np.float32, copy=False))
+            else:
+                self.bd_load_weight(name, inputs.bf16_bits(w))
+
+    # -- decode calls --------------------------------------------------------------------------------------
+    def bd_prefill(self, embeds, ids):
+        n_e = 0 if embeds is None else embeds.shape[0]
+        n_i = 0 if ids is None else ids.shape[0]
+        _check(lib().bd_prefill(self._h, _ptr(embeds), n_e, _ptr(ids), n_i))
+
+    def bd_denoise_step(self, tokens, mask, threshold: float, fixed_k: int = 0, n_unmasked=None, conf_out=None):
+        _check(lib().bd_denoise_step(self._h, _ptr(tokens), _ptr(mask), tokens.shape[0], threshold, fixed_k,
+                                     _ptr(n_unmasked), _ptr(conf_out)))
+
+    def bd_commit_block(self, tokens):
+        _check(lib().bd_commit_block(self._h, _ptr(tokens), tokens.shape[0]))
+
+    def bd_verify_block(self, draft, commit: bool, ar_pred=None, n_accept=None):
+        _check(lib().bd_verify_block(self._h, _ptr(draft), draft.shape[0], int(commit), _ptr(ar_pred), _ptr(n_accept)))
+
+    def bd_crop(self, new_len: int):
+        _check(lib().bd_crop(self._h, new_len))
+
+    def bd_cache_len(self) -> int:
+        return _check(lib().bd_cache_len(self._h))
+
+    # -- inspection ----------------------------------------------------------------------------------------
+    def bd_debug_logits(self, enable: bool):
+        _check(lib().bd_debug_logits(self._h, int(enable)))
+
+    def bd_read_logits(self, rows: int):
+        import torch
+        out = torch.empty((rows, self.shape.vocab), dtype=torch.float32, device="cuda")
+        _check(lib().bd_read_logits(self._h, _ptr(out), rows))
+        return out
+
+    def bd_read_kv(self, layer: int, pos0: int, count: int):
+        import torch
+        k = torch.empty((count, self.shape.n_kv_heads, self.shape.head_dim), dtype=torch.float32, device="cuda")
+        v = torch.empty_like(k)
+        _check(lib().bd_read_kv(self._h, layer, pos0, count, _ptr(k), _ptr(v)))
+        return k, v
+
+    def bd_read_carry(self):
+        import torch
+        cand = torch.empty(1, dtype=torch.int32, device="cuda")
+        conf = torch.empty(1, dtype=torch.float32, device="cuda")
+        _check(lib().bd_read_carry(self._h, _ptr(cand), _ptr(conf)))
+        return int(cand.item()), float(conf.item())
+
+    def bd_read_rows(self, rows: int):
+        import torch
+        cand = torch.empty(rows, dtype=torch.int32, device="cuda")
+        conf = torch.empty(rows, dtype=torch.float32, device="cuda")
+        _check(lib().bd_read_rows(self._h, _ptr(cand), _ptr(conf), rows))
+        return cand, conf
+
+    def bd_forward_bytes(self) -> int:
+        return _check(lib().bd_forward_bytes(self._h))
+
+    # -- per-kernel timing ---------------------------------------------------------------------------------
+    def bd_k_profile(self, enable: bool):
+        _check(lib().bd_k_profile(self._h, int(enable)))
+
+    def bd_k_profile_read(self):
+        """{class name: (total ms, launches, algorithmic bytes per launch)}"""
+        L = lib()
+        out = {}
+        for k in range(L.bd_k_class_count()):
+            ms, cnt = C.c_double(), C.c_int()
+            _check(L.bd_k_profile_read(self._h, k, C.byref(ms), C.byref(cnt)))
+            out[L.bd_k_class_name(k).decode()] = (ms.value, cnt.value, int(L.bd_k_class_bytes(self._h, k)))
+        return out
+
+
+def bd_k_gemm(w_bits, x, iters: int = 1):
+    """Y = bf16(x) @ W^T through the library's skinny GEMM.  w_bits: uint16 [N,K] (cuda, viewed as int16),
+    x: fp32 [M,K] (cuda).  Returns (Y fp32 [M,N], mean kernel ms or 0)."""
+    import torch
+    N, K = w_bits.shape
+    M = x.shape[0]
+    y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    ms = C.c_float(0)
+    _check(lib().bd_k_gemm(C.c_void_p(torch.cuda.current_stream().cuda_stream), _ptr(w_bits), _ptr(x), M, N, K, _ptr(y),
+                           iters, C.byref(ms)))
+    return y, ms.value
+
+
+def bd_k_attention(q, k, v, n_prefix: int, mode: int, iters: int = 1):
+    """Block-causal GQA attention on explicit fp32 cuda operands (see include/bd_kernels.h)."""
+    import torch
+    M, n_q, D = q.shape
+    n_kv = k.shape[1]
+    out = torch.empty((M, n_q * D), dtype=torch.float32, device="cuda")
+    ms = C.c_float(0)
+    _check(lib().bd_k_attention(C.c_void_p(torch.cuda.current_stream().cuda_stream), _ptr(q), _ptr(k), _ptr(v), n_prefix,
+                                M, n_q, n_kv, D, mode, _ptr(out), iters, C.byref(ms)))
+    return out, ms.value

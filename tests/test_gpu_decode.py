@@ -1,0 +1,277 @@
+"""End-to-end parity of the HIP decode path against the CPU oracle, through the C ABI.
+
+Bars: unmask masks and token ids bit-exact wherever the oracle's top-2 logit margin exceeds 1e-2 and the
+revealed set is not decided by a near-tie; logits within 3e-2 of the oracle's logit range (bf16 path);
+cached K/V within bf16 rounding of the oracle's.
+"""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from oracle.bd_oracle import BlockDiffusionOracle
+from paper_2604_06832_amd import binding, inputs
+from tests.gpu_util import MARGIN, Pair, assert_logits_close, fresh_block, top2_margin
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ---- configs[0]: the tiny plumbing model ---------------------------------------------------------------
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_tiny_config_block_decode(storage):
+    _say(f"tiny config, weights {storage}")
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, storage, threads=1)
+    emb, ids = inputs.make_prompt(shape, 64, 64, seed=100)
+    p = Pair(shape, w, max_seq=256)
+    p.prefill(emb, ids)
+    p.check_carry()
+    p.check_kv(0, 128)
+    tok, msk = fresh_block(shape, 4)
+    fwd = 0
+    while msk.any():
+        tok, msk, r = p.denoise_step(tok, msk, tau=0.9)
+        fwd += r["logits"] is not None
+    assert fwd == 3                                   # never clears 0.9 with random weights: one per step
+    p.commit(tok)
+    p.check_kv(128, 4)
+    p.close()
+
+
+def test_block_size_one_is_autoregressive_decoding():
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, "bf16", threads=1)
+    emb, ids = inputs.make_prompt(shape, 8, 8, seed=3)
+    p = Pair(shape, w, max_seq=64)
+    p.prefill(emb, ids)
+    want = BlockDiffusionOracle(shape, w)
+    want.prefill(emb, ids)
+    ar = want.greedy_ar(6)
+    for t in range(6):
+        tok, msk = fresh_block(shape, 1)
+        tok, msk, _ = p.denoise_step(tok, msk, 0.9)
+        assert not msk.any()
+        if top2_margin(p.o.carry) > MARGIN:
+            assert tok[0] == ar[t]
+        p.commit(tok)
+    p.close()
+
+
+# ---- the threshold branch, with confidences spread over (0,1) ---------------------------------------
+
+@pytest.mark.parametrize("tau", [0.0, 0.3, 0.6, 0.9, 1.0])
+def test_threshold_unmask_with_peaked_confidences(tau):
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=40.0, norm_gain_jitter=0.1, threads=1)
+    emb, ids = inputs.make_prompt(shape, 16, 16, seed=4)
+    p = Pair(shape, w, max_seq=128)
+    p.prefill(emb, ids)
+    tok, msk = fresh_block(shape, 16)
+    steps = 0
+    sizes = []
+    while msk.any():
+        before = int(msk.sum())
+        tok, msk, r = p.denoise_step(tok, msk, tau)
+        sizes.append(before - int(msk.sum()))
+        steps += 1
+        assert steps <= 16
+    if tau >= 1.0:
+        assert sizes[0] == 2 and all(s == 1 for s in sizes[1:])
+    if tau == 0.0:
+        assert steps == 1
+    p.commit(tok)
+    p.close()
+
+
+@pytest.mark.parametrize("B,K", [(8, 3), (32, 4), (64, 4), (33, 5)])
+def test_fixed_schedule(B, K):
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=40.0, threads=1)
+    emb, ids = inputs.make_prompt(shape, 20, 17, seed=5)
+    p = Pair(shape, w, max_seq=37 + 2 * B)
+    p.prefill(emb, ids)
+    for blk in range(2):
+        tok, msk = fresh_block(shape, B)
+        fwd = 0
+        while msk.any():
+            tok, msk, _ = p.denoise_step(tok, msk, 0.9, fixed_k=K)
+            fwd += 1
+        assert fwd == -(-(B - 1) // K)
+        p.commit(tok)
+    p.check_kv(0, 37 + 2 * B)
+    p.close()
+
+
+# ---- verify / accept / crop (configs[3] on the tiny model) --------------------------------------------
+
+@pytest.mark.parametrize("B", [4, 8, 16, 32, 64])
+def test_verify_accept_and_crop(B):
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=40.0, threads=1)
+    emb, ids = inputs.make_prompt(shape, 24, 24, seed=6)
+    p = Pair(shape, w, max_seq=48 + 2 * B)
+    p.prefill(emb, ids)
+    import copy
+    clean = copy.deepcopy(p.o).greedy_ar(B)
+    draft, _ = inputs.corrupt_draft(shape, clean, seed=1, p=0.2)
+    r = copy.deepcopy(p.o).verify_block(draft, commit=False)
+    d = torch.from_numpy(draft).cuda()
+    pred = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nacc = torch.zeros(1, dtype=torch.int32, device="cuda")
+    p.ctx.bd_verify_block(d, False, pred, nacc)
+    torch.cuda.synchronize()
+    assert p.ctx.bd_cache_len() == 48
+    glog = p.ctx.bd_read_logits(B).cpu().numpy()
+    assert_logits_close(glog, r["logits"])
+    marg = top2_margin(r["logits"])
+    ok = marg > MARGIN
+    assert np.array_equal(pred.cpu().numpy()[ok], r["ar_pred"][ok])
+    if ok[:max(r["n_accept"], 1)].all() and top2_margin(p.o.carry) > MARGIN:
+        assert int(nacc.item()) == r["n_accept"]
+    # commit, then crop to the accepted prefix and continue: same state as committing only that prefix
+    k = max(1, r["n_accept"])
+    p.ctx.bd_verify_block(d, True, None, None)
+    p.ctx.bd_crop(48 + k)
+    assert p.ctx.bd_cache_len() == 48 + k
+    p.o.commit_block(draft[:k])
+    nxt = np.array([1, 2, 3], np.int32)
+    p.commit(nxt)
+    p.check_kv(0, 48 + k + 3)
+    p.close()
+
+
+# ---- 3B-shaped layers at reduced depth: every block size, ragged prefix, both masks -------------------
+
+def _wide(n_layers, vocab=32000):
+    return inputs.ModelShape(n_layers=n_layers, hidden=2048, n_q_heads=16, n_kv_heads=2, head_dim=128, ffn=11008,
+                             vocab=vocab)
+
+
+@pytest.mark.parametrize("B", [4, 8, 16, 32, 64])
+def test_3b_shaped_two_layers_block_sizes(B):
+    _say(f"3B-shaped x2 layers, B={B}")
+    shape = _wide(2)
+    w = inputs.make_weights(shape, 0, "bf16", threads=8)
+    emb, ids = inputs.make_prompt(shape, 200, 101, seed=103)       # 301: not a multiple of 32 or of 64
+    p = Pair(shape, w, max_seq=301 + 2 * 64)
+    p.prefill(emb, ids)
+    p.check_carry()
+    p.check_kv(0, 301)
+    tok, msk = fresh_block(shape, B)
+    K = min(4, B - 1)
+    while msk.any():
+        tok, msk, _ = p.denoise_step(tok, msk, 0.9, fixed_k=K)
+    p.commit(tok)
+    p.check_kv(301, B)
+    # the same forward twice gives bit-identical logits (fixed-order reductions)
+    t = torch.from_numpy(tok).cuda()
+    p.ctx.bd_verify_block(t, False, None, None)
+    a = p.ctx.bd_read_logits(B).clone()
+    p.ctx.bd_verify_block(t, False, None, None)
+    b = p.ctx.bd_read_logits(B)
+    assert torch.equal(a, b)
+    p.close()
+
+
+def test_long_prefix_3b_shaped_two_layers():
+    _say("3B-shaped x2 layers, prefix 8192 (4 x 1920 embeddings + 512 ids)")
+    shape = _wide(2, vocab=8192)
+    w = inputs.make_weights(shape, 0, "bf16", threads=8)
+    emb, ids = inputs.make_prompt(shape, 4 * 1920, 512, seed=102)
+    p = Pair(shape, w, max_seq=8192 + 64, oracle_dtype=np.float32)
+    p.prefill(emb, ids, oracle_chunk=1024)
+    p.check_carry()
+    p.check_kv(8000, 192)
+    tok, msk = fresh_block(shape, 32)
+    for _ in range(2):
+        tok, msk, _ = p.denoise_step(tok, msk, 0.9, fixed_k=4)
+    p.close()
+
+
+# ---- configs[1] at full size ----------------------------------------------------------------------------
+
+@pytest.mark.slow
+def test_headline_config_first_block_full_depth():
+    shape = inputs.QWEN3B
+    _say("generating 3B-shaped bf16 weights (seed 0)")
+    w = inputs.make_weights(shape, 0, "bf16", threads=16)
+    emb, ids = inputs.make_prompt(shape, 768, 256, seed=101)
+    _say("uploading + oracle prefill of 1024 tokens")
+    p = Pair(shape, w, max_seq=1024 + 256 + 32, oracle_dtype=np.float32)
+    p.prefill(emb, ids, oracle_chunk=256)
+    p.check_carry()
+    tok, msk = fresh_block(shape, 32)
+    fwd = 0
+    while msk.any():
+        tok, msk, r = p.denoise_step(tok, msk, 0.9, fixed_k=4)
+        fwd += 1
+        _say(f"  denoise forward {fwd}: {int((~msk).sum())}/32 revealed")
+    assert fwd == 8
+    p.commit(tok)
+    assert p.ctx.bd_forward_bytes() == 2 * shape.weight_elements() + 36864 * (1024 + 32)
+    p.close()
+
+
+# ---- error paths that need a live context -------------------------------------------------------------------
+
+def test_call_order_and_capacity_errors():
+    shape = inputs.TINY
+    L = binding.lib()
+    ctx = binding.Context(shape, max_seq=40, max_block=16)
+    tok = torch.zeros(4, dtype=torch.int32, device="cuda")
+    msk = torch.ones(4, dtype=torch.uint8, device="cuda")
+    ids = torch.zeros(30, dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.BdError) as e:
+        ctx.bd_prefill(None, ids)                          # weights not loaded
+    assert e.value.code == binding.BD_E_STATE
+    ctx.load_model(inputs.make_weights(shape, 0, "bf16", threads=1))
+    with pytest.raises(binding.BdError) as e:
+        ctx.bd_denoise_step(tok, msk, 0.9)                 # before prefill
+    assert e.value.code == binding.BD_E_STATE
+    with pytest.raises(binding.BdError) as e:
+        ctx.bd_prefill(None, torch.zeros(41, dtype=torch.int32, device="cuda"))
+    assert e.value.code == binding.BD_E_CAPACITY
+    ctx.bd_prefill(None, ids)
+    big = torch.zeros(17, dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.BdError) as e:
+        ctx.bd_commit_block(big)                           # B > max_block
+    assert e.value.code == binding.BD_E_ARG
+    ctx.bd_commit_block(tok)                               # 34
+    ctx.bd_commit_block(tok)                               # 38
+    with pytest.raises(binding.BdError) as e:
+        ctx.bd_commit_block(tok)                           # 42 > 40
+    assert e.value.code == binding.BD_E_CAPACITY
+    with pytest.raises(binding.BdError) as e:
+        ctx.bd_crop(39)
+    assert e.value.code == binding.BD_E_ARG
+    ctx.bd_crop(10)
+    assert ctx.bd_cache_len() == 10
+    with pytest.raises(binding.BdError) as e:
+        ctx.bd_read_carry()                                # undefined after a crop
+    assert e.value.code == binding.BD_E_STATE
+    with pytest.raises(binding.BdError) as e:
+        ctx.bd_load_weight("l7.wq", np.zeros((256, 256), np.float32))
+    assert e.value.code == binding.BD_E_ARG
+    with pytest.raises(binding.BdError) as e:
+        ctx.bd_load_weight("l0.wq", np.zeros((256, 255), np.float32))
+    assert e.value.code == binding.BD_E_ARG
+    torch.cuda.synchronize()
+    ctx.close()
+
+
+@pytest.mark.parametrize("n_embed,n_ids", [(0, 1), (1, 0), (0, 70), (70, 0), (63, 66)])
+def test_prefill_edge_lengths(n_embed, n_ids):
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, "bf16", threads=1)
+    emb, ids = inputs.make_prompt(shape, n_embed, n_ids, seed=7)
+    p = Pair(shape, w, max_seq=256)
+    p.prefill(emb, ids)
+    p.check_carry()
+    p.check_kv(0, n_embed + n_ids)
+    p.close()
