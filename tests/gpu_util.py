@@ -24,6 +24,19 @@ def assert_logits_close(got, want, frac=BF16_LOGIT_TOL, what="logits"):
     return err / rng
 
 
+def check_argmax_ids(got_ids, got_logits, want_logits):
+    """Fused argmax: (a) bit-exact against the argmax (lowest id on ties) of the GPU's own stored logits;
+    (b) equal to the oracle's wherever the oracle's top-2 margin exceeds 1e-2 and twice the measured
+    logit error (with N(0,0.02) weights the error is far below 1e-2 and (b) is the plain 1e-2 rule)."""
+    got_ids = np.asarray(got_ids)
+    assert np.array_equal(got_ids, np.argmax(got_logits, axis=-1)), "fused argmax != argmax of own logits"
+    err = float(np.abs(np.asarray(got_logits, np.float64) - want_logits).max())
+    ok = top2_margin(want_logits) > max(MARGIN, 2.0 * err)
+    want = np.argmax(want_logits, axis=-1)
+    assert np.array_equal(got_ids[ok], want[ok]), (got_ids[ok], want[ok])
+    return ok
+
+
 class Pair:
     """A HIP context and an oracle holding the same model and prompt."""
 
@@ -85,33 +98,47 @@ class Pair:
         oconf = r["conf"]
         gconf = conf.cpu().numpy()
         np.testing.assert_allclose(gconf, oconf, rtol=0.08, atol=1e-7)
-        # is the revealed set uniquely determined?  (near-ties in the confidence ranking / at the threshold)
+        # (a) integer work: the GPU's revealed set must be exactly what the rule gives on the GPU's own
+        #     confidences (both sides decide in the same precision)
         masked = [i for i in range(1, B) if mask[i]]
+        sel = _apply_rule(gconf, masked, tau, fixed_k)
+        want_mask = mask.copy()
+        want_mask[0] = False
+        want_mask[sel] = False
+        assert np.array_equal(gmask, want_mask), (gmask, want_mask)
+        assert int(nun.item()) == int(mask[0]) + len(sel)
+        # (b) against the oracle's set, whenever that set is robust to the measured confidence error
         cm = np.array([oconf[i] for i in masked])
+        cerr = float(np.max(np.abs(gconf - oconf) / np.maximum(oconf, 1e-30)))
+        tol = 2.5 * cerr + rank_tol
         unique = True
+        srt = np.sort(cm)[::-1]
         if fixed_k > 0:
             k = min(fixed_k, len(masked))
-            srt = np.sort(cm)[::-1]
-            if k < len(masked) and (srt[k - 1] - srt[k]) < rank_tol * srt[k - 1]:
+            if k < len(masked) and (srt[k - 1] - srt[k]) < tol * srt[k - 1]:
                 unique = False
         else:
-            if np.any(np.abs(cm - tau) < rank_tol * max(tau, 1e-6)):
+            if np.any(np.abs(cm - tau) < tol * max(tau, 1e-6)):
                 unique = False
-            srt = np.sort(cm)[::-1]
-            if not np.any(cm > tau) and len(srt) > 1 and (srt[0] - srt[1]) < rank_tol * srt[0]:
+            if not np.any(cm > tau) and len(srt) > 1 and (srt[0] - srt[1]) < tol * srt[0]:
                 unique = False
+        # ids written at revealed positions: exactly the argmax of the GPU's own logits row i-1
+        gam = np.argmax(glog, axis=-1)
+        for i in np.flatnonzero(mask & ~gmask):
+            if i > 0:
+                assert gtok[i] == gam[i - 1], (i, gtok[i], gam[i - 1])
+        assert np.array_equal(gtok[~mask], tokens[~mask])          # already revealed positions untouched
         if unique:
             assert np.array_equal(gmask, om), (gmask, om)
             assert int(nun.item()) == r["n_unmasked"]
+            lerr = float(np.abs(glog.astype(np.float64) - r["logits"]).max())
             marg = top2_margin(r["logits"])
             for i in np.flatnonzero(mask & ~om):
                 if i == 0:
-                    if top2_margin(self.o.carry) > MARGIN:
+                    if top2_margin(self.o.carry) > max(MARGIN, 2 * lerr):
                         assert gtok[0] == ot[0]
-                elif marg[i - 1] > MARGIN:
+                elif marg[i - 1] > max(MARGIN, 2 * lerr):
                     assert gtok[i] == ot[i], (i, gtok[i], ot[i])
-        else:
-            assert int(nun.item()) == r["n_unmasked"]
         return ot, om, r
 
     def commit(self, tokens, frac=BF16_LOGIT_TOL):
@@ -124,6 +151,19 @@ class Pair:
         assert_logits_close(glog, ol, frac, "commit logits")
         self.check_carry()
         return ol
+
+
+def _apply_rule(conf, masked, tau, fixed_k):
+    """The unmask rule on given per-position confidences (integer work once the confidences are fixed)."""
+    if not masked:
+        return []
+    if fixed_k > 0:
+        order = sorted(masked, key=lambda i: (-conf[i], i))
+        return order[:min(fixed_k, len(order))]
+    chosen = [i for i in masked if conf[i] > np.float32(tau)]
+    if not chosen:
+        chosen = [min(masked, key=lambda i: (-conf[i], i))]
+    return chosen
 
 
 def _is_bf16(weights):

@@ -12,7 +12,7 @@ import torch
 
 from oracle.bd_oracle import BlockDiffusionOracle
 from paper_2604_06832_amd import binding, inputs
-from tests.gpu_util import MARGIN, Pair, assert_logits_close, fresh_block, top2_margin
+from tests.gpu_util import MARGIN, Pair, check_argmax_ids, assert_logits_close, fresh_block, top2_margin
 
 pytestmark = pytest.mark.gpu
 
@@ -68,7 +68,7 @@ def test_block_size_one_is_autoregressive_decoding():
 @pytest.mark.parametrize("tau", [0.0, 0.3, 0.6, 0.9, 1.0])
 def test_threshold_unmask_with_peaked_confidences(tau):
     shape = inputs.TINY
-    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=40.0, norm_gain_jitter=0.1, threads=1)
+    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, norm_gain_jitter=0.1, threads=1)
     emb, ids = inputs.make_prompt(shape, 16, 16, seed=4)
     p = Pair(shape, w, max_seq=128)
     p.prefill(emb, ids)
@@ -92,9 +92,9 @@ def test_threshold_unmask_with_peaked_confidences(tau):
 @pytest.mark.parametrize("B,K", [(8, 3), (32, 4), (64, 4), (33, 5)])
 def test_fixed_schedule(B, K):
     shape = inputs.TINY
-    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=40.0, threads=1)
+    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, threads=1)
     emb, ids = inputs.make_prompt(shape, 20, 17, seed=5)
-    p = Pair(shape, w, max_seq=37 + 2 * B)
+    p = Pair(shape, w, max_seq=37 + 2 * B, max_block=B)
     p.prefill(emb, ids)
     for blk in range(2):
         tok, msk = fresh_block(shape, B)
@@ -113,9 +113,9 @@ def test_fixed_schedule(B, K):
 @pytest.mark.parametrize("B", [4, 8, 16, 32, 64])
 def test_verify_accept_and_crop(B):
     shape = inputs.TINY
-    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=40.0, threads=1)
+    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, threads=1)
     emb, ids = inputs.make_prompt(shape, 24, 24, seed=6)
-    p = Pair(shape, w, max_seq=48 + 2 * B)
+    p = Pair(shape, w, max_seq=48 + 2 * B, max_block=B)
     p.prefill(emb, ids)
     import copy
     clean = copy.deepcopy(p.o).greedy_ar(B)
@@ -129,9 +129,7 @@ def test_verify_accept_and_crop(B):
     assert p.ctx.bd_cache_len() == 48
     glog = p.ctx.bd_read_logits(B).cpu().numpy()
     assert_logits_close(glog, r["logits"])
-    marg = top2_margin(r["logits"])
-    ok = marg > MARGIN
-    assert np.array_equal(pred.cpu().numpy()[ok], r["ar_pred"][ok])
+    ok = check_argmax_ids(pred.cpu().numpy(), glog, r["logits"])
     if ok[:max(r["n_accept"], 1)].all() and top2_margin(p.o.carry) > MARGIN:
         assert int(nacc.item()) == r["n_accept"]
     # commit, then crop to the accepted prefix and continue: same state as committing only that prefix
