@@ -111,6 +111,10 @@ int bd_crop(bd_ctx* ctx, int new_len);
 /* Committed context length, or a negative error. */
 int bd_cache_len(const bd_ctx* ctx);
 
+/* Synchronise the stream and report the device-side state: BD_E_HIP if a grid barrier of the forward
+ * kernel ever timed out (bounded wait), after which the context must be destroyed. */
+int bd_status(bd_ctx* ctx);
+
 /* ---- inspection, used by the parity tests -------------------------------------------------------- */
 
 /* enable != 0: every later forward also stores its fp32 logits (costs vocab*B*4 bytes of writes). */

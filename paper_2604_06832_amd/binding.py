@@ -22,7 +22,7 @@ BD_MODE_BIDIR, BD_MODE_CAUSAL = 0, 1
 # every symbol the two headers declare
 EXPORTS = [
     "bd_create", "bd_destroy", "bd_load_weight", "bd_prefill", "bd_denoise_step", "bd_commit_block",
-    "bd_verify_block", "bd_crop", "bd_cache_len", "bd_debug_logits", "bd_read_logits", "bd_read_kv",
+    "bd_verify_block", "bd_crop", "bd_cache_len", "bd_status", "bd_debug_logits", "bd_read_logits", "bd_read_kv",
     "bd_read_carry", "bd_read_rows", "bd_forward_bytes", "bd_strerror", "bd_last_error",
     "bd_k_gemm", "bd_k_attention", "bd_k_profile", "bd_k_profile_read", "bd_k_class_count", "bd_k_class_name",
     "bd_k_class_bytes",
@@ -56,6 +56,7 @@ def lib() -> C.CDLL:
     L.bd_verify_block.argtypes = [vp, vp, i32, i32, vp, vp]
     L.bd_crop.argtypes = [vp, i32]
     L.bd_cache_len.argtypes = [vp]
+    L.bd_status.argtypes = [vp]
     L.bd_debug_logits.argtypes = [vp, i32]
     L.bd_read_logits.argtypes = [vp, vp, i32]
     L.bd_read_kv.argtypes = [vp, i32, i32, i32, vp, vp]
@@ -170,6 +171,9 @@ class Context:
 
     def bd_cache_len(self) -> int:
         return _check(lib().bd_cache_len(self._h))
+
+    def bd_status(self):
+        _check(lib().bd_status(self._h))
 
     # -- inspection ----------------------------------------------------------------------------------------
     def bd_debug_logits(self, enable: bool):

@@ -16,6 +16,7 @@
 #include "attention.h"
 #include "common.h"
 #include "gemm.h"
+#include "mega.h"
 #include "misc.h"
 
 using namespace bd;
@@ -40,22 +41,9 @@ static char g_last_error[512] = "";
 
 namespace {
 
-enum KClass {
-  KC_GEMM_QKV = 0, KC_QKV_POST, KC_ATTN_PARTIAL, KC_ATTN_COMBINE, KC_GEMM_O, KC_RESID_NORM, KC_GEMM_GATEUP,
-  KC_GEMM_DOWN, KC_GEMM_LMHEAD, KC_MISC, KC_COUNT
-};
+enum KClass { KC_PROLOGUE = 0, KC_FORWARD, KC_FINISH, KC_COUNT };
 
-struct Layer {
-  u16* wqkv = nullptr;   // packed [q|k|v] x hidden
-  u16* wo = nullptr;     // packed hidden x q_dim
-  u16* wgu = nullptr;    // packed, gate/up tiles interleaved, 2*ffn x hidden
-  u16* wdown = nullptr;  // packed hidden x ffn
-  float* g_attn = nullptr;
-  float* g_ffn = nullptr;
-  unsigned loaded = 0;   // bit per tensor
-};
-
-struct GemmPlan { int NT, ksplit, grid; };
+struct GemmPlan { int NT, ksplit, grid; };   // launch plan of the stand-alone GEMM entry point
 
 }  // namespace
 
@@ -65,35 +53,35 @@ struct bd_ctx {
   int device = 0, num_cus = 256;
   int H, QD, KVD, NQKV, F, V, D, L, G;
   int Mp_max, max_kb;
-  std::vector<Layer> layers;
-  u16* embed = nullptr;
-  u16* lm_head = nullptr;
-  float* g_final = nullptr;
-  unsigned loaded_top = 0;
+  MegaPlan plan;
+  // weights
+  u16* wstream = nullptr;          // all matrices, in per-wavefront streaming order
+  u16* embed = nullptr;            // bf16 [V][H] row-major (gathered, not streamed)
+  float* gains = nullptr;          // [2L+1][H]
+  std::vector<unsigned> loaded;    // per layer bit mask; last entry = top-level tensors
   // KV cache, packed: [L][n_kv][max_kb][32*D] bf16 each
   u16* Kc = nullptr;
   u16* Vc = nullptr;
   size_t kv_layer_elems = 0;
-  // workspaces
-  float* x = nullptr;      // residual stream fp32 [Mp_max][H]
-  u16* xp = nullptr;       // packed normalised activations (K = H)
-  u16* q = nullptr;        // [Mp_max][n_q][D]
-  u16* ap = nullptr;       // packed attention output (K = QD)
-  u16* act = nullptr;      // packed SwiGLU output (K = F)
-  float* ws = nullptr;     // split-K partials
-  size_t ws_floats = 0;
+  // write-once activations of a forward
+  float* xv = nullptr; float* ssq = nullptr; int ssq_parts = 0;
   float2* rope = nullptr;
+  u16* q = nullptr; u16* ap = nullptr; u16* act = nullptr;
+  size_t ap_elems = 0, act_elems = 0;
+  float* wsD = nullptr; size_t wsD_layer_floats = 0;
+  unsigned* counters = nullptr; int n_cntD = 0, n_cntA = 0;
   float* pO = nullptr; float* pm = nullptr; float* pl = nullptr;
-  int attn_items_max = 0;
+  size_t pO_layer_floats = 0, pml_layer_floats = 0;
+  int attn_items_max = 0;          // stand-alone attention entry point only
   float* lm_max = nullptr; int* lm_idx = nullptr; float* lm_sum = nullptr;
-  int lm_parts_max = 0;
   float* logits = nullptr; int logits_on = 0; int last_rows = 0; int last_had_logits = 0;
   int* row_cand = nullptr; float* row_conf = nullptr;
   DevState* st = nullptr;
+  unsigned* bar = nullptr; unsigned bar_epoch = 0;
   // host mirror of the decode state
   int n = 0;
   bool prefilled = false, carry_valid = false;
-  // per-kernel-class timing (bd_k_profile)
+  // per-launch timing (bd_k_profile)
   bool prof_on = false;
   std::vector<hipEvent_t> prof_ev;   // pairs
   std::vector<int> prof_cls;
@@ -113,13 +101,13 @@ struct Prof {
   bd_ctx* c; int cls; hipEvent_t e0 = nullptr, e1 = nullptr;
   Prof(bd_ctx* c_, int cls_) : c(c_), cls(cls_) {
     if (c->prof_on) {
-      hipEventCreate(&e0); hipEventCreate(&e1);
-      hipEventRecord(e0, c->stream);
+      (void)hipEventCreate(&e0); (void)hipEventCreate(&e1);
+      (void)hipEventRecord(e0, c->stream);
     }
   }
   ~Prof() {
     if (c->prof_on) {
-      hipEventRecord(e1, c->stream);
+      (void)hipEventRecord(e1, c->stream);
       c->prof_ev.push_back(e0); c->prof_ev.push_back(e1); c->prof_cls.push_back(cls);
     }
   }
@@ -134,189 +122,130 @@ int check_launch() {
   return BD_OK;
 }
 
-GemmPlan plan_gemm(const bd_ctx* c, int epi, int n_tiles, int KS, int MT) {
-  GemmPlan p;
-  if (epi == EPI_LMHEAD) {
-    p.NT = (MT <= 2 && n_tiles % 4 == 0) ? 4 : ((n_tiles % 2 == 0) ? 2 : 1);
-    p.ksplit = 1;
-    p.grid = std::min(n_tiles / p.NT, std::min(c->lm_parts_max, 4 * c->num_cus));
-    return p;
-  }
-  if (epi == EPI_SWIGLU) {
-    p.NT = 2; p.ksplit = 1; p.grid = n_tiles / 2;
-    return p;
-  }
-  p.NT = (n_tiles % 2 == 0) ? 2 : 1;
-  const int groups = n_tiles / p.NT;
-  int ks = (3 * c->num_cus / 2 + groups - 1) / groups;
-  ks = std::max(1, std::min(ks, std::max(1, KS / 8)));
-  ks = std::min(ks, 16);
-  p.ksplit = ks;
-  p.grid = groups * ks;
-  return p;
-}
+int ceil_even(int v) { return (v + 1) & ~1; }
 
-template <int MT, int NT, int EPI>
-void launch_gemm_t(const GemmArgs& a, int grid, hipStream_t s) {
-  hipLaunchKernelGGL((gemm_kernel<MT, NT, EPI>), dim3(grid), dim3(kWGThreads), 0, s, a);
-}
-
-template <int EPI>
-int launch_gemm_epi(const GemmArgs& a, int MT, int NT, int grid, hipStream_t s) {
-#define BD_CASE(mt, nt) \
-  if (MT == mt && NT == nt) { launch_gemm_t<mt, nt, EPI>(a, grid, s); return check_launch(); }
-  if constexpr (EPI != EPI_SWIGLU) { BD_CASE(1, 1) BD_CASE(2, 1) BD_CASE(3, 1) BD_CASE(4, 1) }
-  BD_CASE(1, 2) BD_CASE(2, 2) BD_CASE(3, 2) BD_CASE(4, 2)
-  if constexpr (EPI == EPI_LMHEAD) { BD_CASE(1, 4) BD_CASE(2, 4) }
-#undef BD_CASE
-  snprintf(g_last_error, sizeof g_last_error, "no GEMM instance for MT=%d NT=%d", MT, NT);
-  return BD_E_HIP;
-}
-
-// Y partials = Xp * Wp^T into c->ws; returns the split count used.
-int gemm_partial(bd_ctx* c, int cls, const u16* Wp, const u16* Xp, int N, int K, int M, int* S_out) {
-  const int MT = ceil_div(M, 16), KS = ceil_div(K, 32);
-  GemmPlan p = plan_gemm(c, EPI_PARTIAL, N / 16, KS, MT);
-  if ((size_t)p.ksplit * MT * 16 * N > c->ws_floats) {
-    snprintf(g_last_error, sizeof g_last_error, "split-K workspace too small");
-    return BD_E_HIP;
-  }
-  GemmArgs a{};
-  a.Wp = reinterpret_cast<const bf16x8*>(Wp); a.Xp = reinterpret_cast<const bf16x8*>(Xp);
-  a.n_tiles = N / 16; a.KS = KS; a.ksplit = p.ksplit; a.M = M; a.N = N; a.partial = c->ws;
-  Prof pr(c, cls);
-  BD_TRY(launch_gemm_epi<EPI_PARTIAL>(a, MT, p.NT, p.grid, c->stream));
-  *S_out = p.ksplit;
+// Row ranges and K splits of every GEMM phase; fails if a wavefront would have to hold more than
+// kMaxKW k-steps of activations.
+int make_plan(bd_ctx* c) {
+  MegaPlan& P = c->plan;
+  P.nwg = c->num_cus; P.L = c->L; P.H = c->H; P.QD = c->QD; P.KVD = c->KVD; P.F = c->F; P.V = c->V; P.D = c->D;
+  P.n_q = c->cfg.n_q_heads; P.n_kv = c->cfg.n_kv_heads;
+  auto set = [&](int p, int N, int K, bool may_split) -> bool {
+    PhasePlan& ph = P.ph[p];
+    ph.N = N; ph.KS = ceil_div(K, 32); ph.ksplit = 1;
+    while (ceil_div(ceil_div(ph.KS, ph.ksplit), kWavesPerWG) > kMaxKW) {
+      if (!may_split || P.nwg % (ph.ksplit * 2) != 0) return false;
+      ph.ksplit *= 2;
+    }
+    const int groups = P.nwg / ph.ksplit;
+    ph.RW = std::max(2, ceil_even(ceil_div(N, groups)));
+    return true;
+  };
+  if (!set(PH_QKV, c->NQKV, c->H, false) || !set(PH_O, c->H, c->QD, false) || !set(PH_GU, 2 * c->F, c->H, false) ||
+      !set(PH_DOWN, c->H, c->F, true) || !set(PH_LM, c->V, c->H, false))
+    return BD_E_ARG;
+  long long mx = 0;
+  for (int wg = 0; wg < P.nwg; ++wg)
+    for (int w = 0; w < kWavesPerWG; ++w) {
+      long long u = (long long)P.L * wave_layer_units(P, wg, w) + wave_phase_units(wave_phase(P, PH_LM, wg, w));
+      mx = std::max(mx, u);
+    }
+  P.wave_stride = (mx + 63) / 64 * 64 + 64;            // a little slack: partial-tile lanes read clamped addresses only
   return BD_OK;
 }
 
-int resid_norm(bd_ctx* c, int S, int M, const float* gain) {
-  const int MT = ceil_div(M, 16);
-  Prof pr(c, KC_RESID_NORM);
-  hipLaunchKernelGGL(resid_norm_kernel, dim3(M), dim3(kWGThreads), 0, c->stream, c->x, c->ws, S, MT * 16, c->H, gain,
-                     c->cfg.rms_eps, c->xp, MT);
-  return check_launch();
-}
-
-int attn_jt(const bd_ctx* c, int MT) {
+// Column tiles per attention item: the stand-alone kernels take up to 4; inside the forward kernel the
+// register budget is shared with the prefetched weights, so it works on pairs.
+int attn_jt(const bd_ctx* c, int MT, bool in_forward = false) {
   const int jt_total = c->G * MT;
+  if (in_forward) return 2;
   return (jt_total % 4 == 0) ? 4 : ((jt_total % 2 == 0) ? 2 : 1);
 }
 
-int attn_max_chunks(const bd_ctx* c, int MT) {
-  const int JT = attn_jt(c, MT);
+int attn_max_chunks(const bd_ctx* c, int MT, bool in_forward = false) {
+  const int JT = attn_jt(c, MT, in_forward);
   const int groups = c->cfg.n_kv_heads * (c->G * MT / JT);
   int mc = (2 * c->num_cus) / groups;
-  return std::max(1, std::min(mc, 128));
+  return std::max(1, std::min(mc, 64));
 }
 
-template <int D>
-int launch_attention_d(bd_ctx* c, const AttnArgs& a, int JT, int grid_p, int grid_c) {
-#define BD_ATT(jt)                                                                                             \
-  if (JT == jt) {                                                                                              \
-    { Prof pr(c, KC_ATTN_PARTIAL);                                                                             \
-      hipLaunchKernelGGL((attn_partial_kernel<D, jt>), dim3(grid_p), dim3(kWGThreads), 0, c->stream, a);        \
-      BD_TRY(check_launch()); }                                                                                \
-    { Prof pr(c, KC_ATTN_COMBINE);                                                                             \
-      hipLaunchKernelGGL((attn_combine_kernel<D, jt>), dim3(grid_c), dim3(kWGThreads), 0, c->stream, a);        \
-      BD_TRY(check_launch()); }                                                                                \
-    return BD_OK;                                                                                              \
+// Dynamic LDS the forward kernel needs: GEMM staging, or the attention phase's buffers if larger.
+template <int MT>
+constexpr int mega_lds_total() { return mega_lds_bytes<MT>() > 56 * 1024 ? mega_lds_bytes<MT>() : 56 * 1024; }
+
+template <int MT, int D, int JT>
+int launch_mega_inst(bd_ctx* c, const MegaArgs& a) {
+  static bool attr_set = false;
+  constexpr int lds = mega_lds_total<MT>();
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&mega_kernel<MT, D, JT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    attr_set = true;
   }
-  BD_ATT(1) BD_ATT(2) BD_ATT(4)
-#undef BD_ATT
-  return BD_E_ARG;
+  hipLaunchKernelGGL((mega_kernel<MT, D, JT>), dim3(c->plan.nwg), dim3(kWGThreads), lds, c->stream, a);
+  return check_launch();
 }
 
-int attention(bd_ctx* c, int layer, int M, int mode) {
-  const int MT = ceil_div(M, 16);
-  const int JT = attn_jt(c, MT);
-  const int groups = c->cfg.n_kv_heads * (c->G * MT / JT);
-  AttnArgs a{};
-  a.Q = c->q;
-  a.Kc = reinterpret_cast<const bf16x8*>(c->Kc + (size_t)layer * c->kv_layer_elems);
-  a.Vc = reinterpret_cast<const bf16x8*>(c->Vc + (size_t)layer * c->kv_layer_elems);
-  a.st = c->st;
-  a.M = M; a.MT = MT; a.n_q = c->cfg.n_q_heads; a.n_kv = c->cfg.n_kv_heads; a.mode = mode; a.max_kb = c->max_kb;
-  a.max_chunks = attn_max_chunks(c, MT);
-  a.scale_log2e = 1.4426950408889634f / std::sqrt((float)c->D);
-  a.pO = c->pO; a.pm = c->pm; a.pl = c->pl; a.out = c->ap;
-  // the grid covers the chunks the current context length needs (the kernels recompute the same geometry)
-  const int n_kb = ceil_div(c->n + M, 32);
-  int chunk_len = std::max(kWavesPerWG, ceil_div(n_kb, a.max_chunks));
-  const int n_chunks = ceil_div(n_kb, chunk_len);
-  const int grid_p = groups * n_chunks;
-  if (grid_p > c->attn_items_max) {
-    snprintf(g_last_error, sizeof g_last_error, "attention partial buffer too small");
-    return BD_E_HIP;
-  }
-  if (c->D == 128) return launch_attention_d<128>(c, a, JT, grid_p, groups);
-  return launch_attention_d<64>(c, a, JT, grid_p, groups);
+template <int MT>
+int launch_mega_mt(bd_ctx* c, const MegaArgs& a) {
+  if (c->D == 128) return launch_mega_inst<MT, 128, 2>(c, a);
+  return launch_mega_inst<MT, 64, 2>(c, a);
 }
 
-// One decoder forward over the M rows already sitting in c->x (fp32), positions n .. n+M-1.
-// Writes the rows' K/V into the cache at those positions (the context length is not advanced here).
-int forward(bd_ctx* c, int M, int mode, bool want_lm) {
+// One decoder forward over M rows: prologue (block assembly) + the persistent forward kernel.
+// Source of the rows: prompt rows [off, off+M) (embeds then ids), or block tokens with an optional mask.
+int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n_embed, const int32_t* ids, int off,
+            int32_t* seed_tokens, uint8_t* seed_mask, const uint8_t* mask) {
   const int MT = ceil_div(M, 16);
+  const int Mp = c->Mp_max;
   hipStream_t s = c->stream;
   {
-    Prof pr(c, KC_MISC);
-    hipLaunchKernelGGL(rope_table_kernel, dim3(M), dim3(64), 0, s, c->rope, c->st, c->D / 2, c->cfg.rope_theta);
+    PrologueArgs p{};
+    p.x0 = c->xv; p.ssq0 = c->ssq; p.H = c->H; p.Mp = Mp;
+    p.embeds = embeds; p.n_embed = n_embed; p.ids = ids; p.off = off;
+    p.seed_tokens = seed_tokens; p.seed_mask = seed_mask; p.mask = mask;
+    p.mask_id = c->cfg.mask_token_id; p.table = c->embed; p.vocab = c->V; p.st = c->st;
+    p.rope = c->rope; p.half = c->D / 2; p.theta = c->cfg.rope_theta;
+    p.counters = c->counters; p.n_counters = c->n_cntD + c->n_cntA;
+    Prof pr(c, KC_PROLOGUE);
+    hipLaunchKernelGGL(prologue_kernel, dim3(M), dim3(kWGThreads), 0, s, p);
     BD_TRY(check_launch());
   }
-  BD_TRY(resid_norm(c, 0, M, c->layers[0].g_attn));
-  for (int l = 0; l < c->L; ++l) {
-    Layer& ly = c->layers[l];
-    int S = 0;
-    BD_TRY(gemm_partial(c, KC_GEMM_QKV, ly.wqkv, c->xp, c->NQKV, c->H, M, &S));
-    {
-      QkvPostArgs qa{};
-      qa.partial = c->ws; qa.S = S; qa.Mp = MT * 16; qa.n_q = c->cfg.n_q_heads; qa.n_kv = c->cfg.n_kv_heads;
-      qa.D = c->D; qa.max_kb = c->max_kb; qa.rope = c->rope; qa.st = c->st; qa.Q = c->q;
-      qa.Kc = c->Kc + (size_t)l * c->kv_layer_elems; qa.Vc = c->Vc + (size_t)l * c->kv_layer_elems;
-      Prof pr(c, KC_QKV_POST);
-      hipLaunchKernelGGL(qkv_post_kernel, dim3(M), dim3(kWGThreads), 0, s, qa);
-      BD_TRY(check_launch());
+  MegaArgs a{};
+  a.P = c->plan;
+  a.wstream = reinterpret_cast<const bf16x8*>(c->wstream);
+  a.st = c->st; a.bar = c->bar; a.bar_epoch = c->bar_epoch;
+  a.M = M; a.MT = MT; a.mode = mode; a.want_lm = want_lm ? 1 : 0;
+  a.xv = c->xv; a.ssq = c->ssq; a.ssq_parts = c->ssq_parts; a.Mp = Mp; a.gains = c->gains; a.rms_eps = c->cfg.rms_eps;
+  a.rope = c->rope; a.Q = c->q; a.Kc = c->Kc; a.Vc = c->Vc; a.kv_layer_elems = c->kv_layer_elems; a.max_kb = c->max_kb;
+  a.ap = c->ap; a.ap_elems = c->ap_elems; a.act = c->act; a.act_elems = c->act_elems;
+  a.wsD = c->wsD; a.wsD_layer_floats = c->wsD_layer_floats; a.cntD = c->counters;
+  a.pO = c->pO; a.pm = c->pm; a.pl = c->pl; a.pO_layer_floats = c->pO_layer_floats; a.pml_layer_floats = c->pml_layer_floats;
+  a.cntA = c->counters + c->n_cntD;
+  a.attn_max_chunks = attn_max_chunks(c, MT, true);
+  a.scale_log2e = 1.4426950408889634f / std::sqrt((float)c->D);
+  a.lm_max = c->lm_max; a.lm_idx = c->lm_idx; a.lm_sum = c->lm_sum;
+  a.logits = (want_lm && c->logits_on) ? c->logits : nullptr;
+  a.row_cand = c->row_cand; a.row_conf = c->row_conf;
+  {
+    Prof pr(c, KC_FORWARD);
+    switch (MT) {
+      case 1: BD_TRY(launch_mega_mt<1>(c, a)); break;
+      case 2: BD_TRY(launch_mega_mt<2>(c, a)); break;
+      case 3: BD_TRY(launch_mega_mt<3>(c, a)); break;
+      default: BD_TRY(launch_mega_mt<4>(c, a)); break;
     }
-    BD_TRY(attention(c, l, M, mode));
-    BD_TRY(gemm_partial(c, KC_GEMM_O, ly.wo, c->ap, c->H, c->QD, M, &S));
-    BD_TRY(resid_norm(c, S, M, ly.g_ffn));
-    {
-      GemmArgs a{};
-      a.Wp = reinterpret_cast<const bf16x8*>(ly.wgu); a.Xp = reinterpret_cast<const bf16x8*>(c->xp);
-      a.n_tiles = 2 * c->F / 16; a.KS = ceil_div(c->H, 32); a.ksplit = 1; a.M = M; a.N = 2 * c->F; a.act_out = c->act;
-      GemmPlan p = plan_gemm(c, EPI_SWIGLU, a.n_tiles, a.KS, MT);
-      Prof pr(c, KC_GEMM_GATEUP);
-      BD_TRY(launch_gemm_epi<EPI_SWIGLU>(a, MT, p.NT, p.grid, s));
-    }
-    BD_TRY(gemm_partial(c, KC_GEMM_DOWN, ly.wdown, c->act, c->H, c->F, M, &S));
-    BD_TRY(resid_norm(c, S, M, l + 1 < c->L ? c->layers[l + 1].g_attn : c->g_final));
   }
+  c->bar_epoch += 5u * (unsigned)c->L + (want_lm ? 1u : 0u);
   c->last_rows = M;
-  c->last_had_logits = 0;
-  if (want_lm) {
-    GemmArgs a{};
-    a.Wp = reinterpret_cast<const bf16x8*>(c->lm_head); a.Xp = reinterpret_cast<const bf16x8*>(c->xp);
-    a.n_tiles = c->V / 16; a.KS = ceil_div(c->H, 32); a.ksplit = 1; a.M = M; a.N = c->V;
-    a.lm_max = c->lm_max; a.lm_idx = c->lm_idx; a.lm_sum = c->lm_sum;
-    a.logits = c->logits_on ? c->logits : nullptr;
-    GemmPlan p = plan_gemm(c, EPI_LMHEAD, a.n_tiles, a.KS, MT);
-    Prof pr(c, KC_GEMM_LMHEAD);
-    BD_TRY(launch_gemm_epi<EPI_LMHEAD>(a, MT, p.NT, p.grid, s));
-    c->last_had_logits = c->logits_on;
-  }
+  c->last_had_logits = (want_lm && c->logits_on) ? 1 : 0;
   return BD_OK;
 }
 
-int lm_parts(const bd_ctx* c, int M) {
-  const int MT = ceil_div(M, 16);
-  return plan_gemm(c, EPI_LMHEAD, c->V / 16, ceil_div(c->H, 32), MT).grid;
-}
-
 bool all_loaded(const bd_ctx* c) {
-  if (c->loaded_top != 7u) return false;
-  for (const Layer& l : c->layers)
-    if (l.loaded != 0x1FFu) return false;
-  return true;
+  for (int l = 0; l < c->L; ++l)
+    if (c->loaded[l] != 0x1FFu) return false;
+  return c->loaded[c->L] == 7u;
 }
 
 int check_decode_call(const bd_ctx* c, int B) {
@@ -329,9 +258,7 @@ int check_decode_call(const bd_ctx* c, int B) {
 
 FinishArgs finish_args(bd_ctx* c, int B) {
   FinishArgs f{};
-  f.lm_max = c->lm_max; f.lm_idx = c->lm_idx; f.lm_sum = c->lm_sum;
-  f.n_parts = lm_parts(c, B); f.Mp = ceil_div(B, 16) * 16; f.B = B; f.st = c->st;
-  f.row_cand = c->row_cand; f.row_conf = c->row_conf;
+  f.B = B; f.st = c->st; f.row_cand = c->row_cand; f.row_conf = c->row_conf;
   return f;
 }
 
@@ -365,6 +292,12 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   if (k.max_block < 1 || k.max_block > 64 || k.max_seq < k.max_block) return BD_E_ARG;
   if (k.mask_token_id >= k.vocab) return BD_E_ARG;
   if (!(k.rope_theta > 0.f) || !(k.rms_eps > 0.f)) return BD_E_ARG;
+  {
+    // the attention phase works on groups of 2 or 4 column tiles (16 query columns each)
+    // the attention phase works on pairs of column tiles (16 query columns each)
+    const int G = k.n_q_heads / k.n_kv_heads;
+    if (G % 2 != 0) return BD_E_ARG;
+  }
   if (k.weight_dtype == BD_FP8_E4M3) return BD_E_DTYPE;   // fp8 weight streaming is not built yet
   if (k.weight_dtype != BD_BF16) return BD_E_DTYPE;
 
@@ -383,55 +316,55 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   c->NQKV = c->QD + 2 * c->KVD; c->F = k.ffn; c->V = k.vocab; c->L = k.n_layers; c->G = k.n_q_heads / k.n_kv_heads;
   c->Mp_max = ceil_div(k.max_block, 16) * 16;
   c->max_kb = ceil_div(k.max_seq, 32);
-  c->layers.resize(c->L);
+  c->loaded.assign(c->L + 1, 0u);
   c->kv_layer_elems = (size_t)k.n_kv_heads * c->max_kb * 32 * c->D;
+  if (make_plan(c) != BD_OK) { delete c; return BD_E_ARG; }
+  const MegaPlan& P = c->plan;
 
   auto fail = [&](int rc) { bd_destroy(c); return rc; };
 #define A(ptr, bytes) { int rc_ = dev_alloc(c, reinterpret_cast<void**>(&(ptr)), (bytes)); if (rc_ != BD_OK) return fail(rc_); }
-  const size_t Mp = c->Mp_max;
-  A(c->Kc, c->kv_layer_elems * c->L * 2);
-  A(c->Vc, c->kv_layer_elems * c->L * 2);
-  A(c->x, Mp * c->H * 4);
-  A(c->xp, (size_t)ceil_div(c->H, 32) * 32 * Mp * 2);
-  A(c->q, Mp * c->QD * 2);
-  A(c->ap, (size_t)ceil_div(c->QD, 32) * 32 * Mp * 2);
-  A(c->act, (size_t)ceil_div(c->F, 32) * 32 * Mp * 2);
-  c->ws_floats = (size_t)16 * Mp * std::max(c->NQKV, c->H);
-  A(c->ws, c->ws_floats * 4);
+  const size_t Mp = c->Mp_max, L = c->L;
+  A(c->wstream, (size_t)P.nwg * kWavesPerWG * P.wave_stride * 16);
+  A(c->embed, (size_t)c->V * c->H * 2);
+  A(c->gains, (2 * L + 1) * c->H * 4);
+  A(c->Kc, c->kv_layer_elems * L * 2);
+  A(c->Vc, c->kv_layer_elems * L * 2);
+  A(c->xv, (2 * L + 1) * Mp * c->H * 4);
+  c->ssq_parts = std::max(phase_tile_slots(P, PH_O), phase_tile_slots(P, PH_DOWN));
+  A(c->ssq, (2 * L + 1) * (size_t)c->ssq_parts * Mp * 4);
   A(c->rope, Mp * (c->D / 2) * sizeof(float2));
+  A(c->q, L * Mp * c->QD * 2);
+  c->ap_elems = (size_t)ceil_div(c->QD, 32) * 32 * Mp;
+  A(c->ap, L * c->ap_elems * 2);
+  c->act_elems = (size_t)ceil_div(c->F, 32) * 32 * Mp;
+  A(c->act, L * c->act_elems * 2);
+  c->wsD_layer_floats = (size_t)P.ph[PH_DOWN].ksplit * phase_tile_slots(P, PH_DOWN) * (Mp / 16) * 64 * 4;
+  A(c->wsD, L * c->wsD_layer_floats * 4);
   {
-    // attention partials: sized for the largest item count any (M, n) can produce
-    int items = 0;
+    // attention partials of one layer: sized for the largest item count any (M, n) can produce
+    size_t tiles = 0; int groups_max = 0;
     for (int MT = 1; MT <= (int)Mp / 16; ++MT) {
-      const int JT = attn_jt(c, MT);
+      const int JT = attn_jt(c, MT, true);
       const int groups = k.n_kv_heads * (c->G * MT / JT);
-      const int mc = attn_max_chunks(c, MT);
-      items = std::max(items, groups * mc * JT);           // in units of one column tile
+      tiles = std::max(tiles, (size_t)groups * attn_max_chunks(c, MT, true) * JT);
+      groups_max = std::max(groups_max, groups);
     }
-    c->attn_items_max = items;                             // conservative: counts JT=1-sized items
-    A(c->pO, (size_t)items * (c->D / 16) * 64 * 16);
-    A(c->pm, (size_t)items * 16 * 4);
-    A(c->pl, (size_t)items * 16 * 4);
+    c->pO_layer_floats = tiles * (c->D / 16) * 64 * 4;
+    c->pml_layer_floats = tiles * 16;
+    A(c->pO, L * c->pO_layer_floats * 4);
+    A(c->pm, L * c->pml_layer_floats * 4);
+    A(c->pl, L * c->pml_layer_floats * 4);
+    c->n_cntD = (int)L * phase_tile_slots(P, PH_DOWN);
+    c->n_cntA = (int)L * groups_max;
+    A(c->counters, (size_t)(c->n_cntD + c->n_cntA) * 4);
   }
-  c->lm_parts_max = 4 * c->num_cus;
-  A(c->lm_max, (size_t)c->lm_parts_max * Mp * 4);
-  A(c->lm_idx, (size_t)c->lm_parts_max * Mp * 4);
-  A(c->lm_sum, (size_t)c->lm_parts_max * Mp * 4);
+  A(c->lm_max, (size_t)P.nwg * Mp * 4);
+  A(c->lm_idx, (size_t)P.nwg * Mp * 4);
+  A(c->lm_sum, (size_t)P.nwg * Mp * 4);
   A(c->row_cand, Mp * 4);
   A(c->row_conf, Mp * 4);
   A(c->st, sizeof(DevState));
-  // weights
-  A(c->embed, (size_t)c->V * c->H * 2);
-  A(c->lm_head, (size_t)c->V * ceil_div(c->H, 32) * 32 * 2);
-  A(c->g_final, (size_t)c->H * 4);
-  for (Layer& l : c->layers) {
-    A(l.wqkv, (size_t)c->NQKV * ceil_div(c->H, 32) * 32 * 2);
-    A(l.wo, (size_t)c->H * ceil_div(c->QD, 32) * 32 * 2);
-    A(l.wgu, (size_t)2 * c->F * ceil_div(c->H, 32) * 32 * 2);
-    A(l.wdown, (size_t)c->H * ceil_div(c->F, 32) * 32 * 2);
-    A(l.g_attn, (size_t)c->H * 4);
-    A(l.g_ffn, (size_t)c->H * 4);
-  }
+  A(c->bar, (size_t)(1 + 2 * ceil_div(P.nwg, kBarGroup)) * 32 * 4);
 #undef A
   hipError_t e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) {
@@ -444,10 +377,10 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
 
 void bd_destroy(bd_ctx* c) {
   if (c == nullptr) return;
-  hipStreamSynchronize(c->stream);
-  for (hipEvent_t e : c->prof_ev) hipEventDestroy(e);
-  for (void* p : c->allocs) hipFree(p);
-  if (c->logits) hipFree(c->logits);
+  (void)hipStreamSynchronize(c->stream);
+  for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
+  for (void* p : c->allocs) (void)hipFree(p);
+  if (c->logits) (void)hipFree(c->logits);
   delete c;
 }
 
@@ -465,27 +398,25 @@ int bd_load_weight(bd_ctx* c, const char* name, const void* host_ptr, size_t byt
     base = nm.substr(dot + 1);
     if (layer < 0 || layer >= c->L) return BD_E_ARG;
   }
-  // destination, logical shape, packing placement
-  int rows = 0, K = 0, tile_off = 0, tile_stride = 1, bit = -1;
-  u16* dst = nullptr;
+  // logical shape and where the rows go in the weight stream
+  int rows = 0, K = 0, ph = -1, row_base = 0, row_map = 0, bit = -1;
   float* gain_dst = nullptr;
-  bool row_major_bf16 = false;
+  bool is_embed = false;
   if (layer < 0) {
-    if (base == "embed") { rows = c->V; K = c->H; dst = c->embed; row_major_bf16 = true; bit = 0; }
-    else if (base == "lm_head") { rows = c->V; K = c->H; dst = c->lm_head; bit = 1; }
-    else if (base == "final_norm") { rows = c->H; gain_dst = c->g_final; bit = 2; }
+    if (base == "embed") { rows = c->V; K = c->H; is_embed = true; bit = 0; }
+    else if (base == "lm_head") { rows = c->V; K = c->H; ph = PH_LM; bit = 1; }
+    else if (base == "final_norm") { rows = c->H; gain_dst = c->gains + (size_t)(2 * c->L) * c->H; bit = 2; }
     else return BD_E_ARG;
   } else {
-    Layer& l = c->layers[layer];
-    if (base == "attn_norm") { rows = c->H; gain_dst = l.g_attn; bit = 0; }
-    else if (base == "ffn_norm") { rows = c->H; gain_dst = l.g_ffn; bit = 1; }
-    else if (base == "wq") { rows = c->QD; K = c->H; dst = l.wqkv; tile_off = 0; bit = 2; }
-    else if (base == "wk") { rows = c->KVD; K = c->H; dst = l.wqkv; tile_off = c->QD / 16; bit = 3; }
-    else if (base == "wv") { rows = c->KVD; K = c->H; dst = l.wqkv; tile_off = (c->QD + c->KVD) / 16; bit = 4; }
-    else if (base == "wo") { rows = c->H; K = c->QD; dst = l.wo; bit = 5; }
-    else if (base == "w_gate") { rows = c->F; K = c->H; dst = l.wgu; tile_off = 0; tile_stride = 2; bit = 6; }
-    else if (base == "w_up") { rows = c->F; K = c->H; dst = l.wgu; tile_off = 1; tile_stride = 2; bit = 7; }
-    else if (base == "w_down") { rows = c->H; K = c->F; dst = l.wdown; bit = 8; }
+    if (base == "attn_norm") { rows = c->H; gain_dst = c->gains + (size_t)(2 * layer) * c->H; bit = 0; }
+    else if (base == "ffn_norm") { rows = c->H; gain_dst = c->gains + (size_t)(2 * layer + 1) * c->H; bit = 1; }
+    else if (base == "wq") { rows = c->QD; K = c->H; ph = PH_QKV; row_base = 0; row_map = 1; bit = 2; }
+    else if (base == "wk") { rows = c->KVD; K = c->H; ph = PH_QKV; row_base = c->QD; row_map = 1; bit = 3; }
+    else if (base == "wv") { rows = c->KVD; K = c->H; ph = PH_QKV; row_base = c->QD + c->KVD; bit = 4; }
+    else if (base == "wo") { rows = c->H; K = c->QD; ph = PH_O; bit = 5; }
+    else if (base == "w_gate") { rows = c->F; K = c->H; ph = PH_GU; row_base = 0; row_map = 2; bit = 6; }
+    else if (base == "w_up") { rows = c->F; K = c->H; ph = PH_GU; row_base = 1; row_map = 2; bit = 7; }
+    else if (base == "w_down") { rows = c->H; K = c->F; ph = PH_DOWN; bit = 8; }
     else return BD_E_ARG;
   }
   if (gain_dst != nullptr) {
@@ -500,32 +431,29 @@ int bd_load_weight(bd_ctx* c, const char* name, const void* host_ptr, size_t byt
     HIP_TRY(hipMalloc(&stage, bytes));
     hipError_t e = hipMemcpy(stage, host_ptr, bytes, hipMemcpyHostToDevice);
     if (e == hipSuccess) {
-      if (row_major_bf16) {
+      if (is_embed) {
         if (dtype == BD_F32)
-          hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(2048), dim3(256), 0, c->stream, (const float*)stage, dst,
+          hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(2048), dim3(256), 0, c->stream, (const float*)stage, c->embed,
                              (size_t)rows * K);
         else
-          e = hipMemcpyAsync(dst, stage, bytes, hipMemcpyDeviceToDevice, c->stream);
+          e = hipMemcpyAsync(c->embed, stage, bytes, hipMemcpyDeviceToDevice, c->stream);
+      } else if (dtype == BD_F32) {
+        hipLaunchKernelGGL(pack_stream_kernel<float>, dim3(4096), dim3(256), 0, c->stream, (const float*)stage, rows, K,
+                           c->plan, ph, std::max(layer, 0), row_base, row_map, c->D, c->wstream);
       } else {
-        const int KS = ceil_div(K, 32);
-        if (dtype == BD_F32)
-          hipLaunchKernelGGL(pack_weight_kernel<float>, dim3(2048), dim3(256), 0, c->stream, (const float*)stage,
-                             (const float*)nullptr, rows, K, KS, dst, tile_off, tile_stride);
-        else
-          hipLaunchKernelGGL(pack_weight_kernel<u16>, dim3(2048), dim3(256), 0, c->stream, (const u16*)stage,
-                             (const float*)nullptr, rows, K, KS, dst, tile_off, tile_stride);
+        hipLaunchKernelGGL(pack_stream_kernel<u16>, dim3(4096), dim3(256), 0, c->stream, (const u16*)stage, rows, K,
+                           c->plan, ph, std::max(layer, 0), row_base, row_map, c->D, c->wstream);
       }
       if (e == hipSuccess) e = hipGetLastError();
       if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     }
-    hipFree(stage);
+    (void)hipFree(stage);
     if (e != hipSuccess) {
       snprintf(g_last_error, sizeof g_last_error, "weight upload failed: %s", hipGetErrorString(e));
       return BD_E_HIP;
     }
   }
-  if (layer < 0) c->loaded_top |= 1u << bit;
-  else c->layers[layer].loaded |= 1u << bit;
+  c->loaded[layer < 0 ? c->L : layer] |= 1u << bit;
   return BD_OK;
 }
 
@@ -543,14 +471,11 @@ int bd_prefill(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* d
   for (int off = 0; off < total; off += step) {
     const int M = std::min(step, total - off);
     const bool last = off + M >= total;
-    hipLaunchKernelGGL(embed_kernel, dim3(M), dim3(256), 0, s, c->x, c->H, dev_embeds, n_embed, dev_ids, off,
-                       (const uint8_t*)nullptr, c->cfg.mask_token_id, c->embed, c->V);
-    BD_TRY(check_launch());
-    BD_TRY(forward(c, M, BD_MODE_CAUSAL, last));
+    BD_TRY(forward(c, M, BD_MODE_CAUSAL, last, dev_embeds, n_embed, dev_ids, off, nullptr, nullptr, nullptr));
     if (last) {
       FinishArgs f = finish_args(c, M);
       f.commit = 1;
-      hipLaunchKernelGGL(finish_causal_kernel, dim3(1), dim3(kWGThreads), 0, s, f);
+      hipLaunchKernelGGL(finish_causal_kernel, dim3(1), dim3(64), 0, s, f);
     } else {
       hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(1), 0, s, c->st, M);
     }
@@ -566,36 +491,30 @@ int bd_denoise_step(bd_ctx* c, int32_t* dev_block_tokens, uint8_t* dev_mask, int
   BD_TRY(check_decode_call(c, B));
   if (dev_block_tokens == nullptr || dev_mask == nullptr || fixed_k < 0) return BD_E_ARG;
   hipStream_t s = c->stream;
-  hipLaunchKernelGGL(seed_kernel, dim3(1), dim3(64), 0, s, dev_block_tokens, dev_mask, c->st);
-  BD_TRY(check_launch());
   if (B == 1) {
+    hipLaunchKernelGGL(seed_kernel, dim3(1), dim3(64), 0, s, dev_block_tokens, dev_mask, c->st);
+    BD_TRY(check_launch());
     hipLaunchKernelGGL(finish_seed_only_kernel, dim3(1), dim3(64), 0, s, c->st, dev_n_unmasked, dev_conf_out);
     return check_launch();
   }
-  hipLaunchKernelGGL(embed_kernel, dim3(B), dim3(256), 0, s, c->x, c->H, (const float*)nullptr, 0, dev_block_tokens, 0,
-                     dev_mask, c->cfg.mask_token_id, c->embed, c->V);
-  BD_TRY(check_launch());
-  BD_TRY(forward(c, B, BD_MODE_BIDIR, true));
+  BD_TRY(forward(c, B, BD_MODE_BIDIR, true, nullptr, 0, dev_block_tokens, 0, dev_block_tokens, dev_mask, dev_mask));
   FinishArgs f = finish_args(c, B);
   f.tokens = dev_block_tokens; f.mask = dev_mask; f.threshold = threshold; f.fixed_k = fixed_k;
   f.n_unmasked = dev_n_unmasked; f.conf_out = dev_conf_out;
-  Prof pr(c, KC_MISC);
-  hipLaunchKernelGGL(finish_denoise_kernel, dim3(1), dim3(kWGThreads), 0, s, f);
+  Prof pr(c, KC_FINISH);
+  hipLaunchKernelGGL(finish_denoise_kernel, dim3(1), dim3(64), 0, s, f);
   return check_launch();
 }
 
 static int causal_pass(bd_ctx* c, const int32_t* dev_tokens, int B, int commit, int32_t* dev_ar_pred,
                        int32_t* dev_n_accept, const int32_t* draft) {
   hipStream_t s = c->stream;
-  hipLaunchKernelGGL(embed_kernel, dim3(B), dim3(256), 0, s, c->x, c->H, (const float*)nullptr, 0, dev_tokens, 0,
-                     (const uint8_t*)nullptr, c->cfg.mask_token_id, c->embed, c->V);
-  BD_TRY(check_launch());
-  BD_TRY(forward(c, B, BD_MODE_CAUSAL, true));
+  BD_TRY(forward(c, B, BD_MODE_CAUSAL, true, nullptr, 0, dev_tokens, 0, nullptr, nullptr, nullptr));
   FinishArgs f = finish_args(c, B);
   f.draft = draft; f.commit = commit; f.ar_pred = dev_ar_pred; f.n_accept = dev_n_accept;
   {
-    Prof pr(c, KC_MISC);
-    hipLaunchKernelGGL(finish_causal_kernel, dim3(1), dim3(kWGThreads), 0, s, f);
+    Prof pr(c, KC_FINISH);
+    hipLaunchKernelGGL(finish_causal_kernel, dim3(1), dim3(64), 0, s, f);
     BD_TRY(check_launch());
   }
   if (commit) { c->n += B; c->carry_valid = true; }
@@ -629,6 +548,18 @@ int bd_crop(bd_ctx* c, int new_len) {
 
 int bd_cache_len(const bd_ctx* c) { return c == nullptr ? BD_E_ARG : c->n; }
 
+int bd_status(bd_ctx* c) {
+  if (c == nullptr) return BD_E_ARG;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  DevState h;
+  HIP_TRY(hipMemcpy(&h, c->st, sizeof h, hipMemcpyDeviceToHost));
+  if (h.error != 0) {
+    snprintf(g_last_error, sizeof g_last_error, "a grid barrier of the forward kernel timed out; the context is unusable");
+    return BD_E_HIP;
+  }
+  return BD_OK;
+}
+
 int bd_debug_logits(bd_ctx* c, int enable) {
   if (c == nullptr) return BD_E_ARG;
   if (enable && c->logits == nullptr) HIP_TRY(hipMalloc(reinterpret_cast<void**>(&c->logits), (size_t)c->Mp_max * c->V * 4));
@@ -648,7 +579,7 @@ int bd_read_kv(bd_ctx* c, int layer, int pos0, int count, float* dev_k_out, floa
   if (pos0 + count > c->cfg.max_seq) return BD_E_ARG;
   hipLaunchKernelGGL(read_kv_kernel, dim3(256), dim3(256), 0, c->stream, c->Kc + (size_t)layer * c->kv_layer_elems,
                      c->Vc + (size_t)layer * c->kv_layer_elems, c->cfg.n_kv_heads, c->D, c->max_kb, pos0, count,
-                     dev_k_out, dev_v_out);
+                     dev_k_out, dev_v_out, 1);
   return check_launch();
 }
 
@@ -680,7 +611,7 @@ int64_t bd_forward_bytes(const bd_ctx* c) {
 int bd_k_profile(bd_ctx* c, int enable) {
   if (c == nullptr) return BD_E_ARG;
   HIP_TRY(hipStreamSynchronize(c->stream));
-  for (hipEvent_t e : c->prof_ev) hipEventDestroy(e);
+  for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   c->prof_ev.clear(); c->prof_cls.clear();
   c->prof_on = enable != 0;
   return BD_OK;
@@ -702,8 +633,7 @@ int bd_k_profile_read(bd_ctx* c, int kclass, double* total_ms, int* launches) {
 }
 
 const char* bd_k_class_name(int kclass) {
-  static const char* names[KC_COUNT] = {"gemm_qkv", "qkv_post", "attn_partial", "attn_combine", "gemm_o", "resid_norm",
-                                        "gemm_gateup_swiglu", "gemm_down", "gemm_lmhead", "misc"};
+  static const char* names[KC_COUNT] = {"prologue", "forward", "finish"};
   return (kclass >= 0 && kclass < KC_COUNT) ? names[kclass] : nullptr;
 }
 
@@ -711,18 +641,68 @@ int bd_k_class_count(void) { return KC_COUNT; }
 
 int64_t bd_k_class_bytes(const bd_ctx* c, int kclass) {
   if (c == nullptr) return BD_E_ARG;
-  switch (kclass) {
-    case KC_GEMM_QKV: return (int64_t)c->H * c->NQKV * 2;
-    case KC_GEMM_O: return (int64_t)c->QD * c->H * 2;
-    case KC_GEMM_GATEUP: return 2ll * c->H * c->F * 2;
-    case KC_GEMM_DOWN: return (int64_t)c->H * c->F * 2;
-    case KC_GEMM_LMHEAD: return (int64_t)c->V * c->H * 2;
-    case KC_ATTN_PARTIAL: return (int64_t)c->n * 2 * c->KVD * 2;
-    default: return 0;
-  }
+  return kclass == KC_FORWARD ? bd_forward_bytes(c) : 0;
 }
 
 }  // extern "C"
+
+namespace {
+// ---- launch helpers of the stand-alone GEMM / attention entry points -----------------------------------
+GemmPlan plan_gemm(int num_cus, int n_tiles, int KS) {
+  GemmPlan p;
+  p.NT = (n_tiles % 2 == 0) ? 2 : 1;
+  const int groups = n_tiles / p.NT;
+  int ks = (3 * num_cus / 2 + groups - 1) / groups;
+  ks = std::max(1, std::min(ks, std::max(1, KS / 8)));
+  p.ksplit = std::min(ks, 16);
+  p.grid = groups * p.ksplit;
+  return p;
+}
+
+int launch_gemm_partial(const GemmArgs& a, int MT, int NT, int grid, hipStream_t s) {
+#define BD_CASE(mt, nt) \
+  if (MT == mt && NT == nt) { hipLaunchKernelGGL((gemm_kernel<mt, nt, EPI_PARTIAL>), dim3(grid), dim3(kWGThreads), 0, s, a); return check_launch(); }
+  BD_CASE(1, 1) BD_CASE(2, 1) BD_CASE(3, 1) BD_CASE(4, 1) BD_CASE(1, 2) BD_CASE(2, 2) BD_CASE(3, 2) BD_CASE(4, 2)
+#undef BD_CASE
+  return BD_E_ARG;
+}
+
+template <int D>
+int launch_attention_d(hipStream_t s, const AttnArgs& a, int JT, int grid_p, int grid_c) {
+#define BD_ATT(jt)                                                                                      \
+  if (JT == jt) {                                                                                       \
+    hipLaunchKernelGGL((attn_partial_kernel<D, jt>), dim3(grid_p), dim3(kWGThreads), 0, s, a);           \
+    BD_TRY(check_launch());                                                                             \
+    hipLaunchKernelGGL((attn_combine_kernel<D, jt>), dim3(grid_c), dim3(kWGThreads), 0, s, a);           \
+    return check_launch();                                                                              \
+  }
+  BD_ATT(1) BD_ATT(2) BD_ATT(4)
+#undef BD_ATT
+  return BD_E_ARG;
+}
+
+int attention(bd_ctx* c, int layer, int M, int mode) {
+  const int MT = ceil_div(M, 16);
+  const int JT = attn_jt(c, MT);
+  const int groups = c->cfg.n_kv_heads * (c->G * MT / JT);
+  AttnArgs a{};
+  a.Q = c->q;
+  a.Kc = reinterpret_cast<const bf16x8*>(c->Kc + (size_t)layer * c->kv_layer_elems);
+  a.Vc = reinterpret_cast<const bf16x8*>(c->Vc + (size_t)layer * c->kv_layer_elems);
+  a.st = c->st;
+  a.M = M; a.MT = MT; a.n_q = c->cfg.n_q_heads; a.n_kv = c->cfg.n_kv_heads; a.mode = mode; a.max_kb = c->max_kb;
+  a.max_chunks = attn_max_chunks(c, MT);
+  a.scale_log2e = 1.4426950408889634f / std::sqrt((float)c->D);
+  a.pO = c->pO; a.pm = c->pm; a.pl = c->pl; a.out = c->ap;
+  const int n_kb = ceil_div(c->n + M, 32);
+  const int chunk_len = std::max(kWavesPerWG, ceil_div(n_kb, a.max_chunks));
+  const int n_chunks = ceil_div(n_kb, chunk_len);
+  const int grid_p = groups * n_chunks;
+  if (grid_p > c->attn_items_max) return BD_E_ARG;
+  if (c->D == 128) return launch_attention_d<128>(c->stream, a, JT, grid_p, groups);
+  return launch_attention_d<64>(c->stream, a, JT, grid_p, groups);
+}
+}  // namespace
 
 namespace {
 struct TmpBufs {
@@ -770,13 +750,11 @@ extern "C" int bd_k_gemm(void* hip_stream, const uint16_t* dev_w, const float* d
   if (M < 1 || M > 64 || N < 16 || N % 16 != 0 || K < 1 || iters < 1) return BD_E_ARG;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int MT = ceil_div(M, 16), KS = ceil_div(K, 32);
-  bd_ctx fake;                                       // only the fields the planner reads
   int dev = 0;
   HIP_TRY(hipGetDevice(&dev));
   hipDeviceProp_t prop;
   HIP_TRY(hipGetDeviceProperties(&prop, dev));
-  fake.num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  GemmPlan p = plan_gemm(&fake, EPI_PARTIAL, N / 16, KS, MT);
+  GemmPlan p = plan_gemm(prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256, N / 16, KS);
   TmpBufs t;
   u16 *wp, *xp; float* ws;
   BD_TRY(t.get(&wp, (size_t)N * KS * 32 * 2));
@@ -788,7 +766,7 @@ extern "C" int bd_k_gemm(void* hip_stream, const uint16_t* dev_w, const float* d
   GemmArgs a{};
   a.Wp = reinterpret_cast<const bf16x8*>(wp); a.Xp = reinterpret_cast<const bf16x8*>(xp);
   a.n_tiles = N / 16; a.KS = KS; a.ksplit = p.ksplit; a.M = M; a.N = N; a.partial = ws;
-  BD_TRY(timed_loop(s, iters, avg_ms, [&]() { return launch_gemm_epi<EPI_PARTIAL>(a, MT, p.NT, p.grid, s); }));
+  BD_TRY(timed_loop(s, iters, avg_ms, [&]() { return launch_gemm_partial(a, MT, p.NT, p.grid, s); }));
   hipLaunchKernelGGL(reduce_partial_kernel, dim3(512), dim3(256), 0, s, ws, p.ksplit, MT * 16, N, M, dev_y);
   BD_TRY(check_launch());
   HIP_TRY(hipStreamSynchronize(s));

@@ -1,0 +1,1026 @@
+// The whole decoder forward as ONE persistent kernel (one workgroup per compute unit).
+//
+// Why: a block-denoising step at B<=64 is a chain of ~180 small dependent operations whose only real
+// cost is streaming 6.2 GB of weights; launched one by one they spend more time between kernels than
+// in them.  Here every compute unit owns a fixed slice of every weight matrix, laid out in HBM in the
+// exact order it will read it (one sequential stream per wavefront), and walks through the phases of
+// every layer with grid-wide barriers in between.  The first chunk of the next phase's weights is
+// requested before a barrier is entered, so HBM keeps streaming while the barrier and the activation
+// hand-over are in flight.
+//
+// Phases of a layer (dependencies force a grid barrier after each):
+//   QKV   RMSNorm-on-load + [Q|K|V] projection + rotary + Q store + KV-cache write
+//   ATT   block-causal attention over the cache (split over key chunks, last arriver merges)
+//   O     output projection + residual + per-tile sum of squares for the next norm
+//   GU    RMSNorm-on-load + gate/up projection + SwiGLU
+//   DOWN  down projection, K split over workgroups, last arriver reduces + residual + sum of squares
+// and after the last layer  LM: RMSNorm-on-load + LM head + per-row (max, argmax, sum exp).
+//
+// Cross-workgroup data discipline (no cache flushes or invalidations inside the kernel):
+//   * every buffer that one workgroup writes and another reads is written with write-through
+//     (agent-scope) stores and is written at most once per forward, in a phase that ends before any
+//     phase that reads it; so no L1/L2 of any XCD can hold a stale copy, and plain loads are safe;
+//   * a workgroup signals (barrier arrival, split-K counters) only after its stores have completed
+//     (s_waitcnt on the in-order vector-memory counter).
+#pragma once
+#include "attention.h"
+#include "common.h"
+#include "gemm.h"
+
+namespace bd {
+
+constexpr int kMaxKW = 16;   // k-steps (of 32) one wavefront covers in a GEMM phase
+constexpr int kT = 2;        // 16-row tiles a wavefront accumulates side by side (one chunk of its stream)
+constexpr int kBarGroup = 16;
+constexpr int kSpinLimit = 1 << 19;
+
+enum { PH_QKV = 0, PH_O = 1, PH_GU = 2, PH_DOWN = 3, PH_LM = 4, PH_COUNT = 5, PH_END = 6 };
+
+struct PhasePlan {
+  int N;        // output rows of the phase (after fusing / interleaving)
+  int KS;       // k-steps
+  int ksplit;   // workgroups that share an output row range and split K
+  int RW;       // rows per row range (even)
+};
+
+struct MegaPlan {
+  int nwg, L, H, QD, KVD, F, V, D, n_q, n_kv;
+  PhasePlan ph[PH_COUNT];
+  long long wave_stride;   // 16-byte units reserved per wavefront in the weight stream
+};
+
+struct WavePhase { int rows, row0, ng, kg, w0, KW; };
+
+// 16-row tiles per row range of a phase, and (row range, tile) pairs of the whole phase
+__host__ __device__ inline int phase_tpg(const PhasePlan& ph) { return (ph.RW + 15) >> 4; }
+__host__ __device__ inline int phase_tile_slots(const MegaPlan& P, int p) {
+  return (P.nwg / P.ph[p].ksplit) * phase_tpg(P.ph[p]);
+}
+
+__host__ __device__ inline WavePhase wave_phase(const MegaPlan& P, int p, int wg, int w) {
+  const PhasePlan& ph = P.ph[p];
+  WavePhase r;
+  const int ng = wg / ph.ksplit;
+  r.ng = ng;
+  r.kg = wg % ph.ksplit;
+  r.row0 = ng * ph.RW;
+  int rows = ph.N - r.row0;
+  if (rows > ph.RW) rows = ph.RW;
+  if (rows < 0) rows = 0;
+  r.rows = rows;
+  const int k0 = (int)((long long)ph.KS * r.kg / ph.ksplit), k1 = (int)((long long)ph.KS * (r.kg + 1) / ph.ksplit);
+  const int len = k1 - k0;
+  r.w0 = k0 + len * w / kWavesPerWG;
+  r.KW = k0 + len * (w + 1) / kWavesPerWG - r.w0;
+  return r;
+}
+// 16-byte units one wavefront streams in a phase: rows x KW fragments of 4 units (64 bytes per row)
+__host__ __device__ inline long long wave_phase_units(const WavePhase& wp) { return (long long)wp.rows * 4 * wp.KW; }
+__host__ __device__ inline long long wave_layer_units(const MegaPlan& P, int wg, int w) {
+  long long s = 0;
+  for (int p = 0; p < PH_LM; ++p) s += wave_phase_units(wave_phase(P, p, wg, w));
+  return s;
+}
+// Position (16-byte units from the wavefront's phase start) of row `lr` (local to the row range),
+// k-step `ksl` (local to the wavefront), k-quarter kq: tiles of 16 rows go in chunks of two.
+__host__ __device__ inline long long stream_pos(int rows, int KW, int lr, int ksl, int kq) {
+  const int tile = lr >> 4, i = lr & 15, c = tile >> 1, t = tile & 1;
+  const int n_tiles = (rows + 15) >> 4;
+  const int R0 = min(16, rows - 32 * c);
+  const int R1 = (2 * c + 1 < n_tiles) ? min(16, rows - 32 * c - 16) : 0;
+  const int R = t ? R1 : R0;
+  return (long long)c * 32 * 4 * KW + (long long)ksl * (R0 + R1) * 4 + (t ? R0 * 4 : 0) + kq * R + i;
+}
+
+struct MegaArgs {
+  MegaPlan P;
+  const bf16x8* wstream;
+  DevState* st;
+  unsigned* bar;              // barrier words (see grid_barrier)
+  unsigned bar_epoch;         // epoch of the last barrier of the previous forward
+  int M, MT, mode, want_lm;
+  // activations (all write-once per forward)
+  float* xv;                  // [2L+1][Mp][H] residual stream versions
+  float* ssq;                 // [2L+1][parts][Mp] partial sums of squares of each version
+  int ssq_parts;              // stride (parts) per version; version 0 has one part, odd versions one per
+                              // tile slot of the O phase, even versions one per tile slot of the DOWN phase
+  int Mp;
+  const float* gains;         // [2L+1][H]: attn_norm l, ffn_norm l, ..., final_norm
+  float rms_eps;
+  const float2* rope;         // [Mp][D/2]
+  u16* Q;                     // [L][Mp][n_q][D]  (dims in rotary-pair order)
+  u16* Kc; u16* Vc;           // packed caches, [L][n_kv][max_kb] blocks
+  size_t kv_layer_elems;
+  int max_kb;
+  u16* ap;                    // [L] packed attention output (K = QD)
+  size_t ap_elems;
+  u16* act;                   // [L] packed SwiGLU output (K = F)
+  size_t act_elems;
+  float* wsD;                 // [L][ksplit][tiles][MT][64] f32x4 partials of the down projection
+  size_t wsD_layer_floats;
+  unsigned* cntD;             // [L][H/16] arrival counters (zeroed by the prologue kernel)
+  // attention
+  float* pO; float* pm; float* pl;   // per layer partials
+  size_t pO_layer_floats, pml_layer_floats;
+  unsigned* cntA;             // [L][groups]
+  int attn_max_chunks;
+  float scale_log2e;
+  // LM head
+  float* lm_max; int* lm_idx; float* lm_sum;   // [nwg][Mp]
+  float* logits;
+  int* row_cand; float* row_conf;
+};
+
+// ---- write-through stores and ordered waits ---------------------------------------------------------------
+__device__ inline void st_wt_u32(void* p, uint32_t v) {
+  __hip_atomic_store(reinterpret_cast<uint32_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_wt_u16(void* p, u16 v) {
+  __hip_atomic_store(reinterpret_cast<u16*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_wt_u64(void* p, uint64_t v) {
+  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_wt_f32(void* p, float v) {
+  __hip_atomic_store(reinterpret_cast<float*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_wt_f32x4(void* p, f32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+// Wait until at most `k` of this wavefront's vector-memory operations are outstanding.  The counter is
+// in order, so with exactly k loads issued after a group of stores this means "the stores are done".
+__device__ inline void wait_vm_allow(int k) {
+#define BD_W(n) case n: asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory"); break;
+  switch (k) {
+    BD_W(1) BD_W(2) BD_W(3) BD_W(4) BD_W(5) BD_W(6) BD_W(7) BD_W(8) BD_W(9) BD_W(10) BD_W(11) BD_W(12) BD_W(13)
+    BD_W(14) BD_W(15) BD_W(16) BD_W(17) BD_W(18) BD_W(19) BD_W(20) BD_W(21) BD_W(22) BD_W(23) BD_W(24) BD_W(25)
+    BD_W(26) BD_W(27) BD_W(28) BD_W(29) BD_W(30) BD_W(31) BD_W(32)
+    default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+  }
+#undef BD_W
+}
+
+// ---- grid barrier --------------------------------------------------------------------------------------
+// Two-level arrival counters (groups of 16 workgroups, one 128-byte line per counter), release words per
+// group.  Counters only grow; `epoch` numbers the barriers of the whole process.  Bounded spin: on
+// time-out the device error flag is set and every later barrier of this launch returns at once.
+// Layout of `bar`: [0] top counter, [32*(1+g)] group counters, [32*(1+ng+g)] release words.
+__device__ inline bool grid_barrier(unsigned* bar, unsigned epoch, int nwg, DevState* st, int* s_flag) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int ok = 1;
+    if (*s_flag != 0) {
+      const int ng = (nwg + kBarGroup - 1) / kBarGroup;
+      const int g = blockIdx.x / kBarGroup;
+      const int gsize = min(kBarGroup, nwg - g * kBarGroup);
+      unsigned* gcnt = bar + 32 * (1 + g);
+      unsigned* rel = bar + 32 * (1 + ng);
+      const unsigned old = __hip_atomic_fetch_add(gcnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old == epoch * (unsigned)gsize - 1u) {
+        const unsigned o2 = __hip_atomic_fetch_add(bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (o2 == epoch * (unsigned)ng - 1u)
+          for (int r = 0; r < ng; ++r)
+            __hip_atomic_store(rel + 32 * r, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      const unsigned* mine = rel + 32 * g;
+      int spins = 0;
+      while ((int)(__hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) < 0) {
+        if (++spins > kSpinLimit) { ok = 0; break; }
+        __builtin_amdgcn_s_sleep(2);
+      }
+      if (!ok) {
+        __hip_atomic_store(&st->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = 0;
+      }
+    }
+  }
+  __syncthreads();
+  return *s_flag != 0;
+}
+
+// ---- weight stream cursor ----------------------------------------------------------------------------------
+struct ChunkRef {
+  const bf16x8* ptr;   // start of the chunk in this wavefront's stream
+  int KW, R0, R1;      // k-steps; rows of the chunk's first / second tile (R1 = 0: single tile)
+};
+
+struct Cursor {
+  const bf16x8* pos;
+  int l, p, c, wg, w, want_lm;
+  __device__ ChunkRef next(const MegaPlan& P) {
+    ChunkRef r;
+    r.ptr = pos; r.KW = 0; r.R0 = 0; r.R1 = 0;
+    while (p != PH_END) {
+      const WavePhase wp = wave_phase(P, p, wg, w);
+      const int n_tiles = (wp.rows + 15) >> 4;
+      const int n_chunks = (n_tiles + 1) >> 1;
+      if (c < n_chunks && wp.KW > 0) {
+        r.ptr = pos;
+        r.KW = wp.KW;
+        r.R0 = min(16, wp.rows - 32 * c);
+        r.R1 = (2 * c + 1 < n_tiles) ? min(16, wp.rows - 32 * c - 16) : 0;
+        pos += (size_t)wp.KW * (r.R0 + r.R1) * 4;
+        ++c;
+        return r;
+      }
+      c = 0;
+      if (p == PH_DOWN) {
+        ++l;
+        p = (l < P.L) ? PH_QKV : (want_lm ? PH_LM : PH_END);
+      } else if (p == PH_LM) {
+        p = PH_END;
+      } else {
+        ++p;
+      }
+    }
+    return r;
+  }
+};
+
+__device__ inline int chunk_loads(const ChunkRef& r) { return r.KW * (r.R1 > 0 ? 2 : 1); }
+
+__device__ inline void load_chunk(bf16x8 (&buf)[kMaxKW][kT], const ChunkRef& r, int lane) {
+  const int i = lane & 15, kq = lane >> 4;
+  const int o0 = kq * r.R0 + min(i, r.R0 - 1);
+  const int o1 = r.R0 * 4 + kq * r.R1 + min(i, max(r.R1 - 1, 0));
+  const int step = (r.R0 + r.R1) * 4;
+#pragma unroll
+  for (int ksl = 0; ksl < kMaxKW; ++ksl) {
+    if (ksl < r.KW) {
+      buf[ksl][0] = __builtin_nontemporal_load(r.ptr + ksl * step + o0);
+      if (r.R1 > 0) buf[ksl][1] = __builtin_nontemporal_load(r.ptr + ksl * step + o1);
+    }
+  }
+}
+
+// Make the prefetched registers "used" at this program point so the wait for their loads is not hoisted
+// above what precedes (a barrier), then hand them over.
+__device__ inline void take_chunk(bf16x8 (&ring)[kMaxKW][kT], bf16x8 (&nxt)[kMaxKW][kT]) {
+#pragma unroll
+  for (int ksl = 0; ksl < kMaxKW; ++ksl)
+#pragma unroll
+    for (int t = 0; t < kT; ++t) {
+      asm volatile("" : "+v"(nxt[ksl][t]));
+      ring[ksl][t] = nxt[ksl][t];
+    }
+}
+
+// ---- activation fragments ----------------------------------------------------------------------------------
+// RMSNorm on load: rows of the fp32 residual stream are scaled by rsqrt(mean square + eps) (the sum of
+// squares arrives as per-tile partials) and by the gain, rounded to bf16, and laid out as B fragments.
+template <int MT>
+__device__ inline void row_scales(float (&rs)[MT], const float* ssq, int parts, int Mp, int H, float eps, int lane) {
+  const int col = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    float s = 0.f;
+    for (int p = g; p < parts; p += 4) s += ssq[(size_t)p * Mp + mt * 16 + col];
+    s += __shfl_xor(s, 16);
+    s += __shfl_xor(s, 32);
+    rs[mt] = rsqrtf(s / (float)H + eps);
+  }
+}
+
+// The fragments of a wavefront's k-steps are staged in a wavefront-private LDS region ([k-step][mt][lane]),
+// a few k-steps per batch so that the loads in flight stay bounded, and read back one k-step at a time.
+template <int MT>
+__device__ inline void stage_x_norm(bf16x8* xs, const float* x, int H, const float* gain, const float (&rs)[MT],
+                                    int ks0, int nk, int lane) {
+  const int col = lane & 15, g = lane >> 4;
+  for (int j0 = 0; j0 < nk; j0 += 4) {
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int j = j0 + jj;
+      if (j < nk) {
+        const int k0 = (ks0 + j) * 32 + 8 * g;
+        const f32x4 g0 = *reinterpret_cast<const f32x4*>(gain + k0);
+        const f32x4 g1 = *reinterpret_cast<const f32x4*>(gain + k0 + 4);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const float* px = x + (size_t)(mt * 16 + col) * H + k0;
+          const f32x4 a = *reinterpret_cast<const f32x4*>(px);
+          const f32x4 b = *reinterpret_cast<const f32x4*>(px + 4);
+          union { bf16x8 v; u16 h[8]; } cv;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            cv.h[e] = f32_to_bf16_bits(a[e] * rs[mt] * g0[e]);
+            cv.h[4 + e] = f32_to_bf16_bits(b[e] * rs[mt] * g1[e]);
+          }
+          xs[(j * MT + mt) * 64 + lane] = cv.v;
+        }
+      }
+    }
+    asm volatile("" ::: "memory");
+  }
+}
+
+template <int MT>
+__device__ inline void stage_x_packed(bf16x8* xs, const bf16x8* xp, int ks0, int nk, int lane) {
+  for (int j0 = 0; j0 < nk; j0 += 8) {
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) {
+      const int j = j0 + jj;
+      if (j < nk)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) xs[(j * MT + mt) * 64 + lane] = xp[((size_t)(ks0 + j) * MT + mt) * 64 + lane];
+    }
+    asm volatile("" ::: "memory");
+  }
+}
+
+// ---- one GEMM phase ------------------------------------------------------------------------------------------
+struct PhaseCtx {
+  const MegaArgs* a;
+  int layer, n;             // layer index, committed context length
+  f32x4* red;               // LDS [4][kT*MT][64]
+  bf16x8* xstage;           // LDS, activation fragments: [4 wavefronts][XH][MT][64]
+  int* s_flags;             // LDS scratch ints
+};
+
+template <int MT, int PH>
+__device__ inline void gemm_epilogue(const PhaseCtx& pc, const WavePhase& wp, int c, int t, int mt, f32x4 v, int lane,
+                                     float (&rmax)[MT], int (&ridx)[MT], float (&rsum)[MT]) {
+  const MegaArgs& a = *pc.a;
+  const MegaPlan& P = a.P;
+  const int col = lane & 15, g = lane >> 4;
+  const int token = mt * 16 + col;
+  const int lr = (2 * c + t) * 16 + 4 * g;               // first of this lane's 4 rows, local to the row range
+  const int r = wp.row0 + lr;                             // phase row
+  const bool live = token < a.M && lr < wp.rows;          // rows come in pairs/quads only when rows % 4 == 0 ...
+  const int nrows = min(4, wp.rows - lr);                 // ... so the last lane group may hold just 2 valid rows
+  if constexpr (PH == PH_QKV) {
+    if (!live) return;
+    const int D = P.D, half = D >> 1;
+    const int key = pc.n + token;
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+      if (2 * pr >= nrows) break;
+      const int rp = r + 2 * pr;                          // even phase row; (rp, rp+1) is a pair
+      if (rp < P.QD + P.KVD) {
+        // rotary pair: phase rows (2i, 2i+1) of a head hold dims (i, i + D/2)
+        const int dp = rp % D;
+        const float2 cs = a.rope[(size_t)token * half + (dp >> 1)];
+        const float lo = v[2 * pr] * cs.x - v[2 * pr + 1] * cs.y;
+        const float hi = v[2 * pr + 1] * cs.x + v[2 * pr] * cs.y;
+        const uint32_t pk = (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+        if (rp < P.QD) {
+          st_wt_u32(a.Q + (((size_t)pc.layer * a.Mp + token) * P.n_q + rp / D) * D + dp, pk);
+        } else {
+          const int rk = rp - P.QD;
+          u16* kc = a.Kc + (size_t)pc.layer * a.kv_layer_elems + (size_t)(rk / D) * a.max_kb * 32 * D;
+          st_wt_u32(kc + kp_index(key, dp, D / 32), pk);
+        }
+      } else {
+        const int rv = rp - P.QD - P.KVD;
+        u16* vc = a.Vc + (size_t)pc.layer * a.kv_layer_elems + (size_t)(rv / D) * a.max_kb * 32 * D;
+        st_wt_u16(vc + vp_index(key, rv % D, D / 16), f32_to_bf16_bits(v[2 * pr]));
+        st_wt_u16(vc + vp_index(key, (rv + 1) % D, D / 16), f32_to_bf16_bits(v[2 * pr + 1]));
+      }
+    }
+  } else if constexpr (PH == PH_O) {
+    // x_new = x_old + o ; partial sum of squares of this tile's channels
+    const int ver = 2 * pc.layer + 1;
+    float ss = 0.f;
+    if (live) {
+      const float* xo = a.xv + ((size_t)(ver - 1) * a.Mp + token) * P.H + r;
+      float* xn = a.xv + ((size_t)ver * a.Mp + token) * P.H + r;
+      if (nrows == 4 && (r & 3) == 0) {
+        const f32x4 o = *reinterpret_cast<const f32x4*>(xo) + v;
+        st_wt_f32x4(xn, o);
+        ss = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
+      } else {
+        for (int e = 0; e < nrows; ++e) { const float o = xo[e] + v[e]; st_wt_f32(xn + e, o); ss += o * o; }
+      }
+    }
+    ss += __shfl_xor(ss, 16);
+    ss += __shfl_xor(ss, 32);
+    if (g == 0)
+      st_wt_f32(a.ssq + ((size_t)ver * a.ssq_parts + (size_t)blockIdx.x * phase_tpg(P.ph[PH_O]) + 2 * c + t) * a.Mp + token, ss);
+  } else if constexpr (PH == PH_GU) {
+    if (!live) return;
+    // rows (2f, 2f+1) = (gate f, up f)
+    u16* base = a.act + (size_t)pc.layer * a.act_elems;
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+      if (2 * pr >= nrows) break;
+      const float gt = v[2 * pr], up = v[2 * pr + 1];
+      st_wt_u16(base + xp_index(token, (r >> 1) + pr, a.MT), f32_to_bf16_bits(gt / (1.f + __expf(-gt)) * up));
+    }
+  } else if constexpr (PH == PH_DOWN) {
+    // partial tile of this K group, in fragment order
+    if (lr < wp.rows) {
+      const int tiles = phase_tile_slots(P, PH_DOWN);
+      const int gt = wp.ng * phase_tpg(P.ph[PH_DOWN]) + 2 * c + t;
+      float* dst = a.wsD + (size_t)pc.layer * a.wsD_layer_floats +
+                   ((((size_t)wp.kg * tiles + gt) * a.MT + mt) * 64 + lane) * 4;
+      st_wt_f32x4(dst, v);
+    }
+  } else {  // PH_LM
+    if (lr < wp.rows) {
+      if (a.logits != nullptr && token < a.M) {
+        float* dst = a.logits + (size_t)token * P.V + r;
+        for (int e = 0; e < nrows; ++e) dst[e] = v[e];
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (e < nrows) stat_merge(rmax[mt], ridx[mt], rsum[mt], v[e], r + e, 1.f);
+    }
+  }
+}
+
+// Down projection: the last of the ksplit workgroups to finish a tile sums all partials in fixed order,
+// adds the residual, stores the new residual version and its per-tile sum of squares.
+template <int MT>
+__device__ inline bool down_finalize(const PhaseCtx& pc, const WavePhase& wp, int wave, int lane) {
+  const MegaArgs& a = *pc.a;
+  const MegaPlan& P = a.P;
+  const int ksplit = P.ph[PH_DOWN].ksplit;
+  const int tiles = phase_tile_slots(P, PH_DOWN);
+  const int my_tiles = (wp.rows + 15) >> 4;
+  const int gt0 = wp.ng * phase_tpg(P.ph[PH_DOWN]);
+  __syncthreads();
+  if ((int)threadIdx.x < my_tiles) {
+    int last = 1;
+    if (ksplit > 1) {
+      const unsigned old = __hip_atomic_fetch_add(a.cntD + (size_t)pc.layer * tiles + gt0 + threadIdx.x, 1u,
+                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      last = old == (unsigned)ksplit - 1u;
+    }
+    pc.s_flags[8 + threadIdx.x] = last;
+  }
+  __syncthreads();
+  const int col = lane & 15, g = lane >> 4;
+  const int ver = 2 * pc.layer + 2;
+  bool stored = false;
+  for (int idx = wave; idx < my_tiles * MT; idx += kWavesPerWG) {
+    const int tl = idx / MT, mt = idx % MT;
+    if (!pc.s_flags[8 + tl]) continue;
+    const int gt = gt0 + tl;
+    const float* src = a.wsD + (size_t)pc.layer * a.wsD_layer_floats;
+    f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int kg = 0; kg < ksplit; ++kg)
+      v += *reinterpret_cast<const f32x4*>(src + ((((size_t)kg * tiles + gt) * a.MT + mt) * 64 + lane) * 4);
+    const int token = mt * 16 + col;
+    const int lr = tl * 16 + 4 * g;
+    const int r = wp.row0 + lr;
+    const int nrows = min(4, wp.rows - lr);
+    float ss = 0.f;
+    if (token < a.M && nrows > 0) {
+      const float* xo = a.xv + ((size_t)(ver - 1) * a.Mp + token) * P.H + r;
+      float* xn = a.xv + ((size_t)ver * a.Mp + token) * P.H + r;
+      if (nrows == 4 && (r & 3) == 0) {
+        const f32x4 o = *reinterpret_cast<const f32x4*>(xo) + v;
+        st_wt_f32x4(xn, o);
+        ss = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
+      } else {
+        for (int e = 0; e < nrows; ++e) { const float o = xo[e] + v[e]; st_wt_f32(xn + e, o); ss += o * o; }
+      }
+    }
+    ss += __shfl_xor(ss, 16);
+    ss += __shfl_xor(ss, 32);
+    if (g == 0) st_wt_f32(a.ssq + ((size_t)ver * a.ssq_parts + gt) * a.Mp + token, ss);
+    stored = true;
+  }
+  return stored;
+}
+
+template <int MT, int PH>
+__device__ inline void gemm_phase(const PhaseCtx& pc, bf16x8 (&nxt)[kMaxKW][kT], Cursor& cur, int wave, int lane) {
+  constexpr int XH = (MT <= 2) ? kMaxKW : 4;          // k-steps of activation fragments staged at a time
+  bf16x8* xs = pc.xstage + (size_t)wave * (XH * MT * 64);
+  const MegaArgs& a = *pc.a;
+  const MegaPlan& P = a.P;
+  const WavePhase wp = wave_phase(P, PH, blockIdx.x, wave);
+  const int n_tiles = (wp.rows + 15) >> 4;
+  const int n_chunks = (n_tiles + 1) >> 1;
+  float rmax[MT], rsum[MT];
+  int ridx[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) { rmax[mt] = -INFINITY; ridx[mt] = 0x7FFFFFFF; rsum[mt] = 0.f; }
+
+  if (n_chunks > 0) {
+    // activation source of this phase
+    constexpr bool kNorm = (PH == PH_QKV || PH == PH_GU || PH == PH_LM);
+    const int ver = (PH == PH_QKV) ? 2 * pc.layer : (PH == PH_GU) ? 2 * pc.layer + 1 : 2 * P.L;
+    const float* xsrc = a.xv + (size_t)ver * a.Mp * P.H;
+    const float* gain = a.gains + (size_t)ver * P.H;
+    const bf16x8* xp = reinterpret_cast<const bf16x8*>(
+        PH == PH_O ? a.ap + (size_t)pc.layer * a.ap_elems : a.act + (size_t)pc.layer * a.act_elems);
+    float rs[MT];
+    if constexpr (kNorm) {
+      const int parts = ver == 0 ? 1 : phase_tile_slots(P, (ver & 1) ? PH_O : PH_DOWN);
+      row_scales<MT>(rs, a.ssq + (size_t)ver * a.ssq_parts * a.Mp, parts, a.Mp, P.H, a.rms_eps, lane);
+      if constexpr (XH == kMaxKW) stage_x_norm<MT>(xs, xsrc, P.H, gain, rs, wp.w0, wp.KW, lane);
+    } else {
+      if constexpr (XH == kMaxKW) stage_x_packed<MT>(xs, xp, wp.w0, wp.KW, lane);
+    }
+
+    for (int c = 0; c < n_chunks; ++c) {
+      const bool last = c == n_chunks - 1;
+      const bool two = 2 * c + 1 < n_tiles;
+      ChunkRef nr;
+      bf16x8 ring[kMaxKW][kT];                          // the chunk being multiplied (dead after this iteration)
+      if (wp.KW > 0) {                                  // a wavefront without k-steps only joins the reduction
+        take_chunk(ring, nxt);
+        if (!last) { nr = cur.next(P); load_chunk(nxt, nr, lane); }
+      } else {
+#pragma unroll
+        for (int ksl = 0; ksl < kMaxKW; ++ksl)
+#pragma unroll
+          for (int t = 0; t < kT; ++t) ring[ksl][t] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      }
+
+      f32x4 acc[kT][MT];
+#pragma unroll
+      for (int t = 0; t < kT; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[t][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ksl = 0; ksl < kMaxKW; ++ksl) {
+        if constexpr (XH < kMaxKW) {
+          if (ksl % XH == 0 && ksl < wp.KW) {
+            if constexpr (kNorm) stage_x_norm<MT>(xs, xsrc, P.H, gain, rs, wp.w0 + ksl, min(XH, wp.KW - ksl), lane);
+            else stage_x_packed<MT>(xs, xp, wp.w0 + ksl, min(XH, wp.KW - ksl), lane);
+          }
+        }
+        if (ksl < wp.KW) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const bf16x8 xk = xs[((ksl % XH) * MT + mt) * 64 + lane];
+            acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[ksl][0], xk, acc[0][mt], 0, 0, 0);
+            if (two) acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[ksl][1], xk, acc[1][mt], 0, 0, 0);
+          }
+        }
+      }
+      // the four wavefronts hold disjoint K ranges: sum them through LDS in fixed order
+#pragma unroll
+      for (int t = 0; t < kT; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) pc.red[(wave * (kT * MT) + t * MT + mt) * 64 + lane] = acc[t][mt];
+      __syncthreads();
+#pragma unroll
+      for (int idx = 0; idx < kT * MT; ++idx) {
+        if ((idx & 3) != wave) continue;
+        const int t = idx / MT, mt = idx % MT;
+        if (t == 1 && !two) continue;
+        f32x4 v = pc.red[(0 * (kT * MT) + idx) * 64 + lane];
+        v += pc.red[(1 * (kT * MT) + idx) * 64 + lane];
+        v += pc.red[(2 * (kT * MT) + idx) * 64 + lane];
+        v += pc.red[(3 * (kT * MT) + idx) * 64 + lane];
+        gemm_epilogue<MT, PH>(pc, wp, c, t, mt, v, lane, rmax, ridx, rsum);
+      }
+      __syncthreads();
+      if (last && wp.KW > 0) {
+        // request the first chunk of the next GEMM phase now, after this phase's stores, and wait only
+        // for what is older than that request
+        nr = cur.next(P);
+        asm volatile("" ::: "memory");
+        load_chunk(nxt, nr, lane);
+        asm volatile("" ::: "memory");
+        wait_vm_allow(chunk_loads(nr));
+      }
+    }
+  }
+  if constexpr (PH == PH_DOWN) {
+    if (down_finalize<MT>(pc, wp, wave, lane)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+  if constexpr (PH == PH_LM) {
+    // fold lane groups, then wavefronts, into this workgroup's row statistics
+    const int col = lane & 15, g = lane >> 4;
+    float* s_m = reinterpret_cast<float*>(pc.red);
+    int* s_i = reinterpret_cast<int*>(pc.red) + 4 * 64;
+    float* s_s = reinterpret_cast<float*>(pc.red) + 8 * 64;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int off = 16; off < 64; off <<= 1) {
+        const float m2 = __shfl_xor(rmax[mt], off);
+        const int i2 = __shfl_xor(ridx[mt], off);
+        const float s2 = __shfl_xor(rsum[mt], off);
+        stat_merge(rmax[mt], ridx[mt], rsum[mt], m2, i2, s2);
+      }
+      if (g == 0) {
+        s_m[wave * 64 + mt * 16 + col] = rmax[mt];
+        s_i[wave * 64 + mt * 16 + col] = ridx[mt];
+        s_s[wave * 64 + mt * 16 + col] = rsum[mt];
+      }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < MT * 16) {
+      const int tt = threadIdx.x;
+      float m = s_m[tt];
+      int i = s_i[tt];
+      float s = s_s[tt];
+      for (int w = 1; w < kWavesPerWG; ++w) stat_merge(m, i, s, s_m[w * 64 + tt], s_i[w * 64 + tt], s_s[w * 64 + tt]);
+      st_wt_f32(a.lm_max + (size_t)blockIdx.x * a.Mp + tt, m);
+      st_wt_u32(a.lm_idx + (size_t)blockIdx.x * a.Mp + tt, (uint32_t)i);
+      st_wt_f32(a.lm_sum + (size_t)blockIdx.x * a.Mp + tt, s);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+}
+
+// ---- attention phase ------------------------------------------------------------------------------------------
+// Items (kv head, group of JT column tiles, key chunk) go round-robin over the workgroups.  Each item
+// stores its partial (unnormalised output, running max, running sum); the workgroup that completes the
+// last chunk of a (kv head, column group) merges all chunks in fixed order and stores the bf16 result.
+template <int D, int JT>
+__device__ inline void attention_phase(const PhaseCtx& pc, char* lds, int wave, int lane) {
+  constexpr int DS = D / 32, DT = D / 16;
+  const MegaArgs& a = *pc.a;
+  const MegaPlan& P = a.P;
+  f32x4* sO = reinterpret_cast<f32x4*>(lds);                               // [DT*JT][64]
+  float* sm = reinterpret_cast<float*>(lds + DT * JT * 64 * 16);           // [4][JT*16]
+  float* sl = sm + kWavesPerWG * JT * 16;                                   // [4][JT*16]
+  float* wgt = sl + kWavesPerWG * JT * 16;                                  // [max 64 chunks][JT*16]
+
+  const int col = lane & 15, g = lane >> 4;
+  const int n = pc.n;
+  const int G = P.n_q / P.n_kv;
+  const int Mp = a.MT * 16;
+  const int n_jg = (G * a.MT) / JT;
+  int n_kb, chunk_len, n_chunks;
+  attn_chunks(n + a.M, a.attn_max_chunks, n_kb, chunk_len, n_chunks);
+  const int n_groups = P.n_kv * n_jg;
+  const int n_items = n_groups * n_chunks;
+  const size_t kv_block = (size_t)32 * D / 8;
+  const u16* Qb = a.Q + (size_t)pc.layer * a.Mp * P.n_q * D;
+  float* pO = a.pO + (size_t)pc.layer * a.pO_layer_floats;
+  float* pm = a.pm + (size_t)pc.layer * a.pml_layer_floats;
+  float* pl = a.pl + (size_t)pc.layer * a.pml_layer_floats;
+
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const int chunk = item % n_chunks;
+    const int grp = item / n_chunks;
+    const int jg = grp % n_jg, kvh = grp / n_jg;
+    const bf16x8* Kh = reinterpret_cast<const bf16x8*>(a.Kc + (size_t)pc.layer * a.kv_layer_elems) + (size_t)kvh * a.max_kb * kv_block;
+    const bf16x8* Vh = reinterpret_cast<const bf16x8*>(a.Vc + (size_t)pc.layer * a.kv_layer_elems) + (size_t)kvh * a.max_kb * kv_block;
+
+    bf16x8 qf[JT][DS];
+    int row[JT];
+#pragma unroll
+    for (int jt = 0; jt < JT; ++jt) {
+      const int cidx = (jg * JT + jt) * 16 + col;
+      const int hq = cidx / Mp, m = cidx - hq * Mp;
+      row[jt] = m;
+      const u16* qp = Qb + ((size_t)m * P.n_q + kvh * G + hq) * D + 8 * g;
+#pragma unroll
+      for (int ds = 0; ds < DS; ++ds) qf[jt][ds] = *reinterpret_cast<const bf16x8*>(qp + ds * 32);
+    }
+    f32x4 O[DT][JT];
+    float mrun[JT], lrun[JT];
+#pragma unroll
+    for (int jt = 0; jt < JT; ++jt) {
+      mrun[jt] = kNegBig;
+      lrun[jt] = 0.f;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) O[dt][jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const int kb_end = min(n_kb, (chunk + 1) * chunk_len);
+    for (int kb = chunk * chunk_len + wave; kb < kb_end; kb += kWavesPerWG) {
+      bf16x8 kf[2][DS], vf[DT];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) kf[t][ds] = Kh[(((size_t)kb * 2 + t) * DS + ds) * 64 + lane];
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) vf[dt] = Vh[((size_t)kb * DT + dt) * 64 + lane];
+      const bool need_mask = (kb * 32 + 31) >= n;
+      bf16x8 pf[JT];
+#pragma unroll
+      for (int jt = 0; jt < JT; ++jt) {
+        f32x4 s[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ds = 0; ds < DS; ++ds)
+            s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][ds], qf[jt][ds], s[t], 0, 0, 0);
+        }
+        float v[8];
+        bool vis[8];
+        float cmax = kNegBig;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          v[e] = s[e >> 2][e & 3] * a.scale_log2e;
+          vis[e] = true;
+          if (need_mask) {
+            const int jb = kb * 32 + 8 * g + e - n;
+            vis[e] = (jb < 0) || (jb < a.M && (a.mode == 0 || jb <= row[jt]));
+          }
+          if (vis[e]) cmax = fmaxf(cmax, v[e]);
+        }
+        cmax = fmaxf(cmax, __shfl_xor(cmax, 16));
+        cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
+        const float mnew = fmaxf(mrun[jt], cmax);
+        const float alpha = exp2f(mrun[jt] - mnew);
+        float psum = 0.f;
+        union { bf16x8 v8; u16 h[8]; } cv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float p = vis[e] ? exp2f(v[e] - mnew) : 0.f;
+          psum += p;
+          cv.h[e] = f32_to_bf16_bits(p);
+        }
+        psum += __shfl_xor(psum, 16);
+        psum += __shfl_xor(psum, 32);
+        lrun[jt] = lrun[jt] * alpha + psum;
+        mrun[jt] = mnew;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) O[dt][jt] *= alpha;
+        pf[jt] = cv.v8;
+      }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int jt = 0; jt < JT; ++jt)
+          O[dt][jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[jt], O[dt][jt], 0, 0, 0);
+    }
+    // merge the four wavefronts
+    if (g == 0) {
+#pragma unroll
+      for (int jt = 0; jt < JT; ++jt) {
+        sm[wave * JT * 16 + jt * 16 + col] = mrun[jt];
+        sl[wave * JT * 16 + jt * 16 + col] = lrun[jt];
+      }
+    }
+    __syncthreads();
+    float mall[JT], lall[JT];
+#pragma unroll
+    for (int jt = 0; jt < JT; ++jt) {
+      float mm = sm[jt * 16 + col];
+#pragma unroll
+      for (int w = 1; w < kWavesPerWG; ++w) mm = fmaxf(mm, sm[w * JT * 16 + jt * 16 + col]);
+      float ll = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWavesPerWG; ++w) ll += sl[w * JT * 16 + jt * 16 + col] * exp2f(sm[w * JT * 16 + jt * 16 + col] - mm);
+      mall[jt] = mm;
+      lall[jt] = ll;
+      const float f = exp2f(mrun[jt] - mm);
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) O[dt][jt] *= f;
+    }
+    for (int w = 0; w < kWavesPerWG; ++w) {
+      if (wave == w) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int jt = 0; jt < JT; ++jt) {
+            if (w == 0) sO[(dt * JT + jt) * 64 + lane] = O[dt][jt];
+            else sO[(dt * JT + jt) * 64 + lane] += O[dt][jt];
+          }
+      }
+      __syncthreads();
+    }
+    float* po = pO + (size_t)item * (DT * JT) * 64 * 4;
+    for (int idx = wave; idx < DT * JT; idx += kWavesPerWG) st_wt_f32x4(po + ((size_t)idx * 64 + lane) * 4, sO[idx * 64 + lane]);
+    if (wave == 0 && g == 0) {
+#pragma unroll
+      for (int jt = 0; jt < JT; ++jt) {
+        st_wt_f32(pm + (size_t)item * (JT * 16) + jt * 16 + col, mall[jt]);
+        st_wt_f32(pl + (size_t)item * (JT * 16) + jt * 16 + col, lall[jt]);
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const unsigned old = __hip_atomic_fetch_add(a.cntA + (size_t)pc.layer * n_groups + grp, 1u, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+      pc.s_flags[4] = old == (unsigned)n_chunks - 1u;
+    }
+    __syncthreads();
+    if (pc.s_flags[4]) {
+      const size_t item0 = (size_t)grp * n_chunks;
+      if ((int)threadIdx.x < JT * 16) {
+        const int cc = threadIdx.x;
+        float mm = kNegBig;
+        for (int ch = 0; ch < n_chunks; ++ch) mm = fmaxf(mm, pm[(item0 + ch) * (JT * 16) + cc]);
+        float ll = 0.f;
+        for (int ch = 0; ch < n_chunks; ++ch) {
+          const float w = exp2f(pm[(item0 + ch) * (JT * 16) + cc] - mm);
+          ll += pl[(item0 + ch) * (JT * 16) + cc] * w;
+          wgt[ch * (JT * 16) + cc] = w;
+        }
+        const float inv = 1.f / ll;
+        for (int ch = 0; ch < n_chunks; ++ch) wgt[ch * (JT * 16) + cc] *= inv;
+      }
+      __syncthreads();
+      const float* pg = pO + item0 * (DT * JT) * 64 * 4;
+      u16* out = a.ap + (size_t)pc.layer * a.ap_elems;
+      for (int idx = wave; idx < DT * JT; idx += kWavesPerWG) {
+        const int dt = idx / JT, jt = idx % JT;
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int ch = 0; ch < n_chunks; ++ch)
+          acc += *reinterpret_cast<const f32x4*>(pg + (((size_t)ch * (DT * JT) + idx) * 64 + lane) * 4) *
+                 wgt[ch * (JT * 16) + jt * 16 + col];
+        const int cidx = (jg * JT + jt) * 16 + col;
+        const int hq = cidx / Mp, m = cidx - hq * Mp;
+        if (m < a.M) {
+          const int f = (kvh * G + hq) * D + dt * 16 + 4 * g;
+          const uint32_t lo = (uint32_t)f32_to_bf16_bits(acc[0]) | ((uint32_t)f32_to_bf16_bits(acc[1]) << 16);
+          const uint32_t hi = (uint32_t)f32_to_bf16_bits(acc[2]) | ((uint32_t)f32_to_bf16_bits(acc[3]) << 16);
+          st_wt_u64(out + xp_index(m, f, a.MT), (uint64_t)lo | ((uint64_t)hi << 32));
+        }
+      }
+    }
+    __syncthreads();
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// ---- the kernel ------------------------------------------------------------------------------------------------
+// Dynamic LDS of the forward kernel: [activation stage | K-reduction buffer]; the attention phase re-uses
+// the front of it.
+template <int MT> constexpr int mega_xh() { return (MT <= 2) ? kMaxKW : 4; }
+template <int MT> constexpr int mega_lds_bytes() {
+  return kWavesPerWG * mega_xh<MT>() * MT * 1024 + kWavesPerWG * kT * MT * 1024;
+}
+
+template <int MT, int D, int JT>
+__global__ __launch_bounds__(kWGThreads, 1) void mega_kernel(MegaArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  __shared__ int s_flags[16];
+  const MegaPlan& P = a.P;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (threadIdx.x == 0) s_flags[0] = (a.st->error == 0);
+  __syncthreads();
+  if (!s_flags[0]) return;
+
+  PhaseCtx pc;
+  pc.a = &a;
+  pc.n = a.st->n;
+  pc.xstage = reinterpret_cast<bf16x8*>(lds);
+  pc.red = reinterpret_cast<f32x4*>(lds + kWavesPerWG * mega_xh<MT>() * MT * 1024);
+  pc.s_flags = s_flags;
+  unsigned epoch = a.bar_epoch;
+
+  Cursor cur;
+  cur.pos = a.wstream + (size_t)(blockIdx.x * kWavesPerWG + wave) * a.P.wave_stride;
+  cur.l = 0; cur.p = PH_QKV; cur.c = 0; cur.wg = blockIdx.x; cur.w = wave; cur.want_lm = a.want_lm;
+  bf16x8 nxt[kMaxKW][kT];
+  {
+    ChunkRef r0 = cur.next(P);
+    load_chunk(nxt, r0, lane);
+  }
+  bool alive = true;
+  for (int l = 0; l < P.L && alive; ++l) {
+    pc.layer = l;
+    gemm_phase<MT, PH_QKV>(pc, nxt, cur, wave, lane);
+    alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
+    if (!alive) break;
+    attention_phase<D, JT>(pc, lds, wave, lane);
+    alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
+    if (!alive) break;
+    gemm_phase<MT, PH_O>(pc, nxt, cur, wave, lane);
+    alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
+    if (!alive) break;
+    gemm_phase<MT, PH_GU>(pc, nxt, cur, wave, lane);
+    alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
+    if (!alive) break;
+    gemm_phase<MT, PH_DOWN>(pc, nxt, cur, wave, lane);
+    alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
+  }
+  if (alive && a.want_lm) {
+    pc.layer = P.L;
+    gemm_phase<MT, PH_LM>(pc, nxt, cur, wave, lane);
+    alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
+    if (alive && (int)blockIdx.x < a.M) {
+      // workgroup r folds row r over all workgroups' statistics
+      const int r = blockIdx.x;
+      float m = -INFINITY, s = 0.f;
+      int i = 0x7FFFFFFF;
+      for (int p = threadIdx.x; p < P.nwg; p += kWGThreads)
+        stat_merge(m, i, s, a.lm_max[(size_t)p * a.Mp + r], a.lm_idx[(size_t)p * a.Mp + r], a.lm_sum[(size_t)p * a.Mp + r]);
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const float m2 = __shfl_xor(m, off);
+        const int i2 = __shfl_xor(i, off);
+        const float s2 = __shfl_xor(s, off);
+        stat_merge(m, i, s, m2, i2, s2);
+      }
+      float* s_m = reinterpret_cast<float*>(lds);
+      int* s_i = reinterpret_cast<int*>(lds) + 8;
+      float* s_s = reinterpret_cast<float*>(lds) + 16;
+      if (lane == 0) { s_m[wave] = m; s_i[wave] = i; s_s[wave] = s; }
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        for (int w = 1; w < kWavesPerWG; ++w) stat_merge(m, i, s, s_m[w], s_i[w], s_s[w]);
+        a.row_cand[r] = i;
+        a.row_conf[r] = 1.f / s;
+      }
+    }
+  }
+}
+
+// ---- prologue: block assembly (seed, embedding gather), first sum of squares, rotary table, counters ------------
+struct PrologueArgs {
+  float* x0; float* ssq0; int H, Mp;
+  const float* embeds; int n_embed; const int* ids; int off;
+  int* seed_tokens; uint8_t* seed_mask;       // denoise only: position 0 takes the carry if still masked
+  const uint8_t* mask; int mask_id; const u16* table; int vocab;
+  DevState* st;
+  float2* rope; int half; float theta;
+  unsigned* counters; int n_counters;
+};
+
+__global__ __launch_bounds__(kWGThreads) void prologue_kernel(PrologueArgs a) {
+  __shared__ float wsum[kWavesPerWG];
+  __shared__ int s_id;
+  const int r = blockIdx.x;
+  for (int i = blockIdx.x * kWGThreads + threadIdx.x; i < a.n_counters; i += gridDim.x * kWGThreads) a.counters[i] = 0u;
+  {
+    const double pos = (double)(a.st->n + r);
+    for (int i = threadIdx.x; i < a.half; i += kWGThreads) {
+      const double inv = exp2(-log2((double)a.theta) * (double)i / (double)a.half);
+      const double ang = pos * inv;
+      a.rope[(size_t)r * a.half + i] = make_float2((float)cos(ang), (float)sin(ang));
+    }
+  }
+  const int p = a.off + r;
+  if (threadIdx.x == 0) {
+    int id = -1;
+    if (p >= a.n_embed) {
+      const int j = p - a.n_embed;
+      if (r == 0 && a.seed_mask != nullptr) {
+        a.st->seeded = 0;
+        if (a.seed_mask[0]) {
+          a.seed_tokens[0] = a.st->carry_cand;
+          a.seed_mask[0] = 0;
+          a.st->seeded = 1;
+        }
+      }
+      id = a.ids[j];
+      if (a.mask != nullptr && a.mask[j]) id = a.mask_id;
+      id = min(max(id, 0), a.vocab - 1);
+    }
+    s_id = id;
+  }
+  __syncthreads();
+  const int id = s_id;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < a.H; c += kWGThreads) {
+    const float v = id < 0 ? a.embeds[(size_t)p * a.H + c] : bf16_bits_to_f32(a.table[(size_t)id * a.H + c]);
+    a.x0[(size_t)r * a.H + c] = v;
+    ss += v * v;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) a.ssq0[r] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+}
+
+// ---- weight stream packing ----------------------------------------------------------------------------------
+// One source matrix (row-major [n_rows][K], fp32 or bf16 bits) goes into the stream of phase `ph` of
+// layer `layer`; `row_map` says where source row r sits among the phase's output rows:
+//   0: row_base + r                       (plain)
+//   1: rotary pairing inside heads of D   (Q and K: dim i -> 2i, dim i + D/2 -> 2i + 1)
+//   2: row_base + 2*r                     (gate: even rows, up: odd rows with row_base = 1)
+template <typename SrcT>
+__global__ void pack_stream_kernel(const SrcT* __restrict__ src, int n_rows, int K, MegaPlan P, int ph, int layer,
+                                   int row_base, int row_map, int D, u16* __restrict__ stream) {
+  const int KS = P.ph[ph].KS;
+  const size_t total = (size_t)n_rows * KS * 4;             // one thread per (row, k-step, k-quarter)
+  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total;
+       idx += (size_t)gridDim.x * blockDim.x) {
+    const int kq = idx & 3;
+    const int ks = (int)((idx >> 2) % KS);
+    const int rs = (int)(idx / ((size_t)KS * 4));
+    int r;
+    if (row_map == 1) {
+      const int h = rs / D, d = rs % D, half = D >> 1;
+      r = row_base + h * D + (d < half ? 2 * d : 2 * (d - half) + 1);
+    } else if (row_map == 2) {
+      r = row_base + 2 * rs;
+    } else {
+      r = row_base + rs;
+    }
+    const PhasePlan& pp = P.ph[ph];
+    const int ng = r / pp.RW, lr = r - ng * pp.RW;
+    // which K group / wavefront holds k-step ks
+    int kg = 0;
+    while ((int)((long long)pp.KS * (kg + 1) / pp.ksplit) <= ks) ++kg;
+    const int wg = ng * pp.ksplit + kg;
+    int w = 0;
+    WavePhase wp = wave_phase(P, ph, wg, 0);
+    while (ks >= wp.w0 + wp.KW) { ++w; wp = wave_phase(P, ph, wg, w); }
+    long long pos = (long long)(wg * kWavesPerWG + w) * P.wave_stride;
+    pos += (ph == PH_LM) ? (long long)P.L * wave_layer_units(P, wg, w) : (long long)layer * wave_layer_units(P, wg, w);
+    for (int q = 0; q < ph && ph != PH_LM; ++q) pos += wave_phase_units(wave_phase(P, q, wg, w));
+    pos += stream_pos(wp.rows, wp.KW, lr, ks - wp.w0, kq);
+    u16* dst = stream + (size_t)pos * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int k = ks * 32 + kq * 8 + e;
+      u16 o = 0;
+      if (k < K) {
+        if constexpr (sizeof(SrcT) == 4) o = f32_to_bf16_bits(((const float*)src)[(size_t)rs * K + k]);
+        else o = ((const u16*)src)[(size_t)rs * K + k];
+      }
+      dst[e] = o;
+    }
+  }
+}
+
+}  // namespace bd

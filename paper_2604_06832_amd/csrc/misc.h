@@ -181,14 +181,17 @@ __global__ __launch_bounds__(kWGThreads) void qkv_post_kernel(QkvPostArgs a) {
 }
 
 // Unpack cache positions [pos0, pos0+count) of one layer to fp32 [count][n_kv][D].
+// rot_pairs: the K cache holds each head's dims in rotary-pair order (dim i at 2i, dim i + D/2 at 2i + 1).
 __global__ void read_kv_kernel(const u16* __restrict__ Kc, const u16* __restrict__ Vc, int n_kv, int D, int max_kb,
-                               int pos0, int count, float* __restrict__ k_out, float* __restrict__ v_out) {
+                               int pos0, int count, float* __restrict__ k_out, float* __restrict__ v_out,
+                               int rot_pairs) {
   const size_t total = (size_t)count * n_kv * D;
   const size_t kv_head_elems = (size_t)max_kb * 32 * D;
   for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total;
        idx += (size_t)gridDim.x * blockDim.x) {
     const int d = idx % D, h = (idx / D) % n_kv, p = (int)(idx / ((size_t)D * n_kv));
-    if (k_out) k_out[idx] = bf16_bits_to_f32(Kc[h * kv_head_elems + kp_index(pos0 + p, d, D / 32)]);
+    const int dk = rot_pairs ? (d < D / 2 ? 2 * d : 2 * (d - D / 2) + 1) : d;
+    if (k_out) k_out[idx] = bf16_bits_to_f32(Kc[h * kv_head_elems + kp_index(pos0 + p, dk, D / 32)]);
     if (v_out) v_out[idx] = bf16_bits_to_f32(Vc[h * kv_head_elems + vp_index(pos0 + p, d, D / 16)]);
   }
 }
@@ -253,38 +256,11 @@ __global__ void seed_kernel(int* tokens, uint8_t* mask, DevState* st) {
   }
 }
 
-// Fold the per-workgroup LM-head statistics into (candidate id, confidence) per row.
-// conf = softmax probability of the argmax = 1 / sum_v exp(logit_v - max).
-__device__ inline void lm_fold_rows(const float* lm_max, const int* lm_idx, const float* lm_sum, int n_parts, int Mp,
-                                    int M, int* s_cand, float* s_conf) {
-  // 4 threads per row, each folds a strided quarter of the partials, then the quarters are merged
-  const int r = threadIdx.x >> 2, q = threadIdx.x & 3;
-  float m = -INFINITY, s = 0.f;
-  int i = 0x7FFFFFFF;
-  if (r < M)
-    for (int p = q; p < n_parts; p += 4)
-      stat_merge(m, i, s, lm_max[(size_t)p * Mp + r], lm_idx[(size_t)p * Mp + r], lm_sum[(size_t)p * Mp + r]);
-#pragma unroll
-  for (int off = 1; off < 4; off <<= 1) {
-    const float m2 = __shfl_xor(m, off);
-    const int i2 = __shfl_xor(i, off);
-    const float s2 = __shfl_xor(s, off);
-    stat_merge(m, i, s, m2, i2, s2);
-  }
-  if (r < M && q == 0) {
-    s_cand[r] = i;
-    s_conf[r] = 1.f / s;
-  }
-}
-
 struct FinishArgs {
-  const float* lm_max;
-  const int* lm_idx;
-  const float* lm_sum;
-  int n_parts, Mp, B;
+  int B;
   DevState* st;
-  int* row_cand;            // [Mp] candidate of every row, kept for inspection
-  float* row_conf;
+  const int* row_cand;      // [B] argmax id of every row of the forward (row i predicts position i+1)
+  const float* row_conf;    // [B] its softmax probability
   // denoise
   int* tokens;
   uint8_t* mask;
@@ -300,21 +276,22 @@ struct FinishArgs {
 };
 
 // Confidence-threshold parallel unmask (Sec. 3.4; "Decoding threshold").  Row i-1 predicts block
-// position i.  Launched with one workgroup of 256 threads.
-__global__ __launch_bounds__(kWGThreads) void finish_denoise_kernel(FinishArgs a) {
+// position i.  Launched with one wavefront.
+__global__ __launch_bounds__(64) void finish_denoise_kernel(FinishArgs a) {
   __shared__ int s_cand[64];
   __shared__ float s_conf[64];
-  lm_fold_rows(a.lm_max, a.lm_idx, a.lm_sum, a.n_parts, a.Mp, a.B, s_cand, s_conf);
-  __syncthreads();
-  if (threadIdx.x < a.B) {
-    a.row_cand[threadIdx.x] = s_cand[threadIdx.x];
-    a.row_conf[threadIdx.x] = s_conf[threadIdx.x];
-    if (a.conf_out) a.conf_out[threadIdx.x] = threadIdx.x == 0 ? a.st->carry_conf : s_conf[threadIdx.x - 1];
+  __shared__ uint8_t s_mask[64];
+  if ((int)threadIdx.x < a.B) {
+    s_cand[threadIdx.x] = a.row_cand[threadIdx.x];
+    s_conf[threadIdx.x] = a.row_conf[threadIdx.x];
+    s_mask[threadIdx.x] = a.mask[threadIdx.x];
+    if (a.conf_out) a.conf_out[threadIdx.x] = threadIdx.x == 0 ? a.st->carry_conf : a.row_conf[threadIdx.x - 1];
   }
+  __syncthreads();
   if (threadIdx.x == 0) {
     int revealed = a.st->seeded;
     int remaining = 0;
-    for (int i = 1; i < a.B; ++i) remaining += a.mask[i] ? 1 : 0;
+    for (int i = 1; i < a.B; ++i) remaining += s_mask[i] ? 1 : 0;
     if (remaining > 0) {
       if (a.fixed_k > 0) {
         const int k = min(a.fixed_k, remaining);
@@ -322,16 +299,17 @@ __global__ __launch_bounds__(kWGThreads) void finish_denoise_kernel(FinishArgs a
           int best = -1;
           float bc = -1.f;
           for (int i = 1; i < a.B; ++i)
-            if (a.mask[i] && s_conf[i - 1] > bc) { bc = s_conf[i - 1]; best = i; }
+            if (s_mask[i] && s_conf[i - 1] > bc) { bc = s_conf[i - 1]; best = i; }
           a.tokens[best] = s_cand[best - 1];
           a.mask[best] = 0;
+          s_mask[best] = 0;
           ++revealed;
         }
       } else {
         int best = -1, cnt = 0;
         float bc = -1.f;
         for (int i = 1; i < a.B; ++i) {
-          if (!a.mask[i]) continue;
+          if (!s_mask[i]) continue;
           const float c = s_conf[i - 1];
           if (c > bc) { bc = c; best = i; }
           if (c > a.threshold) {
@@ -363,16 +341,15 @@ __global__ void finish_seed_only_kernel(DevState* st, int* n_unmasked, float* co
 // Causal pass: row j's argmax is the autoregressive prediction a_j (Alg. 1 verify step).  Accept
 // length = longest prefix of the draft with draft[0] == carry's argmax and draft[j+1] == a_j.
 // With commit, the carry moves to the last row and the context length grows by B.
-__global__ __launch_bounds__(kWGThreads) void finish_causal_kernel(FinishArgs a) {
+__global__ __launch_bounds__(64) void finish_causal_kernel(FinishArgs a) {
   __shared__ int s_cand[64];
   __shared__ float s_conf[64];
-  lm_fold_rows(a.lm_max, a.lm_idx, a.lm_sum, a.n_parts, a.Mp, a.B, s_cand, s_conf);
-  __syncthreads();
-  if (threadIdx.x < a.B) {
-    a.row_cand[threadIdx.x] = s_cand[threadIdx.x];
-    a.row_conf[threadIdx.x] = s_conf[threadIdx.x];
-    if (a.ar_pred) a.ar_pred[threadIdx.x] = s_cand[threadIdx.x];
+  if ((int)threadIdx.x < a.B) {
+    s_cand[threadIdx.x] = a.row_cand[threadIdx.x];
+    s_conf[threadIdx.x] = a.row_conf[threadIdx.x];
+    if (a.ar_pred) a.ar_pred[threadIdx.x] = a.row_cand[threadIdx.x];
   }
+  __syncthreads();
   if (threadIdx.x == 0) {
     if (a.n_accept) {
       int k = 0;

@@ -56,7 +56,7 @@ class Pair:
         e = torch.from_numpy(emb).cuda() if emb is not None and len(emb) else None
         i = torch.from_numpy(ids).cuda() if ids is not None and len(ids) else None
         self.ctx.bd_prefill(e, i)
-        torch.cuda.synchronize()
+        self.ctx.bd_status()
         assert self.ctx.bd_cache_len() == self.o.n
 
     def check_carry(self):
@@ -87,7 +87,7 @@ class Pair:
         nun = torch.zeros(1, dtype=torch.int32, device="cuda")
         conf = torch.zeros(B, dtype=torch.float32, device="cuda")
         self.ctx.bd_denoise_step(gt, gm, tau, fixed_k, nun, conf)
-        torch.cuda.synchronize()
+        self.ctx.bd_status()
         gtok, gmask = gt.cpu().numpy(), gm.cpu().numpy().astype(bool)
         if r["logits"] is None:
             assert np.array_equal(gtok[~gmask], ot[~om]) and np.array_equal(gmask, om)
@@ -145,7 +145,7 @@ class Pair:
         n0 = self.o.n
         ol = self.o.commit_block(tokens)
         self.ctx.bd_commit_block(torch.from_numpy(np.asarray(tokens, np.int32)).cuda())
-        torch.cuda.synchronize()
+        self.ctx.bd_status()
         assert self.ctx.bd_cache_len() == self.o.n == n0 + len(tokens)
         glog = self.ctx.bd_read_logits(len(tokens)).cpu().numpy()
         assert_logits_close(glog, ol, frac, "commit logits")

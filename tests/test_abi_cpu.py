@@ -51,7 +51,7 @@ def _cfg(**kw):
     return binding.bd_config(**base)
 
 
-@pytest.mark.parametrize("bad", [dict(head_dim=48), dict(n_q_heads=3), dict(hidden=250), dict(max_block=0),
+@pytest.mark.parametrize("bad", [dict(head_dim=48), dict(n_q_heads=3), dict(n_q_heads=2, n_kv_heads=2), dict(hidden=250), dict(max_block=0),
                                  dict(max_block=65), dict(max_seq=8), dict(vocab=1000), dict(ffn=100),
                                  dict(mask_token_id=1024), dict(n_layers=0), dict(rope_theta=0.0)])
 def test_create_rejects_bad_shapes_before_any_device_call(L, bad):
@@ -77,6 +77,7 @@ def test_null_context_is_an_argument_error(L):
     assert L.bd_verify_block(None, None, 4, 1, None, None) == binding.BD_E_ARG
     assert L.bd_crop(None, 0) == binding.BD_E_ARG
     assert L.bd_cache_len(None) == binding.BD_E_ARG
+    assert L.bd_status(None) == binding.BD_E_ARG
     assert L.bd_load_weight(None, b"embed", None, 0, 0, None) == binding.BD_E_ARG
     assert L.bd_k_gemm(None, None, None, 4, 16, 32, None, 1, None) == binding.BD_E_ARG
     L.bd_destroy(None)
