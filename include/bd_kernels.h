@@ -42,6 +42,13 @@ const char* bd_k_class_name(int kclass);
  * GEMM, or the layer's cached K/V for the attention); 0 for classes that stream nothing. */
 int64_t bd_k_class_bytes(const bd_ctx* ctx, int kclass);
 
+/* Phase trace of the forward kernel: with enable != 0 every workgroup stores a 100 MHz timestamp at each
+ * phase boundary of the next forwards (start; then per layer: QKV done, barrier, attention done, barrier,
+ * O done, barrier, gate/up done, barrier, down done, barrier; then LM head done, barrier).  read copies
+ * the last forward's [n_wg][per_wg] table to host memory (capacity in entries). */
+int bd_k_trace(bd_ctx* ctx, int enable);
+int bd_k_trace_read(bd_ctx* ctx, unsigned long long* host_out, int capacity, int* n_wg, int* per_wg);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ EXPORTS = [
     "bd_verify_block", "bd_crop", "bd_cache_len", "bd_status", "bd_debug_logits", "bd_read_logits", "bd_read_kv",
     "bd_read_carry", "bd_read_rows", "bd_forward_bytes", "bd_strerror", "bd_last_error",
     "bd_k_gemm", "bd_k_attention", "bd_k_profile", "bd_k_profile_read", "bd_k_class_count", "bd_k_class_name",
-    "bd_k_class_bytes",
+    "bd_k_class_bytes", "bd_k_trace", "bd_k_trace_read",
 ]
 
 
@@ -77,6 +77,8 @@ def lib() -> C.CDLL:
     L.bd_k_class_name.restype = C.c_char_p
     L.bd_k_class_bytes.argtypes = [vp, i32]
     L.bd_k_class_bytes.restype = C.c_int64
+    L.bd_k_trace.argtypes = [vp, i32]
+    L.bd_k_trace_read.argtypes = [vp, vp, i32, C.POINTER(i32), C.POINTER(i32)]
     _lib = L
     return L
 
@@ -222,6 +224,28 @@ class Context:
             _check(L.bd_k_profile_read(self._h, k, C.byref(ms), C.byref(cnt)))
             out[L.bd_k_class_name(k).decode()] = (ms.value, cnt.value, int(L.bd_k_class_bytes(self._h, k)))
         return out
+
+
+def _trace_methods():
+    def bd_k_trace(self, enable: bool):
+        _check(lib().bd_k_trace(self._h, int(enable)))
+
+    def bd_k_trace_read(self):
+        """Timestamps (100 MHz ticks) of the last forward, array [n_wg, per_wg]."""
+        n_layers = self.shape.n_layers
+        cap = 4096 * (10 * n_layers + 4 + 64)
+        buf = np.zeros(cap, dtype=np.uint64)
+        n_wg, per = C.c_int(), C.c_int()
+        _check(lib().bd_k_trace_read(self._h, buf.ctypes.data, cap, C.byref(n_wg), C.byref(per)))
+        n1 = n_wg.value * per.value
+        self.last_subtrace = buf[n1:n1 + n_wg.value * 64].reshape(n_wg.value, 64)
+        return buf[:n1].reshape(n_wg.value, per.value)
+
+    Context.bd_k_trace = bd_k_trace
+    Context.bd_k_trace_read = bd_k_trace_read
+
+
+_trace_methods()
 
 
 def bd_k_gemm(w_bits, x, iters: int = 1):

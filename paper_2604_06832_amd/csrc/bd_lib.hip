@@ -78,6 +78,7 @@ struct bd_ctx {
   int* row_cand = nullptr; float* row_conf = nullptr;
   DevState* st = nullptr;
   unsigned* bar = nullptr; unsigned bar_epoch = 0;
+  unsigned long long* trace = nullptr; int trace_on = 0;
   // host mirror of the decode state
   int n = 0;
   bool prefilled = false, carry_valid = false;
@@ -187,9 +188,28 @@ int launch_mega_inst(bd_ctx* c, const MegaArgs& a) {
 }
 
 template <int MT>
-int launch_mega_mt(bd_ctx* c, const MegaArgs& a) {
-  if (c->D == 128) return launch_mega_inst<MT, 128, 2>(c, a);
-  return launch_mega_inst<MT, 64, 2>(c, a);
+int launch_lm(bd_ctx* c, const MegaArgs& a) {
+  static bool attr_set = false;
+  constexpr int lds = mega_lds_total<MT>();
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_kernel<MT>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((lm_kernel<MT>), dim3(c->plan.nwg), dim3(kWGThreads), lds, c->stream, a);
+  return check_launch();
+}
+
+template <int MT>
+int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
+  if (c->D == 128) BD_TRY((launch_mega_inst<MT, 128, 2>(c, a)));
+  else BD_TRY((launch_mega_inst<MT, 64, 2>(c, a)));
+  c->bar_epoch += 5u * (unsigned)c->L;
+  if (a.want_lm) {
+    a.bar_epoch = c->bar_epoch;
+    BD_TRY(launch_lm<MT>(c, a));
+    c->bar_epoch += 1u;
+  }
+  return BD_OK;
 }
 
 // One decoder forward over M rows: prologue (block assembly) + the persistent forward kernel.
@@ -227,16 +247,22 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
   a.lm_max = c->lm_max; a.lm_idx = c->lm_idx; a.lm_sum = c->lm_sum;
   a.logits = (want_lm && c->logits_on) ? c->logits : nullptr;
   a.row_cand = c->row_cand; a.row_conf = c->row_conf;
+  a.trace = c->trace_on ? c->trace : nullptr;
+  a.trace2 = c->trace_on ? c->trace + (size_t)c->plan.nwg * (10 * c->L + 4) : nullptr;
   {
     Prof pr(c, KC_FORWARD);
+#ifdef BD_DEV_FAST   /* development builds: one instantiation only, to shorten compile time */
+    if (MT != 2) return BD_E_ARG;
+    BD_TRY(launch_mega_mt<2>(c, a));
+#else
     switch (MT) {
       case 1: BD_TRY(launch_mega_mt<1>(c, a)); break;
       case 2: BD_TRY(launch_mega_mt<2>(c, a)); break;
       case 3: BD_TRY(launch_mega_mt<3>(c, a)); break;
       default: BD_TRY(launch_mega_mt<4>(c, a)); break;
     }
+#endif
   }
-  c->bar_epoch += 5u * (unsigned)c->L + (want_lm ? 1u : 0u);
   c->last_rows = M;
   c->last_had_logits = (want_lm && c->logits_on) ? 1 : 0;
   return BD_OK;
@@ -629,6 +655,29 @@ int bd_k_profile_read(bd_ctx* c, int kclass, double* total_ms, int* launches) {
   }
   if (total_ms) *total_ms = tot;
   if (launches) *launches = cnt;
+  return BD_OK;
+}
+
+int bd_k_trace(bd_ctx* c, int enable) {
+  if (c == nullptr) return BD_E_ARG;
+  const size_t n = (size_t)c->plan.nwg * (10 * c->L + 4 + 64);
+  if (enable && c->trace == nullptr) {
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&c->trace), n * 8));
+    c->allocs.push_back(c->trace);
+  }
+  if (enable) HIP_TRY(hipMemsetAsync(c->trace, 0, n * 8, c->stream));
+  c->trace_on = enable ? 1 : 0;
+  return BD_OK;
+}
+
+int bd_k_trace_read(bd_ctx* c, unsigned long long* host_out, int capacity, int* n_wg, int* per_wg) {
+  if (c == nullptr || host_out == nullptr || c->trace == nullptr) return BD_E_ARG;
+  const size_t n = (size_t)c->plan.nwg * (10 * c->L + 4 + 64);
+  if ((size_t)capacity < n) return BD_E_ARG;
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  HIP_TRY(hipMemcpy(host_out, c->trace, n * 8, hipMemcpyDeviceToHost));
+  if (n_wg) *n_wg = c->plan.nwg;
+  if (per_wg) *per_wg = 10 * c->L + 4;   /* followed by [n_wg][64] in-phase stamps of layer 1 */
   return BD_OK;
 }
 

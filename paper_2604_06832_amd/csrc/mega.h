@@ -129,6 +129,8 @@ struct MegaArgs {
   float* lm_max; int* lm_idx; float* lm_sum;   // [nwg][Mp]
   float* logits;
   int* row_cand; float* row_conf;
+  unsigned long long* trace;  // optional [nwg][10L+4] timestamps of phase boundaries (nullptr = off)
+  unsigned long long* trace2; // optional [nwg][64] timestamps inside the GEMM phases of layer 1
 };
 
 // ---- write-through stores and ordered waits ---------------------------------------------------------------
@@ -253,34 +255,9 @@ __device__ inline void load_chunk(bf16x8 (&buf)[kMaxKW][kT], const ChunkRef& r, 
   }
 }
 
-// Make the prefetched registers "used" at this program point so the wait for their loads is not hoisted
-// above what precedes (a barrier), then hand them over.
-__device__ inline void take_chunk(bf16x8 (&ring)[kMaxKW][kT], bf16x8 (&nxt)[kMaxKW][kT]) {
-#pragma unroll
-  for (int ksl = 0; ksl < kMaxKW; ++ksl)
-#pragma unroll
-    for (int t = 0; t < kT; ++t) {
-      asm volatile("" : "+v"(nxt[ksl][t]));
-      ring[ksl][t] = nxt[ksl][t];
-    }
-}
-
 // ---- activation fragments ----------------------------------------------------------------------------------
 // RMSNorm on load: rows of the fp32 residual stream are scaled by rsqrt(mean square + eps) (the sum of
 // squares arrives as per-tile partials) and by the gain, rounded to bf16, and laid out as B fragments.
-template <int MT>
-__device__ inline void row_scales(float (&rs)[MT], const float* ssq, int parts, int Mp, int H, float eps, int lane) {
-  const int col = lane & 15, g = lane >> 4;
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    float s = 0.f;
-    for (int p = g; p < parts; p += 4) s += ssq[(size_t)p * Mp + mt * 16 + col];
-    s += __shfl_xor(s, 16);
-    s += __shfl_xor(s, 32);
-    rs[mt] = rsqrtf(s / (float)H + eps);
-  }
-}
-
 // The fragments of a wavefront's k-steps are staged in a wavefront-private LDS region ([k-step][mt][lane]),
 // a few k-steps per batch so that the loads in flight stay bounded, and read back one k-step at a time.
 template <int MT>
@@ -330,7 +307,6 @@ __device__ inline void stage_x_packed(bf16x8* xs, const bf16x8* xp, int ks0, int
 
 // ---- one GEMM phase ------------------------------------------------------------------------------------------
 struct PhaseCtx {
-  const MegaArgs* a;
   int layer, n;             // layer index, committed context length
   f32x4* red;               // LDS [4][kT*MT][64]
   bf16x8* xstage;           // LDS, activation fragments: [4 wavefronts][XH][MT][64]
@@ -338,9 +314,8 @@ struct PhaseCtx {
 };
 
 template <int MT, int PH>
-__device__ inline void gemm_epilogue(const PhaseCtx& pc, const WavePhase& wp, int c, int t, int mt, f32x4 v, int lane,
+__device__ inline void gemm_epilogue(const MegaArgs& a, const PhaseCtx& pc, const WavePhase& wp, int c, int t, int mt, f32x4 v, int lane,
                                      float (&rmax)[MT], int (&ridx)[MT], float (&rsum)[MT]) {
-  const MegaArgs& a = *pc.a;
   const MegaPlan& P = a.P;
   const int col = lane & 15, g = lane >> 4;
   const int token = mt * 16 + col;
@@ -431,8 +406,7 @@ __device__ inline void gemm_epilogue(const PhaseCtx& pc, const WavePhase& wp, in
 // Down projection: the last of the ksplit workgroups to finish a tile sums all partials in fixed order,
 // adds the residual, stores the new residual version and its per-tile sum of squares.
 template <int MT>
-__device__ inline bool down_finalize(const PhaseCtx& pc, const WavePhase& wp, int wave, int lane) {
-  const MegaArgs& a = *pc.a;
+__device__ inline bool down_finalize(const MegaArgs& a, const PhaseCtx& pc, const WavePhase& wp, int wave, int lane) {
   const MegaPlan& P = a.P;
   const int ksplit = P.ph[PH_DOWN].ksplit;
   const int tiles = phase_tile_slots(P, PH_DOWN);
@@ -484,11 +458,41 @@ __device__ inline bool down_finalize(const PhaseCtx& pc, const WavePhase& wp, in
   return stored;
 }
 
+// Sum the per-tile partial sums of squares of a residual version into rsqrt(mean square + eps) per row,
+// with all 256 threads (fixed summation order), result in LDS.
+__device__ inline void row_scales_lds(float* s_part, float* s_rs, const float* ssq, int parts, int Mp, int rows, int H,
+                                      float eps) {
+  const int slices = kWGThreads / rows;                 // rows is 16, 32, 48 or 64
+  const int row = threadIdx.x % rows, slice = threadIdx.x / rows;
+  float s = 0.f;
+  if (slice < slices) {
+#pragma unroll 8
+    for (int p = slice; p < parts; p += slices) s += ssq[(size_t)p * Mp + row];
+    s_part[slice * rows + row] = s;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < rows) {
+    float t = 0.f;
+    for (int sl = 0; sl < slices; ++sl) t += s_part[sl * rows + threadIdx.x];
+    s_rs[threadIdx.x] = rsqrtf(t / (float)H + eps);
+  }
+  __syncthreads();
+}
+
+// One GEMM phase of one workgroup.  `ring` holds the current chunk of this wavefront's weight stream
+// (requested earlier).  While a chunk is multiplied, every consumed fragment is at once replaced by the
+// same position of the next chunk; only for the last chunk of the phase the refill (first chunk of the
+// next GEMM phase) is issued after the epilogue's stores, so that "stores done" can be awaited without
+// waiting for it.
 template <int MT, int PH>
-__device__ inline void gemm_phase(const PhaseCtx& pc, bf16x8 (&nxt)[kMaxKW][kT], Cursor& cur, int wave, int lane) {
+__device__ inline void gemm_phase(const MegaArgs& a, const PhaseCtx& pc, bf16x8 (&ring)[kMaxKW][kT], Cursor& cur,
+                                  int wave, int lane_in) {
+  // Re-define the lane id opaquely so that nothing derived from it is hoisted out of the layer loop
+  // (five phases' worth of loop-invariant addresses would otherwise live in registers all the time).
+  int lane = lane_in;
+  asm volatile("" : "+v"(lane));
   constexpr int XH = (MT <= 2) ? kMaxKW : 4;          // k-steps of activation fragments staged at a time
   bf16x8* xs = pc.xstage + (size_t)wave * (XH * MT * 64);
-  const MegaArgs& a = *pc.a;
   const MegaPlan& P = a.P;
   const WavePhase wp = wave_phase(P, PH, blockIdx.x, wave);
   const int n_tiles = (wp.rows + 15) >> 4;
@@ -498,6 +502,12 @@ __device__ inline void gemm_phase(const PhaseCtx& pc, bf16x8 (&nxt)[kMaxKW][kT],
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) { rmax[mt] = -INFINITY; ridx[mt] = 0x7FFFFFFF; rsum[mt] = 0.f; }
 
+#define BD_SUBTS(k)                                                                                   \
+  do {                                                                                                \
+    if (a.trace2 != nullptr && pc.layer == 1 && threadIdx.x == 0 && PH < PH_LM)                        \
+      a.trace2[(size_t)blockIdx.x * 64 + PH * 12 + (k)] = wall_clock64();                              \
+  } while (0)
+  BD_SUBTS(0);
   if (n_chunks > 0) {
     // activation source of this phase
     constexpr bool kNorm = (PH == PH_QKV || PH == PH_GU || PH == PH_LM);
@@ -509,26 +519,29 @@ __device__ inline void gemm_phase(const PhaseCtx& pc, bf16x8 (&nxt)[kMaxKW][kT],
     float rs[MT];
     if constexpr (kNorm) {
       const int parts = ver == 0 ? 1 : phase_tile_slots(P, (ver & 1) ? PH_O : PH_DOWN);
-      row_scales<MT>(rs, a.ssq + (size_t)ver * a.ssq_parts * a.Mp, parts, a.Mp, P.H, a.rms_eps, lane);
+      float* s_part = reinterpret_cast<float*>(pc.red);
+      float* s_rs = s_part + kWGThreads;
+      row_scales_lds(s_part, s_rs, a.ssq + (size_t)ver * a.ssq_parts * a.Mp, parts, a.Mp, MT * 16, P.H, a.rms_eps);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) rs[mt] = s_rs[mt * 16 + (lane & 15)];
+      BD_SUBTS(1);
       if constexpr (XH == kMaxKW) stage_x_norm<MT>(xs, xsrc, P.H, gain, rs, wp.w0, wp.KW, lane);
     } else {
+      BD_SUBTS(1);
       if constexpr (XH == kMaxKW) stage_x_packed<MT>(xs, xp, wp.w0, wp.KW, lane);
     }
+    BD_SUBTS(2);
 
     for (int c = 0; c < n_chunks; ++c) {
       const bool last = c == n_chunks - 1;
       const bool two = 2 * c + 1 < n_tiles;
       ChunkRef nr;
-      bf16x8 ring[kMaxKW][kT];                          // the chunk being multiplied (dead after this iteration)
-      if (wp.KW > 0) {                                  // a wavefront without k-steps only joins the reduction
-        take_chunk(ring, nxt);
-        if (!last) { nr = cur.next(P); load_chunk(nxt, nr, lane); }
-      } else {
-#pragma unroll
-        for (int ksl = 0; ksl < kMaxKW; ++ksl)
-#pragma unroll
-          for (int t = 0; t < kT; ++t) ring[ksl][t] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-      }
+      nr.ptr = nullptr; nr.KW = 0; nr.R0 = 0; nr.R1 = 0;
+      if (!last && wp.KW > 0) nr = cur.next(P);
+      const int ni = lane & 15, nkq = lane >> 4;
+      const int no0 = nkq * nr.R0 + min(ni, max(nr.R0 - 1, 0));
+      const int no1 = nr.R0 * 4 + nkq * nr.R1 + min(ni, max(nr.R1 - 1, 0));
+      const int nstep = (nr.R0 + nr.R1) * 4;
 
       f32x4 acc[kT][MT];
 #pragma unroll
@@ -544,14 +557,23 @@ __device__ inline void gemm_phase(const PhaseCtx& pc, bf16x8 (&nxt)[kMaxKW][kT],
           }
         }
         if (ksl < wp.KW) {
+          bf16x8 xk[MT];
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            const bf16x8 xk = xs[((ksl % XH) * MT + mt) * 64 + lane];
-            acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[ksl][0], xk, acc[0][mt], 0, 0, 0);
-            if (two) acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[ksl][1], xk, acc[1][mt], 0, 0, 0);
+          for (int mt = 0; mt < MT; ++mt) xk[mt] = xs[((ksl % XH) * MT + mt) * 64 + lane];
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[ksl][0], xk[mt], acc[0][mt], 0, 0, 0);
+          if (ksl < nr.KW) ring[ksl][0] = __builtin_nontemporal_load(nr.ptr + ksl * nstep + no0);
+          if (two) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[ksl][1], xk[mt], acc[1][mt], 0, 0, 0);
+            if (ksl < nr.KW && nr.R1 > 0) ring[ksl][1] = __builtin_nontemporal_load(nr.ptr + ksl * nstep + no1);
           }
         }
+        __builtin_amdgcn_sched_barrier(0);             // keep the refills in step with the multiplications
       }
+      if (c < 3) BD_SUBTS(3 + 2 * c);
       // the four wavefronts hold disjoint K ranges: sum them through LDS in fixed order
 #pragma unroll
       for (int t = 0; t < kT; ++t)
@@ -567,23 +589,26 @@ __device__ inline void gemm_phase(const PhaseCtx& pc, bf16x8 (&nxt)[kMaxKW][kT],
         v += pc.red[(1 * (kT * MT) + idx) * 64 + lane];
         v += pc.red[(2 * (kT * MT) + idx) * 64 + lane];
         v += pc.red[(3 * (kT * MT) + idx) * 64 + lane];
-        gemm_epilogue<MT, PH>(pc, wp, c, t, mt, v, lane, rmax, ridx, rsum);
+        gemm_epilogue<MT, PH>(a, pc, wp, c, t, mt, v, lane, rmax, ridx, rsum);
       }
       __syncthreads();
+      if (c < 3) BD_SUBTS(4 + 2 * c);
       if (last && wp.KW > 0) {
         // request the first chunk of the next GEMM phase now, after this phase's stores, and wait only
         // for what is older than that request
         nr = cur.next(P);
         asm volatile("" ::: "memory");
-        load_chunk(nxt, nr, lane);
+        load_chunk(ring, nr, lane);
         asm volatile("" ::: "memory");
         wait_vm_allow(chunk_loads(nr));
       }
     }
   }
+  BD_SUBTS(9);
   if constexpr (PH == PH_DOWN) {
-    if (down_finalize<MT>(pc, wp, wave, lane)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (down_finalize<MT>(a, pc, wp, wave, lane)) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
+  BD_SUBTS(10);
   if constexpr (PH == PH_LM) {
     // fold lane groups, then wavefronts, into this workgroup's row statistics
     const int col = lane & 15, g = lane >> 4;
@@ -626,9 +651,10 @@ __device__ inline void gemm_phase(const PhaseCtx& pc, bf16x8 (&nxt)[kMaxKW][kT],
 // stores its partial (unnormalised output, running max, running sum); the workgroup that completes the
 // last chunk of a (kv head, column group) merges all chunks in fixed order and stores the bf16 result.
 template <int D, int JT>
-__device__ inline void attention_phase(const PhaseCtx& pc, char* lds, int wave, int lane) {
+__device__ inline void attention_phase(const MegaArgs& a, const PhaseCtx& pc, char* lds, int wave, int lane_in) {
   constexpr int DS = D / 32, DT = D / 16;
-  const MegaArgs& a = *pc.a;
+  int lane = lane_in;
+  asm volatile("" : "+v"(lane));
   const MegaPlan& P = a.P;
   f32x4* sO = reinterpret_cast<f32x4*>(lds);                               // [DT*JT][64]
   float* sm = reinterpret_cast<float*>(lds + DT * JT * 64 * 16);           // [4][JT*16]
@@ -848,7 +874,6 @@ __global__ __launch_bounds__(kWGThreads, 1) void mega_kernel(MegaArgs a) {
   if (!s_flags[0]) return;
 
   PhaseCtx pc;
-  pc.a = &a;
   pc.n = a.st->n;
   pc.xstage = reinterpret_cast<bf16x8*>(lds);
   pc.red = reinterpret_cast<f32x4*>(lds + kWavesPerWG * mega_xh<MT>() * MT * 1024);
@@ -857,58 +882,99 @@ __global__ __launch_bounds__(kWGThreads, 1) void mega_kernel(MegaArgs a) {
 
   Cursor cur;
   cur.pos = a.wstream + (size_t)(blockIdx.x * kWavesPerWG + wave) * a.P.wave_stride;
-  cur.l = 0; cur.p = PH_QKV; cur.c = 0; cur.wg = blockIdx.x; cur.w = wave; cur.want_lm = a.want_lm;
-  bf16x8 nxt[kMaxKW][kT];
+  cur.l = 0; cur.p = PH_QKV; cur.c = 0; cur.wg = blockIdx.x; cur.w = wave; cur.want_lm = 0;   // the LM head is its own launch
+  bf16x8 ring[kMaxKW][kT];
   {
     ChunkRef r0 = cur.next(P);
-    load_chunk(nxt, r0, lane);
+    load_chunk(ring, r0, lane);
   }
   bool alive = true;
+  int tsi = 0;
+#define BD_TS()                                                                                                  \
+  do {                                                                                                           \
+    if (a.trace != nullptr && threadIdx.x == 0) a.trace[(size_t)blockIdx.x * (10 * P.L + 4) + tsi] = wall_clock64(); \
+    ++tsi;                                                                                                       \
+  } while (0)
+  BD_TS();
   for (int l = 0; l < P.L && alive; ++l) {
     pc.layer = l;
-    gemm_phase<MT, PH_QKV>(pc, nxt, cur, wave, lane);
+    gemm_phase<MT, PH_QKV>(a, pc, ring, cur, wave, lane);
+    BD_TS();
     alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
+    BD_TS();
     if (!alive) break;
-    attention_phase<D, JT>(pc, lds, wave, lane);
+    attention_phase<D, JT>(a, pc, lds, wave, lane);
+    BD_TS();
     alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
+    BD_TS();
     if (!alive) break;
-    gemm_phase<MT, PH_O>(pc, nxt, cur, wave, lane);
+    gemm_phase<MT, PH_O>(a, pc, ring, cur, wave, lane);
+    BD_TS();
     alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
+    BD_TS();
     if (!alive) break;
-    gemm_phase<MT, PH_GU>(pc, nxt, cur, wave, lane);
+    gemm_phase<MT, PH_GU>(a, pc, ring, cur, wave, lane);
+    BD_TS();
     alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
+    BD_TS();
     if (!alive) break;
-    gemm_phase<MT, PH_DOWN>(pc, nxt, cur, wave, lane);
+    gemm_phase<MT, PH_DOWN>(a, pc, ring, cur, wave, lane);
+    BD_TS();
     alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
+    BD_TS();
   }
-  if (alive && a.want_lm) {
-    pc.layer = P.L;
-    gemm_phase<MT, PH_LM>(pc, nxt, cur, wave, lane);
-    alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
-    if (alive && (int)blockIdx.x < a.M) {
-      // workgroup r folds row r over all workgroups' statistics
-      const int r = blockIdx.x;
-      float m = -INFINITY, s = 0.f;
-      int i = 0x7FFFFFFF;
-      for (int p = threadIdx.x; p < P.nwg; p += kWGThreads)
-        stat_merge(m, i, s, a.lm_max[(size_t)p * a.Mp + r], a.lm_idx[(size_t)p * a.Mp + r], a.lm_sum[(size_t)p * a.Mp + r]);
+}
+
+// LM head as its own launch of the same machinery: RMSNorm-on-load + LM head + per-row (max, argmax,
+// sum exp) per workgroup, a grid barrier, then workgroup r folds row r over all workgroups.
+template <int MT>
+__global__ __launch_bounds__(kWGThreads, 1) void lm_kernel(MegaArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  __shared__ int s_flags[16];
+  const MegaPlan& P = a.P;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (threadIdx.x == 0) s_flags[0] = (a.st->error == 0);
+  __syncthreads();
+  if (!s_flags[0]) return;
+  PhaseCtx pc;
+  pc.n = 0;
+  pc.layer = P.L;
+  pc.xstage = reinterpret_cast<bf16x8*>(lds);
+  pc.red = reinterpret_cast<f32x4*>(lds + kWavesPerWG * mega_xh<MT>() * MT * 1024);
+  pc.s_flags = s_flags;
+  Cursor cur;
+  cur.pos = a.wstream + (size_t)(blockIdx.x * kWavesPerWG + wave) * a.P.wave_stride +
+            (size_t)P.L * wave_layer_units(P, blockIdx.x, wave);
+  cur.l = P.L; cur.p = PH_LM; cur.c = 0; cur.wg = blockIdx.x; cur.w = wave; cur.want_lm = 1;
+  bf16x8 ring[kMaxKW][kT];
+  {
+    ChunkRef r0 = cur.next(P);
+    load_chunk(ring, r0, lane);
+  }
+  gemm_phase<MT, PH_LM>(a, pc, ring, cur, wave, lane);
+  if (!grid_barrier(a.bar, a.bar_epoch + 1u, P.nwg, a.st, &s_flags[0])) return;
+  if ((int)blockIdx.x < a.M) {
+    const int r = blockIdx.x;
+    float m = -INFINITY, s = 0.f;
+    int i = 0x7FFFFFFF;
+    for (int p = threadIdx.x; p < P.nwg; p += kWGThreads)
+      stat_merge(m, i, s, a.lm_max[(size_t)p * a.Mp + r], a.lm_idx[(size_t)p * a.Mp + r], a.lm_sum[(size_t)p * a.Mp + r]);
 #pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const float m2 = __shfl_xor(m, off);
-        const int i2 = __shfl_xor(i, off);
-        const float s2 = __shfl_xor(s, off);
-        stat_merge(m, i, s, m2, i2, s2);
-      }
-      float* s_m = reinterpret_cast<float*>(lds);
-      int* s_i = reinterpret_cast<int*>(lds) + 8;
-      float* s_s = reinterpret_cast<float*>(lds) + 16;
-      if (lane == 0) { s_m[wave] = m; s_i[wave] = i; s_s[wave] = s; }
-      __syncthreads();
-      if (threadIdx.x == 0) {
-        for (int w = 1; w < kWavesPerWG; ++w) stat_merge(m, i, s, s_m[w], s_i[w], s_s[w]);
-        a.row_cand[r] = i;
-        a.row_conf[r] = 1.f / s;
-      }
+    for (int off = 1; off < 64; off <<= 1) {
+      const float m2 = __shfl_xor(m, off);
+      const int i2 = __shfl_xor(i, off);
+      const float s2 = __shfl_xor(s, off);
+      stat_merge(m, i, s, m2, i2, s2);
+    }
+    float* s_m = reinterpret_cast<float*>(lds);
+    int* s_i = reinterpret_cast<int*>(lds) + 8;
+    float* s_s = reinterpret_cast<float*>(lds) + 16;
+    if (lane == 0) { s_m[wave] = m; s_i[wave] = i; s_s[wave] = s; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int w = 1; w < kWavesPerWG; ++w) stat_merge(m, i, s, s_m[w], s_i[w], s_s[w]);
+      a.row_cand[r] = i;
+      a.row_conf[r] = 1.f / s;
     }
   }
 }
