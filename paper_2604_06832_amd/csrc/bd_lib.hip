@@ -65,6 +65,7 @@ struct bd_ctx {
   size_t kv_layer_elems = 0;
   // write-once activations of a forward
   float* xv = nullptr; float* ssq = nullptr; int ssq_parts = 0;
+  u16* xb = nullptr; size_t xb_elems = 0;
   float2* rope = nullptr;
   u16* q = nullptr; u16* ap = nullptr; u16* act = nullptr;
   size_t ap_elems = 0, act_elems = 0;
@@ -221,7 +222,7 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
   hipStream_t s = c->stream;
   {
     PrologueArgs p{};
-    p.x0 = c->xv; p.ssq0 = c->ssq; p.H = c->H; p.Mp = Mp;
+    p.x0 = c->xv; p.ssq0 = c->ssq; p.H = c->H; p.Mp = Mp; p.xb0 = c->xb; p.MT = MT;
     p.embeds = embeds; p.n_embed = n_embed; p.ids = ids; p.off = off;
     p.seed_tokens = seed_tokens; p.seed_mask = seed_mask; p.mask = mask;
     p.mask_id = c->cfg.mask_token_id; p.table = c->embed; p.vocab = c->V; p.st = c->st;
@@ -236,7 +237,7 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
   a.wstream = reinterpret_cast<const bf16x8*>(c->wstream);
   a.st = c->st; a.bar = c->bar; a.bar_epoch = c->bar_epoch;
   a.M = M; a.MT = MT; a.mode = mode; a.want_lm = want_lm ? 1 : 0;
-  a.xv = c->xv; a.ssq = c->ssq; a.ssq_parts = c->ssq_parts; a.Mp = Mp; a.gains = c->gains; a.rms_eps = c->cfg.rms_eps;
+  a.xv = c->xv; a.xb = c->xb; a.xb_elems = c->xb_elems; a.ssq = c->ssq; a.ssq_parts = c->ssq_parts; a.Mp = Mp; a.gains = c->gains; a.rms_eps = c->cfg.rms_eps;
   a.rope = c->rope; a.Q = c->q; a.Kc = c->Kc; a.Vc = c->Vc; a.kv_layer_elems = c->kv_layer_elems; a.max_kb = c->max_kb;
   a.ap = c->ap; a.ap_elems = c->ap_elems; a.act = c->act; a.act_elems = c->act_elems;
   a.wsD = c->wsD; a.wsD_layer_floats = c->wsD_layer_floats; a.cntD = c->counters;
@@ -356,6 +357,8 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   A(c->Kc, c->kv_layer_elems * L * 2);
   A(c->Vc, c->kv_layer_elems * L * 2);
   A(c->xv, (2 * L + 1) * Mp * c->H * 4);
+  c->xb_elems = (size_t)c->H * Mp;
+  A(c->xb, (2 * L + 1) * c->xb_elems * 2);
   c->ssq_parts = std::max(phase_tile_slots(P, PH_O), phase_tile_slots(P, PH_DOWN));
   A(c->ssq, (2 * L + 1) * (size_t)c->ssq_parts * Mp * 4);
   A(c->rope, Mp * (c->D / 2) * sizeof(float2));

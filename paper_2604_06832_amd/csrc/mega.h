@@ -100,7 +100,10 @@ struct MegaArgs {
   unsigned bar_epoch;         // epoch of the last barrier of the previous forward
   int M, MT, mode, want_lm;
   // activations (all write-once per forward)
-  float* xv;                  // [2L+1][Mp][H] residual stream versions
+  float* xv;                  // [2L+1][Mp][H] residual stream versions (fp32: the accumulation chain)
+  u16* xb;                    // [2L+1] the same versions rounded to bf16 in packed activation order (K = H): what
+                              // the norm-on-load GEMM phases read
+  size_t xb_elems;
   float* ssq;                 // [2L+1][parts][Mp] partial sums of squares of each version
   int ssq_parts;              // stride (parts) per version; version 0 has one part, odd versions one per
                               // tile slot of the O phase, even versions one per tile slot of the DOWN phase
@@ -149,19 +152,6 @@ __device__ inline void st_wt_f32(void* p, float v) {
 __device__ inline void st_wt_f32x4(void* p, f32x4 v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
 }
-// Wait until at most `k` of this wavefront's vector-memory operations are outstanding.  The counter is
-// in order, so with exactly k loads issued after a group of stores this means "the stores are done".
-__device__ inline void wait_vm_allow(int k) {
-#define BD_W(n) case n: asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory"); break;
-  switch (k) {
-    BD_W(1) BD_W(2) BD_W(3) BD_W(4) BD_W(5) BD_W(6) BD_W(7) BD_W(8) BD_W(9) BD_W(10) BD_W(11) BD_W(12) BD_W(13)
-    BD_W(14) BD_W(15) BD_W(16) BD_W(17) BD_W(18) BD_W(19) BD_W(20) BD_W(21) BD_W(22) BD_W(23) BD_W(24) BD_W(25)
-    BD_W(26) BD_W(27) BD_W(28) BD_W(29) BD_W(30) BD_W(31) BD_W(32)
-    default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-  }
-#undef BD_W
-}
-
 // ---- grid barrier --------------------------------------------------------------------------------------
 // Two-level arrival counters (groups of 16 workgroups, one 128-byte line per counter), release words per
 // group.  Counters only grow; `epoch` numbers the barriers of the whole process.  Bounded spin: on
@@ -201,27 +191,49 @@ __device__ inline bool grid_barrier(unsigned* bar, unsigned epoch, int nwg, DevS
 }
 
 // ---- weight stream cursor ----------------------------------------------------------------------------------
+// All streamed operands are fetched with raw buffer loads: an out-of-range offset returns zeros and moves
+// no data, so the inner loops are straight-line code (every position of a chunk is always "loaded" and
+// multiplied; positions a wavefront does not have read as zero) and the compiler's in-order wait counts
+// stay exact.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
+constexpr int kOob = -1;                                // offset 0xFFFFFFFF: beyond any buffer
+constexpr int kAuxNt = 2;                               // non-temporal (streamed once)
+
+__device__ inline rsrc_t make_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+__device__ inline bf16x8 buf_load_w(rsrc_t r, int byte_off) {
+  return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, kAuxNt));
+}
+__device__ inline bf16x8 buf_load_b(rsrc_t r, int byte_off) {
+  return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0));
+}
+__device__ inline f32x4 buf_load_f(rsrc_t r, int byte_off) {
+  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0));
+}
+
 struct ChunkRef {
-  const bf16x8* ptr;   // start of the chunk in this wavefront's stream
-  int KW, R0, R1;      // k-steps; rows of the chunk's first / second tile (R1 = 0: single tile)
+  int off;             // byte offset of the chunk in this wavefront's stream
+  int KW, R0, R1;      // k-steps; rows of the chunk's first / second tile (R1 = 0: single tile); KW = 0: none
 };
 
 struct Cursor {
-  const bf16x8* pos;
+  int pos;             // byte offset in the wavefront's stream
   int l, p, c, wg, w, want_lm;
   __device__ ChunkRef next(const MegaPlan& P) {
     ChunkRef r;
-    r.ptr = pos; r.KW = 0; r.R0 = 0; r.R1 = 0;
+    r.off = 0; r.KW = 0; r.R0 = 0; r.R1 = 0;
     while (p != PH_END) {
       const WavePhase wp = wave_phase(P, p, wg, w);
       const int n_tiles = (wp.rows + 15) >> 4;
       const int n_chunks = (n_tiles + 1) >> 1;
       if (c < n_chunks && wp.KW > 0) {
-        r.ptr = pos;
+        r.off = pos;
         r.KW = wp.KW;
         r.R0 = min(16, wp.rows - 32 * c);
         r.R1 = (2 * c + 1 < n_tiles) ? min(16, wp.rows - 32 * c - 16) : 0;
-        pos += (size_t)wp.KW * (r.R0 + r.R1) * 4;
+        pos += wp.KW * (r.R0 + r.R1) * 64;
         ++c;
         return r;
       }
@@ -239,19 +251,29 @@ struct Cursor {
   }
 };
 
-__device__ inline int chunk_loads(const ChunkRef& r) { return r.KW * (r.R1 > 0 ? 2 : 1); }
-
-__device__ inline void load_chunk(bf16x8 (&buf)[kMaxKW][kT], const ChunkRef& r, int lane) {
+// Per-lane byte offsets of the two tiles of a chunk at k-step 0, and the k-step stride.
+struct ChunkLane { int o0, o1, step, KW; };
+__device__ inline ChunkLane chunk_lane(const ChunkRef& r, int lane) {
   const int i = lane & 15, kq = lane >> 4;
-  const int o0 = kq * r.R0 + min(i, r.R0 - 1);
-  const int o1 = r.R0 * 4 + kq * r.R1 + min(i, max(r.R1 - 1, 0));
-  const int step = (r.R0 + r.R1) * 4;
+  ChunkLane cl;
+  cl.KW = r.KW;
+  cl.step = (r.R0 + r.R1) * 64;
+  cl.o0 = r.off + (kq * r.R0 + min(i, max(r.R0 - 1, 0))) * 16;
+  cl.o1 = r.R1 > 0 ? r.off + (r.R0 * 4 + kq * r.R1 + min(i, r.R1 - 1)) * 16 : kOob;
+  return cl;
+}
+__device__ inline int chunk_off(const ChunkLane& cl, int ksl, int t) {
+  const int base = t ? cl.o1 : cl.o0;
+  return (ksl < cl.KW && base != kOob) ? base + ksl * cl.step : kOob;
+}
+
+// Always 32 load instructions, whatever the chunk's shape.
+__device__ inline void load_chunk(bf16x8 (&buf)[kMaxKW][kT], rsrc_t wr, const ChunkRef& r, int lane) {
+  const ChunkLane cl = chunk_lane(r, lane);
 #pragma unroll
   for (int ksl = 0; ksl < kMaxKW; ++ksl) {
-    if (ksl < r.KW) {
-      buf[ksl][0] = __builtin_nontemporal_load(r.ptr + ksl * step + o0);
-      if (r.R1 > 0) buf[ksl][1] = __builtin_nontemporal_load(r.ptr + ksl * step + o1);
-    }
+    buf[ksl][0] = buf_load_w(wr, chunk_off(cl, ksl, 0));
+    buf[ksl][1] = buf_load_w(wr, chunk_off(cl, ksl, 1));
   }
 }
 
@@ -259,49 +281,64 @@ __device__ inline void load_chunk(bf16x8 (&buf)[kMaxKW][kT], const ChunkRef& r, 
 // RMSNorm on load: rows of the fp32 residual stream are scaled by rsqrt(mean square + eps) (the sum of
 // squares arrives as per-tile partials) and by the gain, rounded to bf16, and laid out as B fragments.
 // The fragments of a wavefront's k-steps are staged in a wavefront-private LDS region ([k-step][mt][lane]),
-// a few k-steps per batch so that the loads in flight stay bounded, and read back one k-step at a time.
+// four k-steps per batch (all loads of a batch are in flight together), and read back one k-step at a
+// time.  K-steps the wavefront does not have read as zero.
 template <int MT>
-__device__ inline void stage_x_norm(bf16x8* xs, const float* x, int H, const float* gain, const float (&rs)[MT],
-                                    int ks0, int nk, int lane) {
-  const int col = lane & 15, g = lane >> 4;
-  for (int j0 = 0; j0 < nk; j0 += 4) {
+__device__ inline void stage_x_norm(bf16x8* xs, rsrc_t xr, rsrc_t gr, const float (&rs)[MT], int ks0, int nk, int slots,
+                                    int lane) {
+  const int g = lane >> 4;
+  constexpr int NB = (MT <= 2) ? 8 : 4;                  // k-steps per batch (all their loads in flight together)
+  for (int j0 = 0; j0 < slots; j0 += NB) {
+    f32x4 ga[NB][2];
+    bf16x8 xa[NB][MT];
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      const int j = j0 + jj;
-      if (j < nk) {
-        const int k0 = (ks0 + j) * 32 + 8 * g;
-        const f32x4 g0 = *reinterpret_cast<const f32x4*>(gain + k0);
-        const f32x4 g1 = *reinterpret_cast<const f32x4*>(gain + k0 + 4);
+    for (int jj = 0; jj < NB; ++jj) {
+      const bool ok = j0 + jj < nk;
+      const int k0 = (ks0 + j0 + jj) * 32 + 8 * g;
+      ga[jj][0] = buf_load_f(gr, ok ? k0 * 4 : kOob);
+      ga[jj][1] = buf_load_f(gr, ok ? k0 * 4 + 16 : kOob);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const float* px = x + (size_t)(mt * 16 + col) * H + k0;
-          const f32x4 a = *reinterpret_cast<const f32x4*>(px);
-          const f32x4 b = *reinterpret_cast<const f32x4*>(px + 4);
-          union { bf16x8 v; u16 h[8]; } cv;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            cv.h[e] = f32_to_bf16_bits(a[e] * rs[mt] * g0[e]);
-            cv.h[4 + e] = f32_to_bf16_bits(b[e] * rs[mt] * g1[e]);
-          }
-          xs[(j * MT + mt) * 64 + lane] = cv.v;
-        }
-      }
+      for (int mt = 0; mt < MT; ++mt)
+        xa[jj][mt] = buf_load_b(xr, ok ? (((ks0 + j0 + jj) * MT + mt) * 64 + lane) * 16 : kOob);
     }
-    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int jj = 0; jj < NB; ++jj)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        union { bf16x8 v; u16 h[8]; } in, cv;
+        in.v = xa[jj][mt];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          cv.h[e] = f32_to_bf16_bits(bf16_bits_to_f32(in.h[e]) * rs[mt] * ga[jj][e >> 2][e & 3]);
+        xs[((j0 + jj) * MT + mt) * 64 + lane] = cv.v;
+      }
   }
 }
 
 template <int MT>
-__device__ inline void stage_x_packed(bf16x8* xs, const bf16x8* xp, int ks0, int nk, int lane) {
-  for (int j0 = 0; j0 < nk; j0 += 8) {
+__device__ inline void stage_x_packed(bf16x8* xs, rsrc_t xr, int ks0, int nk, int slots, int lane) {
+  for (int j0 = 0; j0 < slots; j0 += 4) {
+    bf16x8 v[4][MT];
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-      const int j = j0 + jj;
-      if (j < nk)
+    for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) xs[(j * MT + mt) * 64 + lane] = xp[((size_t)(ks0 + j) * MT + mt) * 64 + lane];
-    }
-    asm volatile("" ::: "memory");
+      for (int mt = 0; mt < MT; ++mt)
+        v[jj][mt] = buf_load_b(xr, j0 + jj < nk ? (((ks0 + j0 + jj) * MT + mt) * 64 + lane) * 16 : kOob);
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) xs[((j0 + jj) * MT + mt) * 64 + lane] = v[jj][mt];
+  }
+}
+
+// Store channels r .. r+n-1 (n = 2 or 4) of one token into the packed bf16 copy of a residual version.
+__device__ inline void store_xb(u16* xb, int token, int r, int n, const float* o, int MT) {
+  if (n == 4 && (r & 3) == 0) {
+    const uint32_t lo = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
+    const uint32_t hi = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
+    st_wt_u64(xb + xp_index(token, r, MT), (uint64_t)lo | ((uint64_t)hi << 32));
+  } else {
+    for (int e = 0; e < n; ++e) st_wt_u16(xb + xp_index(token, r + e, MT), f32_to_bf16_bits(o[e]));
   }
 }
 
@@ -359,13 +396,16 @@ __device__ inline void gemm_epilogue(const MegaArgs& a, const PhaseCtx& pc, cons
     if (live) {
       const float* xo = a.xv + ((size_t)(ver - 1) * a.Mp + token) * P.H + r;
       float* xn = a.xv + ((size_t)ver * a.Mp + token) * P.H + r;
+      float o[4] = {0.f, 0.f, 0.f, 0.f};
       if (nrows == 4 && (r & 3) == 0) {
-        const f32x4 o = *reinterpret_cast<const f32x4*>(xo) + v;
-        st_wt_f32x4(xn, o);
-        ss = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
+        const f32x4 ov = *reinterpret_cast<const f32x4*>(xo) + v;
+        st_wt_f32x4(xn, ov);
+        for (int e = 0; e < 4; ++e) o[e] = ov[e];
       } else {
-        for (int e = 0; e < nrows; ++e) { const float o = xo[e] + v[e]; st_wt_f32(xn + e, o); ss += o * o; }
+        for (int e = 0; e < nrows; ++e) { o[e] = xo[e] + v[e]; st_wt_f32(xn + e, o[e]); }
       }
+      store_xb(a.xb + (size_t)ver * a.xb_elems, token, r, nrows, o, a.MT);
+      ss = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
     }
     ss += __shfl_xor(ss, 16);
     ss += __shfl_xor(ss, 32);
@@ -442,13 +482,16 @@ __device__ inline bool down_finalize(const MegaArgs& a, const PhaseCtx& pc, cons
     if (token < a.M && nrows > 0) {
       const float* xo = a.xv + ((size_t)(ver - 1) * a.Mp + token) * P.H + r;
       float* xn = a.xv + ((size_t)ver * a.Mp + token) * P.H + r;
+      float o[4] = {0.f, 0.f, 0.f, 0.f};
       if (nrows == 4 && (r & 3) == 0) {
-        const f32x4 o = *reinterpret_cast<const f32x4*>(xo) + v;
-        st_wt_f32x4(xn, o);
-        ss = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
+        const f32x4 ov = *reinterpret_cast<const f32x4*>(xo) + v;
+        st_wt_f32x4(xn, ov);
+        for (int e = 0; e < 4; ++e) o[e] = ov[e];
       } else {
-        for (int e = 0; e < nrows; ++e) { const float o = xo[e] + v[e]; st_wt_f32(xn + e, o); ss += o * o; }
+        for (int e = 0; e < nrows; ++e) { o[e] = xo[e] + v[e]; st_wt_f32(xn + e, o[e]); }
       }
+      store_xb(a.xb + (size_t)ver * a.xb_elems, token, r, nrows, o, a.MT);
+      ss = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
     }
     ss += __shfl_xor(ss, 16);
     ss += __shfl_xor(ss, 32);
@@ -464,10 +507,18 @@ __device__ inline void row_scales_lds(float* s_part, float* s_rs, const float* s
                                       float eps) {
   const int slices = kWGThreads / rows;                 // rows is 16, 32, 48 or 64
   const int row = threadIdx.x % rows, slice = threadIdx.x / rows;
-  float s = 0.f;
   if (slice < slices) {
-#pragma unroll 8
-    for (int p = slice; p < parts; p += slices) s += ssq[(size_t)p * Mp + row];
+    float s = 0.f;
+    for (int p0 = slice; p0 < parts; p0 += 16 * slices) {
+      float v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int p = p0 + u * slices;
+        v[u] = ssq[(size_t)min(p, parts - 1) * Mp + row];
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) s += (p0 + u * slices < parts) ? v[u] : 0.f;
+    }
     s_part[slice * rows + row] = s;
   }
   __syncthreads();
@@ -512,10 +563,12 @@ __device__ inline void gemm_phase(const MegaArgs& a, const PhaseCtx& pc, bf16x8 
     // activation source of this phase
     constexpr bool kNorm = (PH == PH_QKV || PH == PH_GU || PH == PH_LM);
     const int ver = (PH == PH_QKV) ? 2 * pc.layer : (PH == PH_GU) ? 2 * pc.layer + 1 : 2 * P.L;
-    const float* xsrc = a.xv + (size_t)ver * a.Mp * P.H;
-    const float* gain = a.gains + (size_t)ver * P.H;
-    const bf16x8* xp = reinterpret_cast<const bf16x8*>(
-        PH == PH_O ? a.ap + (size_t)pc.layer * a.ap_elems : a.act + (size_t)pc.layer * a.act_elems);
+    const rsrc_t wr = make_rsrc(a.wstream + (size_t)(blockIdx.x * kWavesPerWG + wave) * P.wave_stride,
+                                (unsigned)(P.wave_stride * 16));
+    const rsrc_t xr = kNorm ? make_rsrc(a.xb + (size_t)ver * a.xb_elems, (unsigned)(a.xb_elems * 2))
+                            : (PH == PH_O ? make_rsrc(a.ap + (size_t)pc.layer * a.ap_elems, (unsigned)(a.ap_elems * 2))
+                                          : make_rsrc(a.act + (size_t)pc.layer * a.act_elems, (unsigned)(a.act_elems * 2)));
+    const rsrc_t gr = make_rsrc(a.gains + (size_t)ver * P.H, (unsigned)(P.H * 4));
     float rs[MT];
     if constexpr (kNorm) {
       const int parts = ver == 0 ? 1 : phase_tile_slots(P, (ver & 1) ? PH_O : PH_DOWN);
@@ -525,53 +578,46 @@ __device__ inline void gemm_phase(const MegaArgs& a, const PhaseCtx& pc, bf16x8 
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) rs[mt] = s_rs[mt * 16 + (lane & 15)];
       BD_SUBTS(1);
-      if constexpr (XH == kMaxKW) stage_x_norm<MT>(xs, xsrc, P.H, gain, rs, wp.w0, wp.KW, lane);
+      if constexpr (XH == kMaxKW) stage_x_norm<MT>(xs, xr, gr, rs, wp.w0, wp.KW, XH, lane);
     } else {
       BD_SUBTS(1);
-      if constexpr (XH == kMaxKW) stage_x_packed<MT>(xs, xp, wp.w0, wp.KW, lane);
+      if constexpr (XH == kMaxKW) stage_x_packed<MT>(xs, xr, wp.w0, wp.KW, XH, lane);
     }
     BD_SUBTS(2);
 
     for (int c = 0; c < n_chunks; ++c) {
       const bool last = c == n_chunks - 1;
       const bool two = 2 * c + 1 < n_tiles;
-      ChunkRef nr;
-      nr.ptr = nullptr; nr.KW = 0; nr.R0 = 0; nr.R1 = 0;
-      if (!last && wp.KW > 0) nr = cur.next(P);
-      const int ni = lane & 15, nkq = lane >> 4;
-      const int no0 = nkq * nr.R0 + min(ni, max(nr.R0 - 1, 0));
-      const int no1 = nr.R0 * 4 + nkq * nr.R1 + min(ni, max(nr.R1 - 1, 0));
-      const int nstep = (nr.R0 + nr.R1) * 4;
-
       f32x4 acc[kT][MT];
 #pragma unroll
       for (int t = 0; t < kT; ++t)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[t][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (wp.KW > 0) {                                  // a wavefront without k-steps only joins the reduction
+        ChunkRef nr;
+        nr.off = 0; nr.KW = 0; nr.R0 = 0; nr.R1 = 0;   // last chunk: the in-place refills read nothing
+        if (!last) nr = cur.next(P);
+        const ChunkLane cl = chunk_lane(nr, lane);
 #pragma unroll
-      for (int ksl = 0; ksl < kMaxKW; ++ksl) {
-        if constexpr (XH < kMaxKW) {
-          if (ksl % XH == 0 && ksl < wp.KW) {
-            if constexpr (kNorm) stage_x_norm<MT>(xs, xsrc, P.H, gain, rs, wp.w0 + ksl, min(XH, wp.KW - ksl), lane);
-            else stage_x_packed<MT>(xs, xp, wp.w0 + ksl, min(XH, wp.KW - ksl), lane);
+        for (int ksl = 0; ksl < kMaxKW; ++ksl) {
+          if constexpr (XH < kMaxKW) {
+            if (ksl % XH == 0) {
+              if constexpr (kNorm) stage_x_norm<MT>(xs, xr, gr, rs, wp.w0 + ksl, wp.KW - ksl, XH, lane);
+              else stage_x_packed<MT>(xs, xr, wp.w0 + ksl, wp.KW - ksl, XH, lane);
+            }
           }
-        }
-        if (ksl < wp.KW) {
           bf16x8 xk[MT];
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) xk[mt] = xs[((ksl % XH) * MT + mt) * 64 + lane];
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt)
             acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[ksl][0], xk[mt], acc[0][mt], 0, 0, 0);
-          if (ksl < nr.KW) ring[ksl][0] = __builtin_nontemporal_load(nr.ptr + ksl * nstep + no0);
-          if (two) {
+          ring[ksl][0] = buf_load_w(wr, chunk_off(cl, ksl, 0));
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-              acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[ksl][1], xk[mt], acc[1][mt], 0, 0, 0);
-            if (ksl < nr.KW && nr.R1 > 0) ring[ksl][1] = __builtin_nontemporal_load(nr.ptr + ksl * nstep + no1);
-          }
+          for (int mt = 0; mt < MT; ++mt)
+            acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ring[ksl][1], xk[mt], acc[1][mt], 0, 0, 0);
+          ring[ksl][1] = buf_load_w(wr, chunk_off(cl, ksl, 1));
         }
-        __builtin_amdgcn_sched_barrier(0);             // keep the refills in step with the multiplications
       }
       if (c < 3) BD_SUBTS(3 + 2 * c);
       // the four wavefronts hold disjoint K ranges: sum them through LDS in fixed order
@@ -595,12 +641,11 @@ __device__ inline void gemm_phase(const MegaArgs& a, const PhaseCtx& pc, bf16x8 
       if (c < 3) BD_SUBTS(4 + 2 * c);
       if (last && wp.KW > 0) {
         // request the first chunk of the next GEMM phase now, after this phase's stores, and wait only
-        // for what is older than that request
-        nr = cur.next(P);
+        // for what is older than these 32 loads
+        const ChunkRef nr = cur.next(P);
         asm volatile("" ::: "memory");
-        load_chunk(ring, nr, lane);
-        asm volatile("" ::: "memory");
-        wait_vm_allow(chunk_loads(nr));
+        load_chunk(ring, wr, nr, lane);
+        asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
       }
     }
   }
@@ -817,29 +862,70 @@ __device__ inline void attention_phase(const MegaArgs& a, const PhaseCtx& pc, ch
     }
     __syncthreads();
     if (pc.s_flags[4]) {
+      // last arriver of this (kv head, column group): merge all chunks, every load of a round in flight at once
+      constexpr int NC = JT * 16;                        // columns of the group
+      constexpr int SL = kWGThreads / NC;                // threads per column
       const size_t item0 = (size_t)grp * n_chunks;
-      if ((int)threadIdx.x < JT * 16) {
-        const int cc = threadIdx.x;
-        float mm = kNegBig;
-        for (int ch = 0; ch < n_chunks; ++ch) mm = fmaxf(mm, pm[(item0 + ch) * (JT * 16) + cc]);
-        float ll = 0.f;
-        for (int ch = 0; ch < n_chunks; ++ch) {
-          const float w = exp2f(pm[(item0 + ch) * (JT * 16) + cc] - mm);
-          ll += pl[(item0 + ch) * (JT * 16) + cc] * w;
-          wgt[ch * (JT * 16) + cc] = w;
+      float* s_red = wgt + 64 * NC;                      // [SL][NC]
+      float* s_inv = s_red + SL * NC;                    // [NC]
+      {
+        const int cc = threadIdx.x % NC, sl = threadIdx.x / NC;
+        constexpr int PER = 64 / SL;                     // chunks per thread (at most 64 chunks)
+        float pmv[PER], plv[PER];
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+          const int ch = sl + u * SL;
+          const int chc = min(ch, n_chunks - 1);
+          pmv[u] = pm[(item0 + chc) * NC + cc];
+          plv[u] = pl[(item0 + chc) * NC + cc];
         }
-        const float inv = 1.f / ll;
-        for (int ch = 0; ch < n_chunks; ++ch) wgt[ch * (JT * 16) + cc] *= inv;
+        float mx = kNegBig;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+          if (sl + u * SL >= n_chunks) { pmv[u] = kNegBig; plv[u] = 0.f; }
+          mx = fmaxf(mx, pmv[u]);
+        }
+        s_red[sl * NC + cc] = mx;
+        __syncthreads();
+        float mm = kNegBig;
+#pragma unroll
+        for (int q = 0; q < SL; ++q) mm = fmaxf(mm, s_red[q * NC + cc]);
+        __syncthreads();
+        float lp = 0.f;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+          const int ch = sl + u * SL;
+          const float w = exp2f(pmv[u] - mm);
+          lp += plv[u] * w;
+          if (ch < n_chunks) wgt[ch * NC + cc] = w;
+        }
+        s_red[sl * NC + cc] = lp;
+        __syncthreads();
+        if (sl == 0) {
+          float ll = 0.f;
+#pragma unroll
+          for (int q = 0; q < SL; ++q) ll += s_red[q * NC + cc];
+          s_inv[cc] = 1.f / ll;
+        }
+        __syncthreads();
       }
-      __syncthreads();
       const float* pg = pO + item0 * (DT * JT) * 64 * 4;
       u16* out = a.ap + (size_t)pc.layer * a.ap_elems;
       for (int idx = wave; idx < DT * JT; idx += kWavesPerWG) {
         const int dt = idx / JT, jt = idx % JT;
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int ch = 0; ch < n_chunks; ++ch)
-          acc += *reinterpret_cast<const f32x4*>(pg + (((size_t)ch * (DT * JT) + idx) * 64 + lane) * 4) *
-                 wgt[ch * (JT * 16) + jt * 16 + col];
+        for (int ch0 = 0; ch0 < n_chunks; ch0 += 8) {
+          f32x4 v[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int chc = min(ch0 + u, n_chunks - 1);
+            v[u] = *reinterpret_cast<const f32x4*>(pg + (((size_t)chc * (DT * JT) + idx) * 64 + lane) * 4);
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            if (ch0 + u < n_chunks) acc += v[u] * wgt[(ch0 + u) * NC + jt * 16 + col];
+        }
+        acc *= s_inv[jt * 16 + col];
         const int cidx = (jg * JT + jt) * 16 + col;
         const int hq = cidx / Mp, m = cidx - hq * Mp;
         if (m < a.M) {
@@ -868,7 +954,7 @@ __global__ __launch_bounds__(kWGThreads, 1) void mega_kernel(MegaArgs a) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ int s_flags[16];
   const MegaPlan& P = a.P;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id in an SGPR: all branches on it are scalar
   if (threadIdx.x == 0) s_flags[0] = (a.st->error == 0);
   __syncthreads();
   if (!s_flags[0]) return;
@@ -881,12 +967,14 @@ __global__ __launch_bounds__(kWGThreads, 1) void mega_kernel(MegaArgs a) {
   unsigned epoch = a.bar_epoch;
 
   Cursor cur;
-  cur.pos = a.wstream + (size_t)(blockIdx.x * kWavesPerWG + wave) * a.P.wave_stride;
+  cur.pos = 0;
   cur.l = 0; cur.p = PH_QKV; cur.c = 0; cur.wg = blockIdx.x; cur.w = wave; cur.want_lm = 0;   // the LM head is its own launch
   bf16x8 ring[kMaxKW][kT];
   {
-    ChunkRef r0 = cur.next(P);
-    load_chunk(ring, r0, lane);
+    const rsrc_t wr = make_rsrc(a.wstream + (size_t)(blockIdx.x * kWavesPerWG + wave) * P.wave_stride,
+                                (unsigned)(P.wave_stride * 16));
+    const ChunkRef r0 = cur.next(P);
+    load_chunk(ring, wr, r0, lane);
   }
   bool alive = true;
   int tsi = 0;
@@ -932,7 +1020,7 @@ __global__ __launch_bounds__(kWGThreads, 1) void lm_kernel(MegaArgs a) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ int s_flags[16];
   const MegaPlan& P = a.P;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id in an SGPR: all branches on it are scalar
   if (threadIdx.x == 0) s_flags[0] = (a.st->error == 0);
   __syncthreads();
   if (!s_flags[0]) return;
@@ -943,13 +1031,14 @@ __global__ __launch_bounds__(kWGThreads, 1) void lm_kernel(MegaArgs a) {
   pc.red = reinterpret_cast<f32x4*>(lds + kWavesPerWG * mega_xh<MT>() * MT * 1024);
   pc.s_flags = s_flags;
   Cursor cur;
-  cur.pos = a.wstream + (size_t)(blockIdx.x * kWavesPerWG + wave) * a.P.wave_stride +
-            (size_t)P.L * wave_layer_units(P, blockIdx.x, wave);
+  cur.pos = (int)((long long)P.L * wave_layer_units(P, blockIdx.x, wave) * 16);
   cur.l = P.L; cur.p = PH_LM; cur.c = 0; cur.wg = blockIdx.x; cur.w = wave; cur.want_lm = 1;
   bf16x8 ring[kMaxKW][kT];
   {
-    ChunkRef r0 = cur.next(P);
-    load_chunk(ring, r0, lane);
+    const rsrc_t wr = make_rsrc(a.wstream + (size_t)(blockIdx.x * kWavesPerWG + wave) * P.wave_stride,
+                                (unsigned)(P.wave_stride * 16));
+    const ChunkRef r0 = cur.next(P);
+    load_chunk(ring, wr, r0, lane);
   }
   gemm_phase<MT, PH_LM>(a, pc, ring, cur, wave, lane);
   if (!grid_barrier(a.bar, a.bar_epoch + 1u, P.nwg, a.st, &s_flags[0])) return;
@@ -982,6 +1071,7 @@ __global__ __launch_bounds__(kWGThreads, 1) void lm_kernel(MegaArgs a) {
 // ---- prologue: block assembly (seed, embedding gather), first sum of squares, rotary table, counters ------------
 struct PrologueArgs {
   float* x0; float* ssq0; int H, Mp;
+  u16* xb0; int MT;
   const float* embeds; int n_embed; const int* ids; int off;
   int* seed_tokens; uint8_t* seed_mask;       // denoise only: position 0 takes the carry if still masked
   const uint8_t* mask; int mask_id; const u16* table; int vocab;
@@ -1028,6 +1118,7 @@ __global__ __launch_bounds__(kWGThreads) void prologue_kernel(PrologueArgs a) {
   for (int c = threadIdx.x; c < a.H; c += kWGThreads) {
     const float v = id < 0 ? a.embeds[(size_t)p * a.H + c] : bf16_bits_to_f32(a.table[(size_t)id * a.H + c]);
     a.x0[(size_t)r * a.H + c] = v;
+    a.xb0[xp_index(r, c, a.MT)] = f32_to_bf16_bits(v);
     ss += v * v;
   }
 #pragma unroll
