@@ -68,7 +68,9 @@ void bd_destroy(bd_ctx* ctx);
  * host_ptr holds the row-major [out_features, in_features] matrix (or the gain vector) in `dtype`:
  * BD_F32 (rounded to bf16 on device), BD_BF16 (raw bits) or, for the seven linears of a
  * BD_FP8_E4M3 context, BD_FP8_E4M3 codes (OCP e4m3fn) with host_scales = one fp32 per output row.
- * Gain vectors are BD_F32.  The call copies synchronously; the caller keeps ownership of host_ptr. */
+ * Gain vectors are BD_F32 and must be loaded before the matrices they feed (attn_norm before wq/wk/wv,
+ * ffn_norm before w_gate/w_up, final_norm before lm_head: the gain is folded into those matrices' columns;
+ * BD_E_STATE otherwise).  The call copies synchronously; the caller keeps ownership of host_ptr. */
 int bd_load_weight(bd_ctx* ctx, const char* name, const void* host_ptr, size_t bytes, int dtype,
                    const float* host_scales);
 

@@ -142,7 +142,9 @@ class Context:
         """Upload every tensor of an inputs.make_weights() dict (matrices as bf16 bit patterns when they are
         already bf16-representable, else as fp32, which the library rounds)."""
         from . import inputs
-        for name, w in weights.items():
+        # gain vectors first: the library folds each into the matrices it feeds
+        order = sorted(weights.items(), key=lambda kv: kv[1].ndim != 1)
+        for name, w in order:
             if name.endswith(".scale"):
                 continue
             if w.dtype == np.uint8:

@@ -429,31 +429,44 @@ int bd_load_weight(bd_ctx* c, const char* name, const void* host_ptr, size_t byt
   }
   // logical shape and where the rows go in the weight stream
   int rows = 0, K = 0, ph = -1, row_base = 0, row_map = 0, bit = -1;
+  int norm_ver = -1;              // residual version whose RMSNorm gain is folded into this matrix
   float* gain_dst = nullptr;
   bool is_embed = false;
   if (layer < 0) {
     if (base == "embed") { rows = c->V; K = c->H; is_embed = true; bit = 0; }
-    else if (base == "lm_head") { rows = c->V; K = c->H; ph = PH_LM; bit = 1; }
+    else if (base == "lm_head") { rows = c->V; K = c->H; ph = PH_LM; bit = 1; norm_ver = 2 * c->L; }
     else if (base == "final_norm") { rows = c->H; gain_dst = c->gains + (size_t)(2 * c->L) * c->H; bit = 2; }
     else return BD_E_ARG;
   } else {
     if (base == "attn_norm") { rows = c->H; gain_dst = c->gains + (size_t)(2 * layer) * c->H; bit = 0; }
     else if (base == "ffn_norm") { rows = c->H; gain_dst = c->gains + (size_t)(2 * layer + 1) * c->H; bit = 1; }
-    else if (base == "wq") { rows = c->QD; K = c->H; ph = PH_QKV; row_base = 0; row_map = 1; bit = 2; }
-    else if (base == "wk") { rows = c->KVD; K = c->H; ph = PH_QKV; row_base = c->QD; row_map = 1; bit = 3; }
-    else if (base == "wv") { rows = c->KVD; K = c->H; ph = PH_QKV; row_base = c->QD + c->KVD; bit = 4; }
+    else if (base == "wq") { rows = c->QD; K = c->H; ph = PH_QKV; row_base = 0; row_map = 1; bit = 2; norm_ver = 2 * layer; }
+    else if (base == "wk") { rows = c->KVD; K = c->H; ph = PH_QKV; row_base = c->QD; row_map = 1; bit = 3; norm_ver = 2 * layer; }
+    else if (base == "wv") { rows = c->KVD; K = c->H; ph = PH_QKV; row_base = c->QD + c->KVD; bit = 4; norm_ver = 2 * layer; }
     else if (base == "wo") { rows = c->H; K = c->QD; ph = PH_O; bit = 5; }
-    else if (base == "w_gate") { rows = c->F; K = c->H; ph = PH_GU; row_base = 0; row_map = 2; bit = 6; }
-    else if (base == "w_up") { rows = c->F; K = c->H; ph = PH_GU; row_base = 1; row_map = 2; bit = 7; }
+    else if (base == "w_gate") { rows = c->F; K = c->H; ph = PH_GU; row_base = 0; row_map = 2; bit = 6; norm_ver = 2 * layer + 1; }
+    else if (base == "w_up") { rows = c->F; K = c->H; ph = PH_GU; row_base = 1; row_map = 2; bit = 7; norm_ver = 2 * layer + 1; }
     else if (base == "w_down") { rows = c->H; K = c->F; ph = PH_DOWN; bit = 8; }
     else return BD_E_ARG;
   }
   if (gain_dst != nullptr) {
     if (dtype != BD_F32) return BD_E_DTYPE;
     if (bytes != (size_t)rows * 4) return BD_E_ARG;
+    {
+      const unsigned used_by = layer < 0 ? 2u : (base == "attn_norm" ? 0x1Cu : 0xC0u);   // lm_head | wq,wk,wv | gate,up
+      if (c->loaded[layer < 0 ? c->L : layer] & used_by) return BD_E_STATE;
+    }
     HIP_TRY(hipMemcpy(gain_dst, host_ptr, bytes, hipMemcpyHostToDevice));
   } else {
     if (dtype != BD_F32 && dtype != BD_BF16) return BD_E_DTYPE;
+    const float* col_gain = nullptr;
+    if (norm_ver >= 0) {
+      // the gain of the norm in front of this matrix is folded into its columns, so it must be here already
+      const bool have = norm_ver == 2 * c->L ? (c->loaded[c->L] & 4u) != 0
+                                             : (c->loaded[norm_ver / 2] & (1u << (norm_ver & 1))) != 0;
+      if (!have) return BD_E_STATE;
+      col_gain = c->gains + (size_t)norm_ver * c->H;
+    }
     const size_t esz = dtype == BD_F32 ? 4 : 2;
     if (bytes != (size_t)rows * K * esz) return BD_E_ARG;
     void* stage = nullptr;
@@ -468,10 +481,10 @@ int bd_load_weight(bd_ctx* c, const char* name, const void* host_ptr, size_t byt
           e = hipMemcpyAsync(c->embed, stage, bytes, hipMemcpyDeviceToDevice, c->stream);
       } else if (dtype == BD_F32) {
         hipLaunchKernelGGL(pack_stream_kernel<float>, dim3(4096), dim3(256), 0, c->stream, (const float*)stage, rows, K,
-                           c->plan, ph, std::max(layer, 0), row_base, row_map, c->D, c->wstream);
+                           c->plan, ph, std::max(layer, 0), row_base, row_map, c->D, col_gain, c->wstream);
       } else {
         hipLaunchKernelGGL(pack_stream_kernel<u16>, dim3(4096), dim3(256), 0, c->stream, (const u16*)stage, rows, K,
-                           c->plan, ph, std::max(layer, 0), row_base, row_map, c->D, c->wstream);
+                           c->plan, ph, std::max(layer, 0), row_base, row_map, c->D, col_gain, c->wstream);
       }
       if (e == hipSuccess) e = hipGetLastError();
       if (e == hipSuccess) e = hipStreamSynchronize(c->stream);

@@ -278,43 +278,12 @@ __device__ inline void load_chunk(bf16x8 (&buf)[kMaxKW][kT], rsrc_t wr, const Ch
 }
 
 // ---- activation fragments ----------------------------------------------------------------------------------
-// RMSNorm on load: rows of the fp32 residual stream are scaled by rsqrt(mean square + eps) (the sum of
-// squares arrives as per-tile partials) and by the gain, rounded to bf16, and laid out as B fragments.
+// RMSNorm around the GEMM: the gain is folded into the weight columns when they are packed, the bf16
+// copy of the residual version is the B operand as it is, and the per-row factor rsqrt(mean square + eps)
+// (from the per-tile partial sums of squares) multiplies the accumulators in the epilogue.
 // The fragments of a wavefront's k-steps are staged in a wavefront-private LDS region ([k-step][mt][lane]),
 // four k-steps per batch (all loads of a batch are in flight together), and read back one k-step at a
 // time.  K-steps the wavefront does not have read as zero.
-template <int MT>
-__device__ inline void stage_x_norm(bf16x8* xs, rsrc_t xr, rsrc_t gr, const float (&rs)[MT], int ks0, int nk, int slots,
-                                    int lane) {
-  const int g = lane >> 4;
-  constexpr int NB = (MT <= 2) ? 8 : 4;                  // k-steps per batch (all their loads in flight together)
-  for (int j0 = 0; j0 < slots; j0 += NB) {
-    f32x4 ga[NB][2];
-    bf16x8 xa[NB][MT];
-#pragma unroll
-    for (int jj = 0; jj < NB; ++jj) {
-      const bool ok = j0 + jj < nk;
-      const int k0 = (ks0 + j0 + jj) * 32 + 8 * g;
-      ga[jj][0] = buf_load_f(gr, ok ? k0 * 4 : kOob);
-      ga[jj][1] = buf_load_f(gr, ok ? k0 * 4 + 16 : kOob);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        xa[jj][mt] = buf_load_b(xr, ok ? (((ks0 + j0 + jj) * MT + mt) * 64 + lane) * 16 : kOob);
-    }
-#pragma unroll
-    for (int jj = 0; jj < NB; ++jj)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        union { bf16x8 v; u16 h[8]; } in, cv;
-        in.v = xa[jj][mt];
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          cv.h[e] = f32_to_bf16_bits(bf16_bits_to_f32(in.h[e]) * rs[mt] * ga[jj][e >> 2][e & 3]);
-        xs[((j0 + jj) * MT + mt) * 64 + lane] = cv.v;
-      }
-  }
-}
-
 template <int MT>
 __device__ inline void stage_x_packed(bf16x8* xs, rsrc_t xr, int ks0, int nk, int slots, int lane) {
   for (int j0 = 0; j0 < slots; j0 += 4) {
@@ -568,8 +537,9 @@ __device__ inline void gemm_phase(const MegaArgs& a, const PhaseCtx& pc, bf16x8 
     const rsrc_t xr = kNorm ? make_rsrc(a.xb + (size_t)ver * a.xb_elems, (unsigned)(a.xb_elems * 2))
                             : (PH == PH_O ? make_rsrc(a.ap + (size_t)pc.layer * a.ap_elems, (unsigned)(a.ap_elems * 2))
                                           : make_rsrc(a.act + (size_t)pc.layer * a.act_elems, (unsigned)(a.act_elems * 2)));
-    const rsrc_t gr = make_rsrc(a.gains + (size_t)ver * P.H, (unsigned)(P.H * 4));
     float rs[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) rs[mt] = 1.f;
     if constexpr (kNorm) {
       const int parts = ver == 0 ? 1 : phase_tile_slots(P, (ver & 1) ? PH_O : PH_DOWN);
       float* s_part = reinterpret_cast<float*>(pc.red);
@@ -578,7 +548,7 @@ __device__ inline void gemm_phase(const MegaArgs& a, const PhaseCtx& pc, bf16x8 
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) rs[mt] = s_rs[mt * 16 + (lane & 15)];
       BD_SUBTS(1);
-      if constexpr (XH == kMaxKW) stage_x_norm<MT>(xs, xr, gr, rs, wp.w0, wp.KW, XH, lane);
+      if constexpr (XH == kMaxKW) stage_x_packed<MT>(xs, xr, wp.w0, wp.KW, XH, lane);
     } else {
       BD_SUBTS(1);
       if constexpr (XH == kMaxKW) stage_x_packed<MT>(xs, xr, wp.w0, wp.KW, XH, lane);
@@ -602,8 +572,7 @@ __device__ inline void gemm_phase(const MegaArgs& a, const PhaseCtx& pc, bf16x8 
         for (int ksl = 0; ksl < kMaxKW; ++ksl) {
           if constexpr (XH < kMaxKW) {
             if (ksl % XH == 0) {
-              if constexpr (kNorm) stage_x_norm<MT>(xs, xr, gr, rs, wp.w0 + ksl, wp.KW - ksl, XH, lane);
-              else stage_x_packed<MT>(xs, xr, wp.w0 + ksl, wp.KW - ksl, XH, lane);
+              stage_x_packed<MT>(xs, xr, wp.w0 + ksl, wp.KW - ksl, XH, lane);
             }
           }
           bf16x8 xk[MT];
@@ -635,6 +604,7 @@ __device__ inline void gemm_phase(const MegaArgs& a, const PhaseCtx& pc, bf16x8 
         v += pc.red[(1 * (kT * MT) + idx) * 64 + lane];
         v += pc.red[(2 * (kT * MT) + idx) * 64 + lane];
         v += pc.red[(3 * (kT * MT) + idx) * 64 + lane];
+        if constexpr (kNorm) v *= rs[mt];              // RMSNorm's per-row factor commutes with the product
         gemm_epilogue<MT, PH>(a, pc, wp, c, t, mt, v, lane, rmax, ridx, rsum);
       }
       __syncthreads();
@@ -1136,7 +1106,8 @@ __global__ __launch_bounds__(kWGThreads) void prologue_kernel(PrologueArgs a) {
 //   2: row_base + 2*r                     (gate: even rows, up: odd rows with row_base = 1)
 template <typename SrcT>
 __global__ void pack_stream_kernel(const SrcT* __restrict__ src, int n_rows, int K, MegaPlan P, int ph, int layer,
-                                   int row_base, int row_map, int D, u16* __restrict__ stream) {
+                                   int row_base, int row_map, int D, const float* __restrict__ col_gain,
+                                   u16* __restrict__ stream) {
   const int KS = P.ph[ph].KS;
   const size_t total = (size_t)n_rows * KS * 4;             // one thread per (row, k-step, k-quarter)
   for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total;
@@ -1172,8 +1143,11 @@ __global__ void pack_stream_kernel(const SrcT* __restrict__ src, int n_rows, int
       const int k = ks * 32 + kq * 8 + e;
       u16 o = 0;
       if (k < K) {
-        if constexpr (sizeof(SrcT) == 4) o = f32_to_bf16_bits(((const float*)src)[(size_t)rs * K + k]);
-        else o = ((const u16*)src)[(size_t)rs * K + k];
+        float f;
+        if constexpr (sizeof(SrcT) == 4) f = ((const float*)src)[(size_t)rs * K + k];
+        else f = bf16_bits_to_f32(((const u16*)src)[(size_t)rs * K + k]);
+        if (col_gain != nullptr) f *= col_gain[k];        // gain of the RMSNorm that feeds this matrix
+        o = f32_to_bf16_bits(f);
       }
       dst[e] = o;
     }
