@@ -343,6 +343,16 @@ def test_block_size_annealing_closed_form():
     assert annealed_block_size(0.19, 32) == 2 and annealed_block_size(0.99, 32) == 32
 
 
+def test_block_size_annealing_golden_table():
+    # hand-evaluated values of the paper's closed form (tests/golden/annealing_schedule.txt)
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "annealing_schedule.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 16
+    for b_max, u, want in rows:
+        assert annealed_block_size(float(u), int(b_max)) == int(want), (b_max, u, want)
+
+
 # ---- planted mistakes must be caught ------------------------------------------------------------------
 
 @pytest.mark.parametrize("mutation", ["rope_sign", "no_gain", "wrong_group", "causal_offbyone", "no_scale"])
