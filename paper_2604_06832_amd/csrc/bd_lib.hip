@@ -18,6 +18,7 @@
 #include "gemm.h"
 #include "mega.h"
 #include "misc.h"
+#include "stream_fwd.h"
 
 using namespace bd;
 
@@ -83,6 +84,7 @@ struct bd_ctx {
   // host mirror of the decode state
   int n = 0;
   bool prefilled = false, carry_valid = false;
+  bool use_stream = true;          // forwards of up to 32 rows run the kernel with decoupled weight streaming
   // per-launch timing (bd_k_profile)
   bool prof_on = false;
   std::vector<hipEvent_t> prof_ev;   // pairs
@@ -200,10 +202,40 @@ int launch_lm(bd_ctx* c, const MegaArgs& a) {
   return check_launch();
 }
 
+// The forward kernel with decoupled weight streaming (stream_fwd.h): block sizes up to 32.
+template <int MT, int D>
+int launch_stream_inst(bd_ctx* c, const MegaArgs& a) {
+  static bool attr_set = false;
+  constexpr int lds = stream_lds_bytes<MT>();
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_fwd_kernel<MT, D>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((stream_fwd_kernel<MT, D>), dim3(c->plan.nwg), dim3(kFwdThreads), lds, c->stream, a);
+  return check_launch();
+}
+
+int stream_attn_max_chunks(const bd_ctx* c, int MT) {
+  const int groups = c->cfg.n_kv_heads * c->G * MT;
+  return std::max(1, std::min(c->num_cus / groups, 64));
+}
+
 template <int MT>
 int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
-  if (c->D == 128) BD_TRY((launch_mega_inst<MT, 128, 2>(c, a)));
-  else BD_TRY((launch_mega_inst<MT, 64, 2>(c, a)));
+  if constexpr (MT <= 2) {
+    if (c->use_stream) {
+      a.attn_max_chunks = stream_attn_max_chunks(c, MT);
+      if (c->D == 128) BD_TRY((launch_stream_inst<MT, 128>(c, a)));
+      else BD_TRY((launch_stream_inst<MT, 64>(c, a)));
+    } else {
+      if (c->D == 128) BD_TRY((launch_mega_inst<MT, 128, 2>(c, a)));
+      else BD_TRY((launch_mega_inst<MT, 64, 2>(c, a)));
+    }
+  } else {
+    if (c->D == 128) BD_TRY((launch_mega_inst<MT, 128, 2>(c, a)));
+    else BD_TRY((launch_mega_inst<MT, 64, 2>(c, a)));
+  }
   c->bar_epoch += 5u * (unsigned)c->L;
   if (a.want_lm) {
     a.bar_epoch = c->bar_epoch;
@@ -339,6 +371,7 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   c->stream = static_cast<hipStream_t>(hip_stream);
   c->device = dev;
   c->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  if (const char* e = getenv("BD_FORWARD_KERNEL")) c->use_stream = strcmp(e, "ring") != 0;
   c->H = k.hidden; c->D = k.head_dim; c->QD = k.n_q_heads * k.head_dim; c->KVD = k.n_kv_heads * k.head_dim;
   c->NQKV = c->QD + 2 * c->KVD; c->F = k.ffn; c->V = k.vocab; c->L = k.n_layers; c->G = k.n_q_heads / k.n_kv_heads;
   c->Mp_max = ceil_div(k.max_block, 16) * 16;
@@ -377,6 +410,11 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
       const int groups = k.n_kv_heads * (c->G * MT / JT);
       tiles = std::max(tiles, (size_t)groups * attn_max_chunks(c, MT, true) * JT);
       groups_max = std::max(groups_max, groups);
+      if (MT <= 2) {   // the streaming kernel works on single column tiles
+        const int sg = k.n_kv_heads * c->G * MT;
+        tiles = std::max(tiles, (size_t)sg * stream_attn_max_chunks(c, MT));
+        groups_max = std::max(groups_max, sg);
+      }
     }
     c->pO_layer_floats = tiles * (c->D / 16) * 64 * 4;
     c->pml_layer_floats = tiles * 16;

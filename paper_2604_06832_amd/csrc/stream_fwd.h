@@ -1,0 +1,744 @@
+// The decoder forward as one persistent kernel with DECOUPLED weight streaming (block sizes up to 32).
+//
+// A block-denoising step at B <= 32 is bound by reading 5.5 GB of layer weights, but its ~180 dependent
+// phases each end in a cross-chip hand-over (stores -> acknowledgement -> grid barrier -> loads) during
+// which a compute wavefront cannot also keep HBM busy.  So every workgroup (one per compute unit) runs
+// two kinds of wavefronts:
+//   * four PRODUCERS, one per consumer, that do nothing but copy their consumer's weight stream from HBM
+//     into a ring of 1-KiB slots in LDS with direct-to-LDS buffer loads (no registers involved).  The
+//     stream is the sequence of 16-row x 32-k MFMA A-operand fragments in exactly the order the consumer
+//     will multiply them, across all phases and layers, so the producer needs no knowledge of the
+//     computation: it runs ahead whenever a slot is free, through barriers and attention phases alike;
+//   * four CONSUMERS that hold the activations of their K range in registers, take weight fragments out
+//     of the ring, multiply, reduce over the four K ranges through LDS, and run the fused epilogues,
+//     the attention phase and the grid barriers.  Their own vector-memory counter only ever tracks the
+//     small latency-critical loads and stores of the hand-over, never the bulk stream.
+// Producer and consumer talk through two LDS words per ring ("landed", "consumed").  Because the producer
+// wavefronts never reach a workgroup barrier, the consumers synchronise among themselves with an LDS
+// arrival counter instead of s_barrier.
+//
+// Weight stream layout, activation buffers, epilogues and the cross-workgroup data discipline (write-once
+// buffers, write-through stores, no cache maintenance inside the kernel) are those of mega.h; the two
+// kernels are interchangeable on the same context.
+#pragma once
+#include "mega.h"
+
+namespace bd {
+
+constexpr int kFwdThreads = 512;      // 4 consumer + 4 producer wavefronts
+constexpr int kSlots = 28;            // 1-KiB ring slots per consumer
+constexpr int kProdBatch = 4;         // fragments a producer issues between two publications
+constexpr int kProdDepth = 6;         // loads it leaves in flight when it publishes
+constexpr int kLdsSpin = 1 << 22;     // bound of every LDS wait (a timed-out wait marks the context broken)
+constexpr int kShareBytes = 40 * 1024;  // K-reduction buffers / attention merge buffers (one region, re-used)
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+// words of the LDS synchronisation block
+enum { SY_LANDED = 0, SY_CONSUMED = 4, SY_DEAD = 8, SY_CBAR = 9, SY_ARRIVE = 10, SY_EPOCH = 11, SY_WORDS = 16 };
+
+__device__ inline unsigned lds_addr(const void* p) {
+  return (unsigned)(size_t)(const __attribute__((address_space(3))) char*)p;
+}
+__device__ inline unsigned lds_ld32(unsigned addr) {
+  unsigned v;
+  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+  return (unsigned)__builtin_amdgcn_readfirstlane((int)v);
+}
+__device__ inline void lds_st32(unsigned addr, unsigned v) {
+  asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+__device__ inline void lds_inc(unsigned addr) {
+  const unsigned one = 1u;
+  asm volatile("ds_add_u32 %0, %1" ::"v"(addr), "v"(one) : "memory");
+}
+
+struct FwdSync {
+  unsigned base;          // LDS address of the synchronisation block
+  unsigned cbar_target;   // arrivals expected at the next consumer barrier
+  unsigned arrive_target; // arrivals expected at the next grid barrier
+  bool dead;              // a wait timed out somewhere in this workgroup: stop waiting, just finish
+};
+
+__device__ inline void mark_dead(FwdSync& sy, DevState* st) {
+  sy.dead = true;
+  lds_st32(sy.base + SY_DEAD * 4, 1u);
+  __hip_atomic_store(&st->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Wait until the LDS word at `addr` has reached `target` (wrap-safe); false on time-out or dead workgroup.
+__device__ inline bool lds_wait_ge(FwdSync& sy, unsigned addr, unsigned target, DevState* st) {
+  if (sy.dead) return false;
+  int spins = 0;
+  while ((int)(lds_ld32(addr) - target) < 0) {
+    if ((++spins & 63) == 0) {
+      if (lds_ld32(sy.base + SY_DEAD * 4) != 0u) { sy.dead = true; return false; }
+      if (spins > kLdsSpin) { mark_dead(sy, st); return false; }
+    }
+  }
+  return true;
+}
+
+// Barrier of the four consumer wavefronts.  LDS operations of one wavefront execute in order, so whatever
+// a wavefront wrote to LDS before its arrival is visible to the others after theirs.
+__device__ inline void cbar(FwdSync& sy, int lane, DevState* st) {
+  sy.cbar_target += kWavesPerWG;
+  if (lane == 0) lds_inc(sy.base + SY_CBAR * 4);
+  lds_wait_ge(sy, sy.base + SY_CBAR * 4, sy.cbar_target, st);
+  asm volatile("" ::: "memory");
+}
+
+// ---- producer ----------------------------------------------------------------------------------------------
+__device__ inline void producer_loop(const MegaArgs& a, int cw, char* ring, unsigned sync_base, int lane) {
+  const MegaPlan& P = a.P;
+  const rsrc_t wr = make_rsrc(a.wstream + (size_t)(blockIdx.x * kWavesPerWG + cw) * P.wave_stride,
+                              (unsigned)(P.wave_stride * 16));
+  const unsigned landed_addr = sync_base + (SY_LANDED + cw) * 4;
+  const unsigned consumed_addr = sync_base + (SY_CONSUMED + cw) * 4;
+  const unsigned dead_addr = sync_base + SY_DEAD * 4;
+  Cursor cur;
+  cur.pos = 0; cur.l = 0; cur.p = PH_QKV; cur.c = 0; cur.wg = blockIdx.x; cur.w = cw; cur.want_lm = 0;
+  unsigned issued = 0, landed = 0, consumed = 0;
+  int slot = 0, since = 0;
+  bool ok = true;
+  for (ChunkRef r = cur.next(P); r.KW > 0 && ok; r = cur.next(P)) {
+    const ChunkLane cl = chunk_lane(r, lane);
+    const int nt = r.R1 > 0 ? 2 : 1;
+    for (int ksl = 0; ksl < r.KW && ok; ++ksl) {
+      for (int t = 0; t < nt; ++t) {
+        if (issued - consumed >= (unsigned)kSlots) {
+          // ring full: publish everything that is under way, then wait for the consumer
+          if (landed != issued) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            landed = issued;
+            lds_st32(landed_addr, landed);
+            since = 0;
+          }
+          int spins = 0;
+          while (issued - (consumed = lds_ld32(consumed_addr)) >= (unsigned)kSlots) {
+            __builtin_amdgcn_s_sleep(1);
+            if ((++spins & 31) == 0 && (lds_ld32(dead_addr) != 0u || spins > kLdsSpin)) { ok = false; break; }
+          }
+          if (!ok) break;
+        }
+        const int voff = (t ? cl.o1 : cl.o0) + ksl * cl.step;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (lds_void_t*)(ring + slot * 1024), 16, voff, 0, 0, kAuxNt);
+        ++issued;
+        slot = (slot + 1 == kSlots) ? 0 : slot + 1;
+        if (++since == kProdBatch) {
+          since = 0;
+          asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kProdDepth) : "memory");   // all but the newest kProdDepth are in LDS
+          if (issued > (unsigned)kProdDepth && (int)(issued - kProdDepth - landed) > 0) {
+            landed = issued - kProdDepth;
+            lds_st32(landed_addr, landed);
+          }
+        }
+      }
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  lds_st32(landed_addr, issued);
+}
+
+// ---- consumer side of the ring -------------------------------------------------------------------------------
+struct Ring {
+  const char* base;        // this consumer's slots
+  unsigned landed_addr, consumed_addr;
+  unsigned have;           // fragments known to have landed
+  unsigned taken;          // fragments consumed so far
+  int slot;
+};
+
+__device__ inline void ring_need(Ring& rg, FwdSync& sy, int nf, DevState* st) {
+  const unsigned need = rg.taken + (unsigned)nf;
+  if ((int)(rg.have - need) < 0 && !sy.dead) {
+    int spins = 0;
+    while ((int)((rg.have = lds_ld32(rg.landed_addr)) - need) < 0) {
+      if ((++spins & 63) == 0) {
+        if (lds_ld32(sy.base + SY_DEAD * 4) != 0u) { sy.dead = true; break; }
+        if (spins > kLdsSpin) { mark_dead(sy, st); break; }
+      }
+    }
+  }
+  asm volatile("" ::: "memory");
+}
+__device__ inline bf16x8 ring_take(Ring& rg, int lane) {
+  const bf16x8 v = *reinterpret_cast<const bf16x8*>(rg.base + rg.slot * 1024 + lane * 16);
+  rg.slot = (rg.slot + 1 == kSlots) ? 0 : rg.slot + 1;
+  ++rg.taken;
+  return v;
+}
+__device__ inline void ring_release(Ring& rg) { lds_st32(rg.consumed_addr, rg.taken); }
+
+// One chunk (one or two 16-row tiles x KW k-steps) out of the ring.
+template <int MT, bool TWO>
+__device__ inline void consume_chunk(Ring& rg, FwdSync& sy, DevState* st, const bf16x8 (&xk)[kMaxKW][MT], int KW,
+                                     f32x4 (&acc)[kT][MT], int lane) {
+#pragma unroll
+  for (int kb = 0; kb < kMaxKW; kb += 4) {
+    if (kb < KW) {
+      const int nk = min(4, KW - kb);
+      ring_need(rg, sy, nk * (TWO ? 2 : 1), st);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (u < nk) {
+          const bf16x8 a0 = ring_take(rg, lane);
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, xk[kb + u][mt], acc[0][mt], 0, 0, 0);
+          if constexpr (TWO) {
+            const bf16x8 a1 = ring_take(rg, lane);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, xk[kb + u][mt], acc[1][mt], 0, 0, 0);
+          }
+        }
+      }
+      ring_release(rg);
+    }
+  }
+}
+
+struct FwdCtx {
+  PhaseCtx pc;            // layer, n, red (LDS), s_flags
+  f32x4* red2;            // second K-reduction buffer (chunks alternate)
+  float* s_part;          // LDS [4][64] partial sums of squares per consumer
+  char* share;            // LDS region shared by the K-reduction and the attention merge
+};
+
+// ---- one GEMM phase (consumer wavefronts) ------------------------------------------------------------------------
+template <int MT, int PH>
+__device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg, FwdSync& sy, int wave, int lane_in) {
+  int lane = lane_in;
+  asm volatile("" : "+v"(lane));
+  const MegaPlan& P = a.P;
+  PhaseCtx& pc = fc.pc;
+  const WavePhase wp = wave_phase(P, PH, blockIdx.x, wave);
+  const int n_tiles = (wp.rows + 15) >> 4;
+  const int n_chunks = (n_tiles + 1) >> 1;
+  float rmax[MT], rsum[MT];
+  int ridx[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) { rmax[mt] = -INFINITY; ridx[mt] = 0x7FFFFFFF; rsum[mt] = 0.f; }
+
+  if (n_chunks > 0) {
+    constexpr bool kNorm = (PH == PH_QKV || PH == PH_GU || PH == PH_LM);
+    const int ver = (PH == PH_QKV) ? 2 * pc.layer : (PH == PH_GU) ? 2 * pc.layer + 1 : 2 * P.L;
+    const rsrc_t xr = kNorm ? make_rsrc(a.xb + (size_t)ver * a.xb_elems, (unsigned)(a.xb_elems * 2))
+                            : (PH == PH_O ? make_rsrc(a.ap + (size_t)pc.layer * a.ap_elems, (unsigned)(a.ap_elems * 2))
+                                          : make_rsrc(a.act + (size_t)pc.layer * a.act_elems, (unsigned)(a.act_elems * 2)));
+    // activation fragments of this wavefront's k-steps: one round trip, straight into registers
+    bf16x8 xk[kMaxKW][MT];
+#pragma unroll
+    for (int ksl = 0; ksl < kMaxKW; ++ksl)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        xk[ksl][mt] = buf_load_b(xr, ksl < wp.KW ? (((wp.w0 + ksl) * MT + mt) * 64 + lane) * 16 : kOob);
+    if constexpr (kNorm) {
+      // this wavefront's share (parts = wave*4 + lane group mod 16) of the sums of squares of every row
+      const int parts = ver == 0 ? 1 : phase_tile_slots(P, (ver & 1) ? PH_O : PH_DOWN);
+      const rsrc_t sr = make_rsrc(a.ssq + (size_t)ver * a.ssq_parts * a.Mp, (unsigned)((size_t)parts * a.Mp * 4));
+      const int col = lane & 15, g = lane >> 4;
+      float sv[MT][16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int p = wave * 4 + g + 16 * u;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          sv[mt][u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                    sr, p < parts ? (p * a.Mp + mt * 16 + col) * 4 : kOob, 0, 0));
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        float s = 0.f;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) s += sv[mt][u];
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        if (g == 0) fc.s_part[wave * 64 + mt * 16 + col] = s;
+      }
+    }
+    float rs[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) rs[mt] = 1.f;
+
+    for (int c = 0; c < n_chunks; ++c) {
+      const bool two = 2 * c + 1 < n_tiles;
+      f32x4 acc[kT][MT];
+#pragma unroll
+      for (int t = 0; t < kT; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[t][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (wp.KW > 0) {
+        if (two) consume_chunk<MT, true>(rg, sy, a.st, xk, wp.KW, acc, lane);
+        else consume_chunk<MT, false>(rg, sy, a.st, xk, wp.KW, acc, lane);
+      }
+      // the four consumers hold disjoint K ranges: sum them through LDS in fixed order
+      f32x4* red = (c & 1) ? fc.red2 : pc.red;
+#pragma unroll
+      for (int t = 0; t < kT; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) red[(wave * (kT * MT) + t * MT + mt) * 64 + lane] = acc[t][mt];
+      cbar(sy, lane, a.st);
+      if constexpr (kNorm) {
+        if (c == 0) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const int r = mt * 16 + (lane & 15);
+            const float t = fc.s_part[r] + fc.s_part[64 + r] + fc.s_part[128 + r] + fc.s_part[192 + r];
+            rs[mt] = rsqrtf(t / (float)P.H + a.rms_eps);
+          }
+        }
+      }
+#pragma unroll
+      for (int idx = 0; idx < kT * MT; ++idx) {
+        if ((idx & 3) != wave) continue;
+        const int t = idx / MT, mt = idx % MT;
+        if (t == 1 && !two) continue;
+        f32x4 v = red[(0 * (kT * MT) + idx) * 64 + lane];
+        v += red[(1 * (kT * MT) + idx) * 64 + lane];
+        v += red[(2 * (kT * MT) + idx) * 64 + lane];
+        v += red[(3 * (kT * MT) + idx) * 64 + lane];
+        if constexpr (kNorm) v *= rs[mt];
+        gemm_epilogue<MT, PH>(a, pc, wp, c, t, mt, v, lane, rmax, ridx, rsum);
+      }
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this wavefront's stores have been acknowledged
+
+  if constexpr (PH == PH_DOWN) {
+    // the last of the ksplit workgroups to finish a tile sums all partials, adds the residual, stores the new
+    // residual version and its sum of squares
+    const int ksplit = P.ph[PH_DOWN].ksplit;
+    const int tiles = phase_tile_slots(P, PH_DOWN);
+    const int my_tiles = (wp.rows + 15) >> 4;
+    const int gt0 = wp.ng * phase_tpg(P.ph[PH_DOWN]);
+    cbar(sy, lane, a.st);                                    // every consumer's partials are out
+    if (wave == 0 && lane < my_tiles) {
+      int last = 1;
+      if (ksplit > 1) {
+        const unsigned old = __hip_atomic_fetch_add(a.cntD + (size_t)pc.layer * tiles + gt0 + lane, 1u, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+        last = old == (unsigned)ksplit - 1u;
+      }
+      pc.s_flags[8 + lane] = last;
+    }
+    cbar(sy, lane, a.st);
+    const int col = lane & 15, g = lane >> 4;
+    const int ver = 2 * pc.layer + 2;
+    for (int idx = wave; idx < my_tiles * MT; idx += kWavesPerWG) {
+      const int tl = idx / MT, mt = idx % MT;
+      if (!pc.s_flags[8 + tl]) continue;
+      const int gt = gt0 + tl;
+      const float* src = a.wsD + (size_t)pc.layer * a.wsD_layer_floats;
+      f32x4 pv[8];
+      f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int kg0 = 0; kg0 < ksplit; kg0 += 8) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int kg = min(kg0 + u, ksplit - 1);
+          pv[u] = *reinterpret_cast<const f32x4*>(src + ((((size_t)kg * tiles + gt) * a.MT + mt) * 64 + lane) * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (kg0 + u < ksplit) v += pv[u];
+      }
+      const int token = mt * 16 + col;
+      const int lr = tl * 16 + 4 * g;
+      const int r = wp.row0 + lr;
+      const int nrows = min(4, wp.rows - lr);
+      float ss = 0.f;
+      if (token < a.M && nrows > 0) {
+        const float* xo = a.xv + ((size_t)(ver - 1) * a.Mp + token) * P.H + r;
+        float* xn = a.xv + ((size_t)ver * a.Mp + token) * P.H + r;
+        float o[4] = {0.f, 0.f, 0.f, 0.f};
+        if (nrows == 4 && (r & 3) == 0) {
+          const f32x4 ov = *reinterpret_cast<const f32x4*>(xo) + v;
+          st_wt_f32x4(xn, ov);
+          for (int e = 0; e < 4; ++e) o[e] = ov[e];
+        } else {
+          for (int e = 0; e < nrows; ++e) { o[e] = xo[e] + v[e]; st_wt_f32(xn + e, o[e]); }
+        }
+        store_xb(a.xb + (size_t)ver * a.xb_elems, token, r, nrows, o, a.MT);
+        ss = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
+      }
+      ss += __shfl_xor(ss, 16);
+      ss += __shfl_xor(ss, 32);
+      if (g == 0) st_wt_f32(a.ssq + ((size_t)ver * a.ssq_parts + gt) * a.Mp + token, ss);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+}
+
+// ---- attention phase ------------------------------------------------------------------------------------------
+// Items (kv head, 16-column tile of (head, token) columns, key chunk).  The four consumers of a workgroup take
+// the key blocks of the chunk round-robin, each with its own online softmax, and merge through LDS.  With a
+// single chunk (short contexts) the merged result is final and goes straight out; otherwise the partial is
+// stored and the workgroup completing the last chunk of a tile merges all chunks in fixed order.
+__device__ inline void stream_attn_chunks(int n_keys, int max_chunks, int& n_kb, int& chunk_len, int& n_chunks) {
+  n_kb = (n_keys + 31) >> 5;
+  int want = n_kb <= 96 ? 1 : (n_kb + 39) / 40;
+  if (want > max_chunks) want = max_chunks;
+  chunk_len = ((n_kb + want - 1) / want + 3) & ~3;
+  n_chunks = (n_kb + chunk_len - 1) / chunk_len;
+}
+
+template <int D>
+__device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, FwdSync& sy, int wave, int lane_in) {
+  constexpr int DS = D / 32, DT = D / 16;
+  int lane = lane_in;
+  asm volatile("" : "+v"(lane));
+  const MegaPlan& P = a.P;
+  const PhaseCtx& pc = fc.pc;
+  f32x4* sO = reinterpret_cast<f32x4*>(fc.share);                        // [4][DT][64]
+  float* sm = reinterpret_cast<float*>(fc.share + kWavesPerWG * DT * 1024);   // [4][16]
+  float* sl = sm + kWavesPerWG * 16;                                     // [4][16]
+  float* wgt = sl + kWavesPerWG * 16;                                    // [64 chunks][16]
+  float* s_inv = wgt + 64 * 16;                                          // [16]
+
+  const int col = lane & 15, g = lane >> 4;
+  const int n = pc.n;
+  const int G = P.n_q / P.n_kv;
+  const int Mp = a.MT * 16;
+  const int n_ct = G * a.MT;                                             // column tiles per kv head
+  int n_kb, chunk_len, n_chunks;
+  stream_attn_chunks(n + a.M, a.attn_max_chunks, n_kb, chunk_len, n_chunks);
+  const int n_groups = P.n_kv * n_ct;
+  const int n_items = n_groups * n_chunks;
+  const size_t kv_block = (size_t)32 * D / 8;
+  const u16* Qb = a.Q + (size_t)pc.layer * a.Mp * P.n_q * D;
+  float* pO = a.pO + (size_t)pc.layer * a.pO_layer_floats;
+  float* pm = a.pm + (size_t)pc.layer * a.pml_layer_floats;
+  float* pl = a.pl + (size_t)pc.layer * a.pml_layer_floats;
+  u16* out = a.ap + (size_t)pc.layer * a.ap_elems;
+
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const int chunk = item % n_chunks;
+    const int grp = item / n_chunks;
+    const int ct = grp % n_ct, kvh = grp / n_ct;
+    const bf16x8* Kh = reinterpret_cast<const bf16x8*>(a.Kc + (size_t)pc.layer * a.kv_layer_elems) + (size_t)kvh * a.max_kb * kv_block;
+    const bf16x8* Vh = reinterpret_cast<const bf16x8*>(a.Vc + (size_t)pc.layer * a.kv_layer_elems) + (size_t)kvh * a.max_kb * kv_block;
+    const int cidx = ct * 16 + col;
+    const int hq = cidx / Mp, row = cidx - hq * Mp;
+    bf16x8 qf[DS];
+    {
+      const u16* qp = Qb + ((size_t)row * P.n_q + kvh * G + hq) * D + 8 * g;
+#pragma unroll
+      for (int ds = 0; ds < DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8*>(qp + ds * 32);
+    }
+    f32x4 O[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mrun = kNegBig, lrun = 0.f;
+    const int kb_end = min(n_kb, (chunk + 1) * chunk_len);
+    int kb = chunk * chunk_len + wave;
+    bf16x8 kf[2][DS], vf[DT];
+    if (kb < kb_end) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) kf[t][ds] = Kh[(((size_t)kb * 2 + t) * DS + ds) * 64 + lane];
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) vf[dt] = Vh[((size_t)kb * DT + dt) * 64 + lane];
+    }
+    for (; kb < kb_end; kb += kWavesPerWG) {
+      // next block's operands are requested before this block is worked on
+      bf16x8 kn[2][DS], vn[DT];
+      const int kbn = kb + kWavesPerWG;
+      if (kbn < kb_end) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int ds = 0; ds < DS; ++ds) kn[t][ds] = Kh[(((size_t)kbn * 2 + t) * DS + ds) * 64 + lane];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) vn[dt] = Vh[((size_t)kbn * DT + dt) * 64 + lane];
+      }
+      f32x4 s[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ds = 0; ds < DS; ++ds) s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][ds], qf[ds], s[t], 0, 0, 0);
+      }
+      const bool need_mask = (kb * 32 + 31) >= n;
+      float v[8];
+      bool vis[8];
+      float cmax = kNegBig;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        v[e] = s[e >> 2][e & 3] * a.scale_log2e;
+        vis[e] = true;
+        if (need_mask) {
+          const int jb = kb * 32 + 8 * g + e - n;
+          vis[e] = (jb < 0) || (jb < a.M && (a.mode == 0 || jb <= row));
+        }
+        if (vis[e]) cmax = fmaxf(cmax, v[e]);
+      }
+      cmax = fmaxf(cmax, __shfl_xor(cmax, 16));
+      cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
+      const float mnew = fmaxf(mrun, cmax);
+      const float alpha = exp2f(mrun - mnew);
+      float psum = 0.f;
+      union { bf16x8 v8; u16 h[8]; } cv;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float p = vis[e] ? exp2f(v[e] - mnew) : 0.f;
+        psum += p;
+        cv.h[e] = f32_to_bf16_bits(p);
+      }
+      psum += __shfl_xor(psum, 16);
+      psum += __shfl_xor(psum, 32);
+      lrun = lrun * alpha + psum;
+      mrun = mnew;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        O[dt] *= alpha;
+        O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], cv.v8, O[dt], 0, 0, 0);
+      }
+      if (kbn < kb_end) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int ds = 0; ds < DS; ++ds) kf[t][ds] = kn[t][ds];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) vf[dt] = vn[dt];
+      }
+    }
+    // merge the four consumers: everyone publishes (max, sum, O), then each folds a share of the d tiles
+    if (g == 0) {
+      sm[wave * 16 + col] = mrun;
+      sl[wave * 16 + col] = lrun;
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) sO[(wave * DT + dt) * 64 + lane] = O[dt];
+    cbar(sy, lane, a.st);
+    float mm = sm[col];
+#pragma unroll
+    for (int w = 1; w < kWavesPerWG; ++w) mm = fmaxf(mm, sm[w * 16 + col]);
+    float f[kWavesPerWG];
+    float ll = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWavesPerWG; ++w) {
+      f[w] = exp2f(sm[w * 16 + col] - mm);
+      ll += sl[w * 16 + col] * f[w];
+    }
+    if (n_chunks == 1) {
+      const float inv = 1.f / ll;
+      for (int dt = wave; dt < DT; dt += kWavesPerWG) {
+        f32x4 acc = sO[(0 * DT + dt) * 64 + lane] * f[0];
+#pragma unroll
+        for (int w = 1; w < kWavesPerWG; ++w) acc += sO[(w * DT + dt) * 64 + lane] * f[w];
+        acc *= inv;
+        if (row < a.M) {
+          const int fo = (kvh * G + hq) * D + dt * 16 + 4 * g;
+          const uint32_t lo = (uint32_t)f32_to_bf16_bits(acc[0]) | ((uint32_t)f32_to_bf16_bits(acc[1]) << 16);
+          const uint32_t hi = (uint32_t)f32_to_bf16_bits(acc[2]) | ((uint32_t)f32_to_bf16_bits(acc[3]) << 16);
+          st_wt_u64(out + xp_index(row, fo, a.MT), (uint64_t)lo | ((uint64_t)hi << 32));
+        }
+      }
+      cbar(sy, lane, a.st);                                   // the merge buffers are free again
+      continue;
+    }
+    float* po = pO + (size_t)item * DT * 64 * 4;
+    for (int dt = wave; dt < DT; dt += kWavesPerWG) {
+      f32x4 acc = sO[(0 * DT + dt) * 64 + lane] * f[0];
+#pragma unroll
+      for (int w = 1; w < kWavesPerWG; ++w) acc += sO[(w * DT + dt) * 64 + lane] * f[w];
+      st_wt_f32x4(po + ((size_t)dt * 64 + lane) * 4, acc);
+    }
+    if (wave == 0 && g == 0) {
+      st_wt_f32(pm + (size_t)item * 16 + col, mm);
+      st_wt_f32(pl + (size_t)item * 16 + col, ll);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    cbar(sy, lane, a.st);
+    if (wave == 0 && lane == 0) {
+      const unsigned old = __hip_atomic_fetch_add(a.cntA + (size_t)pc.layer * n_groups + grp, 1u, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+      fc.pc.s_flags[4] = old == (unsigned)n_chunks - 1u;
+    }
+    cbar(sy, lane, a.st);
+    if (fc.pc.s_flags[4]) {
+      // last arriver of this (kv head, column tile): merge all chunks in fixed order
+      const size_t item0 = (size_t)grp * n_chunks;
+      if (wave == 0) {
+        // lane (col, g) looks at chunks g, g+4, ...; at most 64 chunks
+        float pmv[16], plv[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          const int ch = g + 4 * u;
+          const int chc = min(ch, n_chunks - 1);
+          pmv[u] = pm[(item0 + chc) * 16 + col];
+          plv[u] = pl[(item0 + chc) * 16 + col];
+        }
+        float mx = kNegBig;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          if (g + 4 * u >= n_chunks) { pmv[u] = kNegBig; plv[u] = 0.f; }
+          mx = fmaxf(mx, pmv[u]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        float lp = 0.f;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          const int ch = g + 4 * u;
+          const float w = exp2f(pmv[u] - mx);
+          lp += plv[u] * w;
+          if (ch < n_chunks) wgt[ch * 16 + col] = w;
+        }
+        lp += __shfl_xor(lp, 16);
+        lp += __shfl_xor(lp, 32);
+        if (g == 0) s_inv[col] = 1.f / lp;
+      }
+      cbar(sy, lane, a.st);
+      const float* pg = pO + item0 * DT * 64 * 4;
+      for (int dt = wave; dt < DT; dt += kWavesPerWG) {
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int ch0 = 0; ch0 < n_chunks; ch0 += 8) {
+          f32x4 pv[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int chc = min(ch0 + u, n_chunks - 1);
+            pv[u] = *reinterpret_cast<const f32x4*>(pg + (((size_t)chc * DT + dt) * 64 + lane) * 4);
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            if (ch0 + u < n_chunks) acc += pv[u] * wgt[(ch0 + u) * 16 + col];
+        }
+        acc *= s_inv[col];
+        if (row < a.M) {
+          const int fo = (kvh * G + hq) * D + dt * 16 + 4 * g;
+          const uint32_t lo = (uint32_t)f32_to_bf16_bits(acc[0]) | ((uint32_t)f32_to_bf16_bits(acc[1]) << 16);
+          const uint32_t hi = (uint32_t)f32_to_bf16_bits(acc[2]) | ((uint32_t)f32_to_bf16_bits(acc[3]) << 16);
+          st_wt_u64(out + xp_index(row, fo, a.MT), (uint64_t)lo | ((uint64_t)hi << 32));
+        }
+      }
+    }
+    cbar(sy, lane, a.st);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// ---- grid barrier of the consumer wavefronts ---------------------------------------------------------------------
+// Every consumer has waited for its own stores; consumer 0 collects the four arrivals, takes part in the
+// chip-wide barrier (two-level counters of mega.h) and hands the new epoch to the others through LDS.
+__device__ inline bool stream_grid_barrier(const MegaArgs& a, FwdSync& sy, unsigned epoch, int wave, int lane) {
+  const int nwg = a.P.nwg;
+  sy.arrive_target += kWavesPerWG;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if (lane == 0) lds_inc(sy.base + SY_ARRIVE * 4);
+  if (wave == 0) {
+    bool ok = lds_wait_ge(sy, sy.base + SY_ARRIVE * 4, sy.arrive_target, a.st);
+    if (ok && lane == 0) {
+      const int ng = (nwg + kBarGroup - 1) / kBarGroup;
+      const int g = blockIdx.x / kBarGroup;
+      const int gsize = min(kBarGroup, nwg - g * kBarGroup);
+      unsigned* gcnt = a.bar + 32 * (1 + g);
+      unsigned* rel = a.bar + 32 * (1 + ng);
+      const unsigned old = __hip_atomic_fetch_add(gcnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old == epoch * (unsigned)gsize - 1u) {
+        const unsigned o2 = __hip_atomic_fetch_add(a.bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (o2 == epoch * (unsigned)ng - 1u)
+          for (int r = 0; r < ng; ++r) __hip_atomic_store(rel + 32 * r, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      const unsigned* mine = rel + 32 * g;
+      int spins = 0;
+      while ((int)(__hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) < 0) {
+        if (++spins > kSpinLimit) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(1);
+      }
+      if (ok) lds_st32(sy.base + SY_EPOCH * 4, epoch);
+      else {
+        lds_st32(sy.base + SY_DEAD * 4, 1u);
+        __hip_atomic_store(&a.st->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
+  const bool ok = lds_wait_ge(sy, sy.base + SY_EPOCH * 4, epoch, a.st);
+  asm volatile("" ::: "memory");
+  return ok;
+}
+
+// ---- the kernel ------------------------------------------------------------------------------------------------
+template <int MT> constexpr int stream_lds_bytes() { return kWavesPerWG * kSlots * 1024 + kShareBytes; }
+
+template <int MT, int D>
+__global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) {
+  static_assert(2 * kWavesPerWG * kT * MT * 1024 <= kShareBytes, "K-reduction buffers exceed the shared region");
+  static_assert(kWavesPerWG * (D / 16) * 1024 + (8 * 16 + 64 * 16 + 16) * 4 <= kShareBytes, "attention merge buffers exceed the shared region");
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  __shared__ unsigned s_sync[SY_WORDS];
+  __shared__ int s_flags[16];
+  __shared__ float s_part[kWavesPerWG * 64];
+  const MegaPlan& P = a.P;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (threadIdx.x < SY_WORDS) s_sync[threadIdx.x] = 0u;
+  if (threadIdx.x == 0) s_flags[0] = (a.st->error == 0);
+  __syncthreads();                                       // the only workgroup barrier: all eight wavefronts are still here
+  if (!s_flags[0]) return;
+  const unsigned sync_base = lds_addr(s_sync);
+
+  if (wave >= kWavesPerWG) {
+    const int cw = wave - kWavesPerWG;
+    producer_loop(a, cw, lds + cw * kSlots * 1024, sync_base, lane);
+    return;
+  }
+
+  FwdSync sy;
+  sy.base = sync_base; sy.cbar_target = 0u; sy.arrive_target = 0u; sy.dead = false;
+  Ring rg;
+  rg.base = lds + wave * kSlots * 1024;
+  rg.landed_addr = sync_base + (SY_LANDED + wave) * 4;
+  rg.consumed_addr = sync_base + (SY_CONSUMED + wave) * 4;
+  rg.have = 0u; rg.taken = 0u; rg.slot = 0;
+  FwdCtx fc;
+  fc.share = lds + kWavesPerWG * kSlots * 1024;
+  fc.pc.n = a.st->n;
+  fc.pc.xstage = nullptr;
+  fc.pc.red = reinterpret_cast<f32x4*>(fc.share);
+  fc.red2 = fc.pc.red + kWavesPerWG * kT * MT * 64;
+  fc.pc.s_flags = s_flags;
+  fc.s_part = s_part;
+  unsigned epoch = a.bar_epoch;
+
+  int tsi = 0;
+#define BD_TS2()                                                                                                  \
+  do {                                                                                                            \
+    if (a.trace != nullptr && threadIdx.x == 0) a.trace[(size_t)blockIdx.x * (10 * P.L + 4) + tsi] = wall_clock64(); \
+    ++tsi;                                                                                                        \
+  } while (0)
+  BD_TS2();
+  bool alive = true;
+  for (int l = 0; l < P.L && alive; ++l) {
+    fc.pc.layer = l;
+    stream_gemm_phase<MT, PH_QKV>(a, fc, rg, sy, wave, lane);
+    BD_TS2();
+    alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
+    BD_TS2();
+    if (!alive) break;
+    stream_attention_phase<D>(a, fc, sy, wave, lane);
+    BD_TS2();
+    alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
+    BD_TS2();
+    if (!alive) break;
+    stream_gemm_phase<MT, PH_O>(a, fc, rg, sy, wave, lane);
+    BD_TS2();
+    alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
+    BD_TS2();
+    if (!alive) break;
+    stream_gemm_phase<MT, PH_GU>(a, fc, rg, sy, wave, lane);
+    BD_TS2();
+    alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
+    BD_TS2();
+    if (!alive) break;
+    stream_gemm_phase<MT, PH_DOWN>(a, fc, rg, sy, wave, lane);
+    BD_TS2();
+    alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
+    BD_TS2();
+  }
+  if (!alive && lane == 0) lds_st32(sync_base + SY_DEAD * 4, 1u);   // let the producers go
+#undef BD_TS2
+}
+
+}  // namespace bd
