@@ -223,20 +223,20 @@ int stream_attn_max_chunks(const bd_ctx* c, int MT) {
 
 template <int MT>
 int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
-  if constexpr (MT <= 2) {
-    if (c->use_stream) {
+  bool streamed = false;
+  if constexpr (MT <= 2) streamed = c->use_stream;
+  if (streamed) {
+    if constexpr (MT <= 2) {
       a.attn_max_chunks = stream_attn_max_chunks(c, MT);
       if (c->D == 128) BD_TRY((launch_stream_inst<MT, 128>(c, a)));
       else BD_TRY((launch_stream_inst<MT, 64>(c, a)));
-    } else {
-      if (c->D == 128) BD_TRY((launch_mega_inst<MT, 128, 2>(c, a)));
-      else BD_TRY((launch_mega_inst<MT, 64, 2>(c, a)));
+      c->bar_epoch += 5u * (unsigned)c->L;
     }
   } else {
     if (c->D == 128) BD_TRY((launch_mega_inst<MT, 128, 2>(c, a)));
     else BD_TRY((launch_mega_inst<MT, 64, 2>(c, a)));
+    c->bar_epoch += 5u * (unsigned)c->L;
   }
-  c->bar_epoch += 5u * (unsigned)c->L;
   if (a.want_lm) {
     a.bar_epoch = c->bar_epoch;
     BD_TRY(launch_lm<MT>(c, a));

@@ -319,9 +319,18 @@ struct PhaseCtx {
   int* s_flags;             // LDS scratch ints
 };
 
-template <int MT, int PH>
+// Epilogue operands a caller may have fetched ahead of the product (use_pre false: the epilogue loads them itself).
+struct EpiPre {
+  float2 cs[2];   // QKV: (cos, sin) of this lane's two rotary pairs
+  f32x4 xo;       // O: the four residual values this lane adds to
+};
+
+// DC: head dimension when the caller knows it at compile time (0: taken from the plan).
+// USE_PRE: `pre` holds this element's operands.  Either way every load of the epilogue is issued before its
+// first store: a load behind a write-through store would have to wait for that store's acknowledgement.
+template <int MT, int PH, int DC = 0, bool USE_PRE = false>
 __device__ inline void gemm_epilogue(const MegaArgs& a, const PhaseCtx& pc, const WavePhase& wp, int c, int t, int mt, f32x4 v, int lane,
-                                     float (&rmax)[MT], int (&ridx)[MT], float (&rsum)[MT]) {
+                                     float (&rmax)[MT], int (&ridx)[MT], float (&rsum)[MT], const EpiPre pre = EpiPre{}) {
   const MegaPlan& P = a.P;
   const int col = lane & 15, g = lane >> 4;
   const int token = mt * 16 + col;
@@ -331,8 +340,18 @@ __device__ inline void gemm_epilogue(const MegaArgs& a, const PhaseCtx& pc, cons
   const int nrows = min(4, wp.rows - lr);                 // ... so the last lane group may hold just 2 valid rows
   if constexpr (PH == PH_QKV) {
     if (!live) return;
-    const int D = P.D, half = D >> 1;
+    const int D = DC ? DC : P.D, half = D >> 1;
     const int key = pc.n + token;
+    float2 csv[2];
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+      if constexpr (USE_PRE) {
+        csv[pr] = pre.cs[pr];
+      } else {
+        const int rp = r + 2 * pr;
+        csv[pr] = (2 * pr < nrows && rp < P.QD + P.KVD) ? a.rope[(size_t)token * half + ((rp % D) >> 1)] : make_float2(0.f, 0.f);
+      }
+    }
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) {
       if (2 * pr >= nrows) break;
@@ -340,7 +359,7 @@ __device__ inline void gemm_epilogue(const MegaArgs& a, const PhaseCtx& pc, cons
       if (rp < P.QD + P.KVD) {
         // rotary pair: phase rows (2i, 2i+1) of a head hold dims (i, i + D/2)
         const int dp = rp % D;
-        const float2 cs = a.rope[(size_t)token * half + (dp >> 1)];
+        const float2 cs = csv[pr];
         const float lo = v[2 * pr] * cs.x - v[2 * pr + 1] * cs.y;
         const float hi = v[2 * pr + 1] * cs.x + v[2 * pr] * cs.y;
         const uint32_t pk = (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
@@ -367,7 +386,7 @@ __device__ inline void gemm_epilogue(const MegaArgs& a, const PhaseCtx& pc, cons
       float* xn = a.xv + ((size_t)ver * a.Mp + token) * P.H + r;
       float o[4] = {0.f, 0.f, 0.f, 0.f};
       if (nrows == 4 && (r & 3) == 0) {
-        const f32x4 ov = *reinterpret_cast<const f32x4*>(xo) + v;
+        const f32x4 ov = (USE_PRE ? pre.xo : *reinterpret_cast<const f32x4*>(xo)) + v;
         st_wt_f32x4(xn, ov);
         for (int e = 0; e < 4; ++e) o[e] = ov[e];
       } else {

@@ -26,11 +26,20 @@
 namespace bd {
 
 constexpr int kFwdThreads = 512;      // 4 consumer + 4 producer wavefronts
-constexpr int kSlots = 28;            // 1-KiB ring slots per consumer
-constexpr int kProdBatch = 4;         // fragments a producer issues between two publications
-constexpr int kProdDepth = 6;         // loads it leaves in flight when it publishes
-constexpr int kLdsSpin = 1 << 22;     // bound of every LDS wait (a timed-out wait marks the context broken)
-constexpr int kShareBytes = 40 * 1024;  // K-reduction buffers / attention merge buffers (one region, re-used)
+#ifndef BD_SLOTS
+#define BD_SLOTS 28
+#endif
+#ifndef BD_PROD_BATCH
+#define BD_PROD_BATCH 4
+#endif
+#ifndef BD_PROD_DEPTH
+#define BD_PROD_DEPTH 6
+#endif
+constexpr int kSlots = BD_SLOTS;            // 1-KiB ring slots per consumer
+constexpr int kProdBatch = BD_PROD_BATCH;   // fragments a producer issues between two publications
+constexpr int kProdDepth = BD_PROD_DEPTH;   // loads it leaves in flight when it publishes
+constexpr int kLdsSpin = 1 << 22;           // bound of every LDS wait (a timed-out wait marks the context broken)
+constexpr int kShareBytes = 40 * 1024;      // K-reduction buffers / attention merge buffers (one region, re-used)
 
 typedef __attribute__((address_space(3))) void lds_void_t;
 
@@ -170,27 +179,41 @@ __device__ inline bf16x8 ring_take(Ring& rg, int lane) {
 }
 __device__ inline void ring_release(Ring& rg) { lds_st32(rg.consumed_addr, rg.taken); }
 
-// One chunk (one or two 16-row tiles x KW k-steps) out of the ring.
+// One chunk (one or two 16-row tiles x KW k-steps) out of the ring, four k-steps at a time: the LDS reads of a
+// batch are all issued before its first MFMA.
 template <int MT, bool TWO>
 __device__ inline void consume_chunk(Ring& rg, FwdSync& sy, DevState* st, const bf16x8 (&xk)[kMaxKW][MT], int KW,
                                      f32x4 (&acc)[kT][MT], int lane) {
+  constexpr int NT = TWO ? 2 : 1;
 #pragma unroll
   for (int kb = 0; kb < kMaxKW; kb += 4) {
     if (kb < KW) {
       const int nk = min(4, KW - kb);
-      ring_need(rg, sy, nk * (TWO ? 2 : 1), st);
+      ring_need(rg, sy, nk * NT, st);
+      if (nk == 4) {
+        bf16x8 af[4][NT];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (u < nk) {
-          const bf16x8 a0 = ring_take(rg, lane);
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-            acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, xk[kb + u][mt], acc[0][mt], 0, 0, 0);
-          if constexpr (TWO) {
-            const bf16x8 a1 = ring_take(rg, lane);
+          for (int t = 0; t < NT; ++t) af[u][t] = ring_take(rg, lane);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-              acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, xk[kb + u][mt], acc[1][mt], 0, 0, 0);
+              acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[u][t], xk[kb + u][mt], acc[t][mt], 0, 0, 0);
+      } else {
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+          if (u < nk) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+              const bf16x8 af = ring_take(rg, lane);
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt)
+                acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, xk[kb + u][mt], acc[t][mt], 0, 0, 0);
+            }
           }
         }
       }
@@ -207,7 +230,7 @@ struct FwdCtx {
 };
 
 // ---- one GEMM phase (consumer wavefronts) ------------------------------------------------------------------------
-template <int MT, int PH>
+template <int MT, int PH, int D>
 __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg, FwdSync& sy, int wave, int lane_in) {
   int lane = lane_in;
   asm volatile("" : "+v"(lane));
@@ -221,6 +244,12 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) { rmax[mt] = -INFINITY; ridx[mt] = 0x7FFFFFFF; rsum[mt] = 0.f; }
 
+#define BD_SUBTS2(k)                                                                                  \
+  do {                                                                                                \
+    if (a.trace2 != nullptr && pc.layer == 1 && threadIdx.x == 0 && PH < PH_LM)                        \
+      a.trace2[(size_t)blockIdx.x * 64 + PH * 12 + (k)] = wall_clock64();                              \
+  } while (0)
+  BD_SUBTS2(0);
   if (n_chunks > 0) {
     constexpr bool kNorm = (PH == PH_QKV || PH == PH_GU || PH == PH_LM);
     const int ver = (PH == PH_QKV) ? 2 * pc.layer : (PH == PH_GU) ? 2 * pc.layer + 1 : 2 * P.L;
@@ -261,9 +290,36 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
     float rs[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) rs[mt] = 1.f;
+    BD_SUBTS2(1);
 
     for (int c = 0; c < n_chunks; ++c) {
       const bool two = 2 * c + 1 < n_tiles;
+      // operands of this wavefront's epilogue element of the chunk (idx == wave), fetched while the product runs
+      EpiPre pre;
+      pre.cs[0] = pre.cs[1] = make_float2(0.f, 0.f);
+      pre.xo = f32x4{0.f, 0.f, 0.f, 0.f};
+      if constexpr (PH == PH_QKV || PH == PH_O) {
+        static_assert(kT * MT <= kWavesPerWG, "one epilogue element per consumer");
+        if (wave < kT * MT) {
+          const int t = wave / MT, mt = wave % MT;
+          const int token = mt * 16 + (lane & 15);
+          const int lr = (2 * c + t) * 16 + 4 * (lane >> 4);
+          const int r = wp.row0 + lr;
+          if (token < a.M && lr < wp.rows) {
+            if constexpr (PH == PH_QKV) {
+#pragma unroll
+              for (int pr = 0; pr < 2; ++pr) {
+                const int rp = r + 2 * pr;
+                if (2 * pr < min(4, wp.rows - lr) && rp < P.QD + P.KVD)
+                  pre.cs[pr] = a.rope[(size_t)token * (D >> 1) + ((rp % D) >> 1)];
+              }
+            } else {
+              if (min(4, wp.rows - lr) == 4 && (r & 3) == 0)
+                pre.xo = *reinterpret_cast<const f32x4*>(a.xv + ((size_t)(2 * pc.layer) * a.Mp + token) * P.H + r);
+            }
+          }
+        }
+      }
       f32x4 acc[kT][MT];
 #pragma unroll
       for (int t = 0; t < kT; ++t)
@@ -273,6 +329,7 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
         if (two) consume_chunk<MT, true>(rg, sy, a.st, xk, wp.KW, acc, lane);
         else consume_chunk<MT, false>(rg, sy, a.st, xk, wp.KW, acc, lane);
       }
+      if (c < 3) BD_SUBTS2(3 + 2 * c);
       // the four consumers hold disjoint K ranges: sum them through LDS in fixed order
       f32x4* red = (c & 1) ? fc.red2 : pc.red;
 #pragma unroll
@@ -280,6 +337,7 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) red[(wave * (kT * MT) + t * MT + mt) * 64 + lane] = acc[t][mt];
       cbar(sy, lane, a.st);
+      if (c == 0) BD_SUBTS2(2);
       if constexpr (kNorm) {
         if (c == 0) {
 #pragma unroll
@@ -300,11 +358,14 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
         v += red[(2 * (kT * MT) + idx) * 64 + lane];
         v += red[(3 * (kT * MT) + idx) * 64 + lane];
         if constexpr (kNorm) v *= rs[mt];
-        gemm_epilogue<MT, PH>(a, pc, wp, c, t, mt, v, lane, rmax, ridx, rsum);
+        if constexpr (PH == PH_QKV) { if (c == 0) BD_SUBTS2(5); }
+        gemm_epilogue<MT, PH, D, (PH == PH_QKV || PH == PH_O)>(a, pc, wp, c, t, mt, v, lane, rmax, ridx, rsum, pre);
       }
+      if (c < 3) BD_SUBTS2(4 + 2 * c);
     }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this wavefront's stores have been acknowledged
+  BD_SUBTS2(9);
 
   if constexpr (PH == PH_DOWN) {
     // the last of the ksplit workgroups to finish a tile sums all partials, adds the residual, stores the new
@@ -313,6 +374,9 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
     const int tiles = phase_tile_slots(P, PH_DOWN);
     const int my_tiles = (wp.rows + 15) >> 4;
     const int gt0 = wp.ng * phase_tpg(P.ph[PH_DOWN]);
+    const int col = lane & 15, g = lane >> 4;
+    const int ver = 2 * pc.layer + 2;
+    const int n_idx = my_tiles * MT;                          // (tile, row tile of tokens) pairs of this row range
     cbar(sy, lane, a.st);                                    // every consumer's partials are out
     if (wave == 0 && lane < my_tiles) {
       int last = 1;
@@ -324,50 +388,70 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
       pc.s_flags[8 + lane] = last;
     }
     cbar(sy, lane, a.st);
-    const int col = lane & 15, g = lane >> 4;
-    const int ver = 2 * pc.layer + 2;
-    for (int idx = wave; idx < my_tiles * MT; idx += kWavesPerWG) {
-      const int tl = idx / MT, mt = idx % MT;
-      if (!pc.s_flags[8 + tl]) continue;
-      const int gt = gt0 + tl;
-      const float* src = a.wsD + (size_t)pc.layer * a.wsD_layer_floats;
-      f32x4 pv[8];
-      f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-      for (int kg0 = 0; kg0 < ksplit; kg0 += 8) {
+    const float* src = a.wsD + (size_t)pc.layer * a.wsD_layer_floats;
+    for (int idx0 = wave; idx0 < n_idx; idx0 += 2 * kWavesPerWG) {
+      // two pairs per round, every load of the round in flight at once
+      f32x4 pv[2][8], xov[2];
+      bool on[2], vec[2];
+      int tok[2], rr[2], nr[2], gtt[2];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int kg = min(kg0 + u, ksplit - 1);
-          pv[u] = *reinterpret_cast<const f32x4*>(src + ((((size_t)kg * tiles + gt) * a.MT + mt) * 64 + lane) * 4);
+      for (int j = 0; j < 2; ++j) {
+        const int idx = idx0 + j * kWavesPerWG;
+        const int tl = idx / MT, mt = idx % MT;
+        on[j] = idx < n_idx && pc.s_flags[8 + min(tl, my_tiles - 1)];
+        gtt[j] = gt0 + tl;
+        tok[j] = mt * 16 + col;
+        const int lr = tl * 16 + 4 * g;
+        rr[j] = wp.row0 + lr;
+        nr[j] = min(4, wp.rows - lr);
+        vec[j] = nr[j] == 4 && (rr[j] & 3) == 0;
+        xov[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (on[j]) {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int kg = min(u, ksplit - 1);
+            pv[j][u] = *reinterpret_cast<const f32x4*>(src + ((((size_t)kg * tiles + gtt[j]) * a.MT + mt) * 64 + lane) * 4);
+          }
+          if (tok[j] < a.M && vec[j])
+            xov[j] = *reinterpret_cast<const f32x4*>(a.xv + ((size_t)(ver - 1) * a.Mp + tok[j]) * P.H + rr[j]);
         }
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        if (!on[j]) continue;
+        const int idx = idx0 + j * kWavesPerWG;
+        const int mt = idx % MT;
+        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-          if (kg0 + u < ksplit) v += pv[u];
-      }
-      const int token = mt * 16 + col;
-      const int lr = tl * 16 + 4 * g;
-      const int r = wp.row0 + lr;
-      const int nrows = min(4, wp.rows - lr);
-      float ss = 0.f;
-      if (token < a.M && nrows > 0) {
-        const float* xo = a.xv + ((size_t)(ver - 1) * a.Mp + token) * P.H + r;
-        float* xn = a.xv + ((size_t)ver * a.Mp + token) * P.H + r;
-        float o[4] = {0.f, 0.f, 0.f, 0.f};
-        if (nrows == 4 && (r & 3) == 0) {
-          const f32x4 ov = *reinterpret_cast<const f32x4*>(xo) + v;
-          st_wt_f32x4(xn, ov);
-          for (int e = 0; e < 4; ++e) o[e] = ov[e];
-        } else {
-          for (int e = 0; e < nrows; ++e) { o[e] = xo[e] + v[e]; st_wt_f32(xn + e, o[e]); }
+          if (u < ksplit) v += pv[j][u];
+        for (int kg = 8; kg < ksplit; ++kg)
+          v += *reinterpret_cast<const f32x4*>(src + ((((size_t)kg * tiles + gtt[j]) * a.MT + mt) * 64 + lane) * 4);
+        const int token = tok[j], r = rr[j], nrows = nr[j];
+        float ss = 0.f;
+        if (token < a.M && nrows > 0) {
+          const float* xo = a.xv + ((size_t)(ver - 1) * a.Mp + token) * P.H + r;
+          float* xn = a.xv + ((size_t)ver * a.Mp + token) * P.H + r;
+          float o[4] = {0.f, 0.f, 0.f, 0.f};
+          if (vec[j]) {
+            const f32x4 ov = xov[j] + v;
+            st_wt_f32x4(xn, ov);
+            for (int e = 0; e < 4; ++e) o[e] = ov[e];
+          } else {
+            for (int e = 0; e < nrows; ++e) { o[e] = xo[e] + v[e]; st_wt_f32(xn + e, o[e]); }
+          }
+          store_xb(a.xb + (size_t)ver * a.xb_elems, token, r, nrows, o, a.MT);
+          ss = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
         }
-        store_xb(a.xb + (size_t)ver * a.xb_elems, token, r, nrows, o, a.MT);
-        ss = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
+        ss += __shfl_xor(ss, 16);
+        ss += __shfl_xor(ss, 32);
+        if (g == 0) st_wt_f32(a.ssq + ((size_t)ver * a.ssq_parts + gtt[j]) * a.Mp + token, ss);
       }
-      ss += __shfl_xor(ss, 16);
-      ss += __shfl_xor(ss, 32);
-      if (g == 0) st_wt_f32(a.ssq + ((size_t)ver * a.ssq_parts + gt) * a.Mp + token, ss);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    BD_SUBTS2(10);
   }
+#undef BD_SUBTS2
 }
 
 // ---- attention phase ------------------------------------------------------------------------------------------
@@ -381,6 +465,90 @@ __device__ inline void stream_attn_chunks(int n_keys, int max_chunks, int& n_kb,
   if (want > max_chunks) want = max_chunks;
   chunk_len = ((n_kb + want - 1) / want + 3) & ~3;
   n_chunks = (n_kb + chunk_len - 1) / chunk_len;
+}
+
+// Reductions over the four 16-lane rows of a wavefront (the lanes that share a column of a C fragment), with the
+// row-swap instructions of gfx950: two VALU operations per step, no LDS traffic.
+__device__ inline float rows_max(float x) {
+  const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  const float m = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(m), __float_as_uint(m), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ inline float rows_sum(float x) {
+  const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  const float m = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(m), __float_as_uint(m), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+template <int D>
+struct KvBlock {
+  bf16x8 k[2][D / 32];
+  bf16x8 v[D / 16];
+};
+
+template <int D>
+__device__ inline void kv_load(KvBlock<D>& b, const bf16x8* Kh, const bf16x8* Vh, int kb, int lane) {
+  constexpr int DS = D / 32, DT = D / 16;
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) b.k[t][ds] = Kh[(((size_t)kb * 2 + t) * DS + ds) * 64 + lane];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) b.v[dt] = Vh[((size_t)kb * DT + dt) * 64 + lane];
+}
+
+// One block of 32 keys against one tile of 16 query columns.  Scores stay unscaled until the exponent:
+// p = 2^(s*c - m) with c = log2(e)/sqrt(d) folded into one fused multiply-add per score.
+template <int D, bool MASKED>
+__device__ inline void attn_block(const KvBlock<D>& b, const bf16x8 (&qf)[D / 32], f32x4 (&O)[D / 16], float& mrun, float& lrun,
+                                  int kb, int n, int M, int mode, int row, int g, float c) {
+  constexpr int DS = D / 32, DT = D / 16;
+  f32x4 s[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b.k[t][ds], qf[ds], s[t], 0, 0, 0);
+  }
+  float v[8];
+  bool vis[8];
+  float cmax = kNegBig;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    v[e] = s[e >> 2][e & 3];
+    vis[e] = true;
+    if constexpr (MASKED) {
+      const int jb = kb * 32 + 8 * g + e - n;
+      vis[e] = (jb < 0) || (jb < M && (mode == 0 || jb <= row));
+      if (vis[e]) cmax = fmaxf(cmax, v[e]);
+    } else {
+      cmax = fmaxf(cmax, v[e]);
+    }
+  }
+  cmax = rows_max(cmax);
+  const float mnew = fmaxf(mrun, cmax * c);
+  float psum = 0.f;
+  bf16x8 p8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float p = __builtin_amdgcn_exp2f(fmaf(v[e], c, -mnew));
+    if constexpr (MASKED) p = vis[e] ? p : 0.f;
+    psum += p;
+    p8[e] = (__bf16)p;
+  }
+  psum = rows_sum(psum);
+  if (__builtin_amdgcn_ballot_w64(mnew != mrun) != 0ull) {          // some column's maximum moved: rescale
+    const float alpha = __builtin_amdgcn_exp2f(mrun - mnew);
+    lrun *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) O[dt] *= alpha;
+    mrun = mnew;
+  }
+  lrun += psum;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b.v[dt], p8, O[dt], 0, 0, 0);
 }
 
 template <int D>
@@ -411,7 +579,13 @@ __device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, Fwd
   float* pm = a.pm + (size_t)pc.layer * a.pml_layer_floats;
   float* pl = a.pl + (size_t)pc.layer * a.pml_layer_floats;
   u16* out = a.ap + (size_t)pc.layer * a.ap_elems;
+  const float c = a.scale_log2e;
 
+#define BD_ATS(k)                                                                                     \
+  do {                                                                                                \
+    if (a.trace2 != nullptr && pc.layer == 1 && threadIdx.x == 0) a.trace2[(size_t)blockIdx.x * 64 + 48 + (k)] = wall_clock64(); \
+  } while (0)
+  BD_ATS(0);
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int chunk = item % n_chunks;
     const int grp = item / n_chunks;
@@ -431,79 +605,25 @@ __device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, Fwd
     for (int dt = 0; dt < DT; ++dt) O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float mrun = kNegBig, lrun = 0.f;
     const int kb_end = min(n_kb, (chunk + 1) * chunk_len);
-    int kb = chunk * chunk_len + wave;
-    bf16x8 kf[2][DS], vf[DT];
-    if (kb < kb_end) {
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int ds = 0; ds < DS; ++ds) kf[t][ds] = Kh[(((size_t)kb * 2 + t) * DS + ds) * 64 + lane];
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) vf[dt] = Vh[((size_t)kb * DT + dt) * 64 + lane];
-    }
-    for (; kb < kb_end; kb += kWavesPerWG) {
-      // next block's operands are requested before this block is worked on
-      bf16x8 kn[2][DS], vn[DT];
-      const int kbn = kb + kWavesPerWG;
-      if (kbn < kb_end) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int ds = 0; ds < DS; ++ds) kn[t][ds] = Kh[(((size_t)kbn * 2 + t) * DS + ds) * 64 + lane];
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vn[dt] = Vh[((size_t)kbn * DT + dt) * 64 + lane];
-      }
-      f32x4 s[2];
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ds = 0; ds < DS; ++ds) s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][ds], qf[ds], s[t], 0, 0, 0);
-      }
-      const bool need_mask = (kb * 32 + 31) >= n;
-      float v[8];
-      bool vis[8];
-      float cmax = kNegBig;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        v[e] = s[e >> 2][e & 3] * a.scale_log2e;
-        vis[e] = true;
-        if (need_mask) {
-          const int jb = kb * 32 + 8 * g + e - n;
-          vis[e] = (jb < 0) || (jb < a.M && (a.mode == 0 || jb <= row));
-        }
-        if (vis[e]) cmax = fmaxf(cmax, v[e]);
-      }
-      cmax = fmaxf(cmax, __shfl_xor(cmax, 16));
-      cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
-      const float mnew = fmaxf(mrun, cmax);
-      const float alpha = exp2f(mrun - mnew);
-      float psum = 0.f;
-      union { bf16x8 v8; u16 h[8]; } cv;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float p = vis[e] ? exp2f(v[e] - mnew) : 0.f;
-        psum += p;
-        cv.h[e] = f32_to_bf16_bits(p);
-      }
-      psum += __shfl_xor(psum, 16);
-      psum += __shfl_xor(psum, 32);
-      lrun = lrun * alpha + psum;
-      mrun = mnew;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        O[dt] *= alpha;
-        O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], cv.v8, O[dt], 0, 0, 0);
-      }
-      if (kbn < kb_end) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int ds = 0; ds < DS; ++ds) kf[t][ds] = kn[t][ds];
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vf[dt] = vn[dt];
+    const int kb0 = chunk * chunk_len + wave;
+    // two register buffers, loads pinned one block ahead of their use
+    KvBlock<D> b0, b1;
+    if (kb0 < kb_end) kv_load<D>(b0, Kh, Vh, kb0, lane);
+    asm volatile("" ::: "memory");
+    for (int kb = kb0; kb < kb_end; kb += 2 * kWavesPerWG) {
+      const int kb1 = kb + kWavesPerWG, kb2 = kb + 2 * kWavesPerWG;
+      if (kb1 < kb_end) kv_load<D>(b1, Kh, Vh, kb1, lane);
+      asm volatile("" ::: "memory");
+      if (kb * 32 + 31 >= n) attn_block<D, true>(b0, qf, O, mrun, lrun, kb, n, a.M, a.mode, row, g, c);
+      else attn_block<D, false>(b0, qf, O, mrun, lrun, kb, n, a.M, a.mode, row, g, c);
+      if (kb1 < kb_end) {
+        if (kb2 < kb_end) kv_load<D>(b0, Kh, Vh, kb2, lane);
+        asm volatile("" ::: "memory");
+        if (kb1 * 32 + 31 >= n) attn_block<D, true>(b1, qf, O, mrun, lrun, kb1, n, a.M, a.mode, row, g, c);
+        else attn_block<D, false>(b1, qf, O, mrun, lrun, kb1, n, a.M, a.mode, row, g, c);
       }
     }
+    BD_ATS(2);
     // merge the four consumers: everyone publishes (max, sum, O), then each folds a share of the d tiles
     if (g == 0) {
       sm[wave * 16 + col] = mrun;
@@ -512,6 +632,7 @@ __device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, Fwd
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) sO[(wave * DT + dt) * 64 + lane] = O[dt];
     cbar(sy, lane, a.st);
+    BD_ATS(3);
     float mm = sm[col];
 #pragma unroll
     for (int w = 1; w < kWavesPerWG; ++w) mm = fmaxf(mm, sm[w * 16 + col]);
@@ -536,6 +657,7 @@ __device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, Fwd
           st_wt_u64(out + xp_index(row, fo, a.MT), (uint64_t)lo | ((uint64_t)hi << 32));
         }
       }
+      BD_ATS(4);
       cbar(sy, lane, a.st);                                   // the merge buffers are free again
       continue;
     }
@@ -577,8 +699,7 @@ __device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, Fwd
           if (g + 4 * u >= n_chunks) { pmv[u] = kNegBig; plv[u] = 0.f; }
           mx = fmaxf(mx, pmv[u]);
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = rows_max(mx);
         float lp = 0.f;
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
@@ -587,8 +708,7 @@ __device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, Fwd
           lp += plv[u] * w;
           if (ch < n_chunks) wgt[ch * 16 + col] = w;
         }
-        lp += __shfl_xor(lp, 16);
-        lp += __shfl_xor(lp, 32);
+        lp = rows_sum(lp);
         if (g == 0) s_inv[col] = 1.f / lp;
       }
       cbar(sy, lane, a.st);
@@ -618,15 +738,17 @@ __device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, Fwd
     cbar(sy, lane, a.st);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  BD_ATS(5);
+#undef BD_ATS
 }
 
 // ---- grid barrier of the consumer wavefronts ---------------------------------------------------------------------
-// Every consumer has waited for its own stores; consumer 0 collects the four arrivals, takes part in the
-// chip-wide barrier (two-level counters of mega.h) and hands the new epoch to the others through LDS.
+// Every consumer has waited for its own stores (each phase ends with that wait).  Consumer 0 collects the four
+// arrivals, takes part in the chip-wide barrier (two-level counters of mega.h) and hands the new epoch to the
+// others through LDS.
 __device__ inline bool stream_grid_barrier(const MegaArgs& a, FwdSync& sy, unsigned epoch, int wave, int lane) {
   const int nwg = a.P.nwg;
   sy.arrive_target += kWavesPerWG;
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   if (lane == 0) lds_inc(sy.base + SY_ARRIVE * 4);
   if (wave == 0) {
     bool ok = lds_wait_ge(sy, sy.base + SY_ARRIVE * 4, sy.arrive_target, a.st);
@@ -712,7 +834,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
   bool alive = true;
   for (int l = 0; l < P.L && alive; ++l) {
     fc.pc.layer = l;
-    stream_gemm_phase<MT, PH_QKV>(a, fc, rg, sy, wave, lane);
+    stream_gemm_phase<MT, PH_QKV, D>(a, fc, rg, sy, wave, lane);
     BD_TS2();
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
@@ -722,17 +844,17 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
     if (!alive) break;
-    stream_gemm_phase<MT, PH_O>(a, fc, rg, sy, wave, lane);
+    stream_gemm_phase<MT, PH_O, D>(a, fc, rg, sy, wave, lane);
     BD_TS2();
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
     if (!alive) break;
-    stream_gemm_phase<MT, PH_GU>(a, fc, rg, sy, wave, lane);
+    stream_gemm_phase<MT, PH_GU, D>(a, fc, rg, sy, wave, lane);
     BD_TS2();
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
     if (!alive) break;
-    stream_gemm_phase<MT, PH_DOWN>(a, fc, rg, sy, wave, lane);
+    stream_gemm_phase<MT, PH_DOWN, D>(a, fc, rg, sy, wave, lane);
     BD_TS2();
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
