@@ -142,7 +142,8 @@ int make_plan(bd_ctx* c) {
       ph.ksplit *= 2;
     }
     const int groups = P.nwg / ph.ksplit;
-    ph.RW = std::max(2, ceil_even(ceil_div(N, groups)));
+    if (N % 16 != 0) return false;
+    ph.RW = 16 * ceil_div(N / 16, groups);
     return true;
   };
   if (!set(PH_QKV, c->NQKV, c->H, false) || !set(PH_O, c->H, c->QD, false) || !set(PH_GU, 2 * c->F, c->H, false) ||

@@ -37,11 +37,15 @@ constexpr int kSpinLimit = 1 << 19;
 enum { PH_QKV = 0, PH_O = 1, PH_GU = 2, PH_DOWN = 3, PH_LM = 4, PH_COUNT = 5, PH_END = 6 };
 
 struct PhasePlan {
-  int N;        // output rows of the phase (after fusing / interleaving)
+  int N;        // output rows of the phase (after fusing / interleaving); a multiple of 16
   int KS;       // k-steps
   int ksplit;   // workgroups that share an output row range and split K
-  int RW;       // rows per row range (even)
+  int RW;       // rows of the largest row range (a multiple of 16)
 };
+// Row ranges are whole 16-row tiles, spread over the nwg/ksplit row groups as evenly as whole tiles allow
+// (group g holds tiles [T*g/G, T*(g+1)/G)).  So every weight fragment of the stream is a full 1 KiB.
+__host__ __device__ inline int tile0_of_group(int T, int G, int g) { return (int)((long long)T * g / G); }
+__host__ __device__ inline int group_of_tile(int T, int G, int tile) { return (int)((((long long)tile + 1) * G - 1) / T); }
 
 struct MegaPlan {
   int nwg, L, H, QD, KVD, F, V, D, n_q, n_kv;
@@ -63,11 +67,12 @@ __host__ __device__ inline WavePhase wave_phase(const MegaPlan& P, int p, int wg
   const int ng = wg / ph.ksplit;
   r.ng = ng;
   r.kg = wg % ph.ksplit;
-  r.row0 = ng * ph.RW;
-  int rows = ph.N - r.row0;
-  if (rows > ph.RW) rows = ph.RW;
-  if (rows < 0) rows = 0;
-  r.rows = rows;
+  {
+    const int T = ph.N >> 4, G = P.nwg / ph.ksplit;
+    const int t0 = tile0_of_group(T, G, ng), t1 = tile0_of_group(T, G, ng + 1);
+    r.row0 = t0 << 4;
+    r.rows = (t1 - t0) << 4;
+  }
   const int k0 = (int)((long long)ph.KS * r.kg / ph.ksplit), k1 = (int)((long long)ph.KS * (r.kg + 1) / ph.ksplit);
   const int len = k1 - k0;
   r.w0 = k0 + len * w / kWavesPerWG;
@@ -1144,7 +1149,8 @@ __global__ void pack_stream_kernel(const SrcT* __restrict__ src, int n_rows, int
       r = row_base + rs;
     }
     const PhasePlan& pp = P.ph[ph];
-    const int ng = r / pp.RW, lr = r - ng * pp.RW;
+    const int ng = group_of_tile(pp.N >> 4, P.nwg / pp.ksplit, r >> 4);
+    const int lr = r - (tile0_of_group(pp.N >> 4, P.nwg / pp.ksplit, ng) << 4);
     // which K group / wavefront holds k-step ks
     int kg = 0;
     while ((int)((long long)pp.KS * (kg + 1) / pp.ksplit) <= ks) ++kg;

@@ -98,55 +98,97 @@ __device__ inline void cbar(FwdSync& sy, int lane, DevState* st) {
 }
 
 // ---- producer ----------------------------------------------------------------------------------------------
+// Row ranges are whole tiles, so a consumer's stream is a plain sequence of 1-KiB fragments: fragment q of the
+// forward sits at byte q*1024 of the wavefront's stream, lane l's 16 bytes at l*16.
+__device__ inline unsigned stream_fragments(const MegaPlan& P, int cw) {
+  return (unsigned)((long long)P.L * wave_layer_units(P, blockIdx.x, cw) / 64);
+}
+
 __device__ inline void producer_loop(const MegaArgs& a, int cw, char* ring, unsigned sync_base, int lane) {
   const MegaPlan& P = a.P;
-  const rsrc_t wr = make_rsrc(a.wstream + (size_t)(blockIdx.x * kWavesPerWG + cw) * P.wave_stride,
-                              (unsigned)(P.wave_stride * 16));
+  const unsigned total = stream_fragments(P, cw);
+  const rsrc_t wr = make_rsrc(a.wstream + (size_t)(blockIdx.x * kWavesPerWG + cw) * P.wave_stride, total * 1024u);
   const unsigned landed_addr = sync_base + (SY_LANDED + cw) * 4;
   const unsigned consumed_addr = sync_base + (SY_CONSUMED + cw) * 4;
   const unsigned dead_addr = sync_base + SY_DEAD * 4;
-  Cursor cur;
-  cur.pos = 0; cur.l = 0; cur.p = PH_QKV; cur.c = 0; cur.wg = blockIdx.x; cur.w = cw; cur.want_lm = 0;
   unsigned issued = 0, landed = 0, consumed = 0;
   int slot = 0, since = 0;
-  bool ok = true;
-  for (ChunkRef r = cur.next(P); r.KW > 0 && ok; r = cur.next(P)) {
-    const ChunkLane cl = chunk_lane(r, lane);
-    const int nt = r.R1 > 0 ? 2 : 1;
-    for (int ksl = 0; ksl < r.KW && ok; ++ksl) {
-      for (int t = 0; t < nt; ++t) {
-        if (issued - consumed >= (unsigned)kSlots) {
-          // ring full: publish everything that is under way, then wait for the consumer
-          if (landed != issued) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            landed = issued;
-            lds_st32(landed_addr, landed);
-            since = 0;
-          }
-          int spins = 0;
-          while (issued - (consumed = lds_ld32(consumed_addr)) >= (unsigned)kSlots) {
-            __builtin_amdgcn_s_sleep(1);
-            if ((++spins & 31) == 0 && (lds_ld32(dead_addr) != 0u || spins > kLdsSpin)) { ok = false; break; }
-          }
-          if (!ok) break;
-        }
-        const int voff = (t ? cl.o1 : cl.o0) + ksl * cl.step;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (lds_void_t*)(ring + slot * 1024), 16, voff, 0, 0, kAuxNt);
-        ++issued;
-        slot = (slot + 1 == kSlots) ? 0 : slot + 1;
-        if (++since == kProdBatch) {
-          since = 0;
-          asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kProdDepth) : "memory");   // all but the newest kProdDepth are in LDS
-          if (issued > (unsigned)kProdDepth && (int)(issued - kProdDepth - landed) > 0) {
-            landed = issued - kProdDepth;
-            lds_st32(landed_addr, landed);
-          }
-        }
+  while (issued < total) {
+    if (issued - consumed >= (unsigned)kSlots) {
+      // ring full: publish everything that is under way, then wait for the consumer
+      if (landed != issued) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        landed = issued;
+        lds_st32(landed_addr, landed);
+        since = 0;
+      }
+      int spins = 0;
+      bool ok = true;
+      while (issued - (consumed = lds_ld32(consumed_addr)) >= (unsigned)kSlots) {
+        __builtin_amdgcn_s_sleep(1);
+        if ((++spins & 31) == 0 && (lds_ld32(dead_addr) != 0u || spins > kLdsSpin)) { ok = false; break; }
+      }
+      if (!ok) break;
+    }
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (lds_void_t*)(ring + slot * 1024), 16, (int)(issued * 1024u) + lane * 16, 0, 0,
+                                             kAuxNt);
+    ++issued;
+    slot = (slot + 1 == kSlots) ? 0 : slot + 1;
+    if (++since == kProdBatch) {
+      since = 0;
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kProdDepth) : "memory");   // all but the newest kProdDepth are in LDS
+      if (issued > (unsigned)kProdDepth && (int)(issued - kProdDepth - landed) > 0) {
+        landed = issued - kProdDepth;
+        lds_st32(landed_addr, landed);
       }
     }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   lds_st32(landed_addr, issued);
+}
+
+// Producer variant with a register stash: NR fragments are always on their way into (or waiting in) this
+// wavefront's registers; one by one they are written to the ring as slots come free and their register is
+// re-loaded at once with the fragment NR positions further on.  Deeper look-ahead than the ring alone.
+#ifndef BD_STASH
+#define BD_STASH 0
+#endif
+template <int NR>
+__device__ inline void producer_loop_stash(const MegaArgs& a, int cw, char* ring, unsigned sync_base, int lane) {
+  const MegaPlan& P = a.P;
+  const unsigned total = stream_fragments(P, cw);
+  const rsrc_t wr = make_rsrc(a.wstream + (size_t)(blockIdx.x * kWavesPerWG + cw) * P.wave_stride, total * 1024u);
+  const unsigned landed_addr = sync_base + (SY_LANDED + cw) * 4;
+  const unsigned consumed_addr = sync_base + (SY_CONSUMED + cw) * 4;
+  const unsigned dead_addr = sync_base + SY_DEAD * 4;
+  bf16x8 stage[NR];
+#pragma unroll
+  for (int i = 0; i < NR; ++i) stage[i] = buf_load_w(wr, i * 1024 + lane * 16);    // beyond the end: zeros, no traffic
+  unsigned q = 0, consumed = 0;
+  int slot = 0;
+  bool ok = true;
+  // Every pass of the body issues exactly one load, so the in-order load counter the compiler waits on stays exact.
+  while (ok && q < total) {
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+      if (ok && q < total) {
+        if (q - consumed >= (unsigned)kSlots) {
+          int spins = 0;
+          while (q - (consumed = lds_ld32(consumed_addr)) >= (unsigned)kSlots) {
+            __builtin_amdgcn_s_sleep(1);
+            if ((++spins & 31) == 0 && (lds_ld32(dead_addr) != 0u || spins > kLdsSpin)) { ok = false; break; }
+          }
+        }
+        if (ok) {
+          *reinterpret_cast<bf16x8*>(ring + slot * 1024 + lane * 16) = stage[i];
+          ++q;
+          lds_st32(landed_addr, q);
+          slot = (slot + 1 == kSlots) ? 0 : slot + 1;
+        }
+      }
+      stage[i] = buf_load_w(wr, ok ? (int)((q - 1u + NR) * 1024u) + lane * 16 : kOob);
+    }
+  }
 }
 
 // ---- consumer side of the ring -------------------------------------------------------------------------------
@@ -461,7 +503,10 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
 // stored and the workgroup completing the last chunk of a tile merges all chunks in fixed order.
 __device__ inline void stream_attn_chunks(int n_keys, int max_chunks, int& n_kb, int& chunk_len, int& n_chunks) {
   n_kb = (n_keys + 31) >> 5;
-  int want = n_kb <= 96 ? 1 : (n_kb + 39) / 40;
+#ifndef BD_ATT_BLOCKS
+#define BD_ATT_BLOCKS 40
+#endif
+  int want = (n_kb + BD_ATT_BLOCKS - 1) / BD_ATT_BLOCKS;
   if (want > max_chunks) want = max_chunks;
   chunk_len = ((n_kb + want - 1) / want + 3) & ~3;
   n_chunks = (n_kb + chunk_len - 1) / chunk_len;
@@ -803,7 +848,8 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
 
   if (wave >= kWavesPerWG) {
     const int cw = wave - kWavesPerWG;
-    producer_loop(a, cw, lds + cw * kSlots * 1024, sync_base, lane);
+    if constexpr (BD_STASH > 0) producer_loop_stash<BD_STASH>(a, cw, lds + cw * kSlots * 1024, sync_base, lane);
+    else producer_loop(a, cw, lds + cw * kSlots * 1024, sync_base, lane);
     return;
   }
 
