@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--fixed-k", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy kernel (reference for hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a single-GPU path (batch-1 decode); run with --gpus 1. "
@@ -76,14 +78,24 @@ def main():
             ctx.bd_denoise_step(tok, msk, 0.9, K)
         ctx.bd_commit_block(tok)
 
-    def run(n_blocks):
+    def run(n_blocks, after_prefill=None):
         ctx.bd_prefill(d_emb, d_ids)
         torch.cuda.synchronize()
+        if after_prefill is not None:
+            after_prefill()
         t = time.perf_counter()
         for _ in range(n_blocks):
             decode_block()
         torch.cuda.synchronize()
         return time.perf_counter() - t
+
+    if args.calibrate_copy:
+        # a plain copy of known size: 2^28 fp32 read + written once (1 GiB each way), for scaling FETCH_SIZE / WRITE_SIZE
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     run(args.warmup)                              # untimed warm-up blocks, then the prompt is prefilled afresh
     elapsed = run(args.steps)
@@ -99,8 +111,7 @@ def main():
 
     roofline = None
     if not args.no_kernel_pass:
-        ctx.bd_k_profile(True)
-        run(args.steps)
+        run(args.steps, after_prefill=lambda: ctx.bd_k_profile(True))   # events around the decode launches only
         prof = ctx.bd_k_profile_read()
         ctx.bd_k_profile(False)
         stream = {k: v for k, v in prof.items() if v[2] > 0 and v[1] > 0}

@@ -42,7 +42,7 @@ static char g_last_error[512] = "";
 
 namespace {
 
-enum KClass { KC_PROLOGUE = 0, KC_FORWARD, KC_FINISH, KC_COUNT };
+enum KClass { KC_PROLOGUE = 0, KC_LAYERS, KC_LMHEAD, KC_FINISH, KC_COUNT };
 
 struct GemmPlan { int NT, ksplit, grid; };   // launch plan of the stand-alone GEMM entry point
 
@@ -226,6 +226,8 @@ template <int MT>
 int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
   bool streamed = false;
   if constexpr (MT <= 2) streamed = c->use_stream;
+  {
+  Prof pr(c, KC_LAYERS);
   if (streamed) {
     if constexpr (MT <= 2) {
       a.attn_max_chunks = stream_attn_max_chunks(c, MT);
@@ -238,7 +240,9 @@ int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
     else BD_TRY((launch_mega_inst<MT, 64, 2>(c, a)));
     c->bar_epoch += 5u * (unsigned)c->L;
   }
+  }
   if (a.want_lm) {
+    Prof pr(c, KC_LMHEAD);
     a.bar_epoch = c->bar_epoch;
     BD_TRY(launch_lm<MT>(c, a));
     c->bar_epoch += 1u;
@@ -284,7 +288,6 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
   a.trace = c->trace_on ? c->trace : nullptr;
   a.trace2 = c->trace_on ? c->trace + (size_t)c->plan.nwg * (10 * c->L + 4) : nullptr;
   {
-    Prof pr(c, KC_FORWARD);
 #ifdef BD_DEV_FAST   /* development builds: one instantiation only, to shorten compile time */
     if (MT != 2) return BD_E_ARG;
     BD_TRY(launch_mega_mt<2>(c, a));
@@ -737,7 +740,7 @@ int bd_k_trace_read(bd_ctx* c, unsigned long long* host_out, int capacity, int* 
 }
 
 const char* bd_k_class_name(int kclass) {
-  static const char* names[KC_COUNT] = {"prologue", "forward", "finish"};
+  static const char* names[KC_COUNT] = {"prologue", "layers", "lm_head", "finish"};
   return (kclass >= 0 && kclass < KC_COUNT) ? names[kclass] : nullptr;
 }
 
@@ -745,7 +748,10 @@ int bd_k_class_count(void) { return KC_COUNT; }
 
 int64_t bd_k_class_bytes(const bd_ctx* c, int kclass) {
   if (c == nullptr) return BD_E_ARG;
-  return kclass == KC_FORWARD ? bd_forward_bytes(c) : 0;
+  const int64_t lm = (int64_t)c->V * c->H * 2;
+  if (kclass == KC_LAYERS) return bd_forward_bytes(c) - lm;
+  if (kclass == KC_LMHEAD) return lm;
+  return 0;
 }
 
 }  // extern "C"

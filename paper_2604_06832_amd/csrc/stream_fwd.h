@@ -147,50 +147,6 @@ __device__ inline void producer_loop(const MegaArgs& a, int cw, char* ring, unsi
   lds_st32(landed_addr, issued);
 }
 
-// Producer variant with a register stash: NR fragments are always on their way into (or waiting in) this
-// wavefront's registers; one by one they are written to the ring as slots come free and their register is
-// re-loaded at once with the fragment NR positions further on.  Deeper look-ahead than the ring alone.
-#ifndef BD_STASH
-#define BD_STASH 0
-#endif
-template <int NR>
-__device__ inline void producer_loop_stash(const MegaArgs& a, int cw, char* ring, unsigned sync_base, int lane) {
-  const MegaPlan& P = a.P;
-  const unsigned total = stream_fragments(P, cw);
-  const rsrc_t wr = make_rsrc(a.wstream + (size_t)(blockIdx.x * kWavesPerWG + cw) * P.wave_stride, total * 1024u);
-  const unsigned landed_addr = sync_base + (SY_LANDED + cw) * 4;
-  const unsigned consumed_addr = sync_base + (SY_CONSUMED + cw) * 4;
-  const unsigned dead_addr = sync_base + SY_DEAD * 4;
-  bf16x8 stage[NR];
-#pragma unroll
-  for (int i = 0; i < NR; ++i) stage[i] = buf_load_w(wr, i * 1024 + lane * 16);    // beyond the end: zeros, no traffic
-  unsigned q = 0, consumed = 0;
-  int slot = 0;
-  bool ok = true;
-  // Every pass of the body issues exactly one load, so the in-order load counter the compiler waits on stays exact.
-  while (ok && q < total) {
-#pragma unroll
-    for (int i = 0; i < NR; ++i) {
-      if (ok && q < total) {
-        if (q - consumed >= (unsigned)kSlots) {
-          int spins = 0;
-          while (q - (consumed = lds_ld32(consumed_addr)) >= (unsigned)kSlots) {
-            __builtin_amdgcn_s_sleep(1);
-            if ((++spins & 31) == 0 && (lds_ld32(dead_addr) != 0u || spins > kLdsSpin)) { ok = false; break; }
-          }
-        }
-        if (ok) {
-          *reinterpret_cast<bf16x8*>(ring + slot * 1024 + lane * 16) = stage[i];
-          ++q;
-          lds_st32(landed_addr, q);
-          slot = (slot + 1 == kSlots) ? 0 : slot + 1;
-        }
-      }
-      stage[i] = buf_load_w(wr, ok ? (int)((q - 1u + NR) * 1024u) + lane * 16 : kOob);
-    }
-  }
-}
-
 // ---- consumer side of the ring -------------------------------------------------------------------------------
 struct Ring {
   const char* base;        // this consumer's slots
@@ -227,19 +183,20 @@ template <int MT, bool TWO>
 __device__ inline void consume_chunk(Ring& rg, FwdSync& sy, DevState* st, const bf16x8 (&xk)[kMaxKW][MT], int KW,
                                      f32x4 (&acc)[kT][MT], int lane) {
   constexpr int NT = TWO ? 2 : 1;
+  constexpr int CB = 4;                                  // k-steps per batch
 #pragma unroll
-  for (int kb = 0; kb < kMaxKW; kb += 4) {
+  for (int kb = 0; kb < kMaxKW; kb += CB) {
     if (kb < KW) {
-      const int nk = min(4, KW - kb);
+      const int nk = min(CB, KW - kb);
       ring_need(rg, sy, nk * NT, st);
-      if (nk == 4) {
-        bf16x8 af[4][NT];
+      if (nk == CB) {
+        bf16x8 af[CB][NT];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < CB; ++u)
 #pragma unroll
           for (int t = 0; t < NT; ++t) af[u][t] = ring_take(rg, lane);
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < CB; ++u)
 #pragma unroll
           for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -247,7 +204,7 @@ __device__ inline void consume_chunk(Ring& rg, FwdSync& sy, DevState* st, const 
               acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[u][t], xk[kb + u][mt], acc[t][mt], 0, 0, 0);
       } else {
 #pragma unroll
-        for (int u = 0; u < 3; ++u) {
+        for (int u = 0; u < CB - 1; ++u) {
           if (u < nk) {
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
@@ -848,8 +805,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
 
   if (wave >= kWavesPerWG) {
     const int cw = wave - kWavesPerWG;
-    if constexpr (BD_STASH > 0) producer_loop_stash<BD_STASH>(a, cw, lds + cw * kSlots * 1024, sync_base, lane);
-    else producer_loop(a, cw, lds + cw * kSlots * 1024, sync_base, lane);
+    producer_loop(a, cw, lds + cw * kSlots * 1024, sync_base, lane);
     return;
   }
 
