@@ -29,7 +29,10 @@ def main():
     ap.add_argument("--steps", type=int, default=8, help="blocks of 32 tokens to time (8 = 256 tokens)")
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--layers", type=int, default=36, help="debug only: fewer layers (result is then not the metric)")
-    ap.add_argument("--prefix", type=int, default=1024)
+    ap.add_argument("--prefix", type=int, default=None, help="committed prefix length (default 1024; 2048 with --weights fp8)")
+    ap.add_argument("--weights", choices=["bf16", "fp8"], default="bf16",
+                    help="fp8 = configs[4]: e4m3 decoder linears with per-output-channel scales (seed 2), prefix 2048; "
+                         "not the headline metric")
     ap.add_argument("--block", type=int, default=32)
     ap.add_argument("--fixed-k", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -51,17 +54,21 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     B, K = args.block, args.fixed_k
+    fp8 = args.weights == "fp8"
+    if args.prefix is None:
+        args.prefix = 2048 if fp8 else 1024
     shape = inputs.QWEN3B.with_layers(args.layers)
     threads = min(16, os.cpu_count() or 8)
 
     t0 = time.time()
-    w = inputs.make_weights(shape, 0, "bf16", threads=threads)
+    w = inputs.make_weights(shape, 2 if fp8 else 0, args.weights, threads=threads)
     n_embed = args.prefix * 3 // 4
-    emb, ids = inputs.make_prompt(shape, n_embed, args.prefix - n_embed, seed=101)
+    emb, ids = inputs.make_prompt(shape, n_embed, args.prefix - n_embed, seed=104 if fp8 else 101)
     print(f"[bench] weights generated in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
     blocks = args.warmup + args.steps
-    ctx = binding.Context(shape, max_seq=args.prefix + (max(blocks, args.steps) + 1) * B, max_block=64)
+    ctx = binding.Context(shape, max_seq=args.prefix + (max(blocks, args.steps) + 1) * B, max_block=32 if fp8 else 64,
+                          weight_dtype=binding.BD_FP8_E4M3 if fp8 else binding.BD_BF16)
     t0 = time.time()
     ctx.load_model(w)
     print(f"[bench] weights uploaded in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
@@ -106,6 +113,10 @@ def main():
     # algorithmic bytes of the whole run: weights once per forward + cached K/V at each block's length
     kv_pos_bytes = shape.n_layers * 2 * shape.kv_dim * 2
     w_bytes = 2 * shape.weight_elements()
+    if fp8:   # one byte per decoder weight + 4 bytes per output channel; LM head stays bf16
+        lm = shape.vocab * shape.hidden
+        rows = shape.q_dim + 2 * shape.kv_dim + 2 * shape.hidden + 2 * shape.ffn
+        w_bytes = (shape.weight_elements() - lm) + 2 * lm + 4 * rows * shape.n_layers
     total_bytes = sum((n_den + 1) * (w_bytes + kv_pos_bytes * (args.prefix + b * B)) for b in range(args.steps))
     step_frac = total_bytes / elapsed / 1e9 / HBM_PEAK_GBS
 
@@ -146,7 +157,7 @@ def main():
         "value": round(tokens / elapsed, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"configs[1]: 3B-shaped bf16 ({shape.n_layers} layers), prefix {args.prefix} "
+        "config": {"workload": f"configs[{4 if fp8 else 1}]: 3B-shaped {'e4m3-weight' if fp8 else 'bf16'} ({shape.n_layers} layers), prefix {args.prefix} "
                                f"({n_embed} visual embeddings + {args.prefix - n_embed} ids), B={B}, "
                                f"fixed {K} unmasks/step, {tokens} tokens",
                    "block": B, "fixed_k": K, "prefix": args.prefix, "forwards_per_block": n_den + 1},

@@ -53,7 +53,7 @@ typedef struct {
   float rope_theta;      /* rotary base, 1e6 in every configuration                                  */
   float rms_eps;         /* RMSNorm epsilon, 1e-6                                                     */
   int32_t max_seq;       /* KV-cache capacity in positions (committed context + one block)           */
-  int32_t max_block;     /* largest B of any call (<= 64)                                            */
+  int32_t max_block;     /* largest B of any call (<= 64; <= 32 with BD_FP8_E4M3 weights)            */
   int32_t mask_token_id; /* id embedded at masked positions; negative = vocab-1                       */
   int32_t weight_dtype;  /* device storage of the seven decoder linears: BD_BF16 or BD_FP8_E4M3       */
 } bd_config;
@@ -67,7 +67,10 @@ void bd_destroy(bd_ctx* ctx);
  * "l<i>.wk", "l<i>.wv", "l<i>.wo", "l<i>.ffn_norm", "l<i>.w_gate", "l<i>.w_up", "l<i>.w_down".
  * host_ptr holds the row-major [out_features, in_features] matrix (or the gain vector) in `dtype`:
  * BD_F32 (rounded to bf16 on device), BD_BF16 (raw bits) or, for the seven linears of a
- * BD_FP8_E4M3 context, BD_FP8_E4M3 codes (OCP e4m3fn) with host_scales = one fp32 per output row.
+ * BD_FP8_E4M3 context, BD_FP8_E4M3 codes (OCP e4m3fn) with host_scales = one fp32 per output row
+ * (the "W8A8 (FP8)" weights of the paper's "System integration" paragraph, here widened to bf16 in
+ * registers and multiplied with bf16 activations: at B <= 32 the step is bound by weight bytes, not by
+ * matrix throughput; embedding table and LM head stay bf16; other dtypes are refused for these seven).
  * Gain vectors are BD_F32 and must be loaded before the matrices they feed (attn_norm before wq/wk/wv,
  * ffn_norm before w_gate/w_up, final_norm before lm_head: the gain is folded into those matrices' columns;
  * BD_E_STATE otherwise).  The call copies synchronously; the caller keeps ownership of host_ptr. */

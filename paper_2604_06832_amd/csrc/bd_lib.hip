@@ -85,6 +85,8 @@ struct bd_ctx {
   int n = 0;
   bool prefilled = false, carry_valid = false;
   bool use_stream = true;          // forwards of up to 32 rows run the kernel with decoupled weight streaming
+  bool fp8 = false;                // decoder linears stored as e4m3 codes + per-row scales
+  float* wscale = nullptr; int wscale_layer = 0; int wscale_off[4] = {0, 0, 0, 0};
   // per-launch timing (bd_k_profile)
   bool prof_on = false;
   std::vector<hipEvent_t> prof_ev;   // pairs
@@ -134,10 +136,13 @@ int make_plan(bd_ctx* c) {
   MegaPlan& P = c->plan;
   P.nwg = c->num_cus; P.L = c->L; P.H = c->H; P.QD = c->QD; P.KVD = c->KVD; P.F = c->F; P.V = c->V; P.D = c->D;
   P.n_q = c->cfg.n_q_heads; P.n_kv = c->cfg.n_kv_heads;
+  const bool fp8 = c->cfg.weight_dtype == BD_FP8_E4M3;
   auto set = [&](int p, int N, int K, bool may_split) -> bool {
     PhasePlan& ph = P.ph[p];
     ph.N = N; ph.KS = ceil_div(K, 32); ph.ksplit = 1;
-    while (ceil_div(ceil_div(ph.KS, ph.ksplit), kWavesPerWG) > kMaxKW) {
+    ph.kgran = (fp8 && p != PH_LM) ? 2 : 1;
+    ph.wbytes = (fp8 && p != PH_LM) ? 1 : 2;
+    while (ph.kgran * ceil_div(ceil_div(ceil_div(ph.KS, ph.kgran), ph.ksplit), kWavesPerWG) > kMaxKW) {
       if (!may_split || P.nwg % (ph.ksplit * 2) != 0) return false;
       ph.ksplit *= 2;
     }
@@ -152,7 +157,7 @@ int make_plan(bd_ctx* c) {
   long long mx = 0;
   for (int wg = 0; wg < P.nwg; ++wg)
     for (int w = 0; w < kWavesPerWG; ++w) {
-      long long u = (long long)P.L * wave_layer_units(P, wg, w) + wave_phase_units(wave_phase(P, PH_LM, wg, w));
+      long long u = (long long)P.L * wave_layer_units(P, wg, w) + wave_phase_units(P.ph[PH_LM], wave_phase(P, PH_LM, wg, w));
       mx = std::max(mx, u);
     }
   P.wave_stride = (mx + 63) / 64 * 64 + 64;            // a little slack: partial-tile lanes read clamped addresses only
@@ -204,16 +209,16 @@ int launch_lm(bd_ctx* c, const MegaArgs& a) {
 }
 
 // The forward kernel with decoupled weight streaming (stream_fwd.h): block sizes up to 32.
-template <int MT, int D>
+template <int MT, int D, bool FP8>
 int launch_stream_inst(bd_ctx* c, const MegaArgs& a) {
   static bool attr_set = false;
   constexpr int lds = stream_lds_bytes<MT>();
   if (!attr_set) {
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_fwd_kernel<MT, D>),
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_fwd_kernel<MT, D, FP8>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((stream_fwd_kernel<MT, D>), dim3(c->plan.nwg), dim3(kFwdThreads), lds, c->stream, a);
+  hipLaunchKernelGGL((stream_fwd_kernel<MT, D, FP8>), dim3(c->plan.nwg), dim3(kFwdThreads), lds, c->stream, a);
   return check_launch();
 }
 
@@ -231,11 +236,17 @@ int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
   if (streamed) {
     if constexpr (MT <= 2) {
       a.attn_max_chunks = stream_attn_max_chunks(c, MT);
-      if (c->D == 128) BD_TRY((launch_stream_inst<MT, 128>(c, a)));
-      else BD_TRY((launch_stream_inst<MT, 64>(c, a)));
+      if (c->fp8) {
+        if (c->D == 128) BD_TRY((launch_stream_inst<MT, 128, true>(c, a)));
+        else BD_TRY((launch_stream_inst<MT, 64, true>(c, a)));
+      } else {
+        if (c->D == 128) BD_TRY((launch_stream_inst<MT, 128, false>(c, a)));
+        else BD_TRY((launch_stream_inst<MT, 64, false>(c, a)));
+      }
       c->bar_epoch += 5u * (unsigned)c->L;
     }
   } else {
+    if (c->fp8) return BD_E_ARG;                            // e4m3 weights are only streamed by the kernel above
     if (c->D == 128) BD_TRY((launch_mega_inst<MT, 128, 2>(c, a)));
     else BD_TRY((launch_mega_inst<MT, 64, 2>(c, a)));
     c->bar_epoch += 5u * (unsigned)c->L;
@@ -265,6 +276,7 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
     p.mask_id = c->cfg.mask_token_id; p.table = c->embed; p.vocab = c->V; p.st = c->st;
     p.rope = c->rope; p.half = c->D / 2; p.theta = c->cfg.rope_theta;
     p.counters = c->counters; p.n_counters = c->n_cntD + c->n_cntA;
+    p.gain0 = c->fp8 ? c->gains : nullptr;
     Prof pr(c, KC_PROLOGUE);
     hipLaunchKernelGGL(prologue_kernel, dim3(M), dim3(kWGThreads), 0, s, p);
     BD_TRY(check_launch());
@@ -275,6 +287,8 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
   a.st = c->st; a.bar = c->bar; a.bar_epoch = c->bar_epoch;
   a.M = M; a.MT = MT; a.mode = mode; a.want_lm = want_lm ? 1 : 0;
   a.xv = c->xv; a.xb = c->xb; a.xb_elems = c->xb_elems; a.ssq = c->ssq; a.ssq_parts = c->ssq_parts; a.Mp = Mp; a.gains = c->gains; a.rms_eps = c->cfg.rms_eps;
+  a.fp8 = c->fp8 ? 1 : 0; a.wscale = c->wscale; a.wscale_layer = c->wscale_layer;
+  for (int i = 0; i < 4; ++i) a.wscale_off[i] = c->wscale_off[i];
   a.rope = c->rope; a.Q = c->q; a.Kc = c->Kc; a.Vc = c->Vc; a.kv_layer_elems = c->kv_layer_elems; a.max_kb = c->max_kb;
   a.ap = c->ap; a.ap_elems = c->ap_elems; a.act = c->act; a.act_elems = c->act_elems;
   a.wsD = c->wsD; a.wsD_layer_floats = c->wsD_layer_floats; a.cntD = c->counters;
@@ -361,8 +375,8 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
     const int G = k.n_q_heads / k.n_kv_heads;
     if (G % 2 != 0) return BD_E_ARG;
   }
-  if (k.weight_dtype == BD_FP8_E4M3) return BD_E_DTYPE;   // fp8 weight streaming is not built yet
-  if (k.weight_dtype != BD_BF16) return BD_E_DTYPE;
+  if (k.weight_dtype != BD_BF16 && k.weight_dtype != BD_FP8_E4M3) return BD_E_DTYPE;
+  if (k.weight_dtype == BD_FP8_E4M3 && k.max_block > 32) return BD_E_ARG;   // e4m3 weights: forwards of up to 32 rows
 
   int dev = 0;
   HIP_TRY(hipGetDevice(&dev));
@@ -375,7 +389,8 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   c->stream = static_cast<hipStream_t>(hip_stream);
   c->device = dev;
   c->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  if (const char* e = getenv("BD_FORWARD_KERNEL")) c->use_stream = strcmp(e, "ring") != 0;
+  c->fp8 = k.weight_dtype == BD_FP8_E4M3;
+  if (const char* e = getenv("BD_FORWARD_KERNEL")) c->use_stream = c->fp8 || strcmp(e, "ring") != 0;
   c->H = k.hidden; c->D = k.head_dim; c->QD = k.n_q_heads * k.head_dim; c->KVD = k.n_kv_heads * k.head_dim;
   c->NQKV = c->QD + 2 * c->KVD; c->F = k.ffn; c->V = k.vocab; c->L = k.n_layers; c->G = k.n_q_heads / k.n_kv_heads;
   c->Mp_max = ceil_div(k.max_block, 16) * 16;
@@ -391,6 +406,11 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   A(c->wstream, (size_t)P.nwg * kWavesPerWG * P.wave_stride * 16);
   A(c->embed, (size_t)c->V * c->H * 2);
   A(c->gains, (2 * L + 1) * c->H * 4);
+  if (c->fp8) {
+    c->wscale_off[0] = 0; c->wscale_off[1] = c->NQKV; c->wscale_off[2] = c->NQKV + c->H; c->wscale_off[3] = c->NQKV + c->H + 2 * c->F;
+    c->wscale_layer = c->NQKV + 2 * c->H + 2 * c->F;
+    A(c->wscale, L * (size_t)c->wscale_layer * 4);
+  }
   A(c->Kc, c->kv_layer_elems * L * 2);
   A(c->Vc, c->kv_layer_elems * L * 2);
   A(c->xv, (2 * L + 1) * Mp * c->H * 4);
@@ -458,7 +478,6 @@ void bd_destroy(bd_ctx* c) {
 int bd_load_weight(bd_ctx* c, const char* name, const void* host_ptr, size_t bytes, int dtype,
                    const float* host_scales) {
   if (c == nullptr || name == nullptr || host_ptr == nullptr) return BD_E_ARG;
-  (void)host_scales;
   std::string nm(name);
   int layer = -1;
   std::string base = nm;
@@ -499,6 +518,30 @@ int bd_load_weight(bd_ctx* c, const char* name, const void* host_ptr, size_t byt
       if (c->loaded[layer < 0 ? c->L : layer] & used_by) return BD_E_STATE;
     }
     HIP_TRY(hipMemcpy(gain_dst, host_ptr, bytes, hipMemcpyHostToDevice));
+  } else if (c->fp8 && ph >= 0 && ph != PH_LM) {
+    // one of the seven decoder linears of an e4m3 context: codes + one fp32 scale per output row
+    if (dtype != BD_FP8_E4M3) return BD_E_DTYPE;
+    if (host_scales == nullptr || bytes != (size_t)rows * K) return BD_E_ARG;
+    void* stage = nullptr;
+    float* sc = nullptr;
+    HIP_TRY(hipMalloc(&stage, bytes));
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&sc), (size_t)rows * 4);
+    if (e == hipSuccess) e = hipMemcpy(stage, host_ptr, bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(sc, host_scales, (size_t)rows * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) {
+      hipLaunchKernelGGL(pack_stream_fp8_kernel, dim3(4096), dim3(256), 0, c->stream, (const uint8_t*)stage, rows, K, c->plan,
+                         ph, layer, row_base, row_map, c->D, reinterpret_cast<uint8_t*>(c->wstream));
+      hipLaunchKernelGGL(scatter_scales_kernel, dim3(64), dim3(256), 0, c->stream, sc, rows, row_base, row_map, c->D,
+                         c->wscale + (size_t)layer * c->wscale_layer + c->wscale_off[ph]);
+      e = hipGetLastError();
+      if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    }
+    (void)hipFree(stage);
+    if (sc) (void)hipFree(sc);
+    if (e != hipSuccess) {
+      snprintf(g_last_error, sizeof g_last_error, "weight upload failed: %s", hipGetErrorString(e));
+      return BD_E_HIP;
+    }
   } else {
     if (dtype != BD_F32 && dtype != BD_BF16) return BD_E_DTYPE;
     const float* col_gain = nullptr;
@@ -551,7 +594,7 @@ int bd_prefill(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* d
   hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, s, c->st, 0, 1);
   BD_TRY(check_launch());
   c->n = 0; c->prefilled = false; c->carry_valid = false;
-  const int step = c->cfg.max_block;
+  const int step = c->cfg.max_block;                   // (at most 32 with e4m3 weights, checked at creation)
   for (int off = 0; off < total; off += step) {
     const int M = std::min(step, total - off);
     const bool last = off + M >= total;
@@ -685,7 +728,8 @@ int bd_read_rows(bd_ctx* c, int32_t* dev_cand, float* dev_conf, int rows) {
 int64_t bd_forward_bytes(const bd_ctx* c) {
   if (c == nullptr) return BD_E_ARG;
   const int64_t per_layer = (int64_t)c->H * c->NQKV + (int64_t)c->QD * c->H + 3ll * c->H * c->F;
-  const int64_t w = (per_layer * c->L + (int64_t)c->V * c->H) * 2;
+  const int64_t w = c->fp8 ? (per_layer + 4ll * c->wscale_layer) * c->L + (int64_t)c->V * c->H * 2
+                           : (per_layer * c->L + (int64_t)c->V * c->H) * 2;
   const int64_t kv = (int64_t)c->n * c->L * 2 * c->KVD * 2;
   return w + kv;
 }

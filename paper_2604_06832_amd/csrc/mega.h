@@ -41,6 +41,9 @@ struct PhasePlan {
   int KS;       // k-steps
   int ksplit;   // workgroups that share an output row range and split K
   int RW;       // rows of the largest row range (a multiple of 16)
+  int kgran;    // k-steps per unit of the K split: 1 (bf16 weights) or 2 (fp8 weights: a 1-KiB fragment of 16 rows
+                // x 64 k holds two k-steps, so wavefront ranges start and end on even k-steps)
+  int wbytes;   // bytes per streamed weight element: 2 (bf16) or 1 (e4m3)
 };
 // Row ranges are whole 16-row tiles, spread over the nwg/ksplit row groups as evenly as whole tiles allow
 // (group g holds tiles [T*g/G, T*(g+1)/G)).  So every weight fragment of the stream is a full 1 KiB.
@@ -73,17 +76,22 @@ __host__ __device__ inline WavePhase wave_phase(const MegaPlan& P, int p, int wg
     r.row0 = t0 << 4;
     r.rows = (t1 - t0) << 4;
   }
-  const int k0 = (int)((long long)ph.KS * r.kg / ph.ksplit), k1 = (int)((long long)ph.KS * (r.kg + 1) / ph.ksplit);
+  // the K split works on units of kgran k-steps (the last unit may reach past KS: zero weights, zero activations)
+  const int KU = (ph.KS + ph.kgran - 1) / ph.kgran;
+  const int k0 = (int)((long long)KU * r.kg / ph.ksplit), k1 = (int)((long long)KU * (r.kg + 1) / ph.ksplit);
   const int len = k1 - k0;
-  r.w0 = k0 + len * w / kWavesPerWG;
-  r.KW = k0 + len * (w + 1) / kWavesPerWG - r.w0;
+  const int u0 = k0 + len * w / kWavesPerWG, u1 = k0 + len * (w + 1) / kWavesPerWG;
+  r.w0 = u0 * ph.kgran;
+  r.KW = (u1 - u0) * ph.kgran;
   return r;
 }
-// 16-byte units one wavefront streams in a phase: rows x KW fragments of 4 units (64 bytes per row)
-__host__ __device__ inline long long wave_phase_units(const WavePhase& wp) { return (long long)wp.rows * 4 * wp.KW; }
+// 16-byte units one wavefront streams in a phase: per row and k-step 32 weights of wbytes each
+__host__ __device__ inline long long wave_phase_units(const PhasePlan& ph, const WavePhase& wp) {
+  return (long long)wp.rows * 2 * ph.wbytes * wp.KW;
+}
 __host__ __device__ inline long long wave_layer_units(const MegaPlan& P, int wg, int w) {
   long long s = 0;
-  for (int p = 0; p < PH_LM; ++p) s += wave_phase_units(wave_phase(P, p, wg, w));
+  for (int p = 0; p < PH_LM; ++p) s += wave_phase_units(P.ph[p], wave_phase(P, p, wg, w));
   return s;
 }
 // Position (16-byte units from the wavefront's phase start) of row `lr` (local to the row range),
@@ -114,6 +122,12 @@ struct MegaArgs {
                               // tile slot of the O phase, even versions one per tile slot of the DOWN phase
   int Mp;
   const float* gains;         // [2L+1][H]: attn_norm l, ffn_norm l, ..., final_norm
+  int fp8;                    // the decoder linears are e4m3 codes with one scale per output row: the scale multiplies
+                              // the accumulators, and the norm gains (which cannot be folded into the codes) multiply
+                              // the bf16 copies of the residual versions that feed them
+  const float* wscale;        // [L][wscale_layer] scales in phase-row order: QKV | O | gate/up | down
+  int wscale_layer;
+  int wscale_off[4];
   float rms_eps;
   const float2* rope;         // [Mp][D/2]
   u16* Q;                     // [L][Mp][n_q][D]  (dims in rotary-pair order)
@@ -238,7 +252,7 @@ struct Cursor {
         r.KW = wp.KW;
         r.R0 = min(16, wp.rows - 32 * c);
         r.R1 = (2 * c + 1 < n_tiles) ? min(16, wp.rows - 32 * c - 16) : 0;
-        pos += wp.KW * (r.R0 + r.R1) * 64;
+        pos += wp.KW * (r.R0 + r.R1) * 32 * P.ph[p].wbytes;
         ++c;
         return r;
       }
@@ -328,6 +342,7 @@ struct PhaseCtx {
 struct EpiPre {
   float2 cs[2];   // QKV: (cos, sin) of this lane's two rotary pairs
   f32x4 xo;       // O: the four residual values this lane adds to
+  f32x4 gn;       // O (fp8 weights): gains of the next norm for this lane's four channels
 };
 
 // DC: head dimension when the caller knows it at compile time (0: taken from the plan).
@@ -397,8 +412,12 @@ __device__ inline void gemm_epilogue(const MegaArgs& a, const PhaseCtx& pc, cons
       } else {
         for (int e = 0; e < nrows; ++e) { o[e] = xo[e] + v[e]; st_wt_f32(xn + e, o[e]); }
       }
-      store_xb(a.xb + (size_t)ver * a.xb_elems, token, r, nrows, o, a.MT);
       ss = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
+      if (a.fp8) {
+        if constexpr (USE_PRE) { for (int e = 0; e < 4; ++e) o[e] *= pre.gn[e]; }
+        else { for (int e = 0; e < nrows; ++e) o[e] *= a.gains[(size_t)ver * P.H + r + e]; }
+      }
+      store_xb(a.xb + (size_t)ver * a.xb_elems, token, r, nrows, o, a.MT);
     }
     ss += __shfl_xor(ss, 16);
     ss += __shfl_xor(ss, 32);
@@ -1072,6 +1091,7 @@ struct PrologueArgs {
   DevState* st;
   float2* rope; int half; float theta;
   unsigned* counters; int n_counters;
+  const float* gain0;                         // fp8 weights: gain of the first norm, applied to the bf16 copy (else nullptr)
 };
 
 __global__ __launch_bounds__(kWGThreads) void prologue_kernel(PrologueArgs a) {
@@ -1112,7 +1132,7 @@ __global__ __launch_bounds__(kWGThreads) void prologue_kernel(PrologueArgs a) {
   for (int c = threadIdx.x; c < a.H; c += kWGThreads) {
     const float v = id < 0 ? a.embeds[(size_t)p * a.H + c] : bf16_bits_to_f32(a.table[(size_t)id * a.H + c]);
     a.x0[(size_t)r * a.H + c] = v;
-    a.xb0[xp_index(r, c, a.MT)] = f32_to_bf16_bits(v);
+    a.xb0[xp_index(r, c, a.MT)] = f32_to_bf16_bits(a.gain0 != nullptr ? v * a.gain0[c] : v);
     ss += v * v;
   }
 #pragma unroll
@@ -1160,7 +1180,7 @@ __global__ void pack_stream_kernel(const SrcT* __restrict__ src, int n_rows, int
     while (ks >= wp.w0 + wp.KW) { ++w; wp = wave_phase(P, ph, wg, w); }
     long long pos = (long long)(wg * kWavesPerWG + w) * P.wave_stride;
     pos += (ph == PH_LM) ? (long long)P.L * wave_layer_units(P, wg, w) : (long long)layer * wave_layer_units(P, wg, w);
-    for (int q = 0; q < ph && ph != PH_LM; ++q) pos += wave_phase_units(wave_phase(P, q, wg, w));
+    for (int q = 0; q < ph && ph != PH_LM; ++q) pos += wave_phase_units(P.ph[q], wave_phase(P, q, wg, w));
     pos += stream_pos(wp.rows, wp.KW, lr, ks - wp.w0, kq);
     u16* dst = stream + (size_t)pos * 8;
 #pragma unroll
@@ -1176,6 +1196,69 @@ __global__ void pack_stream_kernel(const SrcT* __restrict__ src, int n_rows, int
       }
       dst[e] = o;
     }
+  }
+}
+
+// e4m3 codes of one matrix into the stream: a fragment is 16 rows x 64 k (two k-steps); lane (row i, k-quarter kq)
+// holds 8 codes of the even k-step (k = 64j + 8kq ..) followed by 8 codes of the odd one (k = 64j + 32 + 8kq ..).
+__global__ void pack_stream_fp8_kernel(const uint8_t* __restrict__ src, int n_rows, int K, MegaPlan P, int ph, int layer,
+                                       int row_base, int row_map, int D, uint8_t* __restrict__ stream) {
+  const PhasePlan& pp = P.ph[ph];
+  const int KP = (pp.KS + 1) / 2;                            // k-step pairs
+  const size_t total = (size_t)n_rows * KP * 4;              // one thread per (row, pair, k-quarter)
+  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+    const int kq = idx & 3;
+    const int kp = (int)((idx >> 2) % KP);
+    const int rs = (int)(idx / ((size_t)KP * 4));
+    int r;
+    if (row_map == 1) {
+      const int h = rs / D, d = rs % D, half = D >> 1;
+      r = row_base + h * D + (d < half ? 2 * d : 2 * (d - half) + 1);
+    } else if (row_map == 2) {
+      r = row_base + 2 * rs;
+    } else {
+      r = row_base + rs;
+    }
+    const int ng = group_of_tile(pp.N >> 4, P.nwg / pp.ksplit, r >> 4);
+    const int lr = r - (tile0_of_group(pp.N >> 4, P.nwg / pp.ksplit, ng) << 4);
+    const int ks = 2 * kp;
+    int kg = 0;
+    while ((int)((long long)KP * (kg + 1) / pp.ksplit) <= kp) ++kg;
+    const int wg = ng * pp.ksplit + kg;
+    int w = 0;
+    WavePhase wp = wave_phase(P, ph, wg, 0);
+    while (ks >= wp.w0 + wp.KW) { ++w; wp = wave_phase(P, ph, wg, w); }
+    long long pos = (long long)(wg * kWavesPerWG + w) * P.wave_stride + (long long)layer * wave_layer_units(P, wg, w);
+    for (int q = 0; q < ph; ++q) pos += wave_phase_units(P.ph[q], wave_phase(P, q, wg, w));
+    // fragment index inside the phase: chunks of two tiles, pairs in order, tiles side by side
+    const int tile = lr >> 4, c = tile >> 1, t = tile & 1;
+    const int n_tiles = wp.rows >> 4;
+    const int nt = (2 * c + 1 < n_tiles) ? 2 : 1;
+    const int KWP = wp.KW >> 1;
+    const long long frag = (long long)c * 2 * KWP + (long long)((ks - wp.w0) >> 1) * nt + t;
+    uint8_t* dst = stream + ((size_t)pos + (size_t)frag * 64 + kq * 16 + (lr & 15)) * 16;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int k = ks * 32 + (e >> 3) * 32 + kq * 8 + (e & 7);
+      dst[e] = k < K ? src[(size_t)rs * K + k] : (uint8_t)0;
+    }
+  }
+}
+
+// Per-output-row scales of one fp8 matrix into phase-row order.
+__global__ void scatter_scales_kernel(const float* __restrict__ src, int n_rows, int row_base, int row_map, int D,
+                                      float* __restrict__ dst) {
+  for (int rs = blockIdx.x * blockDim.x + threadIdx.x; rs < n_rows; rs += gridDim.x * blockDim.x) {
+    int r;
+    if (row_map == 1) {
+      const int h = rs / D, d = rs % D, half = D >> 1;
+      r = row_base + h * D + (d < half ? 2 * d : 2 * (d - half) + 1);
+    } else if (row_map == 2) {
+      r = row_base + 2 * rs;
+    } else {
+      r = row_base + rs;
+    }
+    dst[r] = src[rs];
   }
 }
 

@@ -177,41 +177,133 @@ __device__ inline bf16x8 ring_take(Ring& rg, int lane) {
 }
 __device__ inline void ring_release(Ring& rg) { lds_st32(rg.consumed_addr, rg.taken); }
 
-// One chunk (one or two 16-row tiles x KW k-steps) out of the ring, four k-steps at a time: the LDS reads of a
-// batch are all issued before its first MFMA.
+// One chunk (one or two 16-row tiles x KW k-steps) out of the ring, in batches of kBK k-steps, software
+// pipelined over two small register sets: the LDS reads of batch b+1 are issued (and their slots handed back to
+// the producer: LDS executes a wavefront's operations in order) before the MFMAs of batch b.
+#ifndef BD_BK
+#define BD_BK 2
+#endif
+constexpr int kBK = BD_BK;
+template <int NT>
+__device__ inline void ring_fetch(Ring& rg, FwdSync& sy, DevState* st, int nk, bf16x8 (&f)[kBK][NT], int lane) {
+  ring_need(rg, sy, nk * NT, st);
+#pragma unroll
+  for (int u = 0; u < kBK; ++u)
+    if (u < nk) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) f[u][t] = ring_take(rg, lane);
+    }
+  ring_release(rg);
+  asm volatile("" ::: "memory");                            // the reads are issued before anything that follows
+}
+// The same with the number of k-steps known at compile time: straight-line code, so the compiler's LDS wait
+// counts leave the reads of the next batch in flight during the MFMAs of this one.
+template <int MT, bool TWO, int K0, int KWC>
+__device__ inline void consume_chunk_static(Ring& rg, FwdSync& sy, DevState* st, const bf16x8 (&xk)[kMaxKW][MT],
+                                            f32x4 (&acc)[kT][MT], int lane) {
+  static_assert(KWC % kBK == 0, "whole batches");
+  constexpr int NT = TWO ? 2 : 1;
+  static_assert(KWC * NT <= kSlots, "a run must fit the ring");
+  bf16x8 f[2][kBK][NT];
+  ring_need(rg, sy, KWC * NT, st);                          // one check for the whole run
+#pragma unroll
+  for (int u = 0; u < kBK; ++u)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) f[0][u][t] = ring_take(rg, lane);
+#pragma unroll
+  for (int b = 0; b < KWC / kBK; ++b) {
+    if (b + 1 < KWC / kBK) {
+#pragma unroll
+      for (int u = 0; u < kBK; ++u)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) f[(b + 1) & 1][u][t] = ring_take(rg, lane);
+    }
+#pragma unroll
+    for (int u = 0; u < kBK; ++u)
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[b & 1][u][t], xk[K0 + b * kBK + u][mt], acc[t][mt], 0, 0, 0);
+  }
+  ring_release(rg);
+}
+
 template <int MT, bool TWO>
 __device__ inline void consume_chunk(Ring& rg, FwdSync& sy, DevState* st, const bf16x8 (&xk)[kMaxKW][MT], int KW,
                                      f32x4 (&acc)[kT][MT], int lane) {
   constexpr int NT = TWO ? 2 : 1;
-  constexpr int CB = 4;                                  // k-steps per batch
+  if (KW == kMaxKW) {                                       // the common case: a full K range, in runs that fit the ring
+    if constexpr (TWO) {
+      consume_chunk_static<MT, TWO, 0, kMaxKW / 2>(rg, sy, st, xk, acc, lane);
+      consume_chunk_static<MT, TWO, kMaxKW / 2, kMaxKW / 2>(rg, sy, st, xk, acc, lane);
+    } else {
+      consume_chunk_static<MT, TWO, 0, kMaxKW>(rg, sy, st, xk, acc, lane);
+    }
+    return;
+  }
+  bf16x8 f[2][kBK][NT];
+  ring_fetch<NT>(rg, sy, st, min(kBK, KW), f[0], lane);
 #pragma unroll
-  for (int kb = 0; kb < kMaxKW; kb += CB) {
+  for (int b = 0; b < kMaxKW / kBK; ++b) {
+    const int kb = b * kBK;
     if (kb < KW) {
-      const int nk = min(CB, KW - kb);
-      ring_need(rg, sy, nk * NT, st);
-      if (nk == CB) {
-        bf16x8 af[CB][NT];
+      if (kb + kBK < KW) ring_fetch<NT>(rg, sy, st, min(kBK, KW - kb - kBK), f[(b + 1) & 1], lane);
+      const int nk = min(kBK, KW - kb);
 #pragma unroll
-        for (int u = 0; u < CB; ++u)
-#pragma unroll
-          for (int t = 0; t < NT; ++t) af[u][t] = ring_take(rg, lane);
-#pragma unroll
-        for (int u = 0; u < CB; ++u)
+      for (int u = 0; u < kBK; ++u)
+        if (u < nk) {
 #pragma unroll
           for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-              acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[u][t], xk[kb + u][mt], acc[t][mt], 0, 0, 0);
-      } else {
+              acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[b & 1][u][t], xk[kb + u][mt], acc[t][mt], 0, 0, 0);
+        }
+    }
+  }
+}
+
+// e4m3 weights: one ring fragment holds a 16-row tile for TWO k-steps (lane: 8 codes of the even step, then 8 of
+// the odd one).  The codes are widened to bf16 in registers (exact) and multiplied with the bf16 MFMA; the
+// per-row scale is applied to the accumulators afterwards.
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+__device__ inline void widen_e4m3(const u32x4 raw, bf16x8& even, bf16x8& odd) {
+  union { bf16x8 v; bf16x2_t h[4]; } a, b;
+  a.h[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[0], 1.0f, false);
+  a.h[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[0], 1.0f, true);
+  a.h[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[1], 1.0f, false);
+  a.h[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[1], 1.0f, true);
+  b.h[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[2], 1.0f, false);
+  b.h[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[2], 1.0f, true);
+  b.h[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[3], 1.0f, false);
+  b.h[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(raw[3], 1.0f, true);
+  even = a.v;
+  odd = b.v;
+}
+
+template <int MT, bool TWO>
+__device__ inline void consume_chunk_fp8(Ring& rg, FwdSync& sy, DevState* st, const bf16x8 (&xk)[kMaxKW][MT], int KW,
+                                         f32x4 (&acc)[kT][MT], int lane) {
+  constexpr int NT = TWO ? 2 : 1;
 #pragma unroll
-        for (int u = 0; u < CB - 1; ++u) {
-          if (u < nk) {
+  for (int kb = 0; kb < kMaxKW; kb += 4) {                // two fragments per tile and batch
+    if (kb < KW) {
+      const int np = min(2, (KW - kb) >> 1);               // k-step pairs in this batch (KW is even)
+      ring_need(rg, sy, np * NT, st);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-              const bf16x8 af = ring_take(rg, lane);
+      for (int u = 0; u < 2; ++u) {
+        if (u < np) {
+          u32x4 raw[NT];
 #pragma unroll
-              for (int mt = 0; mt < MT; ++mt)
-                acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, xk[kb + u][mt], acc[t][mt], 0, 0, 0);
+          for (int t = 0; t < NT; ++t) raw[t] = __builtin_bit_cast(u32x4, ring_take(rg, lane));
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+            bf16x8 we, wo;
+            widen_e4m3(raw[t], we, wo);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+              acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(we, xk[kb + 2 * u][mt], acc[t][mt], 0, 0, 0);
+              acc[t][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wo, xk[kb + 2 * u + 1][mt], acc[t][mt], 0, 0, 0);
             }
           }
         }
@@ -229,7 +321,7 @@ struct FwdCtx {
 };
 
 // ---- one GEMM phase (consumer wavefronts) ------------------------------------------------------------------------
-template <int MT, int PH, int D>
+template <int MT, int PH, int D, bool FP8>
 __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg, FwdSync& sy, int wave, int lane_in) {
   int lane = lane_in;
   asm volatile("" : "+v"(lane));
@@ -297,6 +389,16 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
       EpiPre pre;
       pre.cs[0] = pre.cs[1] = make_float2(0.f, 0.f);
       pre.xo = f32x4{0.f, 0.f, 0.f, 0.f};
+      pre.gn = f32x4{1.f, 1.f, 1.f, 1.f};
+      f32x4 wsc = f32x4{1.f, 1.f, 1.f, 1.f};                 // fp8: scales of this lane's four output rows
+      if constexpr (FP8) {
+        static_assert(kT * MT <= kWavesPerWG, "one epilogue element per consumer");
+        if (wave < kT * MT) {
+          const int lr = (2 * c + wave / MT) * 16 + 4 * (lane >> 4);
+          if (lr < wp.rows)
+            wsc = *reinterpret_cast<const f32x4*>(a.wscale + (size_t)pc.layer * a.wscale_layer + a.wscale_off[PH] + wp.row0 + lr);
+        }
+      }
       if constexpr (PH == PH_QKV || PH == PH_O) {
         static_assert(kT * MT <= kWavesPerWG, "one epilogue element per consumer");
         if (wave < kT * MT) {
@@ -313,8 +415,10 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
                   pre.cs[pr] = a.rope[(size_t)token * (D >> 1) + ((rp % D) >> 1)];
               }
             } else {
-              if (min(4, wp.rows - lr) == 4 && (r & 3) == 0)
+              if (min(4, wp.rows - lr) == 4 && (r & 3) == 0) {
                 pre.xo = *reinterpret_cast<const f32x4*>(a.xv + ((size_t)(2 * pc.layer) * a.Mp + token) * P.H + r);
+                if constexpr (FP8) pre.gn = *reinterpret_cast<const f32x4*>(a.gains + (size_t)(2 * pc.layer + 1) * P.H + r);
+              }
             }
           }
         }
@@ -324,9 +428,22 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
       for (int t = 0; t < kT; ++t)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[t][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if constexpr (PH == PH_QKV) {
+        if (c == 0) {
+          // (trace) the activations have arrived when the first MFMA could start
+          unsigned x = __builtin_bit_cast(u32x4, xk[kMaxKW - 1][MT - 1])[0] | __builtin_bit_cast(u32x4, xk[0][0])[0];
+          asm volatile("" ::"v"(x));
+          BD_SUBTS2(6);
+        }
+      }
       if (wp.KW > 0) {
-        if (two) consume_chunk<MT, true>(rg, sy, a.st, xk, wp.KW, acc, lane);
-        else consume_chunk<MT, false>(rg, sy, a.st, xk, wp.KW, acc, lane);
+        if constexpr (FP8) {
+          if (two) consume_chunk_fp8<MT, true>(rg, sy, a.st, xk, wp.KW, acc, lane);
+          else consume_chunk_fp8<MT, false>(rg, sy, a.st, xk, wp.KW, acc, lane);
+        } else {
+          if (two) consume_chunk<MT, true>(rg, sy, a.st, xk, wp.KW, acc, lane);
+          else consume_chunk<MT, false>(rg, sy, a.st, xk, wp.KW, acc, lane);
+        }
       }
       if (c < 3) BD_SUBTS2(3 + 2 * c);
       // the four consumers hold disjoint K ranges: sum them through LDS in fixed order
@@ -357,6 +474,7 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
         v += red[(2 * (kT * MT) + idx) * 64 + lane];
         v += red[(3 * (kT * MT) + idx) * 64 + lane];
         if constexpr (kNorm) v *= rs[mt];
+        if constexpr (FP8) v *= wsc;
         if constexpr (PH == PH_QKV) { if (c == 0) BD_SUBTS2(5); }
         gemm_epilogue<MT, PH, D, (PH == PH_QKV || PH == PH_O)>(a, pc, wp, c, t, mt, v, lane, rmax, ridx, rsum, pre);
       }
@@ -390,7 +508,7 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
     const float* src = a.wsD + (size_t)pc.layer * a.wsD_layer_floats;
     for (int idx0 = wave; idx0 < n_idx; idx0 += 2 * kWavesPerWG) {
       // two pairs per round, every load of the round in flight at once
-      f32x4 pv[2][8], xov[2];
+      f32x4 pv[2][8], xov[2], gnv[2];
       bool on[2], vec[2];
       int tok[2], rr[2], nr[2], gtt[2];
 #pragma unroll
@@ -405,6 +523,10 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
         nr[j] = min(4, wp.rows - lr);
         vec[j] = nr[j] == 4 && (rr[j] & 3) == 0;
         xov[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        gnv[j] = f32x4{1.f, 1.f, 1.f, 1.f};
+        if constexpr (FP8) {
+          if (on[j] && vec[j] && ver < 2 * P.L) gnv[j] = *reinterpret_cast<const f32x4*>(a.gains + (size_t)ver * P.H + rr[j]);
+        }
         if (on[j]) {
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
@@ -439,8 +561,12 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
           } else {
             for (int e = 0; e < nrows; ++e) { o[e] = xo[e] + v[e]; st_wt_f32(xn + e, o[e]); }
           }
-          store_xb(a.xb + (size_t)ver * a.xb_elems, token, r, nrows, o, a.MT);
           ss = o[0] * o[0] + o[1] * o[1] + o[2] * o[2] + o[3] * o[3];
+          if constexpr (FP8) {
+            if (ver < 2 * P.L)
+              for (int e = 0; e < nrows; ++e) o[e] *= gnv[j][e];
+          }
+          store_xb(a.xb + (size_t)ver * a.xb_elems, token, r, nrows, o, a.MT);
         }
         ss += __shfl_xor(ss, 16);
         ss += __shfl_xor(ss, 32);
@@ -787,7 +913,7 @@ __device__ inline bool stream_grid_barrier(const MegaArgs& a, FwdSync& sy, unsig
 // ---- the kernel ------------------------------------------------------------------------------------------------
 template <int MT> constexpr int stream_lds_bytes() { return kWavesPerWG * kSlots * 1024 + kShareBytes; }
 
-template <int MT, int D>
+template <int MT, int D, bool FP8>
 __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) {
   static_assert(2 * kWavesPerWG * kT * MT * 1024 <= kShareBytes, "K-reduction buffers exceed the shared region");
   static_assert(kWavesPerWG * (D / 16) * 1024 + (8 * 16 + 64 * 16 + 16) * 4 <= kShareBytes, "attention merge buffers exceed the shared region");
@@ -836,7 +962,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
   bool alive = true;
   for (int l = 0; l < P.L && alive; ++l) {
     fc.pc.layer = l;
-    stream_gemm_phase<MT, PH_QKV, D>(a, fc, rg, sy, wave, lane);
+    stream_gemm_phase<MT, PH_QKV, D, FP8>(a, fc, rg, sy, wave, lane);
     BD_TS2();
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
@@ -846,17 +972,17 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
     if (!alive) break;
-    stream_gemm_phase<MT, PH_O, D>(a, fc, rg, sy, wave, lane);
+    stream_gemm_phase<MT, PH_O, D, FP8>(a, fc, rg, sy, wave, lane);
     BD_TS2();
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
     if (!alive) break;
-    stream_gemm_phase<MT, PH_GU, D>(a, fc, rg, sy, wave, lane);
+    stream_gemm_phase<MT, PH_GU, D, FP8>(a, fc, rg, sy, wave, lane);
     BD_TS2();
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
     if (!alive) break;
-    stream_gemm_phase<MT, PH_DOWN, D>(a, fc, rg, sy, wave, lane);
+    stream_gemm_phase<MT, PH_DOWN, D, FP8>(a, fc, rg, sy, wave, lane);
     BD_TS2();
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();

@@ -6,6 +6,7 @@ from oracle.bd_oracle import BlockDiffusionOracle
 from paper_2604_06832_amd import binding, inputs
 
 BF16_LOGIT_TOL = 3e-2      # max-abs logit error as a fraction of the oracle's logit range (bf16 path)
+FP8_LOGIT_TOL = 1e-1       # the same bar for the path with e4m3 decoder weights
 MARGIN = 1e-2              # ids are compared where the oracle's top-2 logit margin exceeds this
 
 
@@ -43,7 +44,9 @@ class Pair:
     def __init__(self, shape, weights, max_seq, max_block=64, oracle_dtype=np.float64, gpu_weights=None):
         self.shape = shape
         self.o = BlockDiffusionOracle(shape, weights, dtype=oracle_dtype)
-        self.ctx = binding.Context(shape, max_seq=max_seq, max_block=max_block)
+        fp8 = weights["l0.wq"].dtype == np.uint8
+        self.ctx = binding.Context(shape, max_seq=max_seq, max_block=min(max_block, 32) if fp8 else max_block,
+                                   weight_dtype=binding.BD_FP8_E4M3 if fp8 else binding.BD_BF16)
         self.ctx.load_model(gpu_weights if gpu_weights is not None else weights,
                             as_bf16_bits=gpu_weights is None and _is_bf16(weights))
         self.ctx.bd_debug_logits(True)
@@ -172,7 +175,7 @@ def _apply_rule(conf, masked, tau, fixed_k):
 
 
 def _is_bf16(weights):
-    w = weights["l0.wq"]
+    w = weights["lm_head"]
     return w.dtype == np.float32 and not np.any(w.view(np.uint32) & np.uint32(0xFFFF))
 
 

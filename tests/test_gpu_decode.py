@@ -12,7 +12,7 @@ import torch
 
 from oracle.bd_oracle import BlockDiffusionOracle
 from paper_2604_06832_amd import binding, inputs
-from tests.gpu_util import MARGIN, Pair, check_argmax_ids, assert_logits_close, fresh_block, top2_margin
+from tests.gpu_util import FP8_LOGIT_TOL, MARGIN, Pair, check_argmax_ids, assert_logits_close, fresh_block, top2_margin
 
 pytestmark = pytest.mark.gpu
 
@@ -190,6 +190,58 @@ def test_long_prefix_3b_shaped_two_layers():
     for _ in range(2):
         tok, msk, _ = p.denoise_step(tok, msk, 0.9, fixed_k=4)
     p.close()
+
+
+# ---- configs[4]: e4m3 decoder weights with per-output-channel scales ---------------------------------------
+
+def test_fp8_tiny_block_decode():
+    _say("tiny config, e4m3 decoder linears (seed 2), jittered norm gains")
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 2, "fp8", norm_gain_jitter=0.1, threads=1)
+    emb, ids = inputs.make_prompt(shape, 40, 37, seed=104)
+    p = Pair(shape, w, max_seq=256)
+    p.prefill(emb, ids)
+    p.check_carry(logit_err=0.05)
+    p.check_kv(0, 77, frac=6e-2)
+    tok, msk = fresh_block(shape, 8)
+    while msk.any():
+        tok, msk, _ = p.denoise_step(tok, msk, 0.9, fixed_k=3, frac=FP8_LOGIT_TOL)
+    p.commit(tok, frac=FP8_LOGIT_TOL)
+    p.close()
+
+
+@pytest.mark.parametrize("B", [4, 16, 32])
+def test_fp8_3b_shaped_two_layers(B):
+    _say(f"3B-shaped x2 layers, e4m3 decoder linears, B={B}")
+    shape = _wide(2)
+    w = inputs.make_weights(shape, 2, "fp8", threads=8)
+    emb, ids = inputs.make_prompt(shape, 150, 83, seed=104)
+    p = Pair(shape, w, max_seq=233 + 64)
+    p.prefill(emb, ids)
+    p.check_kv(0, 233, frac=6e-2)
+    tok, msk = fresh_block(shape, B)
+    K = min(4, B - 1)
+    while msk.any():
+        tok, msk, _ = p.denoise_step(tok, msk, 0.9, fixed_k=K, frac=FP8_LOGIT_TOL)
+    p.commit(tok, frac=FP8_LOGIT_TOL)
+    p.check_kv(233, B, frac=6e-2)
+    assert p.ctx.bd_forward_bytes() == (shape.weight_elements() - shape.vocab * shape.hidden) \
+        + 2 * shape.vocab * shape.hidden + 4 * 2 * (shape.q_dim + 2 * shape.kv_dim + 2 * shape.hidden + 2 * shape.ffn) \
+        + 2 * 2 * 2 * shape.kv_dim * (233 + B)
+    p.close()
+
+
+def test_fp8_context_rejects_wide_blocks_and_bf16_linears():
+    shape = inputs.TINY
+    with pytest.raises(binding.BdError) as e:
+        binding.Context(shape, max_seq=128, max_block=64, weight_dtype=binding.BD_FP8_E4M3)
+    assert e.value.code == binding.BD_E_ARG
+    ctx = binding.Context(shape, max_seq=128, max_block=32, weight_dtype=binding.BD_FP8_E4M3)
+    ctx.bd_load_weight("l0.attn_norm", np.ones(shape.hidden, np.float32))
+    with pytest.raises(binding.BdError) as e:
+        ctx.bd_load_weight("l0.wq", np.zeros((shape.q_dim, shape.hidden), np.float32))
+    assert e.value.code == binding.BD_E_DTYPE
+    ctx.close()
 
 
 # ---- configs[1] at full size ----------------------------------------------------------------------------
