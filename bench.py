@@ -21,6 +21,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes one launch of the layers kernel moves on the default workload, from hardware counters
+# (profiles/streaming_forward_config1_hbm_traffic.txt: FETCH_SIZE and WRITE_SIZE, scaled by a reference copy)
+MEASURED_TRAFFIC_BYTES = {("bf16", 36, 1024, 32): 6.360e9}
 
 
 def main():
@@ -130,7 +133,8 @@ def main():
         ms, cnt, nbytes = stream[dom]
         achieved = nbytes / (ms / cnt * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                    "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.weights, args.layers, args.prefix, B)) if dom == "layers" else None,
                     "avg_kernel_us": round(ms / cnt * 1e3, 2), "launches": cnt,
                     "classes": {k: {"avg_us": round(v[0] / v[1] * 1e3, 2), "launches": v[1],
                                     "GBps": round(v[2] / (v[0] / v[1] * 1e-3) / 1e9, 1) if v[2] else None}
