@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--fixed-k", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-pass", action="store_true")
+    ap.add_argument("--verify", action="store_true",
+                    help="also time the speculative verify pass (configs[3]): B drafted ids, one causal forward + accept")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -123,6 +125,21 @@ def main():
     total_bytes = sum((n_den + 1) * (w_bytes + kv_pos_bytes * (args.prefix + b * B)) for b in range(args.steps))
     step_frac = total_bytes / elapsed / 1e9 / HBM_PEAK_GBS
 
+    verify_ms = None
+    if args.verify:
+        draft = torch.randint(0, shape.vocab - 1, (B,), dtype=torch.int32, device="cuda")
+        pred = torch.zeros(B, dtype=torch.int32, device="cuda")
+        nacc = torch.zeros(1, dtype=torch.int32, device="cuda")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ctx.bd_verify_block(draft, False, pred, nacc)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            ctx.bd_verify_block(draft, False, pred, nacc)
+        e1.record()
+        torch.cuda.synchronize()
+        verify_ms = e0.elapsed_time(e1) / 10
+
     roofline = None
     if not args.no_kernel_pass:
         run(args.steps, after_prefill=lambda: ctx.bd_k_profile(True))   # events around the decode launches only
@@ -161,7 +178,7 @@ def main():
         "value": round(tokens / elapsed, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"configs[{4 if fp8 else 1}]: 3B-shaped {'e4m3-weight' if fp8 else 'bf16'} ({shape.n_layers} layers), prefix {args.prefix} "
+        "config": {"workload": f"configs[{4 if fp8 else {1024: 1, 8192: 2, 2048: 3}.get(args.prefix, 1)}]: 3B-shaped {'e4m3-weight' if fp8 else 'bf16'} ({shape.n_layers} layers), prefix {args.prefix} "
                                f"({n_embed} visual embeddings + {args.prefix - n_embed} ids), B={B}, "
                                f"fixed {K} unmasks/step, {tokens} tokens",
                    "block": B, "fixed_k": K, "prefix": args.prefix, "forwards_per_block": n_den + 1},
@@ -169,6 +186,8 @@ def main():
         "algorithmic_GB_per_forward": round(total_bytes / forwards / 1e9, 4),
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    if verify_ms is not None:
+        out["verify_pass_ms"] = round(verify_ms, 4)
     print(json.dumps(out), flush=True)
     ctx.close()
 

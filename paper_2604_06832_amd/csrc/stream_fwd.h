@@ -586,10 +586,7 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
 // stored and the workgroup completing the last chunk of a tile merges all chunks in fixed order.
 __device__ inline void stream_attn_chunks(int n_keys, int max_chunks, int& n_kb, int& chunk_len, int& n_chunks) {
   n_kb = (n_keys + 31) >> 5;
-#ifndef BD_ATT_BLOCKS
-#define BD_ATT_BLOCKS 40
-#endif
-  int want = (n_kb + BD_ATT_BLOCKS - 1) / BD_ATT_BLOCKS;
+  int want = n_kb <= 96 ? 1 : (n_kb + 39) / 40;              // short contexts: one chunk (a cross-workgroup merge costs more)
   if (want > max_chunks) want = max_chunks;
   chunk_len = ((n_kb + want - 1) / want + 3) & ~3;
   n_chunks = (n_kb + chunk_len - 1) / chunk_len;
