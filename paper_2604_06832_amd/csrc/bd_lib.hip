@@ -80,6 +80,8 @@ struct bd_ctx {
   int* row_cand = nullptr; float* row_conf = nullptr;
   DevState* st = nullptr;
   unsigned* bar = nullptr; unsigned bar_epoch = 0;
+  unsigned* xbar = nullptr; unsigned xbar_epoch = 0;   // barriers among the workgroups of one XCD (stream_fwd.h)
+  int xcds = 0;                    // XCDs, if workgroup b of a forward-shaped launch runs on XCD b mod xcds (probed); else 0
   unsigned long long* trace = nullptr; int trace_on = 0;
   // host mirror of the decode state
   int n = 0;
@@ -154,6 +156,13 @@ int make_plan(bd_ctx* c) {
   if (!set(PH_QKV, c->NQKV, c->H, false) || !set(PH_O, c->H, c->QD, false) || !set(PH_GU, 2 * c->F, c->H, false) ||
       !set(PH_DOWN, c->H, c->F, true) || !set(PH_LM, c->V, c->H, false))
     return BD_E_ARG;
+  // Gate/up rows dealt out per XCD so that the SwiGLU output never leaves the XCD that produced it: needs the K slices
+  // of the down projection to coincide with XCDs (workgroup b holds K slice b mod ksplit and runs on XCD b mod xcds).
+  P.xcd_gu = 0;
+  if (c->xcds > 0 && !fp8 && P.nwg % c->xcds == 0 && P.ph[PH_DOWN].ksplit == c->xcds && P.ph[PH_GU].ksplit == 1 &&
+      (P.ph[PH_GU].N / 16) % c->xcds == 0 && P.ph[PH_DOWN].KS % c->xcds == 0 &&
+      (P.ph[PH_GU].N / 2 / c->xcds) == (P.ph[PH_DOWN].KS / c->xcds) * 32)
+    P.xcd_gu = c->xcds;
   long long mx = 0;
   for (int wg = 0; wg < P.nwg; ++wg)
     for (int w = 0; w < kWavesPerWG; ++w) {
@@ -222,6 +231,27 @@ int launch_stream_inst(bd_ctx* c, const MegaArgs& a) {
   return check_launch();
 }
 
+// Does workgroup b of a launch shaped like the streaming forward kernel's run on XCD b mod 8?  Returns 8 if so, else 0.
+int probe_xcds(bd_ctx* c) {
+  if (const char* e = getenv("BD_XCD_LOCAL")) if (strcmp(e, "0") == 0) return 0;
+  const int nwg = c->num_cus, nx = 8;
+  if (nwg % nx != 0) return 0;
+  unsigned* d = nullptr;
+  if (hipMalloc(reinterpret_cast<void**>(&d), (size_t)nwg * 4) != hipSuccess) { (void)hipGetLastError(); return 0; }
+  constexpr int lds = stream_lds_bytes<2>();
+  std::vector<unsigned> h((size_t)nwg, ~0u);
+  bool ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&xcc_probe_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess;
+  for (int rep = 0; rep < 2 && ok; ++rep) {
+    hipLaunchKernelGGL(xcc_probe_kernel, dim3(nwg), dim3(kFwdThreads), lds, c->stream, d);
+    ok = hipGetLastError() == hipSuccess && hipMemcpyAsync(h.data(), d, (size_t)nwg * 4, hipMemcpyDeviceToHost, c->stream) == hipSuccess &&
+         hipStreamSynchronize(c->stream) == hipSuccess;
+    for (int b = 0; b < nwg && ok; ++b) ok = h[(size_t)b] == (unsigned)(b % nx);
+  }
+  (void)hipFree(d);
+  (void)hipGetLastError();
+  return ok ? nx : 0;
+}
+
 int stream_attn_max_chunks(const bd_ctx* c, int MT) {
   const int groups = c->cfg.n_kv_heads * c->G * MT;
   return std::max(1, std::min(c->num_cus / groups, 64));
@@ -236,6 +266,8 @@ int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
   if (streamed) {
     if constexpr (MT <= 2) {
       a.attn_max_chunks = stream_attn_max_chunks(c, MT);
+      a.local_gu = c->plan.xcd_gu > 0 ? 1 : 0;
+      a.xbar = c->xbar; a.xbar_epoch = c->xbar_epoch;
       if (c->fp8) {
         if (c->D == 128) BD_TRY((launch_stream_inst<MT, 128, true>(c, a)));
         else BD_TRY((launch_stream_inst<MT, 64, true>(c, a)));
@@ -243,7 +275,9 @@ int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
         if (c->D == 128) BD_TRY((launch_stream_inst<MT, 128, false>(c, a)));
         else BD_TRY((launch_stream_inst<MT, 64, false>(c, a)));
       }
-      c->bar_epoch += 5u * (unsigned)c->L;
+      c->bar_epoch += (a.local_gu ? 4u : 5u) * (unsigned)c->L;
+      if (a.local_gu) c->xbar_epoch += (unsigned)c->L;
+      a.local_gu = 0;
     }
   } else {
     if (c->fp8) return BD_E_ARG;                            // e4m3 weights are only streamed by the kernel above
@@ -397,6 +431,7 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   c->max_kb = ceil_div(k.max_seq, 32);
   c->loaded.assign(c->L + 1, 0u);
   c->kv_layer_elems = (size_t)k.n_kv_heads * c->max_kb * 32 * c->D;
+  c->xcds = c->use_stream ? probe_xcds(c) : 0;
   if (make_plan(c) != BD_OK) { delete c; return BD_E_ARG; }
   const MegaPlan& P = c->plan;
 
@@ -456,6 +491,7 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   A(c->row_conf, Mp * 4);
   A(c->st, sizeof(DevState));
   A(c->bar, (size_t)(1 + 2 * ceil_div(P.nwg, kBarGroup)) * 32 * 4);
+  A(c->xbar, (size_t)8 * 32 * 4);
 #undef A
   hipError_t e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) {

@@ -54,7 +54,19 @@ struct MegaPlan {
   int nwg, L, H, QD, KVD, F, V, D, n_q, n_kv;
   PhasePlan ph[PH_COUNT];
   long long wave_stride;   // 16-byte units reserved per wavefront in the weight stream
+  int xcd_gu;              // > 0: number of XCDs; the row groups of the gate/up phase are dealt out so that the
+                           // workgroups of XCD x (workgroup id mod xcd_gu) produce exactly the features that K slice x of
+                           // the down projection (also held by the workgroups of XCD x) consumes
 };
+// Row group of workgroup `wg` in phase p, and the inverse.
+__host__ __device__ inline int row_group_of_wg(const MegaPlan& P, int p, int wg) {
+  if (p == PH_GU && P.xcd_gu > 0) return (wg % P.xcd_gu) * (P.nwg / P.xcd_gu) + wg / P.xcd_gu;
+  return wg / P.ph[p].ksplit;
+}
+__host__ __device__ inline int wg_of_row_group(const MegaPlan& P, int p, int ng, int kg) {
+  if (p == PH_GU && P.xcd_gu > 0) return (ng % (P.nwg / P.xcd_gu)) * P.xcd_gu + ng / (P.nwg / P.xcd_gu);
+  return ng * P.ph[p].ksplit + kg;
+}
 
 struct WavePhase { int rows, row0, ng, kg, w0, KW; };
 
@@ -67,7 +79,7 @@ __host__ __device__ inline int phase_tile_slots(const MegaPlan& P, int p) {
 __host__ __device__ inline WavePhase wave_phase(const MegaPlan& P, int p, int wg, int w) {
   const PhasePlan& ph = P.ph[p];
   WavePhase r;
-  const int ng = wg / ph.ksplit;
+  const int ng = row_group_of_wg(P, p, wg);
   r.ng = ng;
   r.kg = wg % ph.ksplit;
   {
@@ -122,6 +134,9 @@ struct MegaArgs {
                               // tile slot of the O phase, even versions one per tile slot of the DOWN phase
   int Mp;
   const float* gains;         // [2L+1][H]: attn_norm l, ffn_norm l, ..., final_norm
+  int local_gu;               // the gate/up -> down hand-over stays inside each XCD (stream_fwd.h): plain stores, XCD barrier
+  unsigned* xbar;             // [xcd][32 words] arrival counters of the XCD barriers
+  unsigned xbar_epoch;        // XCD barriers run before this launch
   int fp8;                    // the decoder linears are e4m3 codes with one scale per output row: the scale multiplies
                               // the accumulators, and the norm gains (which cannot be folded into the codes) multiply
                               // the bf16 copies of the residual versions that feed them
@@ -431,7 +446,9 @@ __device__ inline void gemm_epilogue(const MegaArgs& a, const PhaseCtx& pc, cons
     for (int pr = 0; pr < 2; ++pr) {
       if (2 * pr >= nrows) break;
       const float gt = v[2 * pr], up = v[2 * pr + 1];
-      st_wt_u16(base + xp_index(token, (r >> 1) + pr, a.MT), f32_to_bf16_bits(gt / (1.f + __expf(-gt)) * up));
+      const u16 hv = f32_to_bf16_bits(gt / (1.f + __expf(-gt)) * up);
+      if (a.local_gu) base[xp_index(token, (r >> 1) + pr, a.MT)] = hv;      // read only inside this XCD: its L2 is coherent
+      else st_wt_u16(base + xp_index(token, (r >> 1) + pr, a.MT), hv);
     }
   } else if constexpr (PH == PH_DOWN) {
     // partial tile of this K group, in fragment order
@@ -1174,7 +1191,7 @@ __global__ void pack_stream_kernel(const SrcT* __restrict__ src, int n_rows, int
     // which K group / wavefront holds k-step ks
     int kg = 0;
     while ((int)((long long)pp.KS * (kg + 1) / pp.ksplit) <= ks) ++kg;
-    const int wg = ng * pp.ksplit + kg;
+    const int wg = wg_of_row_group(P, ph, ng, kg);
     int w = 0;
     WavePhase wp = wave_phase(P, ph, wg, 0);
     while (ks >= wp.w0 + wp.KW) { ++w; wp = wave_phase(P, ph, wg, w); }
@@ -1224,7 +1241,7 @@ __global__ void pack_stream_fp8_kernel(const uint8_t* __restrict__ src, int n_ro
     const int ks = 2 * kp;
     int kg = 0;
     while ((int)((long long)KP * (kg + 1) / pp.ksplit) <= kp) ++kg;
-    const int wg = ng * pp.ksplit + kg;
+    const int wg = wg_of_row_group(P, ph, ng, kg);
     int w = 0;
     WavePhase wp = wave_phase(P, ph, wg, 0);
     while (ks >= wp.w0 + wp.KW) { ++w; wp = wave_phase(P, ph, wg, w); }

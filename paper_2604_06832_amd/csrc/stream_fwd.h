@@ -44,7 +44,7 @@ constexpr int kShareBytes = 40 * 1024;      // K-reduction buffers / attention m
 typedef __attribute__((address_space(3))) void lds_void_t;
 
 // words of the LDS synchronisation block
-enum { SY_LANDED = 0, SY_CONSUMED = 4, SY_DEAD = 8, SY_CBAR = 9, SY_ARRIVE = 10, SY_EPOCH = 11, SY_WORDS = 16 };
+enum { SY_LANDED = 0, SY_CONSUMED = 4, SY_DEAD = 8, SY_CBAR = 9, SY_ARRIVE = 10, SY_EPOCH = 11, SY_XEPOCH = 12, SY_WORDS = 16 };
 
 __device__ inline unsigned lds_addr(const void* p) {
   return (unsigned)(size_t)(const __attribute__((address_space(3))) char*)p;
@@ -695,8 +695,8 @@ __device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, Fwd
   const int Mp = a.MT * 16;
   const int n_ct = G * a.MT;                                             // column tiles per kv head
   int n_kb, chunk_len, n_chunks;
-  stream_attn_chunks(n + a.M, a.attn_max_chunks, n_kb, chunk_len, n_chunks);
   const int n_groups = P.n_kv * n_ct;
+  stream_attn_chunks(n + a.M, a.attn_max_chunks, n_kb, chunk_len, n_chunks);
   const int n_items = n_groups * n_chunks;
   const size_t kv_block = (size_t)32 * D / 8;
   const u16* Qb = a.Q + (size_t)pc.layer * a.Mp * P.n_q * D;
@@ -907,6 +907,57 @@ __device__ inline bool stream_grid_barrier(const MegaArgs& a, FwdSync& sy, unsig
   return ok;
 }
 
+// ---- barrier of the workgroups of one XCD ------------------------------------------------------------------------
+// Workgroup b runs on XCD b mod 8 (checked when the kernel starts), and the CUs of one XCD share one L2.  Between
+// workgroups of one XCD a hand-over therefore needs no write-through: plain stores are complete (s_waitcnt) once that
+// L2 holds them, and every later load from a CU of the same XCD that misses its L1 reads them there.  The arrival
+// counter of XCD x is touched by the workgroups of XCD x only, through read-modify-write atomics, which never execute
+// in an L1.
+__device__ inline unsigned xcc_id() {
+  unsigned x;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));
+  return x & 15u;
+}
+__device__ inline unsigned l2_atomic_peek(unsigned* p) {
+  unsigned v;
+  const unsigned zero = 0u;
+  asm volatile("global_atomic_or %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p), "v"(zero) : "memory");
+  return v;
+}
+__device__ inline bool stream_xcd_barrier(const MegaArgs& a, FwdSync& sy, unsigned xepoch, int wave, int lane) {
+  sy.arrive_target += kWavesPerWG;
+  if (lane == 0) lds_inc(sy.base + SY_ARRIVE * 4);
+  if (wave == 0) {
+    bool ok = lds_wait_ge(sy, sy.base + SY_ARRIVE * 4, sy.arrive_target, a.st);
+    if (ok && lane == 0) {
+      const int nx = a.P.xcd_gu;
+      unsigned* cnt = a.xbar + 32 * (blockIdx.x % nx);
+      const unsigned target = xepoch * (unsigned)(a.P.nwg / nx);
+      __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      int spins = 0;
+      while ((int)(l2_atomic_peek(cnt) - target) < 0) {
+        if (++spins > kSpinLimit) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(1);
+      }
+      if (ok) lds_st32(sy.base + SY_XEPOCH * 4, xepoch);
+      else {
+        lds_st32(sy.base + SY_DEAD * 4, 1u);
+        __hip_atomic_store(&a.st->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
+  const bool ok = lds_wait_ge(sy, sy.base + SY_XEPOCH * 4, xepoch, a.st);
+  asm volatile("" ::: "memory");
+  return ok;
+}
+
+// Writes the XCD id of every workgroup of a launch shaped like the forward kernel's (host-side check of the
+// workgroup -> XCD rule before a plan relies on it).
+__global__ __launch_bounds__(kFwdThreads, 1) void xcc_probe_kernel(unsigned* out) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  if (threadIdx.x == 0) { lds[0] = 1; out[blockIdx.x] = xcc_id(); }
+}
+
 // ---- the kernel ------------------------------------------------------------------------------------------------
 template <int MT> constexpr int stream_lds_bytes() { return kWavesPerWG * kSlots * 1024 + kShareBytes; }
 
@@ -921,7 +972,14 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
   const MegaPlan& P = a.P;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (threadIdx.x < SY_WORDS) s_sync[threadIdx.x] = 0u;
-  if (threadIdx.x == 0) s_flags[0] = (a.st->error == 0);
+  if (threadIdx.x == 0) {
+    int go = (a.st->error == 0);
+    if (go && a.local_gu && xcc_id() != blockIdx.x % 8u) {   // the XCD-local hand-over would be unsafe
+      __hip_atomic_store(&a.st->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      go = 0;
+    }
+    s_flags[0] = go;
+  }
   __syncthreads();                                       // the only workgroup barrier: all eight wavefronts are still here
   if (!s_flags[0]) return;
   const unsigned sync_base = lds_addr(s_sync);
@@ -947,7 +1005,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
   fc.red2 = fc.pc.red + kWavesPerWG * kT * MT * 64;
   fc.pc.s_flags = s_flags;
   fc.s_part = s_part;
-  unsigned epoch = a.bar_epoch;
+  unsigned epoch = a.bar_epoch, xepoch = a.xbar_epoch;
 
   int tsi = 0;
 #define BD_TS2()                                                                                                  \
@@ -976,7 +1034,8 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
     if (!alive) break;
     stream_gemm_phase<MT, PH_GU, D, FP8>(a, fc, rg, sy, wave, lane);
     BD_TS2();
-    alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
+    if (a.local_gu) alive = stream_xcd_barrier(a, sy, ++xepoch, wave, lane);
+    else alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
     if (!alive) break;
     stream_gemm_phase<MT, PH_DOWN, D, FP8>(a, fc, rg, sy, wave, lane);
