@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes one launch of the layers kernel moves on the default workload, from hardware counters
 # (profiles/streaming_forward_config1_hbm_traffic.txt: FETCH_SIZE and WRITE_SIZE, scaled by a reference copy)
-MEASURED_TRAFFIC_BYTES = {("bf16", 36, 1024, 32): 6.360e9}
+MEASURED_TRAFFIC_BYTES = {("bf16", 36, 1024, 32): 6.333e9}
 
 
 def main():
