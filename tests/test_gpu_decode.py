@@ -177,6 +177,50 @@ def test_3b_shaped_two_layers_block_sizes(B):
     p.close()
 
 
+
+def test_xcd_local_handover_is_bit_identical_to_the_chip_wide_one(monkeypatch):
+    """The gate/up -> down hand-over inside each XCD moves the same values through other caches: logits, K/V and
+    the revealed ids of a whole block must not change by a bit against the chip-wide path, and a forward repeated
+    many times (alternating with forwards of another block size, which rewrite the same buffers) must repeat
+    exactly.  A stale line anywhere in the hand-over would show up as a difference."""
+    _say("3B-shaped x2 layers: XCD-local vs chip-wide hand-over, B=32 and B=8 interleaved")
+    shape = _wide(2, vocab=8192)
+    w = inputs.make_weights(shape, 5, "bf16", threads=8)
+    emb, ids = inputs.make_prompt(shape, 96, 37, seed=11)
+
+    def run(local):
+        if local:
+            monkeypatch.delenv("BD_XCD_LOCAL", raising=False)
+        else:
+            monkeypatch.setenv("BD_XCD_LOCAL", "0")
+        ctx = binding.Context(shape, max_seq=133 + 64, max_block=32)
+        ctx.load_model(w, as_bf16_bits=True)
+        ctx.bd_debug_logits(True)
+        ctx.bd_prefill(torch.from_numpy(emb).cuda(), torch.from_numpy(ids).cuda())
+        out = []
+        rng = np.random.default_rng(3)
+        big = torch.from_numpy(rng.integers(0, shape.vocab - 1, 32).astype(np.int32)).cuda()
+        small = torch.from_numpy(rng.integers(0, shape.vocab - 1, 8).astype(np.int32)).cuda()
+        for rep in range(6):
+            ctx.bd_verify_block(big, False, None, None)
+            out.append(ctx.bd_read_logits(32).clone())
+            ctx.bd_verify_block(small, False, None, None)
+            out.append(ctx.bd_read_logits(8).clone())
+        ctx.bd_status()
+        ctx.bd_commit_block(big)
+        k, v = ctx.bd_read_kv(1, 133, 32)
+        out += [k.clone(), v.clone()]
+        ctx.close()
+        return out
+
+    a = run(True)
+    b = run(False)
+    for rep in range(2, 12):
+        assert torch.equal(a[rep], a[rep % 2]), f"repeat {rep} of the XCD-local forward differs"
+    for i, (x, y) in enumerate(zip(a, b)):
+        assert torch.equal(x, y), f"output {i} differs between the two hand-overs"
+
+
 def test_long_prefix_3b_shaped_two_layers():
     _say("3B-shaped x2 layers, prefix 8192 (4 x 1920 embeddings + 512 ids)")
     shape = _wide(2, vocab=8192)
