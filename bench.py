@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--no-kernel-pass", action="store_true")
     ap.add_argument("--verify", action="store_true",
                     help="also time the speculative verify pass (configs[3]): B drafted ids, one causal forward + accept")
+    ap.add_argument("--speculative", type=int, default=0, metavar="N",
+                    help="also time N iterations of the linear self-speculative loop (Alg. 1: draft + verify + accept "
+                         "per call); with random weights nearly every draft is rejected, so this is ~2 forwards per token")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -140,6 +143,23 @@ def main():
         torch.cuda.synchronize()
         verify_ms = e0.elapsed_time(e1) / 10
 
+    spec = None
+    if args.speculative > 0:
+        n_it = min(args.speculative, args.steps)            # the cache was sized for `steps` blocks
+        ctx.bd_prefill(d_emb, d_ids)
+        outp = torch.zeros(B, dtype=torch.int32, device="cuda")
+        ctx.bd_speculative_step(B, outp)
+        ctx.bd_prefill(d_emb, d_ids)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        emitted = 0
+        for _ in range(n_it):
+            emitted += ctx.bd_speculative_step(B, outp)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        spec = {"iterations": n_it, "tokens": emitted, "tokens_per_s": round(emitted / dt, 1),
+                "ms_per_iteration": round(dt * 1e3 / n_it, 4), "forwards_per_iteration": 2 if B > 1 else 1}
+
     roofline = None
     if not args.no_kernel_pass:
         run(args.steps, after_prefill=lambda: ctx.bd_k_profile(True))   # events around the decode launches only
@@ -183,6 +203,7 @@ def main():
                                f"fixed {K} unmasks/step, {tokens} tokens",
                    "block": B, "fixed_k": K, "prefix": args.prefix, "forwards_per_block": n_den + 1},
         "ms_per_forward": round(ms_fwd, 4), "hbm_roofline_frac_step": round(step_frac, 4),
+        **({"speculative": spec} if spec is not None else {}),
         "algorithmic_GB_per_forward": round(total_bytes / forwards / 1e9, 4),
         "roofline": roofline, "cpu_baseline": cpu,
     }

@@ -109,6 +109,19 @@ int bd_commit_block(bd_ctx* ctx, const int32_t* dev_block_tokens, int B);
 int bd_verify_block(bd_ctx* ctx, const int32_t* dev_draft, int B, int commit, int32_t* dev_ar_pred,
                     int32_t* dev_n_accept);
 
+/* One iteration of the linear self-speculative loop (appendix "Details of Speculative Decoding", Alg. 1), with no
+ * host decision in between: the block [x_n, MASK, ...] (x_n = the carry's argmax, i.e. the token predicted for
+ * position cache_len) is drafted in one bidirectional forward without cache update (row i-1 fills position i);
+ * the draft is verified by one causal forward that writes K/V of all B positions; with a_j = argmax of causal
+ * row j, k = 1 + the number of leading drafts d_1.. equal to a_0..; the k emitted tokens are a_0..a_{k-1}; the
+ * cache keeps d_0..d_{k-1} (cache_len += k) and a_{k-1} becomes the carry.  B = 1 is one step of ordinary
+ * autoregressive decoding.
+ * dev_tokens_out: device int32[B]; entries [0, k) are the emitted tokens (all B predictions are written).
+ * host_n_accepted: host int32, receives k (1 <= k <= B).  The call synchronises the stream to read k.
+ * Errors: BD_E_STATE before prefill or without a valid carry (after bd_crop), BD_E_CAPACITY if
+ * cache_len + B > max_seq, BD_E_ARG for NULL pointers or B outside [1, max_block]. */
+int bd_speculative_step(bd_ctx* ctx, int B, int32_t* dev_tokens_out, int32_t* host_n_accepted);
+
 /* Alg. 1 Crop: forget cache positions >= new_len (0 <= new_len <= cache_len).  The carry becomes
  * undefined: the next block must bring its own first token (mask[0] = 0). */
 int bd_crop(bd_ctx* ctx, int new_len);

@@ -78,6 +78,7 @@ struct bd_ctx {
   float* lm_max = nullptr; int* lm_idx = nullptr; float* lm_sum = nullptr;
   float* logits = nullptr; int logits_on = 0; int last_rows = 0; int last_had_logits = 0;
   int* row_cand = nullptr; float* row_conf = nullptr;
+  int32_t* spec_tokens = nullptr; uint8_t* spec_mask = nullptr; int32_t* spec_k = nullptr;   // bd_speculative_step
   DevState* st = nullptr;
   unsigned* bar = nullptr; unsigned bar_epoch = 0;
   unsigned* xbar = nullptr; unsigned xbar_epoch = 0;   // barriers among the workgroups of one XCD (stream_fwd.h)
@@ -489,6 +490,9 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   A(c->lm_sum, (size_t)P.nwg * Mp * 4);
   A(c->row_cand, Mp * 4);
   A(c->row_conf, Mp * 4);
+  A(c->spec_tokens, Mp * 4);
+  A(c->spec_mask, Mp);
+  A(c->spec_k, 4);
   A(c->st, sizeof(DevState));
   A(c->bar, (size_t)(1 + 2 * ceil_div(P.nwg, kBarGroup)) * 32 * 4);
   A(c->xbar, (size_t)8 * 32 * 4);
@@ -696,6 +700,47 @@ int bd_verify_block(bd_ctx* c, const int32_t* dev_draft, int B, int commit, int3
   if (dev_draft == nullptr) return BD_E_ARG;
   if (dev_n_accept != nullptr && !c->carry_valid) return BD_E_STATE;
   return causal_pass(c, dev_draft, B, commit ? 1 : 0, dev_ar_pred, dev_n_accept, dev_draft);
+}
+
+int bd_speculative_step(bd_ctx* c, int B, int32_t* dev_tokens_out, int32_t* host_n_accepted) {
+  BD_TRY(check_decode_call(c, B));
+  if (dev_tokens_out == nullptr || host_n_accepted == nullptr) return BD_E_ARG;
+  if (!c->carry_valid) return BD_E_STATE;
+  hipStream_t s = c->stream;
+  // draft: [x_n, MASK, ...] -> every masked position filled by the argmax of the row before it, in one pass
+  hipLaunchKernelGGL(fill_masked_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, B, c->cfg.mask_token_id);
+  BD_TRY(check_launch());
+  if (B == 1) {
+    hipLaunchKernelGGL(seed_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, c->st);
+    BD_TRY(check_launch());
+  } else {
+    BD_TRY(forward(c, B, BD_MODE_BIDIR, true, nullptr, 0, c->spec_tokens, 0, c->spec_tokens, c->spec_mask, c->spec_mask));
+    FinishArgs f = finish_args(c, B);
+    f.tokens = c->spec_tokens; f.mask = c->spec_mask; f.threshold = 2.f; f.fixed_k = B - 1;
+    Prof pr(c, KC_FINISH);
+    hipLaunchKernelGGL(finish_denoise_kernel, dim3(1), dim3(64), 0, s, f);
+    BD_TRY(check_launch());
+  }
+  // verify: causal forward with cache update; accept and crop on the device
+  BD_TRY(forward(c, B, BD_MODE_CAUSAL, true, nullptr, 0, c->spec_tokens, 0, nullptr, nullptr, nullptr));
+  {
+    FinishArgs f = finish_args(c, B);
+    f.draft = c->spec_tokens; f.commit = 2; f.ar_pred = dev_tokens_out; f.n_accept = c->spec_k;
+    Prof pr(c, KC_FINISH);
+    hipLaunchKernelGGL(finish_causal_kernel, dim3(1), dim3(64), 0, s, f);
+    BD_TRY(check_launch());
+  }
+  int32_t k = 0;
+  HIP_TRY(hipMemcpyAsync(&k, c->spec_k, 4, hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  if (k < 1 || k > B) {
+    snprintf(g_last_error, sizeof g_last_error, "speculative step returned an accept length of %d for a block of %d", (int)k, B);
+    return BD_E_HIP;
+  }
+  c->n += k;
+  c->carry_valid = true;
+  *host_n_accepted = k;
+  return BD_OK;
 }
 
 int bd_crop(bd_ctx* c, int new_len) {

@@ -351,17 +351,34 @@ __global__ __launch_bounds__(64) void finish_causal_kernel(FinishArgs a) {
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    if (a.n_accept) {
+    if (a.n_accept && a.commit != 2) {
       int k = 0;
       while (k < a.B && a.draft[k] == (k == 0 ? a.st->carry_cand : s_cand[k - 1])) ++k;
       *a.n_accept = k;
     }
-    if (a.commit) {
+    if (a.commit == 1) {
       a.st->carry_cand = s_cand[a.B - 1];
       a.st->carry_conf = s_conf[a.B - 1];
       a.st->n += a.B;
+    } else if (a.commit == 2) {
+      // Alg. 1 accept + crop in place: draft[0] is the already accepted first token; k = 1 + the number of leading
+      // drafts draft[1..] that equal the predictions a_0..; the emitted tokens are a_0..a_{k-1}; the cache keeps the
+      // positions of draft[0..k-1] (the rows beyond were written but the length does not cover them), and a_{k-1}
+      // becomes the prediction for the new position n.
+      int k = 1;
+      while (k < a.B && s_cand[k - 1] == a.draft[k]) ++k;
+      *a.n_accept = k;
+      a.st->carry_cand = s_cand[k - 1];
+      a.st->carry_conf = s_conf[k - 1];
+      a.st->n += k;
     }
   }
+}
+
+// All positions of a block masked (the state before the draft pass of Alg. 1).
+__global__ void fill_masked_kernel(int* tokens, uint8_t* mask, int B, int mask_id) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < B) { tokens[i] = mask_id; mask[i] = 1; }
 }
 
 // Commit without an LM-head pass (prompt chunks before the last one).

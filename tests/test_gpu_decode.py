@@ -144,6 +144,147 @@ def test_verify_accept_and_crop(B):
     p.close()
 
 
+
+# ---- linear self-speculative loop (Alg. 1) as one call per iteration ------------------------------------------
+
+def _oracle_spec_iteration(o, x_n, B):
+    """One iteration of Alg. 1 on the oracle, step by step (same steps as its linear_speculative loop), returning
+    what the device call reports plus the logits the decisions were taken on."""
+    from oracle.bd_oracle import BIDIR, CAUSAL
+    d = np.full(B, o.mask_id, np.int32)
+    d[0] = x_n
+    lg_d = None
+    if B > 1:
+        lg_d, _, _ = o.forward(o.embed(d), BIDIR)
+        d[1:] = o.cand_conf(lg_d)[0][:-1]
+    n0 = o.n
+    lg_v, nk, nv = o.forward(o.embed(d), CAUSAL)
+    o._append(nk, nv)
+    a, _ = o.cand_conf(lg_v)
+    mism = [j for j in range(B - 1) if a[j] != d[j + 1]]
+    k = (mism[0] + 1) if mism else B
+    o.crop(n0 + k)
+    return dict(draft=d, a=a, k=k, draft_logits=lg_d, verify_logits=lg_v)
+
+
+def _cyclic_model(shape, flip):
+    """A model whose predictions depend on the current token only (attention and MLP outputs switched off by zero
+    output projections, one-hot embeddings): every ordinary token and the mask token predict token A; A predicts A
+    (flip=False: every draft is accepted) or A predicts Bt and Bt predicts A (flip=True: the drafts A, A, ... after
+    the first are rejected where the sequence alternates)."""
+    w = inputs.make_weights(shape, 3, "bf16", threads=1)
+    A, Bt = 5, 9
+    emb = np.zeros((shape.vocab, shape.hidden), np.float32)
+    emb[:, 0] = 1.0
+    head = np.zeros((shape.vocab, shape.hidden), np.float32)
+    head[A, 0] = 1.0
+    if flip:
+        emb[A] = 0.0; emb[A, 1] = 1.0          # A -> class 1 -> Bt
+        emb[Bt] = 0.0; emb[Bt, 2] = 1.0        # Bt -> class 2 -> A
+        head[Bt, 1] = 1.0
+        head[A, 2] = 1.0
+    w["embed"] = emb
+    w["lm_head"] = head
+    for l in range(shape.n_layers):
+        w[f"l{l}.wo"] = np.zeros_like(w[f"l{l}.wo"])
+        w[f"l{l}.w_down"] = np.zeros_like(w[f"l{l}.w_down"])
+    return w, A, Bt
+
+
+@pytest.mark.parametrize("B,flip", [(1, True), (4, False), (8, True), (32, True), (33, False), (64, True)])
+def test_speculative_step_accept_lengths_on_a_token_cycle(B, flip):
+    _say(f"speculative step on the cyclic model, B={B}, flip={flip}")
+    shape = inputs.TINY
+    w, A, Bt = _cyclic_model(shape, flip)
+    ids = np.array([3, 17, 200, 41, 7], np.int32)
+    p = Pair(shape, w, max_seq=5 + 6 * B + B, max_block=B)
+    p.prefill(None, ids)
+    x_n = int(np.argmax(p.o.carry))
+    assert x_n == A
+    out = torch.zeros(B, dtype=torch.int32, device="cuda")
+    ks = []
+    for it in range(5):
+        r = _oracle_spec_iteration(p.o, x_n, B)
+        k = p.ctx.bd_speculative_step(B, out)
+        got = out.cpu().numpy()
+        assert k == r["k"], (it, k, r["k"])
+        assert np.array_equal(got[:k], r["a"][:k]), (it, got[:k], r["a"][:k])
+        assert p.ctx.bd_cache_len() == p.o.n
+        x_n = int(r["a"][k - 1])
+        cand, _ = p.ctx.bd_read_carry()
+        assert cand == x_n
+        ks.append(k)
+    # closed form of the accept lengths: fixed point -> whole blocks; alternation -> 3 (from A: A Bt A | A) then 2
+    if not flip:
+        assert ks == [B] * 5
+    elif B >= 4:
+        assert ks == [3, 2, 2, 2, 2]
+    p.check_kv(0, p.o.n)
+    p.close()
+
+
+@pytest.mark.parametrize("B", [4, 16])
+def test_speculative_steps_emit_the_greedy_sequence(B):
+    """Alg. 1 emits exactly the greedy autoregressive continuation, whatever the drafts are worth: with random
+    weights nearly every draft is rejected, so every iteration exercises reject + crop."""
+    _say(f"speculative steps vs greedy decoding, tiny config, B={B}")
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, threads=1)
+    emb, ids = inputs.make_prompt(shape, 24, 24, seed=6)
+    p = Pair(shape, w, max_seq=48 + 12 * B, max_block=B)
+    p.prefill(emb, ids)
+    import copy
+    greedy = copy.deepcopy(p.o).greedy_ar(12)
+    x_n = int(np.argmax(p.o.carry))
+    if top2_margin(p.o.carry) <= MARGIN:
+        pytest.skip("near-tie in the carry of this seed")
+    emitted = [x_n]
+    out = torch.zeros(B, dtype=torch.int32, device="cuda")
+    while len(emitted) < 12:
+        r = _oracle_spec_iteration(p.o, x_n, B)
+        k = p.ctx.bd_speculative_step(B, out)
+        got = out.cpu().numpy()
+        glog = p.ctx.bd_read_logits(B).cpu().numpy()              # logits of the verify pass
+        # row 0 of the verify pass has the same input on both sides whatever the drafts are: its error measures the
+        # numerical noise, and decisions count only where the oracle's margins are clear of it
+        rng = float(r["verify_logits"].max() - r["verify_logits"].min())
+        e0 = float(np.abs(glog[0] - r["verify_logits"][0]).max())
+        assert e0 <= 3e-2 * rng, (e0, rng)
+        thr = max(MARGIN, 2.5 * e0)
+        robust = top2_margin(r["verify_logits"])[:r["k"]].min() > thr and \
+            (r["draft_logits"] is None or top2_margin(r["draft_logits"])[:B - 1].min() > thr)
+        if not robust:
+            break                                                  # a near-tie decides from here on: stop comparing
+        assert_logits_close(glog, r["verify_logits"])
+        assert k == r["k"] and np.array_equal(got[:k], r["a"][:k])
+        emitted += [int(t) for t in got[:k]]
+        x_n = int(r["a"][k - 1])
+        assert p.ctx.bd_cache_len() == p.o.n
+    n = min(len(emitted), 12)
+    assert n >= 4
+    assert np.array_equal(np.array(emitted[:n]), greedy[:n])
+    p.close()
+
+
+def test_speculative_step_needs_a_carry():
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, "bf16", threads=1)
+    ctx = binding.Context(shape, max_seq=64, max_block=8)
+    ctx.load_model(w, as_bf16_bits=True)
+    out = torch.zeros(8, dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.BdError):
+        ctx.bd_speculative_step(4, out)                            # before prefill
+    ctx.bd_prefill(None, torch.arange(10, dtype=torch.int32, device="cuda"))
+    ctx.bd_crop(6)
+    with pytest.raises(binding.BdError):
+        ctx.bd_speculative_step(4, out)                            # the crop dropped the carry
+    ctx.bd_commit_block(torch.tensor([1, 2], dtype=torch.int32, device="cuda"))
+    assert ctx.bd_speculative_step(4, out) >= 1
+    with pytest.raises(binding.BdError):
+        ctx.bd_speculative_step(9, out)                            # block larger than max_block
+    ctx.close()
+
+
 # ---- 3B-shaped layers at reduced depth: every block size, ragged prefix, both masks -------------------
 
 def _wide(n_layers, vocab=32000):
