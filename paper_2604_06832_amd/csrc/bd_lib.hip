@@ -19,6 +19,7 @@
 #include "mega.h"
 #include "misc.h"
 #include "stream_fwd.h"
+#include "prefill.h"
 
 using namespace bd;
 
@@ -78,6 +79,11 @@ struct bd_ctx {
   float* lm_max = nullptr; int* lm_idx = nullptr; float* lm_sum = nullptr;
   float* logits = nullptr; int logits_on = 0; int last_rows = 0; int last_had_logits = 0;
   int* row_cand = nullptr; float* row_conf = nullptr;
+  // large-M prefill (prefill.h): tile-major copy of the decoder weights and the activations of one chunk
+  bool pf_on = false; int pf_rows = 0;
+  u16* pf_w = nullptr; size_t pf_layer_elems = 0; size_t pf_off[4] = {0, 0, 0, 0};
+  float* pf_x = nullptr; u16* pf_xb = nullptr; float* pf_rs = nullptr; float2* pf_rope = nullptr;
+  u16* pf_q = nullptr; u16* pf_ap = nullptr; u16* pf_act = nullptr;
   int32_t* spec_tokens = nullptr; uint8_t* spec_mask = nullptr; int32_t* spec_k = nullptr;   // bd_speculative_step
   DevState* st = nullptr;
   unsigned* bar = nullptr; unsigned bar_epoch = 0;
@@ -377,6 +383,74 @@ FinishArgs finish_args(bd_ctx* c, int B) {
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------------------
+namespace {
+
+// Tile shapes per phase (rows per workgroup = 32*WN, k-steps per stage BKS), picked by measurement at 1008 rows:
+// gate/up 128 rows x 2 k-steps (two workgroups per CU), down and O 64 x 4, QKV 64 x 2.
+template <int PH, int WN, int BKS>
+int launch_pf_gemm(bd_ctx* c, PfGemmArgs a, int n_rows) {
+  static bool attr_set = false;
+  constexpr int lds = pf_gemm_lds<WN, BKS>();
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<PH, WN, BKS>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    attr_set = true;
+  }
+  a.NT = n_rows / 16;
+  a.RG = ceil_div(a.NT, 2 * WN);
+  a.TG = ceil_div(a.MTc, 8);
+  const int grid = ceil_div(a.RG, 8) * 8 * a.TG;
+  hipLaunchKernelGGL((pf_gemm_kernel<PH, WN, BKS>), dim3(grid), dim3(kPfThreads), lds, c->stream, a);
+  return check_launch();
+}
+
+// One chunk of mc prompt rows (a multiple of 16) starting at prompt row `off` = cache position c->n: all layers,
+// K/V into the cache, no LM head.  The device-side length is advanced by the caller.
+int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* dev_ids, int off, int mc) {
+  hipStream_t s = c->stream;
+  const int MTc = mc / 16;
+  hipLaunchKernelGGL(embed_kernel, dim3(mc), dim3(kWGThreads), 0, s, c->pf_x, c->H, dev_embeds, n_embed, dev_ids, off,
+                     (const uint8_t*)nullptr, c->cfg.mask_token_id, c->embed, c->V);
+  BD_TRY(check_launch());
+  hipLaunchKernelGGL(rope_table_kernel, dim3(mc), dim3(64), 0, s, c->pf_rope, c->st, c->D / 2, c->cfg.rope_theta);
+  BD_TRY(check_launch());
+  PfGemmArgs g{};
+  g.MTc = MTc; g.rs = c->pf_rs; g.rope = c->pf_rope; g.x = c->pf_x; g.q = c->pf_q; g.max_kb = c->max_kb; g.n0 = c->n;
+  g.act = c->pf_act; g.H = c->H; g.QD = c->QD; g.KVD = c->KVD; g.D = c->D; g.n_q = c->cfg.n_q_heads;
+  for (int l = 0; l < c->L; ++l) {
+    const u16* wl = c->pf_w + (size_t)l * c->pf_layer_elems;
+    g.Kc = c->Kc + (size_t)l * c->kv_layer_elems;
+    g.Vc = c->Vc + (size_t)l * c->kv_layer_elems;
+    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs);
+    BD_TRY(check_launch());
+    g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[0]); g.KS = ceil_div(c->H, 32);
+    g.xin = reinterpret_cast<const bf16x8*>(c->pf_xb);
+    BD_TRY((launch_pf_gemm<PH_QKV, 2, 2>(c, g, c->NQKV)));
+    {
+      PfAttnArgs t{};
+      t.q = c->pf_q; t.Kc = g.Kc; t.Vc = g.Vc; t.max_kb = c->max_kb; t.n0 = c->n; t.Mc = mc; t.n_q = c->cfg.n_q_heads;
+      t.n_kv = c->cfg.n_kv_heads; t.scale_log2e = 1.4426950408889634f / std::sqrt((float)c->D); t.out = c->pf_ap; t.MTc = MTc;
+      const int items = t.n_q * (mc / 16);
+      if (c->D == 128) hipLaunchKernelGGL(pf_attn_kernel<128>, dim3(ceil_div(items, 4)), dim3(kPfThreads), 0, s, t);
+      else hipLaunchKernelGGL(pf_attn_kernel<64>, dim3(ceil_div(items, 4)), dim3(kPfThreads), 0, s, t);
+      BD_TRY(check_launch());
+    }
+    g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[1]); g.KS = ceil_div(c->QD, 32);
+    g.xin = reinterpret_cast<const bf16x8*>(c->pf_ap);
+    BD_TRY((launch_pf_gemm<PH_O, 2, 4>(c, g, c->H)));
+    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs);
+    BD_TRY(check_launch());
+    g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[2]); g.KS = ceil_div(c->H, 32);
+    g.xin = reinterpret_cast<const bf16x8*>(c->pf_xb);
+    BD_TRY((launch_pf_gemm<PH_GU, 4, 2>(c, g, 2 * c->F)));
+    g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[3]); g.KS = ceil_div(c->F, 32);
+    g.xin = reinterpret_cast<const bf16x8*>(c->pf_act);
+    BD_TRY((launch_pf_gemm<PH_DOWN, 2, 4>(c, g, c->H)));
+  }
+  return BD_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* bd_strerror(int code) {
@@ -493,6 +567,28 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   A(c->spec_tokens, Mp * 4);
   A(c->spec_mask, Mp);
   A(c->spec_k, 4);
+  {
+    // Large-M prefill for bf16 contexts whose cache can hold a chunk of 128 rows plus the prompt's last rows.
+    const char* e = getenv("BD_PREFILL");
+    c->pf_on = !c->fp8 && k.max_seq > kPfTokens && !(e != nullptr && strcmp(e, "chunked") == 0);
+    if (c->pf_on) {
+      c->pf_rows = std::min(1024, (k.max_seq - 1) / kPfTokens * kPfTokens);
+      const size_t R = (size_t)c->pf_rows;
+      const int NP[4] = {c->NQKV, c->H, 2 * c->F, c->H};
+      const int KP[4] = {c->H, c->QD, c->H, c->F};
+      size_t off = 0;
+      for (int ph = 0; ph < 4; ++ph) { c->pf_off[ph] = off; off += (size_t)NP[ph] * ceil_div(KP[ph], 32) * 32; }
+      c->pf_layer_elems = off;
+      A(c->pf_w, L * c->pf_layer_elems * 2);
+      A(c->pf_x, R * c->H * 4);
+      A(c->pf_xb, R * c->H * 2);
+      A(c->pf_rs, R * 4);
+      A(c->pf_rope, R * (c->D / 2) * sizeof(float2));
+      A(c->pf_q, R * c->QD * 2);
+      A(c->pf_ap, R * (size_t)ceil_div(c->QD, 32) * 32 * 2);
+      A(c->pf_act, R * (size_t)ceil_div(c->F, 32) * 32 * 2);
+    }
+  }
   A(c->st, sizeof(DevState));
   A(c->bar, (size_t)(1 + 2 * ceil_div(P.nwg, kBarGroup)) * 32 * 4);
   A(c->xbar, (size_t)8 * 32 * 4);
@@ -611,6 +707,15 @@ int bd_load_weight(bd_ctx* c, const char* name, const void* host_ptr, size_t byt
         hipLaunchKernelGGL(pack_stream_kernel<u16>, dim3(4096), dim3(256), 0, c->stream, (const u16*)stage, rows, K,
                            c->plan, ph, std::max(layer, 0), row_base, row_map, c->D, col_gain, c->wstream);
       }
+      if (c->pf_on && !is_embed && ph >= 0 && ph != PH_LM) {
+        u16* dst = c->pf_w + (size_t)layer * c->pf_layer_elems + c->pf_off[ph];
+        if (dtype == BD_F32)
+          hipLaunchKernelGGL(pack_tiles_kernel<float>, dim3(4096), dim3(256), 0, c->stream, (const float*)stage, rows, K,
+                             ceil_div(K, 32), row_base, row_map, c->D, col_gain, dst);
+        else
+          hipLaunchKernelGGL(pack_tiles_kernel<u16>, dim3(4096), dim3(256), 0, c->stream, (const u16*)stage, rows, K,
+                             ceil_div(K, 32), row_base, row_map, c->D, col_gain, dst);
+      }
       if (e == hipSuccess) e = hipGetLastError();
       if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     }
@@ -635,7 +740,21 @@ int bd_prefill(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* d
   BD_TRY(check_launch());
   c->n = 0; c->prefilled = false; c->carry_valid = false;
   const int step = c->cfg.max_block;                   // (at most 32 with e4m3 weights, checked at creation)
-  for (int off = 0; off < total; off += step) {
+  int off0 = 0;
+  if (c->pf_on) {
+    // the bulk of the prompt in large chunks; at least one row is left for the pass that produces the carry
+    const int fast = (total - 1) / 16 * 16;
+    while (off0 < fast && fast >= kPfTokens) {
+      int mc = std::min(c->pf_rows, fast - off0);
+      if (fast - off0 - mc > 0 && fast - off0 - mc < kPfTokens && mc > kPfTokens) mc -= kPfTokens;   // no sliver of a last chunk
+      BD_TRY(prefill_chunk(c, dev_embeds, n_embed, dev_ids, off0, mc));
+      hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(1), 0, s, c->st, mc);
+      BD_TRY(check_launch());
+      c->n += mc;
+      off0 += mc;
+    }
+  }
+  for (int off = off0; off < total; off += step) {
     const int M = std::min(step, total - off);
     const bool last = off + M >= total;
     BD_TRY(forward(c, M, BD_MODE_CAUSAL, last, dev_embeds, n_embed, dev_ids, off, nullptr, nullptr, nullptr));

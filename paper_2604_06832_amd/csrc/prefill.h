@@ -1,0 +1,312 @@
+// Large-M prefill (Alg. 1 "prefill": one causal forward over the prompt that fills the KV cache).
+//
+// The decode kernels stream every weight once per forward of at most 64 rows, so a prompt of n tokens pushed
+// through them re-reads the model n/64 times.  For the bulk of the prompt this file provides the compute-bound
+// form: chunks of up to 1024 rows, each layer as a sequence of tiled MFMA GEMMs with the same fused epilogues as the
+// decode path (RMS factor, rotary + Q store + K/V store; residual add; SwiGLU) and a causal attention kernel that
+// walks the packed cache with the decode path's per-block routine.  The last rows of the prompt (and the LM head,
+// which is needed for the last row only) still go through the decode kernels.
+//
+// Operand layout: both GEMM operands are kept as 1-KiB MFMA fragments (16 rows x 32 k, lane (row i, k-quarter kq)
+// holds 8 consecutive k at lane*16 bytes).  Weights: fragment (row tile T, k-step ks) of a layer's phase at
+// ((T*KS + ks)*64 + lane) 16-byte units, rows in the decode path's phase-row order (rotary pairs of q/k adjacent,
+// (gate f, up f) adjacent, norm gains folded into the columns).  Activations: the packed order of xp_index().
+#pragma once
+#include "stream_fwd.h"
+
+namespace bd {
+
+constexpr int kPfTokens = 128;        // tokens per workgroup tile (8 token tiles of 16)
+constexpr int kPfThreads = 256;       // four wavefronts, 2 (rows) x 2 (tokens)
+
+struct PfGemmArgs {
+  const bf16x8* w;        // fragments of this layer's phase, tile-major
+  int NT, KS;             // 16-row tiles and k-steps of the phase
+  const bf16x8* xin;      // packed activations of the chunk
+  int MTc;                // token tiles of the chunk (any number: a workgroup's eight may reach past the end)
+  int RG, TG;             // workgroup grid: row groups x token groups
+  const float* rs;        // [Mc] 1/rms of the rows of the residual stream (QKV, gate/up)
+  const float2* rope;     // [Mc][D/2] (QKV)
+  float* x;               // [Mc][H] residual stream, updated in place (O, down)
+  u16* q;                 // [Mc][n_q][D] (QKV)
+  u16* Kc; u16* Vc;       // this layer's packed cache (QKV)
+  int max_kb, n0;         // key blocks per kv head; position of the chunk's first row
+  u16* act;               // packed SwiGLU output (gate/up)
+  int H, QD, KVD, D, n_q;
+};
+
+// C[rows of the phase][tokens] = W * X^T, fp32 accumulation, epilogue per phase.  A workgroup computes
+// (2*WN*16) rows x 128 tokens; each wavefront WN x 4 tiles of 16 x 16.  K advances by BKS k-steps per iteration
+// through two LDS stages; the operands of a stage travel global memory -> registers -> LDS, the loads of stage i+1
+// being issued before the MFMAs of stage i.  (A second register set, two stages ahead, costs more in registers than
+// it hides in latency: measured slower for every shape here.)
+template <int PH, int WN, int BKS>
+__global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 8 * BKS * 64) * 16 <= 80 * 1024) ? 2 : 1) void pf_gemm_kernel(PfGemmArgs a) {
+  constexpr int AT = 2 * WN;                                        // row tiles per workgroup
+  constexpr int A_UNITS = AT * BKS * 64, B_UNITS = 8 * BKS * 64;    // 16-byte units per stage
+  constexpr int STAGE = A_UNITS + B_UNITS;
+  constexpr int A_PER = A_UNITS / kPfThreads, B_PER = B_UNITS / kPfThreads;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  bf16x8* sm = reinterpret_cast<bf16x8*>(lds);
+  // Row group rg runs on XCD rg mod 8 for all of its token groups, so that a weight tile is fetched into one L2.
+  const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+  const int rg = (slot / a.TG) * 8 + xcd, tg = slot % a.TG;
+  if (rg >= a.RG) return;
+  const int T0 = rg * AT, mt0 = tg * 8;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wn = wave >> 1, wm = wave & 1;
+  const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+
+  // Operands come through raw buffer loads (an offset past the end returns zeros and moves nothing).  Unit u = thread
+  // + 256 i of a stage: for the weights tile u / (BKS*64), unit u mod (BKS*64) of its BKS KiB; for the activations
+  // k-step u / 512, unit u mod 512 of the eight token tiles.
+  const rsrc_t wr = make_rsrc(a.w, (unsigned)((size_t)a.NT * a.KS * 1024));
+  const rsrc_t xr = make_rsrc(a.xin, (unsigned)((size_t)a.KS * a.MTc * 1024));
+  struct Regs { bf16x8 a[A_PER], b[B_PER]; };
+  constexpr int TU = BKS * 64;                                      // units per weight tile and stage
+  const int a_tile = threadIdx.x / TU, a_within = threadIdx.x % TU; // (256 / TU tiles per round of 256 units)
+  const int a_base = ((T0 + a_tile) * a.KS) * 1024 + a_within * 16;
+  const int a_ksl = a_within >> 6;
+  const int b_base = mt0 * 1024 + threadIdx.x * 16;
+  const int b_tile = threadIdx.x >> 6;
+  auto gload = [&](Regs& R, int it) {
+    const int ks0 = it * BKS;
+    const bool a_ok = ks0 + a_ksl < a.KS;
+#pragma unroll
+    for (int i = 0; i < A_PER; ++i) {
+      const int off = a_base + (i * (kPfThreads / TU) * a.KS + ks0) * 1024;
+      R.a[i] = buf_load_b(wr, (a_ok && T0 + a_tile + i * (kPfThreads / TU) < a.NT) ? off : kOob);
+    }
+#pragma unroll
+    for (int i = 0; i < B_PER; ++i) {
+      const int ksl = i >> 1, half = i & 1;
+      const int off = b_base + ((ks0 + ksl) * a.MTc) * 1024 + half * 4096;
+      R.b[i] = buf_load_b(xr, (ks0 + ksl < a.KS && mt0 + b_tile + 4 * half < a.MTc) ? off : kOob);
+    }
+  };
+  auto lstore = [&](const Regs& R, int stage) {
+    bf16x8* A = sm + stage * STAGE;
+#pragma unroll
+    for (int i = 0; i < A_PER; ++i) A[threadIdx.x + i * kPfThreads] = R.a[i];
+#pragma unroll
+    for (int i = 0; i < B_PER; ++i) A[A_UNITS + threadIdx.x + i * kPfThreads] = R.b[i];
+  };
+
+  f32x4 acc[WN][4];
+#pragma unroll
+  for (int i = 0; i < WN; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  auto compute = [&](int stage) {
+    const bf16x8* A = sm + stage * STAGE;
+    const bf16x8* Bm = A + A_UNITS;
+#pragma unroll
+    for (int ksl = 0; ksl < BKS; ++ksl) {
+      bf16x8 af[WN], bfr[4];
+#pragma unroll
+      for (int i = 0; i < WN; ++i) af[i] = A[((wn * WN + i) * BKS + ksl) * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bfr[j] = Bm[(ksl * 8 + wm * 4 + j) * 64 + lane];
+#pragma unroll
+      for (int i = 0; i < WN; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  const int n_it = (a.KS + BKS - 1) / BKS;
+  Regs R0;
+  gload(R0, 0);
+  lstore(R0, 0);
+  __syncthreads();
+  for (int it = 0; it < n_it; ++it) {
+    if (it + 1 < n_it) gload(R0, it + 1);
+    compute(it & 1);
+    if (it + 1 < n_it) lstore(R0, (it + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: lane (token column col, row quad g) holds rows r .. r+3 of one token ----
+  const int col = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < WN; ++i) {
+    const int T = T0 + wn * WN + i;
+    if (T >= a.NT) continue;
+    const int r = T * 16 + 4 * g;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (mt0 + wm * 4 + j >= a.MTc) continue;
+      const int token = (mt0 + wm * 4 + j) * 16 + col;
+      f32x4 v = acc[i][j];
+      if constexpr (PH == PH_QKV) {
+        const int D = a.D, half = D >> 1;
+        v *= a.rs[token];
+        const int key = a.n0 + token;
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+          const int rp = r + 2 * pr;
+          if (rp < a.QD + a.KVD) {
+            // rotary pair: phase rows (2i, 2i+1) of a head hold dims (i, i + D/2)
+            const int dp = rp % D;
+            const float2 cs = a.rope[(size_t)token * half + (dp >> 1)];
+            const float lo = v[2 * pr] * cs.x - v[2 * pr + 1] * cs.y;
+            const float hi = v[2 * pr + 1] * cs.x + v[2 * pr] * cs.y;
+            const uint32_t pk = (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+            u16* dst;
+            if (rp < a.QD) {
+              dst = a.q + ((size_t)token * a.n_q + rp / D) * D + dp;
+            } else {
+              const int rk = rp - a.QD;
+              dst = a.Kc + (size_t)(rk / D) * a.max_kb * 32 * D + kp_index(key, dp, D / 32);
+            }
+            *reinterpret_cast<uint32_t*>(dst) = pk;
+          } else {
+            const int rv = rp - a.QD - a.KVD;
+            u16* vc = a.Vc + (size_t)(rv / D) * a.max_kb * 32 * D;
+            vc[vp_index(key, rv % D, D / 16)] = f32_to_bf16_bits(v[2 * pr]);
+            vc[vp_index(key, (rv + 1) % D, D / 16)] = f32_to_bf16_bits(v[2 * pr + 1]);
+          }
+        }
+      } else if constexpr (PH == PH_O || PH == PH_DOWN) {
+        f32x4* xp = reinterpret_cast<f32x4*>(a.x + (size_t)token * a.H + r);
+        *xp = *xp + v;
+      } else {
+        v *= a.rs[token];
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+          const float gt = v[2 * pr], up = v[2 * pr + 1];
+          a.act[xp_index(token, (r >> 1) + pr, a.MTc)] = f32_to_bf16_bits(gt / (1.f + __expf(-gt)) * up);
+        }
+      }
+    }
+  }
+}
+
+template <int WN, int BKS> constexpr int pf_gemm_lds() { return 2 * (2 * WN * BKS * 64 + 8 * BKS * 64) * 16; }
+
+// One workgroup per row: 1/rms of the fp32 residual row and its bf16 copy in packed order (the norm gain lives in
+// the weights, the factor is applied by the GEMM epilogue: same arithmetic as the decode path).
+__global__ __launch_bounds__(kPfThreads) void pf_norm_kernel(const float* __restrict__ x, int H, float eps, u16* __restrict__ xb,
+                                                             int MTc, float* __restrict__ rs) {
+  __shared__ float part[kPfThreads / 64];
+  const int token = blockIdx.x;
+  const float* row = x + (size_t)token * H;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < H; c += kPfThreads) {
+    const float v = row[c];
+    ss += v * v;
+    xb[xp_index(token, c, MTc)] = f32_to_bf16_bits(v);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int w = 0; w < kPfThreads / 64; ++w) t += part[w];
+    rs[token] = rsqrtf(t / (float)H + eps);
+  }
+}
+
+// Causal attention of a chunk against the packed cache (which already holds the chunk's own keys and values):
+// one wavefront per (head, tile of 16 query rows), walking the 32-key blocks up to its last visible key with the
+// decode path's block routine and two register buffers.  Four consecutive items (heads of one kv head first) share
+// a workgroup, so their key/value blocks meet in the caches.
+struct PfAttnArgs {
+  const u16* q;           // [Mc][n_q][D], rotated, dims in rotary-pair order
+  const u16* Kc; const u16* Vc;
+  int max_kb, n0, Mc, n_q, n_kv;
+  float scale_log2e;
+  u16* out;               // packed attention output (K = n_q*D)
+  int MTc;
+};
+
+template <int D>
+__global__ __launch_bounds__(kPfThreads) void pf_attn_kernel(PfAttnArgs a) {
+  constexpr int DS = D / 32, DT = D / 16;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int col = lane & 15, g = lane >> 4;
+  const int G = a.n_q / a.n_kv, QT = a.Mc >> 4;
+  const int item = blockIdx.x * (kPfThreads / 64) + wave;
+  if (item >= a.n_kv * QT * G) return;
+  const int hq = item % G, qt = (item / G) % QT, kvh = item / (G * QT);
+  const int head = kvh * G + hq;
+  const int row = qt * 16 + col;
+  const size_t kv_block = (size_t)32 * D / 8;
+  const bf16x8* Kh = reinterpret_cast<const bf16x8*>(a.Kc) + (size_t)kvh * a.max_kb * kv_block;
+  const bf16x8* Vh = reinterpret_cast<const bf16x8*>(a.Vc) + (size_t)kvh * a.max_kb * kv_block;
+  bf16x8 qf[DS];
+  {
+    const u16* qp = a.q + ((size_t)row * a.n_q + head) * D + 8 * g;
+#pragma unroll
+    for (int ds = 0; ds < DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8*>(qp + ds * 32);
+  }
+  f32x4 O[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float mrun = kNegBig, lrun = 0.f;
+  const int kb_end = (a.n0 + qt * 16 + 15) / 32 + 1;            // blocks holding a key some row of the tile may see
+  const float c = a.scale_log2e;
+  KvBlock<D> b0, b1;
+  kv_load<D>(b0, Kh, Vh, 0, lane);
+  asm volatile("" ::: "memory");
+  for (int kb = 0; kb < kb_end; kb += 2) {
+    if (kb + 1 < kb_end) kv_load<D>(b1, Kh, Vh, kb + 1, lane);
+    asm volatile("" ::: "memory");
+    if (kb * 32 + 31 >= a.n0) attn_block<D, true>(b0, qf, O, mrun, lrun, kb, a.n0, a.Mc, 1, row, g, c);
+    else attn_block<D, false>(b0, qf, O, mrun, lrun, kb, a.n0, a.Mc, 1, row, g, c);
+    if (kb + 1 < kb_end) {
+      if (kb + 2 < kb_end) kv_load<D>(b0, Kh, Vh, kb + 2, lane);
+      asm volatile("" ::: "memory");
+      if ((kb + 1) * 32 + 31 >= a.n0) attn_block<D, true>(b1, qf, O, mrun, lrun, kb + 1, a.n0, a.Mc, 1, row, g, c);
+      else attn_block<D, false>(b1, qf, O, mrun, lrun, kb + 1, a.n0, a.Mc, 1, row, g, c);
+    }
+  }
+  const float inv = 1.f / lrun;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    const f32x4 o = O[dt] * inv;
+    const int fo = head * D + dt * 16 + 4 * g;
+    const uint32_t lo = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
+    const uint32_t hi = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
+    *reinterpret_cast<uint64_t*>(a.out + xp_index(row, fo, a.MTc)) = (uint64_t)lo | ((uint64_t)hi << 32);
+  }
+}
+
+// One matrix into the tile-major fragment order of the prefill GEMMs (same row maps and column gains as the
+// weight stream of the decode kernels).
+template <typename SrcT>
+__global__ void pack_tiles_kernel(const SrcT* __restrict__ src, int n_rows, int K, int KS, int row_base, int row_map, int D,
+                                  const float* __restrict__ col_gain, u16* __restrict__ dst) {
+  const size_t total = (size_t)n_rows * KS * 4;             // one thread per (row, k-step, k-quarter)
+  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
+    const int kq = idx & 3;
+    const int ks = (int)((idx >> 2) % KS);
+    const int rs = (int)(idx / ((size_t)KS * 4));
+    int r;
+    if (row_map == 1) {
+      const int h = rs / D, d = rs % D, half = D >> 1;
+      r = row_base + h * D + (d < half ? 2 * d : 2 * (d - half) + 1);
+    } else if (row_map == 2) {
+      r = row_base + 2 * rs;
+    } else {
+      r = row_base + rs;
+    }
+    u16* o = dst + ((((size_t)(r >> 4) * KS + ks) * 64) + kq * 16 + (r & 15)) * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int k = ks * 32 + kq * 8 + e;
+      u16 v = 0;
+      if (k < K) {
+        float f;
+        if constexpr (sizeof(SrcT) == 4) f = ((const float*)src)[(size_t)rs * K + k];
+        else f = bf16_bits_to_f32(((const u16*)src)[(size_t)rs * K + k]);
+        if (col_gain != nullptr) f *= col_gain[k];
+        v = f32_to_bf16_bits(f);
+      }
+      o[e] = v;
+    }
+  }
+}
+
+}  // namespace bd

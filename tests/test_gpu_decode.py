@@ -500,13 +500,45 @@ def test_call_order_and_capacity_errors():
     ctx.close()
 
 
-@pytest.mark.parametrize("n_embed,n_ids", [(0, 1), (1, 0), (0, 70), (70, 0), (63, 66)])
+@pytest.mark.parametrize("n_embed,n_ids", [(0, 1), (1, 0), (0, 70), (70, 0), (63, 66), (0, 128), (130, 126), (0, 144),
+                                           (700, 400)])
 def test_prefill_edge_lengths(n_embed, n_ids):
+    """Prompts of fewer than 129 rows go through the decode kernels only; longer ones put all but their last 1-16 rows
+    through the large-M path: 128 -> 112 + 16, 256 -> 240 + 16, 144 -> 128 + 16, 1100 -> chunks of 896 and 192 + 12."""
     shape = inputs.TINY
     w = inputs.make_weights(shape, 0, "bf16", threads=1)
     emb, ids = inputs.make_prompt(shape, n_embed, n_ids, seed=7)
-    p = Pair(shape, w, max_seq=256)
+    p = Pair(shape, w, max_seq=max(256, n_embed + n_ids + 32))
     p.prefill(emb, ids)
     p.check_carry()
     p.check_kv(0, n_embed + n_ids)
+    tok, msk = fresh_block(shape, 8)
+    p.denoise_step(tok, msk, 0.9, fixed_k=3)            # a decode step on top of the prefilled cache
     p.close()
+
+
+def test_large_m_prefill_agrees_with_the_chunked_one(monkeypatch):
+    """The same prompt through the large-M kernels and through 64-row decode forwards: same cache and carry up to
+    bf16 rounding of a different summation order (each path is also held against the oracle elsewhere)."""
+    _say("3B-shaped x2 layers: large-M prefill vs chunked prefill, 700 rows")
+    shape = _wide(2, vocab=8192)
+    w = inputs.make_weights(shape, 4, "bf16", threads=8)
+    emb, ids = inputs.make_prompt(shape, 500, 200, seed=12)
+    res = []
+    for mode in ("large", "chunked"):
+        if mode == "chunked":
+            monkeypatch.setenv("BD_PREFILL", "chunked")
+        else:
+            monkeypatch.delenv("BD_PREFILL", raising=False)
+        ctx = binding.Context(shape, max_seq=768, max_block=64)
+        ctx.load_model(w, as_bf16_bits=True)
+        ctx.bd_prefill(torch.from_numpy(emb).cuda(), torch.from_numpy(ids).cuda())
+        assert ctx.bd_cache_len() == 700
+        k, v = ctx.bd_read_kv(1, 0, 700)
+        res.append((k.clone(), v.clone(), ctx.bd_read_carry()))
+        ctx.bd_status()
+        ctx.close()
+    (k0, v0, c0), (k1, v1, c1) = res
+    for a, b in ((k0, k1), (v0, v1)):
+        assert float((a - b).abs().max()) <= 2e-2 * float(b.abs().max())
+    assert c0[0] == c1[0] and abs(c0[1] - c1[1]) <= 0.05 * c1[1]
