@@ -93,9 +93,13 @@ def main():
             ctx.bd_denoise_step(tok, msk, 0.9, K)
         ctx.bd_commit_block(tok)
 
+    prefill_s = []
+
     def run(n_blocks, after_prefill=None):
+        tp = time.perf_counter()
         ctx.bd_prefill(d_emb, d_ids)
         torch.cuda.synchronize()
+        prefill_s.append(time.perf_counter() - tp)
         if after_prefill is not None:
             after_prefill()
         t = time.perf_counter()
@@ -204,6 +208,10 @@ def main():
                    "block": B, "fixed_k": K, "prefix": args.prefix, "forwards_per_block": n_den + 1},
         "ms_per_forward": round(ms_fwd, 4), "hbm_roofline_frac_step": round(step_frac, 4),
         **({"speculative": spec} if spec is not None else {}),
+        # the prompt pass (not part of `value`): large-M kernels for all but its last rows; linears only in the flop count
+        "prefill": {"ms": round(min(prefill_s) * 1e3, 3), "tokens_per_s": round(args.prefix / min(prefill_s), 1),
+                    "TFLOPs": round(2.0 * args.prefix * (shape.weight_elements() - shape.vocab * shape.hidden)
+                                    / min(prefill_s) / 1e12, 1)},
         "algorithmic_GB_per_forward": round(total_bytes / forwards / 1e9, 4),
         "roofline": roofline, "cpu_baseline": cpu,
     }
