@@ -111,6 +111,15 @@ int bd_commit_block(bd_ctx* ctx, const int32_t* dev_block_tokens, int B);
 int bd_verify_block(bd_ctx* ctx, const int32_t* dev_draft, int B, int commit, int32_t* dev_ar_pred,
                     int32_t* dev_n_accept);
 
+/* A whole block with no host decision and no synchronisation in between (Sec. 3.4 block-by-block decoding with
+ * confidence-aware parallel unmasking): seed from the carry, denoising steps until nothing is masked, commit.
+ * The library enqueues as many steps as any block can need (B-1 under the threshold rule, ceil((B-1)/fixed_k)
+ * under the fixed schedule); a flag on the device tells the kernels of the steps after the last useful one to do
+ * nothing, so a block that completes early costs only their launches.
+ * dev_tokens_out: device int32[B], the block's tokens.  dev_steps_out: device int32 (may be NULL), the number of
+ * denoising forwards that really ran.  Errors as bd_denoise_step, plus BD_E_STATE without a valid carry. */
+int bd_decode_block(bd_ctx* ctx, int B, float threshold, int fixed_k, int32_t* dev_tokens_out, int32_t* dev_steps_out);
+
 /* One iteration of the linear self-speculative loop (appendix "Details of Speculative Decoding", Alg. 1), with no
  * host decision in between: the block [x_n, MASK, ...] (x_n = the carry's argmax, i.e. the token predicted for
  * position cache_len) is drafted in one bidirectional forward without cache update (row i-1 fills position i);

@@ -305,7 +305,7 @@ int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
 // One decoder forward over M rows: prologue (block assembly) + the persistent forward kernel.
 // Source of the rows: prompt rows [off, off+M) (embeds then ids), or block tokens with an optional mask.
 int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n_embed, const int32_t* ids, int off,
-            int32_t* seed_tokens, uint8_t* seed_mask, const uint8_t* mask) {
+            int32_t* seed_tokens, uint8_t* seed_mask, const uint8_t* mask, bool skippable = false) {
   const int MT = ceil_div(M, 16);
   const int Mp = c->Mp_max;
   hipStream_t s = c->stream;
@@ -318,6 +318,7 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
     p.rope = c->rope; p.half = c->D / 2; p.theta = c->cfg.rope_theta;
     p.counters = c->counters; p.n_counters = c->n_cntD + c->n_cntA;
     p.gain0 = c->fp8 ? c->gains : nullptr;
+    p.skippable = skippable ? 1 : 0;
     Prof pr(c, KC_PROLOGUE);
     hipLaunchKernelGGL(prologue_kernel, dim3(M), dim3(kWGThreads), 0, s, p);
     BD_TRY(check_launch());
@@ -327,6 +328,7 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
   a.wstream = reinterpret_cast<const bf16x8*>(c->wstream);
   a.st = c->st; a.bar = c->bar; a.bar_epoch = c->bar_epoch;
   a.M = M; a.MT = MT; a.mode = mode; a.want_lm = want_lm ? 1 : 0;
+  a.skippable = skippable ? 1 : 0;
   a.xv = c->xv; a.xb = c->xb; a.xb_elems = c->xb_elems; a.ssq = c->ssq; a.ssq_parts = c->ssq_parts; a.Mp = Mp; a.gains = c->gains; a.rms_eps = c->cfg.rms_eps;
   a.fp8 = c->fp8 ? 1 : 0; a.wscale = c->wscale; a.wscale_layer = c->wscale_layer;
   for (int i = 0; i < 4; ++i) a.wscale_off[i] = c->wscale_off[i];
@@ -821,13 +823,45 @@ int bd_verify_block(bd_ctx* c, const int32_t* dev_draft, int B, int commit, int3
   return causal_pass(c, dev_draft, B, commit ? 1 : 0, dev_ar_pred, dev_n_accept, dev_draft);
 }
 
+int bd_decode_block(bd_ctx* c, int B, float threshold, int fixed_k, int32_t* dev_tokens_out, int32_t* dev_steps_out) {
+  BD_TRY(check_decode_call(c, B));
+  if (dev_tokens_out == nullptr || fixed_k < 0) return BD_E_ARG;
+  if (!c->carry_valid) return BD_E_STATE;
+  hipStream_t s = c->stream;
+  hipLaunchKernelGGL(fill_masked_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, B, c->cfg.mask_token_id, c->st);
+  BD_TRY(check_launch());
+  if (B == 1) {
+    hipLaunchKernelGGL(seed_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, c->st);
+    BD_TRY(check_launch());
+  } else {
+    // every step reveals at least one position (min(fixed_k, left) under the fixed schedule), so this many complete
+    // any block; the steps after the last useful one find DevState::skip set and do nothing
+    const int steps = fixed_k > 0 ? ceil_div(B - 1, fixed_k) : B - 1;
+    for (int i = 0; i < steps; ++i) {
+      BD_TRY(forward(c, B, BD_MODE_BIDIR, true, nullptr, 0, c->spec_tokens, 0, c->spec_tokens, c->spec_mask, c->spec_mask, true));
+      FinishArgs f = finish_args(c, B);
+      f.tokens = c->spec_tokens; f.mask = c->spec_mask; f.threshold = threshold; f.fixed_k = fixed_k; f.skippable = 1;
+      Prof pr(c, KC_FINISH);
+      hipLaunchKernelGGL(finish_denoise_kernel, dim3(1), dim3(64), 0, s, f);
+      BD_TRY(check_launch());
+    }
+  }
+  BD_TRY(causal_pass(c, c->spec_tokens, B, 1, nullptr, nullptr, nullptr));
+  HIP_TRY(hipMemcpyAsync(dev_tokens_out, c->spec_tokens, (size_t)B * 4, hipMemcpyDeviceToDevice, s));
+  if (dev_steps_out != nullptr) {
+    hipLaunchKernelGGL(read_steps_kernel, dim3(1), dim3(1), 0, s, c->st, dev_steps_out);
+    BD_TRY(check_launch());
+  }
+  return BD_OK;
+}
+
 int bd_speculative_step(bd_ctx* c, int B, int32_t* dev_tokens_out, int32_t* host_n_accepted) {
   BD_TRY(check_decode_call(c, B));
   if (dev_tokens_out == nullptr || host_n_accepted == nullptr) return BD_E_ARG;
   if (!c->carry_valid) return BD_E_STATE;
   hipStream_t s = c->stream;
   // draft: [x_n, MASK, ...] -> every masked position filled by the argmax of the row before it, in one pass
-  hipLaunchKernelGGL(fill_masked_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, B, c->cfg.mask_token_id);
+  hipLaunchKernelGGL(fill_masked_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, B, c->cfg.mask_token_id, c->st);
   BD_TRY(check_launch());
   if (B == 1) {
     hipLaunchKernelGGL(seed_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, c->st);

@@ -48,6 +48,8 @@ struct DevState {
   int carry_cand;    // prediction for position n
   float carry_conf;
   int error;         // sticky device-side error flag (bounded waits)
+  int skip;          // bd_decode_block: the current block has no masked position left; its remaining steps do nothing
+  int steps;         // bd_decode_block: denoising forwards that really ran for the current block
 };
 
 }  // namespace bd

@@ -134,6 +134,7 @@ struct MegaArgs {
                               // tile slot of the O phase, even versions one per tile slot of the DOWN phase
   int Mp;
   const float* gains;         // [2L+1][H]: attn_norm l, ffn_norm l, ..., final_norm
+  int skippable;              // this launch belongs to a step that does nothing once the block is complete (DevState::skip)
   int local_gu;               // the gate/up -> down hand-over stays inside each XCD (stream_fwd.h): plain stores, XCD barrier
   unsigned* xbar;             // [xcd][32 words] arrival counters of the XCD barriers
   unsigned xbar_epoch;        // XCD barriers run before this launch
@@ -222,6 +223,18 @@ __device__ inline bool grid_barrier(unsigned* bar, unsigned epoch, int nwg, DevS
   }
   __syncthreads();
   return *s_flag != 0;
+}
+
+// A launch that is skipped on the device (a step of a block that is already complete) still owes the barrier
+// counters the arrivals the host has counted for it: per chip-wide barrier one arrival of every workgroup on its
+// group counter and one of every group on the top counter, per XCD barrier one arrival of every workgroup on its XCD's
+// counter.  The release words stay behind; the next real barrier overwrites them with a larger epoch.
+__device__ inline void skip_barriers(unsigned* bar, unsigned* xbar, unsigned n_global, unsigned n_xcd) {
+  if (threadIdx.x != 0) return;
+  const int g = blockIdx.x / kBarGroup;
+  __hip_atomic_fetch_add(bar + 32 * (1 + g), n_global, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (blockIdx.x % kBarGroup == 0) __hip_atomic_fetch_add(bar, n_global, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (n_xcd != 0u) __hip_atomic_fetch_add(xbar + 32 * (blockIdx.x % 8), n_xcd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---- weight stream cursor ----------------------------------------------------------------------------------
@@ -985,7 +998,14 @@ __global__ __launch_bounds__(kWGThreads, 1) void mega_kernel(MegaArgs a) {
   __shared__ int s_flags[16];
   const MegaPlan& P = a.P;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id in an SGPR: all branches on it are scalar
-  if (threadIdx.x == 0) s_flags[0] = (a.st->error == 0);
+  if (threadIdx.x == 0) {
+    int go = (a.st->error == 0);
+    if (go && a.skippable && a.st->skip) {
+      skip_barriers(a.bar, nullptr, 5u * (unsigned)P.L, 0u);
+      go = 0;
+    }
+    s_flags[0] = go;
+  }
   __syncthreads();
   if (!s_flags[0]) return;
 
@@ -1051,7 +1071,14 @@ __global__ __launch_bounds__(kWGThreads, 1) void lm_kernel(MegaArgs a) {
   __shared__ int s_flags[16];
   const MegaPlan& P = a.P;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id in an SGPR: all branches on it are scalar
-  if (threadIdx.x == 0) s_flags[0] = (a.st->error == 0);
+  if (threadIdx.x == 0) {
+    int go = (a.st->error == 0);
+    if (go && a.skippable && a.st->skip) {
+      skip_barriers(a.bar, nullptr, 1u, 0u);
+      go = 0;
+    }
+    s_flags[0] = go;
+  }
   __syncthreads();
   if (!s_flags[0]) return;
   PhaseCtx pc;
@@ -1108,6 +1135,7 @@ struct PrologueArgs {
   DevState* st;
   float2* rope; int half; float theta;
   unsigned* counters; int n_counters;
+  int skippable;                              // nothing to do once the block is complete (DevState::skip)
   const float* gain0;                         // fp8 weights: gain of the first norm, applied to the bf16 copy (else nullptr)
 };
 
@@ -1115,6 +1143,7 @@ __global__ __launch_bounds__(kWGThreads) void prologue_kernel(PrologueArgs a) {
   __shared__ float wsum[kWavesPerWG];
   __shared__ int s_id;
   const int r = blockIdx.x;
+  if (a.skippable && a.st->skip) return;
   for (int i = blockIdx.x * kWGThreads + threadIdx.x; i < a.n_counters; i += gridDim.x * kWGThreads) a.counters[i] = 0u;
   {
     const double pos = (double)(a.st->n + r);

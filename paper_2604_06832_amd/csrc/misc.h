@@ -273,6 +273,7 @@ struct FinishArgs {
   int commit;
   int* ar_pred;
   int* n_accept;
+  int skippable;            // bd_decode_block: do nothing once the block is complete, else count the step and set the flag
 };
 
 // Confidence-threshold parallel unmask (Sec. 3.4; "Decoding threshold").  Row i-1 predicts block
@@ -281,6 +282,7 @@ __global__ __launch_bounds__(64) void finish_denoise_kernel(FinishArgs a) {
   __shared__ int s_cand[64];
   __shared__ float s_conf[64];
   __shared__ uint8_t s_mask[64];
+  if (a.skippable && a.st->skip) return;
   if ((int)threadIdx.x < a.B) {
     s_cand[threadIdx.x] = a.row_cand[threadIdx.x];
     s_conf[threadIdx.x] = a.row_conf[threadIdx.x];
@@ -315,18 +317,26 @@ __global__ __launch_bounds__(64) void finish_denoise_kernel(FinishArgs a) {
           if (c > a.threshold) {
             a.tokens[i] = s_cand[i - 1];
             a.mask[i] = 0;
+            s_mask[i] = 0;
             ++cnt;
           }
         }
         if (cnt == 0) {
           a.tokens[best] = s_cand[best - 1];
           a.mask[best] = 0;
+          s_mask[best] = 0;
           cnt = 1;
         }
         revealed += cnt;
       }
     }
     if (a.n_unmasked) *a.n_unmasked = revealed;
+    if (a.skippable) {
+      int left = 0;
+      for (int i = 1; i < a.B; ++i) left += s_mask[i] ? 1 : 0;
+      a.st->steps += 1;
+      a.st->skip = left == 0;
+    }
   }
 }
 
@@ -376,9 +386,13 @@ __global__ __launch_bounds__(64) void finish_causal_kernel(FinishArgs a) {
 }
 
 // All positions of a block masked (the state before the draft pass of Alg. 1).
-__global__ void fill_masked_kernel(int* tokens, uint8_t* mask, int B, int mask_id) {
+__global__ void fill_masked_kernel(int* tokens, uint8_t* mask, int B, int mask_id, DevState* st) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < B) { tokens[i] = mask_id; mask[i] = 1; }
+  if (i == 0) { st->skip = 0; st->steps = 0; }
+}
+__global__ void read_steps_kernel(const DevState* st, int* out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *out = st->steps;
 }
 
 // Commit without an LM-head pass (prompt chunks before the last one).

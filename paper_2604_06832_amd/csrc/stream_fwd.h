@@ -974,6 +974,10 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
   if (threadIdx.x < SY_WORDS) s_sync[threadIdx.x] = 0u;
   if (threadIdx.x == 0) {
     int go = (a.st->error == 0);
+    if (go && a.skippable && a.st->skip) {
+      skip_barriers(a.bar, a.xbar, (a.local_gu ? 4u : 5u) * (unsigned)P.L, a.local_gu ? (unsigned)P.L : 0u);
+      go = 0;
+    }
     if (go && a.local_gu && xcc_id() != blockIdx.x % 8u) {   // the XCD-local hand-over would be unsafe
       __hip_atomic_store(&a.st->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       go = 0;

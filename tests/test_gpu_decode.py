@@ -145,6 +145,63 @@ def test_verify_accept_and_crop(B):
 
 
 
+
+# ---- a whole block per call, early-out on the device ---------------------------------------------------------
+
+@pytest.mark.parametrize("shape_name,B,tau,fixed_k", [("tiny", 16, 0.3, 0), ("tiny", 16, 0.0, 0), ("tiny", 16, 1.0, 0),
+                                                      ("tiny", 1, 0.5, 0), ("tiny", 64, 0.6, 0), ("tiny", 33, 0.9, 5),
+                                                      ("wide", 32, 0.02, 0), ("wide", 16, 0.9, 4)])
+def test_decode_block_equals_the_step_by_step_loop(shape_name, B, tau, fixed_k):
+    """bd_decode_block enqueues the largest number of steps a block can need and lets the device skip the ones after
+    the block is complete.  Against a second context driven step by step (host reads the mask after every step):
+    same tokens, same number of forwards, same cache and carry, bit for bit, over three blocks -- and the step-by-step
+    loop itself is held against the oracle."""
+    _say(f"bd_decode_block vs step-by-step, {shape_name}, B={B}, tau={tau}, fixed_k={fixed_k}")
+    if shape_name == "tiny":
+        shape = inputs.TINY
+        w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, norm_gain_jitter=0.1, threads=1)
+    else:
+        shape = _wide(2, vocab=8192)
+        w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, threads=8)
+    emb, ids = inputs.make_prompt(shape, 16, 16, seed=4)
+    p = Pair(shape, w, max_seq=32 + 3 * B, max_block=B)
+    p.prefill(emb, ids)
+    ctx2 = binding.Context(shape, max_seq=32 + 3 * B, max_block=B)
+    ctx2.load_model(w, as_bf16_bits=True)
+    ctx2.bd_prefill(torch.from_numpy(emb).cuda(), torch.from_numpy(ids).cuda())
+    out = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nst = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for blk in range(3):
+        ctx2.bd_decode_block(B, tau, fixed_k, out, nst)
+        tok, msk = fresh_block(shape, B)
+        gt = torch.from_numpy(tok.astype(np.int32)).cuda()
+        gm = torch.from_numpy(msk.astype(np.uint8)).cuda()
+        fwd = 0
+        while True:
+            p.ctx.bd_denoise_step(gt, gm, tau, fixed_k, None, None)
+            fwd += int(B > 1)
+            if not bool(gm.any().item()):
+                break
+            assert fwd < B
+        p.ctx.bd_commit_block(gt)
+        assert torch.equal(out, gt), (blk, out, gt)
+        assert int(nst.item()) == fwd, (blk, int(nst.item()), fwd)
+        assert ctx2.bd_cache_len() == p.ctx.bd_cache_len()
+        assert ctx2.bd_read_carry() == p.ctx.bd_read_carry()
+    n = p.ctx.bd_cache_len()
+    for l in range(shape.n_layers):
+        ka, va = ctx2.bd_read_kv(l, 0, n)
+        kb, vb = p.ctx.bd_read_kv(l, 0, n)
+        assert torch.equal(ka, kb) and torch.equal(va, vb)
+    ctx2.bd_status()
+    p.ctx.bd_status()
+    if fixed_k == 0 and tau <= 0.0 and B > 1:
+        assert int(nst.item()) == 1                     # everything clears a threshold of zero in one step
+    if fixed_k == 0 and tau >= 1.0:
+        assert int(nst.item()) == B - 1                 # one position per step
+    ctx2.close()
+    p.close()
+
 # ---- linear self-speculative loop (Alg. 1) as one call per iteration ------------------------------------------
 
 def _oracle_spec_iteration(o, x_n, B):
