@@ -99,17 +99,20 @@ class BlockDiffusionOracle:
         a, b = x[..., :half], x[..., half:]
         return np.concatenate([a * c - b * s, b * c + a * s], axis=-1)
 
-    def attention(self, q, keys, vals, n_prefix, mode):
+    def attention(self, q, keys, vals, n_prefix, mode, vis_block=None):
         """q [M,n_q,d] (rotated), keys/vals [n_prefix+M, n_kv, d] -> [M, n_q*d].
 
         Visibility (Sec. 3.3 mask rules; Alg. 1 draft / verify masks): every prefix key is visible
         to every row; in-block key j is visible to row i always (BIDIR) or iff j <= i (CAUSAL).
+        vis_block [M, M] (Alg. 2: the quadratic mask) replaces the in-block rule when given.
         """
         M = q.shape[0]
         T = keys.shape[0]
         G = self.s.n_q_heads // self.s.n_kv_heads
         vis = np.ones((M, T), dtype=bool)
-        if mode == CAUSAL:
+        if vis_block is not None:
+            vis[:, n_prefix:] = np.asarray(vis_block, bool)
+        elif mode == CAUSAL:
             i = np.arange(M)[:, None]
             j = np.arange(T)[None, :] - n_prefix
             vis = (j < 0) | (j <= i)
@@ -125,15 +128,16 @@ class BlockDiffusionOracle:
             out[:, h, :] = p @ vals[:, g, :]
         return out.reshape(M, -1)
 
-    def forward(self, x, mode, want_logits_rows=None):
+    def forward(self, x, mode, want_logits_rows=None, pos=None, vis_block=None):
         """One decoder forward over M new rows at positions n..n+M-1 against the cached prefix.
 
         Returns (logits [rows, vocab], new K per layer, new V per layer); the cache is untouched.
+        pos / vis_block (Alg. 2): explicit position ids of the rows and an explicit [M, M] in-block mask.
         """
         s = self.s
         x = np.asarray(x, self.dt)
         M = x.shape[0]
-        pos = np.arange(self.n, self.n + M)
+        pos = np.arange(self.n, self.n + M) if pos is None else np.asarray(pos)
         newK, newV = [], []
         for l in range(s.n_layers):
             p = f"l{l}."
@@ -145,7 +149,7 @@ class BlockDiffusionOracle:
             k = self.rope(k, pos)
             keys = np.concatenate([self.K[l][:self.n], k], axis=0)
             vals = np.concatenate([self.V[l][:self.n], v], axis=0)
-            o = self.attention(q, keys, vals, self.n, mode)
+            o = self.attention(q, keys, vals, self.n, mode, vis_block)
             x = x + o @ self._mat(p + "wo").T
             hh = self.rmsnorm(x, self.w[p + "ffn_norm"])
             gate = hh @ self._mat(p + "w_gate").T
@@ -309,6 +313,68 @@ class BlockDiffusionOracle:
             out.extend(int(t) for t in a[:k])
             self.crop(n0 + k)                        # keep cache rows of d_0 .. d_{k-1}
             x_n = int(a[k - 1])
+        return np.array(out[:n_tokens], np.int32), fwd
+
+
+    # ---- Alg. 2: quadratic speculative decoding --------------------------------------------------
+    @staticmethod
+    def quad_mask(B):
+        """In-block visibility of the B(B+1) rows of Alg. 2 (group i = [d_i, MASK x B]): the first token of
+        group i sees the first tokens of groups <= i; every other token sees all tokens of its own group and
+        nothing of other groups.  (The cached prefix is visible to every row.)"""
+        W = B + 1
+        r = np.arange(B * W)
+        gi, gj = r // W, r % W
+        first = gj == 0
+        vis = first[:, None] & first[None, :] & (gi[None, :] <= gi[:, None])
+        vis |= (~first)[:, None] & (gi[None, :] == gi[:, None])
+        return vis
+
+    def quad_draft(self, B):
+        """Alg. 2 step 1: B mask tokens after the context, bidirectional pass without cache update; draft i is the
+        argmax of the hidden state one position earlier (draft 0: of the last context row, i.e. the carry)."""
+        d = np.full(B, self.mask_id, np.int32)
+        out = np.empty(B, np.int32)
+        out[0] = int(np.argmax(self.carry))
+        if B > 1:
+            logits, _, _ = self.forward(self.embed(d), BIDIR)
+            out[1:] = self.cand_conf(logits)[0][:-1]
+        return out
+
+    def quad_step(self, d):
+        """Alg. 2 loop body on the draft block d[0..B-1] (d[0] is the exact next token): one forward over the B
+        groups [d_i, MASK x B] with position ids n+i .. n+i+B and the quadratic mask.  P[i][j] = argmax of group i,
+        entry j, predicts position n+i+j+1 (shift by one).  k = 1 + number of leading drafts d_1.. equal to the
+        autoregressive predictions P[0][0], P[1][0], ..; d_0..d_{k-1} are accepted, the cache keeps the keys and
+        values of those groups' first tokens, and the next draft block is P[k-1][0..B-1] (tokens n+k .. n+k+B-1, the
+        first of them exact)."""
+        d = np.asarray(d, np.int32)
+        B = len(d)
+        W = B + 1
+        q = np.full(B * W, self.mask_id, np.int32)
+        q[::W] = d
+        r = np.arange(B * W)
+        pos = self.n + r // W + r % W
+        logits, nk, nv = self.forward(self.embed(q), None, pos=pos, vis_block=self.quad_mask(B))
+        P = self.cand_conf(logits)[0].reshape(B, W)
+        k = 1
+        while k < B and P[k - 1, 0] == d[k]:
+            k += 1
+        rows = [i * W for i in range(k)]
+        self._append([x[rows] for x in nk], [x[rows] for x in nv])
+        self.carry = logits[(k - 1) * W]
+        return dict(k=k, accepted=d[:k].copy(), next_draft=P[k - 1, :B].astype(np.int32), logits=logits, P=P)
+
+    def quadratic_speculative(self, n_tokens, B):
+        """Alg. 2: draft once, then one forward per iteration.  Returns (tokens, forwards)."""
+        d = self.quad_draft(B)
+        fwd = int(B > 1)
+        out = []
+        while len(out) < n_tokens:
+            r = self.quad_step(d)
+            fwd += 1
+            out.extend(int(t) for t in r["accepted"])
+            d = r["next_draft"]
         return np.array(out[:n_tokens], np.int32), fwd
 
 

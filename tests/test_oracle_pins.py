@@ -321,6 +321,88 @@ def test_linear_speculative_emits_greedy_ar_sequence(B):
     assert fwd % 2 == 0 and fwd <= 2 * 19           # two forwards per block, >= 1 new token each
 
 
+# ---- Alg. 2: quadratic speculative decoding -------------------------------------------------------------
+
+@pytest.mark.parametrize("B", [1, 2, 3, 5, 7])
+def test_quadratic_mask_structure(B):
+    """Counting form of the mask rules: the first token of group i sees exactly the i+1 first tokens up to its own
+    (and no mask token, not even of its own group); any other token sees exactly the B+1 tokens of its group."""
+    vis = BlockDiffusionOracle.quad_mask(B)
+    W = B + 1
+    assert vis.shape == (B * W, B * W)
+    for i in range(B):
+        row = vis[i * W]
+        assert row.sum() == i + 1 and all(row[g * W] for g in range(i + 1))
+        for j in range(1, W):
+            row = vis[i * W + j]
+            assert row.sum() == W and row[i * W:(i + 1) * W].all()
+    # brute force against the four rules spelled out per pair
+    for a in range(B * W):
+        for b in range(B * W):
+            ai, aj, bi, bj = a // W, a % W, b // W, b % W
+            want = (bj == 0 and bi <= ai) if aj == 0 else (bi == ai)
+            assert vis[a, b] == want
+
+
+@pytest.mark.parametrize("B", [1, 2, 3, 5])
+def test_quadratic_speculative_emits_greedy_ar_sequence(B):
+    """Whatever the proposals are worth, the accepted tokens are the greedy autoregressive continuation: every
+    accepted draft was compared with the prediction of a causal row that saw exactly the accepted tokens before it."""
+    o, _, _ = _prefilled()
+    want = copy.deepcopy(o).greedy_ar(14)
+    got, fwd = copy.deepcopy(o).quadratic_speculative(14, B)
+    assert list(got) == list(want)
+    assert fwd <= 14 + 1                                # one forward per iteration (+ the draft), >= 1 token each
+
+
+def test_quadratic_step_first_tokens_are_a_causal_pass():
+    """The first tokens of the groups, taken alone, form an ordinary causal forward over d: same logits, same keys and
+    values (their mask rows see the prefix and the earlier first tokens only, their positions are n, n+1, ..)."""
+    o, _, _ = _prefilled()
+    B = 4
+    d = copy.deepcopy(o).greedy_ar(B)
+    d[2] = (d[2] + 1) % (SMALL.vocab - 1)               # a wrong draft: accepted length 2
+    a = copy.deepcopy(o)
+    r = a.quad_step(d)
+    b = copy.deepcopy(o)
+    v = b.verify_block(d, commit=False)
+    np.testing.assert_allclose(r["logits"][::B + 1], v["logits"], atol=TOL)
+    assert r["k"] == 2 and list(r["accepted"]) == list(d[:2])
+    assert r["next_draft"][0] == v["ar_pred"][1]        # the exact token after the accepted ones
+    b.commit_block(d[:2])
+    assert a.n == b.n
+    for l in range(SMALL.n_layers):
+        np.testing.assert_allclose(a.K[l], b.K[l], atol=TOL)
+        np.testing.assert_allclose(a.V[l], b.V[l], atol=TOL)
+    np.testing.assert_allclose(a.carry, b.carry, atol=TOL)
+
+
+def test_quadratic_groups_do_not_leak_into_each_other():
+    """No token other than a group's first sees another group: group 0 is untouched by the other drafts, and the
+    proposals of group i change with d_i's own context only through the first tokens before it."""
+    o, _, _ = _prefilled()
+    B = 3
+    d = np.array([5, 11, 23], np.int32)
+    r = copy.deepcopy(o).quad_step(d)
+    d2 = np.array([5, 40, 77], np.int32)
+    r2 = copy.deepcopy(o).quad_step(d2)
+    W = B + 1
+    np.testing.assert_allclose(r["logits"][:W], r2["logits"][:W], atol=TOL)          # group 0: identical
+    assert np.abs(r["logits"][W:2 * W] - r2["logits"][W:2 * W]).max() > 1e-3          # group 1 follows its own d_1
+    d3 = np.array([5, 11, 77], np.int32)
+    r3 = copy.deepcopy(o).quad_step(d3)
+    np.testing.assert_allclose(r["logits"][:2 * W], r3["logits"][:2 * W], atol=TOL)  # groups 0, 1 ignore d_2
+    # positions: group i sits at n+i .. n+i+B, so group 0 alone is the block [d_0, MASK x B] at position n whose first
+    # token sees only itself and whose mask tokens see the whole block
+    blk = np.full(W, o.mask_id, np.int32)
+    blk[0] = d[0]
+    vis = np.ones((W, W), bool)
+    vis[0, 1:] = False
+    oo = copy.deepcopy(o)
+    lg, _, _ = oo.forward(oo.embed(blk), None, vis_block=vis)
+    np.testing.assert_allclose(r["logits"][:W], lg, atol=TOL)
+
+
 def test_crop_restores_earlier_state():
     o, _, _ = _prefilled()
     a = copy.deepcopy(o); a.commit_block(np.array([1, 2, 3, 4])); a.crop(o.n + 2); a.commit_block(np.array([9]))
@@ -366,13 +448,13 @@ def test_pins_catch_planted_mistakes(mutation, monkeypatch):
         monkeypatch.setattr(o, "rmsnorm", lambda x, g: x / np.sqrt(np.mean(x * x, -1, keepdims=True) + 1e-6))
     elif mutation == "wrong_group":
         orig = o.attention
-        monkeypatch.setattr(o, "attention", lambda q, k, v, n, mode: orig(q, k[:, ::-1], v[:, ::-1], n, mode))
+        monkeypatch.setattr(o, "attention", lambda q, k, v, n, mode, vb=None: orig(q, k[:, ::-1], v[:, ::-1], n, mode, vb))
     elif mutation == "causal_offbyone":
         orig = o.attention
-        monkeypatch.setattr(o, "attention", lambda q, k, v, n, mode: orig(q, k, v, n + (mode == CAUSAL), mode))
+        monkeypatch.setattr(o, "attention", lambda q, k, v, n, mode, vb=None: orig(q, k, v, n + (mode == CAUSAL), mode, vb))
     elif mutation == "no_scale":
         orig = o.attention
-        monkeypatch.setattr(o, "attention", lambda q, k, v, n, mode: orig(q * 4.0, k, v, n, mode))
+        monkeypatch.setattr(o, "attention", lambda q, k, v, n, mode, vb=None: orig(q * 4.0, k, v, n, mode, vb))
     blk = np.array([3, 8, 11, 4])
     logits, _, _ = o.forward(o.embed(blk), CAUSAL)
     x = torch.cat([xp, ref.embed_rows(w, blk)], 0)
