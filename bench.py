@@ -45,6 +45,9 @@ def main():
     ap.add_argument("--speculative", type=int, default=0, metavar="N",
                     help="also time N iterations of the linear self-speculative loop (Alg. 1: draft + verify + accept "
                          "per call); with random weights nearly every draft is rejected, so this is ~2 forwards per token")
+    ap.add_argument("--quadratic", type=int, default=0, metavar="B",
+                    help="also time 8 iterations of the quadratic speculative loop (Alg. 2) with block size B "
+                         "(B*(B+1) <= 64 rows, one forward per iteration)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -164,6 +167,27 @@ def main():
         spec = {"iterations": n_it, "tokens": emitted, "tokens_per_s": round(emitted / dt, 1),
                 "ms_per_iteration": round(dt * 1e3 / n_it, 4), "forwards_per_iteration": 2 if B > 1 else 1}
 
+    quad = None
+    if args.quadratic > 0:
+        qB = args.quadratic
+        ctx.bd_prefill(d_emb, d_ids)
+        dq = torch.zeros(qB, dtype=torch.int32, device="cuda")
+        nq = torch.zeros(qB, dtype=torch.int32, device="cuda")
+        ctx.bd_quad_draft(qB, dq)
+        ctx.bd_quad_step(qB, dq, nq)
+        ctx.bd_prefill(d_emb, d_ids)
+        ctx.bd_quad_draft(qB, dq)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        emitted = 0
+        for _ in range(8):
+            emitted += ctx.bd_quad_step(qB, dq, nq)
+            dq, nq = nq, dq
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        quad = {"block": qB, "rows_per_forward": qB * (qB + 1), "iterations": 8, "tokens": emitted,
+                "tokens_per_s": round(emitted / dt, 1), "ms_per_iteration": round(dt * 1e3 / 8, 4)}
+
     roofline = None
     if not args.no_kernel_pass:
         run(args.steps, after_prefill=lambda: ctx.bd_k_profile(True))   # events around the decode launches only
@@ -208,6 +232,7 @@ def main():
                    "block": B, "fixed_k": K, "prefix": args.prefix, "forwards_per_block": n_den + 1},
         "ms_per_forward": round(ms_fwd, 4), "hbm_roofline_frac_step": round(step_frac, 4),
         **({"speculative": spec} if spec is not None else {}),
+        **({"quadratic": quad} if quad is not None else {}),
         # the prompt pass (not part of `value`): large-M kernels for all but its last rows; linears only in the flop count
         "prefill": {"ms": round(min(prefill_s) * 1e3, 3), "tokens_per_s": round(args.prefix / min(prefill_s), 1),
                     "TFLOPs": round(2.0 * args.prefix * (shape.weight_elements() - shape.vocab * shape.hidden)

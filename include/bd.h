@@ -133,6 +133,21 @@ int bd_decode_block(bd_ctx* ctx, int B, float threshold, int fixed_k, int32_t* d
  * cache_len + B > max_seq, BD_E_ARG for NULL pointers or B outside [1, max_block]. */
 int bd_speculative_step(bd_ctx* ctx, int B, int32_t* dev_tokens_out, int32_t* host_n_accepted);
 
+/* Quadratic speculative decoding (appendix "Details of Speculative Decoding", Alg. 2), for blocks with
+ * B*(B+1) <= max_block rows.
+ * bd_quad_draft: step 1, the first block's draft: B mask tokens after the context, one bidirectional forward without
+ *   cache update; dev_draft_out[0] = the carry's argmax, dev_draft_out[i] = argmax of the row before position i.
+ * bd_quad_step: one iteration: a single forward over the B groups [draft[i], MASK x B] (group i at positions
+ *   cache_len+i .. cache_len+i+B; a group's first token sees the prefix and the first tokens of the groups up to its
+ *   own, every other token the prefix and its own group).  With P[i][j] = argmax of group i, entry j: k = 1 + the
+ *   number of leading drafts draft[1..] equal to P[0][0], P[1][0], ..; draft[0..k-1] are the accepted tokens (draft[0]
+ *   is exact by construction); their keys and values go to cache positions cache_len .. cache_len+k-1, cache_len += k,
+ *   P[k-1][0] becomes the carry, and dev_next_draft[0..B-1] = P[k-1][0..B-1] is the draft of the next iteration.
+ *   *host_n_accepted = k; the call synchronises the stream to read it.  dev_draft and dev_next_draft may not alias.
+ *   The forward uses cache positions cache_len .. cache_len+B*(B+1)-1 as scratch: BD_E_CAPACITY if they do not fit. */
+int bd_quad_draft(bd_ctx* ctx, int B, int32_t* dev_draft_out);
+int bd_quad_step(bd_ctx* ctx, int B, const int32_t* dev_draft, int32_t* dev_next_draft, int32_t* host_n_accepted);
+
 /* Alg. 1 Crop: forget cache positions >= new_len (0 <= new_len <= cache_len).  The carry becomes
  * undefined: the next block must bring its own first token (mask[0] = 0). */
 int bd_crop(bd_ctx* ctx, int new_len);

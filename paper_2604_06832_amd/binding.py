@@ -22,7 +22,7 @@ BD_MODE_BIDIR, BD_MODE_CAUSAL = 0, 1
 # every symbol the two headers declare
 EXPORTS = [
     "bd_create", "bd_destroy", "bd_load_weight", "bd_prefill", "bd_denoise_step", "bd_commit_block",
-    "bd_verify_block", "bd_decode_block", "bd_speculative_step", "bd_crop", "bd_cache_len", "bd_status", "bd_debug_logits", "bd_read_logits", "bd_read_kv",
+    "bd_verify_block", "bd_decode_block", "bd_speculative_step", "bd_quad_draft", "bd_quad_step", "bd_crop", "bd_cache_len", "bd_status", "bd_debug_logits", "bd_read_logits", "bd_read_kv",
     "bd_read_carry", "bd_read_rows", "bd_forward_bytes", "bd_strerror", "bd_last_error",
     "bd_k_gemm", "bd_k_attention", "bd_k_profile", "bd_k_profile_read", "bd_k_class_count", "bd_k_class_name",
     "bd_k_class_bytes", "bd_k_trace", "bd_k_trace_read",
@@ -55,6 +55,8 @@ def lib() -> C.CDLL:
     L.bd_commit_block.argtypes = [vp, vp, i32]
     L.bd_verify_block.argtypes = [vp, vp, i32, i32, vp, vp]
     L.bd_decode_block.argtypes = [vp, i32, f32, i32, vp, vp]
+    L.bd_quad_draft.argtypes = [vp, i32, vp]
+    L.bd_quad_step.argtypes = [vp, i32, vp, vp, C.POINTER(C.c_int32)]
     L.bd_speculative_step.argtypes = [vp, i32, vp, C.POINTER(C.c_int32)]
     L.bd_crop.argtypes = [vp, i32]
     L.bd_cache_len.argtypes = [vp]
@@ -174,6 +176,14 @@ class Context:
 
     def bd_decode_block(self, B: int, threshold: float, fixed_k: int, tokens_out, steps_out=None):
         _check(lib().bd_decode_block(self._h, B, threshold, fixed_k, _ptr(tokens_out), _ptr(steps_out)))
+
+    def bd_quad_draft(self, B: int, draft_out):
+        _check(lib().bd_quad_draft(self._h, B, _ptr(draft_out)))
+
+    def bd_quad_step(self, B: int, draft, next_draft) -> int:
+        k = C.c_int32(0)
+        _check(lib().bd_quad_step(self._h, B, _ptr(draft), _ptr(next_draft), C.byref(k)))
+        return int(k.value)
 
     def bd_speculative_step(self, B: int, tokens_out) -> int:
         k = C.c_int32(0)

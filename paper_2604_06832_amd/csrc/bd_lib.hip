@@ -84,7 +84,8 @@ struct bd_ctx {
   u16* pf_w = nullptr; size_t pf_layer_elems = 0; size_t pf_off[4] = {0, 0, 0, 0};
   float* pf_x = nullptr; u16* pf_xb = nullptr; float* pf_rs = nullptr; float2* pf_rope = nullptr;
   u16* pf_q = nullptr; u16* pf_ap = nullptr; u16* pf_act = nullptr;
-  int32_t* spec_tokens = nullptr; uint8_t* spec_mask = nullptr; int32_t* spec_k = nullptr;   // bd_speculative_step
+  int32_t* spec_tokens = nullptr; uint8_t* spec_mask = nullptr; int32_t* spec_k = nullptr;   // bd_speculative_step, bd_decode_block, bd_quad_*
+  int32_t* quad_ids = nullptr;     // rows of the quadratic forward
   DevState* st = nullptr;
   unsigned* bar = nullptr; unsigned bar_epoch = 0;
   unsigned* xbar = nullptr; unsigned xbar_epoch = 0;   // barriers among the workgroups of one XCD (stream_fwd.h)
@@ -305,7 +306,7 @@ int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
 // One decoder forward over M rows: prologue (block assembly) + the persistent forward kernel.
 // Source of the rows: prompt rows [off, off+M) (embeds then ids), or block tokens with an optional mask.
 int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n_embed, const int32_t* ids, int off,
-            int32_t* seed_tokens, uint8_t* seed_mask, const uint8_t* mask, bool skippable = false) {
+            int32_t* seed_tokens, uint8_t* seed_mask, const uint8_t* mask, bool skippable = false, int quad_B = 0) {
   const int MT = ceil_div(M, 16);
   const int Mp = c->Mp_max;
   hipStream_t s = c->stream;
@@ -319,6 +320,7 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
     p.counters = c->counters; p.n_counters = c->n_cntD + c->n_cntA;
     p.gain0 = c->fp8 ? c->gains : nullptr;
     p.skippable = skippable ? 1 : 0;
+    p.quad_W = quad_B > 0 ? quad_B + 1 : 0;
     Prof pr(c, KC_PROLOGUE);
     hipLaunchKernelGGL(prologue_kernel, dim3(M), dim3(kWGThreads), 0, s, p);
     BD_TRY(check_launch());
@@ -569,6 +571,7 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   A(c->spec_tokens, Mp * 4);
   A(c->spec_mask, Mp);
   A(c->spec_k, 4);
+  A(c->quad_ids, Mp * 4);
   {
     // Large-M prefill for bf16 contexts whose cache can hold a chunk of 128 rows plus the prompt's last rows.
     const char* e = getenv("BD_PREFILL");
@@ -828,7 +831,7 @@ int bd_decode_block(bd_ctx* c, int B, float threshold, int fixed_k, int32_t* dev
   if (dev_tokens_out == nullptr || fixed_k < 0) return BD_E_ARG;
   if (!c->carry_valid) return BD_E_STATE;
   hipStream_t s = c->stream;
-  hipLaunchKernelGGL(fill_masked_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, B, c->cfg.mask_token_id, c->st);
+  hipLaunchKernelGGL(fill_masked_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, B, c->cfg.mask_token_id, c->st, 0);
   BD_TRY(check_launch());
   if (B == 1) {
     hipLaunchKernelGGL(seed_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, c->st);
@@ -855,13 +858,66 @@ int bd_decode_block(bd_ctx* c, int B, float threshold, int fixed_k, int32_t* dev
   return BD_OK;
 }
 
+int bd_quad_draft(bd_ctx* c, int B, int32_t* dev_draft_out) {
+  BD_TRY(check_decode_call(c, B));
+  if (dev_draft_out == nullptr) return BD_E_ARG;
+  if (!c->carry_valid) return BD_E_STATE;
+  hipStream_t s = c->stream;
+  if (B > 1) {
+    // B mask tokens, none of them seeded: position 0 is handed over as already revealed but holds the mask id
+    hipLaunchKernelGGL(fill_masked_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, B, c->cfg.mask_token_id, c->st, 1);
+    BD_TRY(check_launch());
+    BD_TRY(forward(c, B, BD_MODE_BIDIR, true, nullptr, 0, c->spec_tokens, 0, c->spec_tokens, c->spec_mask, c->spec_mask));
+    FinishArgs f = finish_args(c, B);
+    f.tokens = c->spec_tokens; f.mask = c->spec_mask; f.threshold = 2.f; f.fixed_k = B - 1;
+    hipLaunchKernelGGL(finish_denoise_kernel, dim3(1), dim3(64), 0, s, f);
+    BD_TRY(check_launch());
+  }
+  hipLaunchKernelGGL(quad_first_kernel, dim3(1), dim3(1), 0, s, c->spec_tokens, c->st);
+  BD_TRY(check_launch());
+  HIP_TRY(hipMemcpyAsync(dev_draft_out, c->spec_tokens, (size_t)B * 4, hipMemcpyDeviceToDevice, s));
+  return BD_OK;
+}
+
+int bd_quad_step(bd_ctx* c, int B, const int32_t* dev_draft, int32_t* dev_next_draft, int32_t* host_n_accepted) {
+  if (c == nullptr || B < 1 || dev_draft == nullptr || dev_next_draft == nullptr || host_n_accepted == nullptr) return BD_E_ARG;
+  const int M = B * (B + 1);
+  if (M > c->cfg.max_block) return BD_E_ARG;
+  BD_TRY(check_decode_call(c, M));                       // the forward parks its B(B+1) rows at [cache_len, cache_len + M)
+  hipStream_t s = c->stream;
+  hipLaunchKernelGGL(quad_assemble_kernel, dim3(ceil_div(M, 64)), dim3(64), 0, s, dev_draft, B, c->cfg.mask_token_id, c->quad_ids);
+  BD_TRY(check_launch());
+  BD_TRY(forward(c, M, 2 | (B << 8), true, nullptr, 0, c->quad_ids, 0, nullptr, nullptr, nullptr, false, B));
+  {
+    FinishArgs f = finish_args(c, B);
+    f.draft = dev_draft; f.n_accept = c->spec_k;
+    Prof pr(c, KC_FINISH);
+    hipLaunchKernelGGL(finish_quad_kernel, dim3(1), dim3(64), 0, s, f, dev_next_draft);
+    BD_TRY(check_launch());
+    hipLaunchKernelGGL(quad_compact_kv_kernel, dim3(c->L * c->cfg.n_kv_heads), dim3(256), 0, s, c->Kc, c->Vc, c->kv_layer_elems,
+                       c->cfg.n_kv_heads, c->D, c->max_kb, c->st, c->spec_k, B);
+    BD_TRY(check_launch());
+  }
+  int32_t k = 0;
+  HIP_TRY(hipMemcpyAsync(&k, c->spec_k, 4, hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  if (k < 1 || k > B) {
+    snprintf(g_last_error, sizeof g_last_error, "quadratic step returned an accept length of %d for a block of %d", (int)k, B);
+    return BD_E_HIP;
+  }
+  c->n += k;
+  c->carry_valid = true;
+  *host_n_accepted = k;
+  return BD_OK;
+}
+
 int bd_speculative_step(bd_ctx* c, int B, int32_t* dev_tokens_out, int32_t* host_n_accepted) {
   BD_TRY(check_decode_call(c, B));
   if (dev_tokens_out == nullptr || host_n_accepted == nullptr) return BD_E_ARG;
   if (!c->carry_valid) return BD_E_STATE;
   hipStream_t s = c->stream;
   // draft: [x_n, MASK, ...] -> every masked position filled by the argmax of the row before it, in one pass
-  hipLaunchKernelGGL(fill_masked_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, B, c->cfg.mask_token_id, c->st);
+  hipLaunchKernelGGL(fill_masked_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, B, c->cfg.mask_token_id, c->st, 0);
   BD_TRY(check_launch());
   if (B == 1) {
     hipLaunchKernelGGL(seed_kernel, dim3(1), dim3(64), 0, s, c->spec_tokens, c->spec_mask, c->st);

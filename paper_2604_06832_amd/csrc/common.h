@@ -41,6 +41,18 @@ __device__ inline size_t xp_index(int m, int k, int MT) {
   return (((size_t)ks * MT + mt) * 64 + lane) * 8 + e;
 }
 
+// In-block visibility of the block's key jb (0-based index inside the block) for the block's query row `row`
+// (Sec. 3.3 mask rules; Alg. 1 draft / verify masks; Alg. 2 quadratic mask).  mode 0: all visible; 1: causal;
+// 2 + (B << 8): B groups of B+1 rows, a group's first row sees the first rows of the groups up to its own, every other
+// row sees the rows of its own group.  (Keys of the committed prefix are visible to every row.)
+__device__ inline bool block_key_visible(int mode, int row, int jb) {
+  if (mode == 0) return true;
+  if (mode == 1) return jb <= row;
+  const int W = (mode >> 8) + 1;
+  const int gi = row / W, gj = row - gi * W, ki = jb / W, kj = jb - ki * W;
+  return gj == 0 ? (kj == 0 && ki <= gi) : ki == gi;
+}
+
 // State that lives on the device so that replayed launch sequences need no new kernel arguments.
 struct DevState {
   int n;             // committed context length

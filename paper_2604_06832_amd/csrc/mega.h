@@ -821,7 +821,7 @@ __device__ inline void attention_phase(const MegaArgs& a, const PhaseCtx& pc, ch
           vis[e] = true;
           if (need_mask) {
             const int jb = kb * 32 + 8 * g + e - n;
-            vis[e] = (jb < 0) || (jb < a.M && (a.mode == 0 || jb <= row[jt]));
+            vis[e] = (jb < 0) || (jb < a.M && block_key_visible(a.mode, row[jt], jb));
           }
           if (vis[e]) cmax = fmaxf(cmax, v[e]);
         }
@@ -1136,6 +1136,7 @@ struct PrologueArgs {
   float2* rope; int half; float theta;
   unsigned* counters; int n_counters;
   int skippable;                              // nothing to do once the block is complete (DevState::skip)
+  int quad_W;                                 // > 0: rows are groups of quad_W tokens, row r sits at position n + r / W + r % W (Alg. 2)
   const float* gain0;                         // fp8 weights: gain of the first norm, applied to the bf16 copy (else nullptr)
 };
 
@@ -1146,7 +1147,7 @@ __global__ __launch_bounds__(kWGThreads) void prologue_kernel(PrologueArgs a) {
   if (a.skippable && a.st->skip) return;
   for (int i = blockIdx.x * kWGThreads + threadIdx.x; i < a.n_counters; i += gridDim.x * kWGThreads) a.counters[i] = 0u;
   {
-    const double pos = (double)(a.st->n + r);
+    const double pos = (double)(a.st->n + (a.quad_W > 0 ? r / a.quad_W + r % a.quad_W : r));
     for (int i = threadIdx.x; i < a.half; i += kWGThreads) {
       const double inv = exp2(-log2((double)a.theta) * (double)i / (double)a.half);
       const double ang = pos * inv;

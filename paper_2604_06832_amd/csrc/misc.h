@@ -385,10 +385,53 @@ __global__ __launch_bounds__(64) void finish_causal_kernel(FinishArgs a) {
   }
 }
 
+// ---- Alg. 2 (quadratic speculative decoding) ------------------------------------------------------------------
+// Rows of the quadratic forward: group i = [draft[i], MASK x B].
+__global__ void quad_assemble_kernel(const int* draft, int B, int mask_id, int* ids) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  const int W = B + 1;
+  if (r < B * W) ids[r] = (r % W == 0) ? draft[r / W] : mask_id;
+}
+// Draft 0 of Alg. 2's first block is the carry's prediction (the hidden state of the last context row).
+__global__ void quad_first_kernel(int* draft, const DevState* st) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) draft[0] = st->carry_cand;
+}
+// Accept: P[i][j] = argmax of group i, entry j (predicts position n+i+j+1).  k = 1 + leading drafts d_1.. that equal
+// P[0][0], P[1][0], ..; the next draft block is P[k-1][0..B-1]; the prediction of group k-1's first row becomes the
+// carry and the context grows by k (the keys and values of the accepted first rows are moved into place afterwards).
+__global__ __launch_bounds__(64) void finish_quad_kernel(FinishArgs a, int* next_draft) {
+  const int W = a.B + 1;
+  if (threadIdx.x == 0) {
+    int k = 1;
+    while (k < a.B && a.row_cand[(k - 1) * W] == a.draft[k]) ++k;
+    *a.n_accept = k;
+    for (int j = 0; j < a.B; ++j) next_draft[j] = a.row_cand[(k - 1) * W + j];
+    a.st->carry_cand = a.row_cand[(k - 1) * W];
+    a.st->carry_conf = a.row_conf[(k - 1) * W];
+    a.st->n += k;
+  }
+}
+// The quadratic forward left the keys and values of row r at cache position n0 + r; the accepted tokens are the
+// first rows of groups 0..k-1, i.e. rows i*(B+1), and belong at positions n0 + i.  (Destinations 1..k-1 < B+1 never
+// coincide with a source, so all moves are independent.)  One workgroup per (layer, kv head).
+__global__ void quad_compact_kv_kernel(u16* Kc, u16* Vc, size_t kv_layer_elems, int n_kv, int D, int max_kb, const DevState* st,
+                                       const int* k_ptr, int B) {
+  const int layer = blockIdx.x / n_kv, h = blockIdx.x % n_kv;
+  const int k = *k_ptr;
+  const int n0 = st->n - k;                       // the accept kernel has already advanced the length
+  u16* kc = Kc + (size_t)layer * kv_layer_elems + (size_t)h * max_kb * 32 * D;
+  u16* vc = Vc + (size_t)layer * kv_layer_elems + (size_t)h * max_kb * 32 * D;
+  for (int t = threadIdx.x; t < (k - 1) * D; t += blockDim.x) {
+    const int i = 1 + t / D, d = t % D;
+    kc[kp_index(n0 + i, d, D / 32)] = kc[kp_index(n0 + i * (B + 1), d, D / 32)];
+    vc[vp_index(n0 + i, d, D / 16)] = vc[vp_index(n0 + i * (B + 1), d, D / 16)];
+  }
+}
+
 // All positions of a block masked (the state before the draft pass of Alg. 1).
-__global__ void fill_masked_kernel(int* tokens, uint8_t* mask, int B, int mask_id, DevState* st) {
+__global__ void fill_masked_kernel(int* tokens, uint8_t* mask, int B, int mask_id, DevState* st, int first_revealed = 0) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < B) { tokens[i] = mask_id; mask[i] = 1; }
+  if (i < B) { tokens[i] = mask_id; mask[i] = (i == 0 && first_revealed) ? 0 : 1; }
   if (i == 0) { st->skip = 0; st->steps = 0; }
 }
 __global__ void read_steps_kernel(const DevState* st, int* out) {

@@ -646,7 +646,7 @@ __device__ inline void attn_block(const KvBlock<D>& b, const bf16x8 (&qf)[D / 32
     vis[e] = true;
     if constexpr (MASKED) {
       const int jb = kb * 32 + 8 * g + e - n;
-      vis[e] = (jb < 0) || (jb < M && (mode == 0 || jb <= row));
+      vis[e] = (jb < 0) || (jb < M && block_key_visible(mode, row, jb));
       if (vis[e]) cmax = fmaxf(cmax, v[e]);
     } else {
       cmax = fmaxf(cmax, v[e]);

@@ -342,6 +342,141 @@ def test_speculative_step_needs_a_carry():
     ctx.close()
 
 
+
+# ---- quadratic speculative decoding (Alg. 2): one forward per iteration -----------------------------------------
+
+@pytest.mark.parametrize("B", [1, 2, 3, 5, 7])
+def test_quadratic_step_against_the_oracle(B):
+    """Draft, then iterations of the quadratic step, each held against the oracle's on the same state: logits of all
+    B(B+1) rows, accept length, next draft, carry, and the cache (keys and values of the accepted first tokens moved
+    into place).  B = 5 (30 rows) runs on the streaming kernel, B = 7 (56 rows) on the register-ring kernel."""
+    _say(f"quadratic step vs oracle, tiny config, B={B}")
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, threads=1)
+    emb, ids = inputs.make_prompt(shape, 24, 24, seed=6)
+    M = B * (B + 1)
+    p = Pair(shape, w, max_seq=48 + 6 * B + M, max_block=max(M, 4))
+    p.prefill(emb, ids)
+    import copy
+    greedy = copy.deepcopy(p.o).greedy_ar(6)
+    d_gpu = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nxt = torch.zeros(B, dtype=torch.int32, device="cuda")
+    p.ctx.bd_quad_draft(B, d_gpu)
+    d = p.o.quad_draft(B)
+    thr0 = MARGIN
+    if B > 1:
+        glog = p.ctx.bd_read_logits(B).cpu().numpy()
+        from oracle.bd_oracle import BIDIR
+        olog, _, _ = p.o.forward(p.o.embed(np.full(B, p.o.mask_id, np.int32)), BIDIR)
+        err = assert_logits_close(glog, olog) * float(olog.max() - olog.min())
+        thr0 = max(MARGIN, 2.5 * err)
+        if top2_margin(olog)[:B - 1].min() <= thr0 or top2_margin(p.o.carry) <= thr0:
+            pytest.skip("near-tie in the first draft of this seed")
+    assert np.array_equal(d_gpu.cpu().numpy(), d)
+    emitted = []
+    for it in range(6):
+        r = p.o.quad_step(d)
+        k = p.ctx.bd_quad_step(B, d_gpu, nxt)
+        glog = p.ctx.bd_read_logits(M).cpu().numpy()
+        e = assert_logits_close(glog, r["logits"]) * float(r["logits"].max() - r["logits"].min())
+        thr = max(MARGIN, 2.5 * e)
+        W = B + 1
+        firsts = top2_margin(r["logits"])[::W]
+        robust = firsts[:r["k"]].min() > thr and top2_margin(r["logits"])[(r["k"] - 1) * W:(r["k"] - 1) * W + B].min() > thr
+        if not robust:
+            break
+        assert k == r["k"], (it, k, r["k"])
+        assert np.array_equal(nxt.cpu().numpy(), r["next_draft"])
+        assert p.ctx.bd_cache_len() == p.o.n
+        cand, _ = p.ctx.bd_read_carry()
+        assert cand == int(np.argmax(p.o.carry))
+        p.check_kv(max(0, p.o.n - k - 2), min(k + 2, p.o.n))
+        emitted += [int(t) for t in r["accepted"]]
+        d = r["next_draft"]
+        d_gpu.copy_(nxt)
+    assert len(emitted) >= 2
+    n = min(len(emitted), 6)
+    assert emitted[:n] == [int(t) for t in greedy[:n]]
+    p.check_kv(0, p.o.n)
+    p.close()
+
+
+@pytest.mark.parametrize("B,flip", [(3, False), (5, True), (7, True)])
+def test_quadratic_step_accept_lengths_on_a_token_cycle(B, flip):
+    _say(f"quadratic step on the cyclic model, B={B}, flip={flip}")
+    shape = inputs.TINY
+    w, A, Bt = _cyclic_model(shape, flip)
+    ids = np.array([3, 17, 200, 41, 7], np.int32)
+    M = B * (B + 1)
+    p = Pair(shape, w, max_seq=5 + 6 * B + M, max_block=M)
+    p.prefill(None, ids)
+    d_gpu = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nxt = torch.zeros(B, dtype=torch.int32, device="cuda")
+    p.ctx.bd_quad_draft(B, d_gpu)
+    d = p.o.quad_draft(B)
+    assert np.array_equal(d_gpu.cpu().numpy(), d) and list(d) == [A] * B
+    ks = []
+    for it in range(5):
+        r = p.o.quad_step(d)
+        k = p.ctx.bd_quad_step(B, d_gpu, nxt)
+        assert k == r["k"] and np.array_equal(nxt.cpu().numpy(), r["next_draft"])
+        assert p.ctx.bd_cache_len() == p.o.n
+        ks.append(k)
+        d = r["next_draft"]
+        d_gpu.copy_(nxt)
+    # fixed point: whole blocks; alternation A, Bt, A, ..: the all-A draft fails at once, then [Bt, A, A, ..] gives 2
+    assert ks == ([B] * 5 if not flip else [1, 2, 2, 2, 2])
+    p.check_kv(0, p.o.n)
+    p.close()
+
+
+def test_quadratic_step_rejects_blocks_that_do_not_fit():
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, "bf16", threads=1)
+    ctx = binding.Context(shape, max_seq=64, max_block=32)
+    ctx.load_model(w, as_bf16_bits=True)
+    d = torch.zeros(8, dtype=torch.int32, device="cuda")
+    nxt = torch.zeros(8, dtype=torch.int32, device="cuda")
+    with pytest.raises(binding.BdError):
+        ctx.bd_quad_step(3, d, nxt)                                # before prefill
+    ctx.bd_prefill(None, torch.arange(40, dtype=torch.int32, device="cuda"))
+    with pytest.raises(binding.BdError):
+        ctx.bd_quad_step(6, d, nxt)                                # 42 rows > max_block
+    with pytest.raises(binding.BdError):
+        ctx.bd_quad_step(5, d, nxt)                                # 40 + 30 rows > max_seq
+    ctx.bd_quad_draft(4, d)
+    assert 1 <= ctx.bd_quad_step(4, d, nxt) <= 4                   # 40 + 20 rows fit
+    ctx.close()
+
+
+def test_quadratic_step_3b_shaped_two_layers():
+    _say("quadratic step vs oracle, 3B-shaped x2 layers, B=5 (30 rows)")
+    shape = _wide(2, vocab=8192)
+    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, threads=8)
+    emb, ids = inputs.make_prompt(shape, 100, 41, seed=13)
+    B, M = 5, 30
+    p = Pair(shape, w, max_seq=141 + 3 * B + M, max_block=32)
+    p.prefill(emb, ids)
+    d_gpu = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nxt = torch.zeros(B, dtype=torch.int32, device="cuda")
+    p.ctx.bd_quad_draft(B, d_gpu)
+    d = d_gpu.cpu().numpy()                       # the oracle follows the device's draft: the step is what is compared
+    for it in range(2):
+        r = p.o.quad_step(d)
+        k = p.ctx.bd_quad_step(B, d_gpu, nxt)
+        glog = p.ctx.bd_read_logits(M).cpu().numpy()
+        e = assert_logits_close(glog, r["logits"]) * float(r["logits"].max() - r["logits"].min())
+        thr = max(MARGIN, 2.5 * e)
+        W = B + 1
+        if top2_margin(r["logits"])[::W][:r["k"]].min() <= thr or \
+                top2_margin(r["logits"])[(r["k"] - 1) * W:(r["k"] - 1) * W + B].min() <= thr:
+            break
+        assert k == r["k"] and np.array_equal(nxt.cpu().numpy(), r["next_draft"])
+        p.check_kv(p.o.n - k, k)
+        d = r["next_draft"]
+        d_gpu.copy_(nxt)
+    p.close()
+
 # ---- 3B-shaped layers at reduced depth: every block size, ragged prefix, both masks -------------------
 
 def _wide(n_layers, vocab=32000):
