@@ -144,7 +144,7 @@ __global__ __launch_bounds__(kWGThreads) void attn_partial_kernel(AttnArgs a) {
           if (need_mask) {
             const int key = kb * 32 + 8 * g + e;
             const int jb = key - n;                     // index inside the block, if >= 0
-            vis[e] = (jb < 0) || (jb < a.M && block_key_visible(a.mode, row[jt], jb));
+            vis[e] = (jb < 0) || (jb < a.M && block_key_visible<false>(a.mode, row[jt], jb));
           }
           if (vis[e]) cmax = fmaxf(cmax, v[e]);
         }

@@ -200,16 +200,16 @@ int attn_max_chunks(const bd_ctx* c, int MT, bool in_forward = false) {
 template <int MT>
 constexpr int mega_lds_total() { return mega_lds_bytes<MT>() > 56 * 1024 ? mega_lds_bytes<MT>() : 56 * 1024; }
 
-template <int MT, int D, int JT>
+template <int MT, int D, int JT, bool QUAD = false>
 int launch_mega_inst(bd_ctx* c, const MegaArgs& a) {
   static bool attr_set = false;
   constexpr int lds = mega_lds_total<MT>();
   if (!attr_set) {
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&mega_kernel<MT, D, JT>),
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&mega_kernel<MT, D, JT, QUAD>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((mega_kernel<MT, D, JT>), dim3(c->plan.nwg), dim3(kWGThreads), lds, c->stream, a);
+  hipLaunchKernelGGL((mega_kernel<MT, D, JT, QUAD>), dim3(c->plan.nwg), dim3(kWGThreads), lds, c->stream, a);
   return check_launch();
 }
 
@@ -226,16 +226,16 @@ int launch_lm(bd_ctx* c, const MegaArgs& a) {
 }
 
 // The forward kernel with decoupled weight streaming (stream_fwd.h): block sizes up to 32.
-template <int MT, int D, bool FP8>
+template <int MT, int D, bool FP8, bool QUAD = false>
 int launch_stream_inst(bd_ctx* c, const MegaArgs& a) {
   static bool attr_set = false;
   constexpr int lds = stream_lds_bytes<MT>();
   if (!attr_set) {
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_fwd_kernel<MT, D, FP8>),
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_fwd_kernel<MT, D, FP8, QUAD>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     attr_set = true;
   }
-  hipLaunchKernelGGL((stream_fwd_kernel<MT, D, FP8>), dim3(c->plan.nwg), dim3(kFwdThreads), lds, c->stream, a);
+  hipLaunchKernelGGL((stream_fwd_kernel<MT, D, FP8, QUAD>), dim3(c->plan.nwg), dim3(kFwdThreads), lds, c->stream, a);
   return check_launch();
 }
 
@@ -276,7 +276,11 @@ int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
       a.attn_max_chunks = stream_attn_max_chunks(c, MT);
       a.local_gu = c->plan.xcd_gu > 0 ? 1 : 0;
       a.xbar = c->xbar; a.xbar_epoch = c->xbar_epoch;
-      if (c->fp8) {
+      if (a.mode >= 2) {                                     // quadratic mask (Alg. 2): its own instantiations
+        if (c->fp8) return BD_E_ARG;
+        if (c->D == 128) BD_TRY((launch_stream_inst<MT, 128, false, true>(c, a)));
+        else BD_TRY((launch_stream_inst<MT, 64, false, true>(c, a)));
+      } else if (c->fp8) {
         if (c->D == 128) BD_TRY((launch_stream_inst<MT, 128, true>(c, a)));
         else BD_TRY((launch_stream_inst<MT, 64, true>(c, a)));
       } else {
@@ -289,7 +293,10 @@ int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
     }
   } else {
     if (c->fp8) return BD_E_ARG;                            // e4m3 weights are only streamed by the kernel above
-    if (c->D == 128) BD_TRY((launch_mega_inst<MT, 128, 2>(c, a)));
+    if (a.mode >= 2) {
+      if (c->D == 128) BD_TRY((launch_mega_inst<MT, 128, 2, true>(c, a)));
+      else BD_TRY((launch_mega_inst<MT, 64, 2, true>(c, a)));
+    } else if (c->D == 128) BD_TRY((launch_mega_inst<MT, 128, 2>(c, a)));
     else BD_TRY((launch_mega_inst<MT, 64, 2>(c, a)));
     c->bar_epoch += 5u * (unsigned)c->L;
   }
@@ -882,7 +889,7 @@ int bd_quad_draft(bd_ctx* c, int B, int32_t* dev_draft_out) {
 int bd_quad_step(bd_ctx* c, int B, const int32_t* dev_draft, int32_t* dev_next_draft, int32_t* host_n_accepted) {
   if (c == nullptr || B < 1 || dev_draft == nullptr || dev_next_draft == nullptr || host_n_accepted == nullptr) return BD_E_ARG;
   const int M = B * (B + 1);
-  if (M > c->cfg.max_block) return BD_E_ARG;
+  if (M > c->cfg.max_block || c->fp8) return BD_E_ARG;   // (bf16 contexts only)
   BD_TRY(check_decode_call(c, M));                       // the forward parks its B(B+1) rows at [cache_len, cache_len + M)
   hipStream_t s = c->stream;
   hipLaunchKernelGGL(quad_assemble_kernel, dim3(ceil_div(M, 64)), dim3(64), 0, s, dev_draft, B, c->cfg.mask_token_id, c->quad_ids);

@@ -45,12 +45,17 @@ __device__ inline size_t xp_index(int m, int k, int MT) {
 // (Sec. 3.3 mask rules; Alg. 1 draft / verify masks; Alg. 2 quadratic mask).  mode 0: all visible; 1: causal;
 // 2 + (B << 8): B groups of B+1 rows, a group's first row sees the first rows of the groups up to its own, every other
 // row sees the rows of its own group.  (Keys of the committed prefix are visible to every row.)
+// QUAD is a compile-time switch: the kernels of ordinary forwards are built without the quadratic rule (its index
+// arithmetic costs registers in every phase of the persistent kernels), the quadratic step runs its own instantiations.
+template <bool QUAD>
 __device__ inline bool block_key_visible(int mode, int row, int jb) {
-  if (mode == 0) return true;
-  if (mode == 1) return jb <= row;
-  const int W = (mode >> 8) + 1;
-  const int gi = row / W, gj = row - gi * W, ki = jb / W, kj = jb - ki * W;
-  return gj == 0 ? (kj == 0 && ki <= gi) : ki == gi;
+  if constexpr (!QUAD) {
+    return mode == 0 || jb <= row;
+  } else {
+    const int W = (mode >> 8) + 1;
+    const int gi = row / W, gj = row - gi * W, ki = jb / W, kj = jb - ki * W;
+    return gj == 0 ? (kj == 0 && ki <= gi) : ki == gi;
+  }
 }
 
 // State that lives on the device so that replayed launch sequences need no new kernel arguments.

@@ -738,7 +738,7 @@ __device__ inline void gemm_phase(const MegaArgs& a, const PhaseCtx& pc, bf16x8 
 // Items (kv head, group of JT column tiles, key chunk) go round-robin over the workgroups.  Each item
 // stores its partial (unnormalised output, running max, running sum); the workgroup that completes the
 // last chunk of a (kv head, column group) merges all chunks in fixed order and stores the bf16 result.
-template <int D, int JT>
+template <int D, int JT, bool QUAD>
 __device__ inline void attention_phase(const MegaArgs& a, const PhaseCtx& pc, char* lds, int wave, int lane_in) {
   constexpr int DS = D / 32, DT = D / 16;
   int lane = lane_in;
@@ -821,7 +821,7 @@ __device__ inline void attention_phase(const MegaArgs& a, const PhaseCtx& pc, ch
           vis[e] = true;
           if (need_mask) {
             const int jb = kb * 32 + 8 * g + e - n;
-            vis[e] = (jb < 0) || (jb < a.M && block_key_visible(a.mode, row[jt], jb));
+            vis[e] = (jb < 0) || (jb < a.M && block_key_visible<QUAD>(a.mode, row[jt], jb));
           }
           if (vis[e]) cmax = fmaxf(cmax, v[e]);
         }
@@ -992,7 +992,7 @@ template <int MT> constexpr int mega_lds_bytes() {
   return kWavesPerWG * mega_xh<MT>() * MT * 1024 + kWavesPerWG * kT * MT * 1024;
 }
 
-template <int MT, int D, int JT>
+template <int MT, int D, int JT, bool QUAD = false>
 __global__ __launch_bounds__(kWGThreads, 1) void mega_kernel(MegaArgs a) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ int s_flags[16];
@@ -1041,7 +1041,7 @@ __global__ __launch_bounds__(kWGThreads, 1) void mega_kernel(MegaArgs a) {
     alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
     BD_TS();
     if (!alive) break;
-    attention_phase<D, JT>(a, pc, lds, wave, lane);
+    attention_phase<D, JT, QUAD>(a, pc, lds, wave, lane);
     BD_TS();
     alive = grid_barrier(a.bar, ++epoch, P.nwg, a.st, &s_flags[0]);
     BD_TS();

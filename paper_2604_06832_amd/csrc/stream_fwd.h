@@ -626,7 +626,7 @@ __device__ inline void kv_load(KvBlock<D>& b, const bf16x8* Kh, const bf16x8* Vh
 
 // One block of 32 keys against one tile of 16 query columns.  Scores stay unscaled until the exponent:
 // p = 2^(s*c - m) with c = log2(e)/sqrt(d) folded into one fused multiply-add per score.
-template <int D, bool MASKED>
+template <int D, bool MASKED, bool QUAD = false>
 __device__ inline void attn_block(const KvBlock<D>& b, const bf16x8 (&qf)[D / 32], f32x4 (&O)[D / 16], float& mrun, float& lrun,
                                   int kb, int n, int M, int mode, int row, int g, float c) {
   constexpr int DS = D / 32, DT = D / 16;
@@ -646,7 +646,7 @@ __device__ inline void attn_block(const KvBlock<D>& b, const bf16x8 (&qf)[D / 32
     vis[e] = true;
     if constexpr (MASKED) {
       const int jb = kb * 32 + 8 * g + e - n;
-      vis[e] = (jb < 0) || (jb < M && block_key_visible(mode, row, jb));
+      vis[e] = (jb < 0) || (jb < M && block_key_visible<QUAD>(mode, row, jb));
       if (vis[e]) cmax = fmaxf(cmax, v[e]);
     } else {
       cmax = fmaxf(cmax, v[e]);
@@ -676,7 +676,7 @@ __device__ inline void attn_block(const KvBlock<D>& b, const bf16x8 (&qf)[D / 32
   for (int dt = 0; dt < DT; ++dt) O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b.v[dt], p8, O[dt], 0, 0, 0);
 }
 
-template <int D>
+template <int D, bool QUAD>
 __device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, FwdSync& sy, int wave, int lane_in) {
   constexpr int DS = D / 32, DT = D / 16;
   int lane = lane_in;
@@ -739,12 +739,12 @@ __device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, Fwd
       const int kb1 = kb + kWavesPerWG, kb2 = kb + 2 * kWavesPerWG;
       if (kb1 < kb_end) kv_load<D>(b1, Kh, Vh, kb1, lane);
       asm volatile("" ::: "memory");
-      if (kb * 32 + 31 >= n) attn_block<D, true>(b0, qf, O, mrun, lrun, kb, n, a.M, a.mode, row, g, c);
+      if (kb * 32 + 31 >= n) attn_block<D, true, QUAD>(b0, qf, O, mrun, lrun, kb, n, a.M, a.mode, row, g, c);
       else attn_block<D, false>(b0, qf, O, mrun, lrun, kb, n, a.M, a.mode, row, g, c);
       if (kb1 < kb_end) {
         if (kb2 < kb_end) kv_load<D>(b0, Kh, Vh, kb2, lane);
         asm volatile("" ::: "memory");
-        if (kb1 * 32 + 31 >= n) attn_block<D, true>(b1, qf, O, mrun, lrun, kb1, n, a.M, a.mode, row, g, c);
+        if (kb1 * 32 + 31 >= n) attn_block<D, true, QUAD>(b1, qf, O, mrun, lrun, kb1, n, a.M, a.mode, row, g, c);
         else attn_block<D, false>(b1, qf, O, mrun, lrun, kb1, n, a.M, a.mode, row, g, c);
       }
     }
@@ -961,7 +961,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void xcc_probe_kernel(unsigned* out
 // ---- the kernel ------------------------------------------------------------------------------------------------
 template <int MT> constexpr int stream_lds_bytes() { return kWavesPerWG * kSlots * 1024 + kShareBytes; }
 
-template <int MT, int D, bool FP8>
+template <int MT, int D, bool FP8, bool QUAD = false>
 __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) {
   static_assert(2 * kWavesPerWG * kT * MT * 1024 <= kShareBytes, "K-reduction buffers exceed the shared region");
   static_assert(kWavesPerWG * (D / 16) * 1024 + (8 * 16 + 64 * 16 + 16) * 4 <= kShareBytes, "attention merge buffers exceed the shared region");
@@ -1026,7 +1026,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
     if (!alive) break;
-    stream_attention_phase<D>(a, fc, sy, wave, lane);
+    stream_attention_phase<D, QUAD>(a, fc, sy, wave, lane);
     BD_TS2();
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
