@@ -266,10 +266,10 @@ int stream_attn_max_chunks(const bd_ctx* c, int MT) {
 }
 
 template <int MT>
-int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
+int launch_mega_mt(bd_ctx* c, MegaArgs& a, bool lm_only = false) {
   bool streamed = false;
   if constexpr (MT <= 2) streamed = c->use_stream;
-  {
+  if (!lm_only) {
   Prof pr(c, KC_LAYERS);
   if (streamed) {
     if constexpr (MT <= 2) {
@@ -313,11 +313,14 @@ int launch_mega_mt(bd_ctx* c, MegaArgs& a) {
 // One decoder forward over M rows: prologue (block assembly) + the persistent forward kernel.
 // Source of the rows: prompt rows [off, off+M) (embeds then ids), or block tokens with an optional mask.
 int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n_embed, const int32_t* ids, int off,
-            int32_t* seed_tokens, uint8_t* seed_mask, const uint8_t* mask, bool skippable = false, int quad_B = 0) {
+            int32_t* seed_tokens, uint8_t* seed_mask, const uint8_t* mask, bool skippable = false, int quad_B = 0,
+            bool lm_only = false) {
+  // lm_only: the last residual version of the rows (bf16 copy and sums of squares) is already in place; only the final
+  // norm + LM head run (the large-M prefill hands its last row over this way)
   const int MT = ceil_div(M, 16);
   const int Mp = c->Mp_max;
   hipStream_t s = c->stream;
-  {
+  if (!lm_only) {
     PrologueArgs p{};
     p.x0 = c->xv; p.ssq0 = c->ssq; p.H = c->H; p.Mp = Mp; p.xb0 = c->xb; p.MT = MT;
     p.embeds = embeds; p.n_embed = n_embed; p.ids = ids; p.off = off;
@@ -356,13 +359,13 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
   {
 #ifdef BD_DEV_FAST   /* development builds: one instantiation only, to shorten compile time */
     if (MT != 2) return BD_E_ARG;
-    BD_TRY(launch_mega_mt<2>(c, a));
+    BD_TRY(launch_mega_mt<2>(c, a, lm_only));
 #else
     switch (MT) {
-      case 1: BD_TRY(launch_mega_mt<1>(c, a)); break;
-      case 2: BD_TRY(launch_mega_mt<2>(c, a)); break;
-      case 3: BD_TRY(launch_mega_mt<3>(c, a)); break;
-      default: BD_TRY(launch_mega_mt<4>(c, a)); break;
+      case 1: BD_TRY(launch_mega_mt<1>(c, a, lm_only)); break;
+      case 2: BD_TRY(launch_mega_mt<2>(c, a, lm_only)); break;
+      case 3: BD_TRY(launch_mega_mt<3>(c, a, lm_only)); break;
+      default: BD_TRY(launch_mega_mt<4>(c, a, lm_only)); break;
     }
 #endif
   }
@@ -414,18 +417,24 @@ int launch_pf_gemm(bd_ctx* c, PfGemmArgs a, int n_rows) {
   return check_launch();
 }
 
-// One chunk of mc prompt rows (a multiple of 16) starting at prompt row `off` = cache position c->n: all layers,
-// K/V into the cache, no LM head.  The device-side length is advanced by the caller.
-int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* dev_ids, int off, int mc) {
+// One chunk of `rows` prompt rows starting at prompt row `off` = cache position c->n: all layers, K/V into the cache,
+// no LM head.  The kernels work on whole tiles of 16 rows: the rows that pad the last tile are zero on entry, take part
+// in every product and write nothing to the cache.  The device-side length is advanced by the caller.
+int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* dev_ids, int off, int rows) {
   hipStream_t s = c->stream;
-  const int MTc = mc / 16;
-  hipLaunchKernelGGL(embed_kernel, dim3(mc), dim3(kWGThreads), 0, s, c->pf_x, c->H, dev_embeds, n_embed, dev_ids, off,
+  const int MTc = ceil_div(rows, 16);
+  const int mc = MTc * 16;
+  hipLaunchKernelGGL(embed_kernel, dim3(rows), dim3(kWGThreads), 0, s, c->pf_x, c->H, dev_embeds, n_embed, dev_ids, off,
                      (const uint8_t*)nullptr, c->cfg.mask_token_id, c->embed, c->V);
   BD_TRY(check_launch());
+  if (mc > rows) {
+    hipLaunchKernelGGL(zero_rows_kernel, dim3(mc - rows), dim3(kWGThreads), 0, s, c->pf_x + (size_t)rows * c->H, c->H);
+    BD_TRY(check_launch());
+  }
   hipLaunchKernelGGL(rope_table_kernel, dim3(mc), dim3(64), 0, s, c->pf_rope, c->st, c->D / 2, c->cfg.rope_theta);
   BD_TRY(check_launch());
   PfGemmArgs g{};
-  g.MTc = MTc; g.rs = c->pf_rs; g.rope = c->pf_rope; g.x = c->pf_x; g.q = c->pf_q; g.max_kb = c->max_kb; g.n0 = c->n;
+  g.MTc = MTc; g.Mvalid = rows; g.rs = c->pf_rs; g.rope = c->pf_rope; g.x = c->pf_x; g.q = c->pf_q; g.max_kb = c->max_kb; g.n0 = c->n;
   g.act = c->pf_act; g.H = c->H; g.QD = c->QD; g.KVD = c->KVD; g.D = c->D; g.n_q = c->cfg.n_q_heads;
   for (int l = 0; l < c->L; ++l) {
     const u16* wl = c->pf_w + (size_t)l * c->pf_layer_elems;
@@ -753,18 +762,38 @@ int bd_prefill(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* d
   c->n = 0; c->prefilled = false; c->carry_valid = false;
   const int step = c->cfg.max_block;                   // (at most 32 with e4m3 weights, checked at creation)
   int off0 = 0;
-  if (c->pf_on) {
-    // the bulk of the prompt in large chunks; at least one row is left for the pass that produces the carry
-    const int fast = (total - 1) / 16 * 16;
-    while (off0 < fast && fast >= kPfTokens) {
-      int mc = std::min(c->pf_rows, fast - off0);
-      if (fast - off0 - mc > 0 && fast - off0 - mc < kPfTokens && mc > kPfTokens) mc -= kPfTokens;   // no sliver of a last chunk
-      BD_TRY(prefill_chunk(c, dev_embeds, n_embed, dev_ids, off0, mc));
-      hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(1), 0, s, c->st, mc);
+  if (c->pf_on && total > kPfTokens) {
+    // The whole prompt in large chunks; the last row's residual stream is then handed to the final norm + LM head.
+    while (off0 < total) {
+      int rows = std::min(c->pf_rows, total - off0);
+      if (total - off0 - rows > 0 && total - off0 - rows < kPfTokens && rows > kPfTokens) rows -= kPfTokens;   // no sliver
+      BD_TRY(prefill_chunk(c, dev_embeds, n_embed, dev_ids, off0, rows));
+      const bool last = off0 + rows >= total;
+      hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(1), 0, s, c->st, last ? rows - 1 : rows);
       BD_TRY(check_launch());
-      c->n += mc;
-      off0 += mc;
+      if (last) {
+        const int ver = 2 * c->L;
+        hipLaunchKernelGGL(pf_last_row_kernel, dim3(1), dim3(kPfThreads), 0, s, c->pf_x + (size_t)(rows - 1) * c->H, c->H,
+                           c->xb + (size_t)ver * c->xb_elems, c->ssq + (size_t)ver * c->ssq_parts * c->Mp_max,
+                           phase_tile_slots(c->plan, PH_DOWN), c->Mp_max);
+        BD_TRY(check_launch());
+        c->n += rows - 1;
+        BD_TRY(forward(c, 1, BD_MODE_CAUSAL, true, nullptr, 0, nullptr, 0, nullptr, nullptr, nullptr, false, 0, true));
+        FinishArgs f = finish_args(c, 1);
+        f.commit = 1;
+        hipLaunchKernelGGL(finish_causal_kernel, dim3(1), dim3(64), 0, s, f);
+        BD_TRY(check_launch());
+        hipLaunchKernelGGL(pf_clear_ssq_kernel, dim3(4), dim3(256), 0, s, c->ssq + (size_t)ver * c->ssq_parts * c->Mp_max,
+                           phase_tile_slots(c->plan, PH_DOWN), c->Mp_max);
+        BD_TRY(check_launch());
+        c->n += 1;
+      } else {
+        c->n += rows;
+      }
+      off0 += rows;
     }
+    c->prefilled = true; c->carry_valid = true;
+    return BD_OK;
   }
   for (int off = off0; off < total; off += step) {
     const int M = std::min(step, total - off);

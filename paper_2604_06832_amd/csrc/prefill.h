@@ -4,8 +4,8 @@
 // through them re-reads the model n/64 times.  For the bulk of the prompt this file provides the compute-bound
 // form: chunks of up to 1024 rows, each layer as a sequence of tiled MFMA GEMMs with the same fused epilogues as the
 // decode path (RMS factor, rotary + Q store + K/V store; residual add; SwiGLU) and a causal attention kernel that
-// walks the packed cache with the decode path's per-block routine.  The last rows of the prompt (and the LM head,
-// which is needed for the last row only) still go through the decode kernels.
+// walks the packed cache with the decode path's per-block routine.  Only the LM head, needed for the last row alone,
+// is the decode path's.
 //
 // Operand layout: both GEMM operands are kept as 1-KiB MFMA fragments (16 rows x 32 k, lane (row i, k-quarter kq)
 // holds 8 consecutive k at lane*16 bytes).  Weights: fragment (row tile T, k-step ks) of a layer's phase at
@@ -24,6 +24,7 @@ struct PfGemmArgs {
   int NT, KS;             // 16-row tiles and k-steps of the phase
   const bf16x8* xin;      // packed activations of the chunk
   int MTc;                // token tiles of the chunk (any number: a workgroup's eight may reach past the end)
+  int Mvalid;             // rows of the chunk; the rows that pad its last tile write no Q, K or V
   int RG, TG;             // workgroup grid: row groups x token groups
   const float* rs;        // [Mc] 1/rms of the rows of the residual stream (QKV, gate/up)
   const float2* rope;     // [Mc][D/2] (QKV)
@@ -139,6 +140,7 @@ __global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 8 * BKS * 64)
       const int token = (mt0 + wm * 4 + j) * 16 + col;
       f32x4 v = acc[i][j];
       if constexpr (PH == PH_QKV) {
+        if (token >= a.Mvalid) continue;
         const int D = a.D, half = D >> 1;
         v *= a.rs[token];
         const int key = a.n0 + token;
@@ -206,6 +208,42 @@ __global__ __launch_bounds__(kPfThreads) void pf_norm_kernel(const float* __rest
     for (int w = 0; w < kPfThreads / 64; ++w) t += part[w];
     rs[token] = rsqrtf(t / (float)H + eps);
   }
+}
+
+__global__ __launch_bounds__(kPfThreads) void zero_rows_kernel(float* __restrict__ x, int H) {
+  for (int c = threadIdx.x; c < H; c += kPfThreads) x[(size_t)blockIdx.x * H + c] = 0.f;
+}
+
+// Hand-over of the prompt's last row to the final norm + LM head of the decode path: its bf16 copy becomes row 0 of the
+// last residual version (packed order of a 16-row tile, the other rows zero) and its sum of squares part 0 of that
+// version's partial sums (the other parts zero; rows 1..15 get a harmless 1).
+__global__ __launch_bounds__(kPfThreads) void pf_last_row_kernel(const float* __restrict__ xrow, int H, u16* __restrict__ xb,
+                                                                 float* __restrict__ ssq, int parts, int Mp) {
+  __shared__ float part[kPfThreads / 64];
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < H; c += kPfThreads) {
+    const float v = xrow[c];
+    ss += v * v;
+    xb[xp_index(0, c, 1)] = f32_to_bf16_bits(v);
+    for (int m = 1; m < 16; ++m) xb[xp_index(m, c, 1)] = 0;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  float t = 0.f;
+  for (int w = 0; w < kPfThreads / 64; ++w) t += part[w];
+  for (int i = threadIdx.x; i < parts * 16; i += kPfThreads) {
+    const int p = i / 16, m = i % 16;
+    ssq[(size_t)p * Mp + m] = p == 0 ? (m == 0 ? t : 1.f) : 0.f;
+  }
+}
+
+// The decode kernels rely on the slots of the partial sums that no tile owns staying zero: clear what the hand-over
+// wrote once the LM head has read it.
+__global__ void pf_clear_ssq_kernel(float* __restrict__ ssq, int parts, int Mp) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < parts * 16; i += gridDim.x * blockDim.x)
+    ssq[(size_t)(i / 16) * Mp + i % 16] = 0.f;
 }
 
 // Causal attention of a chunk against the packed cache (which already holds the chunk's own keys and values):

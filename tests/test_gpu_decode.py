@@ -695,8 +695,9 @@ def test_call_order_and_capacity_errors():
 @pytest.mark.parametrize("n_embed,n_ids", [(0, 1), (1, 0), (0, 70), (70, 0), (63, 66), (0, 128), (130, 126), (0, 144),
                                            (700, 400)])
 def test_prefill_edge_lengths(n_embed, n_ids):
-    """Prompts of fewer than 129 rows go through the decode kernels only; longer ones put all but their last 1-16 rows
-    through the large-M path: 128 -> 112 + 16, 256 -> 240 + 16, 144 -> 128 + 16, 1100 -> chunks of 896 and 192 + 12."""
+    """Prompts of up to 128 rows go through the decode kernels; longer ones wholly through the large-M path (the last
+    tile padded to 16 rows), the last row's residual stream handed to the LM head: 129 -> chunks of 128 and 1,
+    256 -> 128 + 128, 144 -> 128 + 16, 1100 -> 896 + 204 rows (max_seq bounds the chunk size here)."""
     shape = inputs.TINY
     w = inputs.make_weights(shape, 0, "bf16", threads=1)
     emb, ids = inputs.make_prompt(shape, n_embed, n_ids, seed=7)
