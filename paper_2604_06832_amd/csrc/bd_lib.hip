@@ -399,21 +399,22 @@ FinishArgs finish_args(bd_ctx* c, int B) {
 // ---------------------------------------------------------------------------------------------------------
 namespace {
 
-// Tile shapes per phase (rows per workgroup = 32*WN, k-steps per stage BKS), picked by measurement at 1008 rows:
-// gate/up 128 rows x 2 k-steps (two workgroups per CU), down and O 64 x 4, QKV 64 x 2.
-template <int PH, int WN, int BKS>
+// Tile shapes per phase (rows per workgroup = 32*WN, k-steps per stage BKS, tokens per workgroup = 32*TW), picked by
+// measurement at 1024 rows: gate/up 128 rows x 128 tokens x 2 k-steps, down and O 64 x 64 x 4, QKV 64 x 64 x 2 (the
+// phases with 2048-2560 output rows need the smaller token tile to put two workgroups on every CU).
+template <int PH, int WN, int BKS, int TW>
 int launch_pf_gemm(bd_ctx* c, PfGemmArgs a, int n_rows) {
   static bool attr_set = false;
-  constexpr int lds = pf_gemm_lds<WN, BKS>();
+  constexpr int lds = pf_gemm_lds<WN, BKS, TW>();
   if (!attr_set) {
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<PH, WN, BKS>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<PH, WN, BKS, TW>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     attr_set = true;
   }
   a.NT = n_rows / 16;
   a.RG = ceil_div(a.NT, 2 * WN);
-  a.TG = ceil_div(a.MTc, 8);
+  a.TG = ceil_div(a.MTc, 2 * TW);
   const int grid = ceil_div(a.RG, 8) * 8 * a.TG;
-  hipLaunchKernelGGL((pf_gemm_kernel<PH, WN, BKS>), dim3(grid), dim3(kPfThreads), lds, c->stream, a);
+  hipLaunchKernelGGL((pf_gemm_kernel<PH, WN, BKS, TW>), dim3(grid), dim3(kPfThreads), lds, c->stream, a);
   return check_launch();
 }
 
@@ -444,7 +445,7 @@ int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t
     BD_TRY(check_launch());
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[0]); g.KS = ceil_div(c->H, 32);
     g.xin = reinterpret_cast<const bf16x8*>(c->pf_xb);
-    BD_TRY((launch_pf_gemm<PH_QKV, 2, 2>(c, g, c->NQKV)));
+    BD_TRY((launch_pf_gemm<PH_QKV, 2, 2, 2>(c, g, c->NQKV)));
     {
       PfAttnArgs t{};
       t.q = c->pf_q; t.Kc = g.Kc; t.Vc = g.Vc; t.max_kb = c->max_kb; t.n0 = c->n; t.Mc = mc; t.n_q = c->cfg.n_q_heads;
@@ -456,15 +457,15 @@ int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t
     }
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[1]); g.KS = ceil_div(c->QD, 32);
     g.xin = reinterpret_cast<const bf16x8*>(c->pf_ap);
-    BD_TRY((launch_pf_gemm<PH_O, 2, 4>(c, g, c->H)));
+    BD_TRY((launch_pf_gemm<PH_O, 2, 4, 2>(c, g, c->H)));
     hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs);
     BD_TRY(check_launch());
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[2]); g.KS = ceil_div(c->H, 32);
     g.xin = reinterpret_cast<const bf16x8*>(c->pf_xb);
-    BD_TRY((launch_pf_gemm<PH_GU, 4, 2>(c, g, 2 * c->F)));
+    BD_TRY((launch_pf_gemm<PH_GU, 4, 2, 4>(c, g, 2 * c->F)));
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[3]); g.KS = ceil_div(c->F, 32);
     g.xin = reinterpret_cast<const bf16x8*>(c->pf_act);
-    BD_TRY((launch_pf_gemm<PH_DOWN, 2, 4>(c, g, c->H)));
+    BD_TRY((launch_pf_gemm<PH_DOWN, 2, 4, 2>(c, g, c->H)));
   }
   return BD_OK;
 }

@@ -37,14 +37,15 @@ struct PfGemmArgs {
 };
 
 // C[rows of the phase][tokens] = W * X^T, fp32 accumulation, epilogue per phase.  A workgroup computes
-// (2*WN*16) rows x 128 tokens; each wavefront WN x 4 tiles of 16 x 16.  K advances by BKS k-steps per iteration
+// (2*WN*16) rows x (2*TW*16) tokens; each wavefront WN x TW tiles of 16 x 16.  K advances by BKS k-steps per iteration
 // through two LDS stages; the operands of a stage travel global memory -> registers -> LDS, the loads of stage i+1
 // being issued before the MFMAs of stage i.  (A second register set, two stages ahead, costs more in registers than
 // it hides in latency: measured slower for every shape here.)
-template <int PH, int WN, int BKS>
-__global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 8 * BKS * 64) * 16 <= 80 * 1024) ? 2 : 1) void pf_gemm_kernel(PfGemmArgs a) {
+template <int PH, int WN, int BKS, int TW>
+__global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 2 * TW * BKS * 64) * 16 <= 80 * 1024) ? 2 : 1) void pf_gemm_kernel(PfGemmArgs a) {
   constexpr int AT = 2 * WN;                                        // row tiles per workgroup
-  constexpr int A_UNITS = AT * BKS * 64, B_UNITS = 8 * BKS * 64;    // 16-byte units per stage
+  constexpr int BT = 2 * TW;                                        // token tiles per workgroup
+  constexpr int A_UNITS = AT * BKS * 64, B_UNITS = BT * BKS * 64;   // 16-byte units per stage
   constexpr int STAGE = A_UNITS + B_UNITS;
   constexpr int A_PER = A_UNITS / kPfThreads, B_PER = B_UNITS / kPfThreads;
   extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 8 * BKS * 64)
   const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
   const int rg = (slot / a.TG) * 8 + xcd, tg = slot % a.TG;
   if (rg >= a.RG) return;
-  const int T0 = rg * AT, mt0 = tg * 8;
+  const int T0 = rg * AT, mt0 = tg * BT;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wn = wave >> 1, wm = wave & 1;
   const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -68,6 +69,7 @@ __global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 8 * BKS * 64)
   const int a_tile = threadIdx.x / TU, a_within = threadIdx.x % TU; // (256 / TU tiles per round of 256 units)
   const int a_base = ((T0 + a_tile) * a.KS) * 1024 + a_within * 16;
   const int a_ksl = a_within >> 6;
+  constexpr int UB = BT * 64;                                       // activation units per k-step
   const int b_base = mt0 * 1024 + threadIdx.x * 16;
   const int b_tile = threadIdx.x >> 6;
   auto gload = [&](Regs& R, int it) {
@@ -80,9 +82,9 @@ __global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 8 * BKS * 64)
     }
 #pragma unroll
     for (int i = 0; i < B_PER; ++i) {
-      const int ksl = i >> 1, half = i & 1;
-      const int off = b_base + ((ks0 + ksl) * a.MTc) * 1024 + half * 4096;
-      R.b[i] = buf_load_b(xr, (ks0 + ksl < a.KS && mt0 + b_tile + 4 * half < a.MTc) ? off : kOob);
+      const int ksl = (i * kPfThreads) / UB, part = (i * kPfThreads) % UB;      // units part .. part+255 of that k-step
+      const int off = b_base + ((ks0 + ksl) * a.MTc) * 1024 + part * 16;
+      R.b[i] = buf_load_b(xr, (ks0 + ksl < a.KS && mt0 + b_tile + part / 64 < a.MTc) ? off : kOob);
     }
   };
   auto lstore = [&](const Regs& R, int stage) {
@@ -93,25 +95,25 @@ __global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 8 * BKS * 64)
     for (int i = 0; i < B_PER; ++i) A[A_UNITS + threadIdx.x + i * kPfThreads] = R.b[i];
   };
 
-  f32x4 acc[WN][4];
+  f32x4 acc[WN][TW];
 #pragma unroll
   for (int i = 0; i < WN; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < TW; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   auto compute = [&](int stage) {
     const bf16x8* A = sm + stage * STAGE;
     const bf16x8* Bm = A + A_UNITS;
 #pragma unroll
     for (int ksl = 0; ksl < BKS; ++ksl) {
-      bf16x8 af[WN], bfr[4];
+      bf16x8 af[WN], bfr[TW];
 #pragma unroll
       for (int i = 0; i < WN; ++i) af[i] = A[((wn * WN + i) * BKS + ksl) * 64 + lane];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) bfr[j] = Bm[(ksl * 8 + wm * 4 + j) * 64 + lane];
+      for (int j = 0; j < TW; ++j) bfr[j] = Bm[(ksl * BT + wm * TW + j) * 64 + lane];
 #pragma unroll
       for (int i = 0; i < WN; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TW; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
   };
 
@@ -135,9 +137,9 @@ __global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 8 * BKS * 64)
     if (T >= a.NT) continue;
     const int r = T * 16 + 4 * g;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (mt0 + wm * 4 + j >= a.MTc) continue;
-      const int token = (mt0 + wm * 4 + j) * 16 + col;
+    for (int j = 0; j < TW; ++j) {
+      if (mt0 + wm * TW + j >= a.MTc) continue;
+      const int token = (mt0 + wm * TW + j) * 16 + col;
       f32x4 v = acc[i][j];
       if constexpr (PH == PH_QKV) {
         if (token >= a.Mvalid) continue;
@@ -184,7 +186,7 @@ __global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 8 * BKS * 64)
   }
 }
 
-template <int WN, int BKS> constexpr int pf_gemm_lds() { return 2 * (2 * WN * BKS * 64 + 8 * BKS * 64) * 16; }
+template <int WN, int BKS, int TW> constexpr int pf_gemm_lds() { return 2 * (2 * WN * BKS * 64 + 2 * TW * BKS * 64) * 16; }
 
 // One workgroup per row: 1/rms of the fp32 residual row and its bf16 copy in packed order (the norm gain lives in
 // the weights, the factor is applied by the GEMM epilogue: same arithmetic as the decode path).
