@@ -587,6 +587,44 @@ def test_fp8_tiny_block_decode():
     p.close()
 
 
+def test_fp8_whole_block_and_speculative_calls():
+    """The calls that chain forwards on the device, on a context with e4m3 weights: a whole block per call equals the
+    step-by-step loop bit for bit, a speculative iteration accepts between 1 and B tokens and leaves a valid carry, and
+    the quadratic step (bf16 contexts only) is refused."""
+    _say("tiny config, e4m3 weights: bd_decode_block, bd_speculative_step, bd_quad_step")
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 2, "fp8", lm_head_scale=20.0, threads=1)
+    emb, ids = inputs.make_prompt(shape, 20, 20, seed=105)
+    ctxs = []
+    for _ in range(2):
+        c = binding.Context(shape, max_seq=200, max_block=32, weight_dtype=binding.BD_FP8_E4M3)
+        c.load_model(w)
+        c.bd_prefill(torch.from_numpy(emb).cuda(), torch.from_numpy(ids).cuda())
+        ctxs.append(c)
+    a, b = ctxs
+    B = 16
+    out = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nst = torch.zeros(1, dtype=torch.int32, device="cuda")
+    a.bd_decode_block(B, 0.3, 0, out, nst)
+    tok = torch.full((B,), shape.mask_token_id, dtype=torch.int32, device="cuda")
+    msk = torch.ones(B, dtype=torch.uint8, device="cuda")
+    fwd = 0
+    while bool(msk.any().item()):
+        b.bd_denoise_step(tok, msk, 0.3, 0, None, None)
+        fwd += 1
+    b.bd_commit_block(tok)
+    assert torch.equal(out, tok) and int(nst.item()) == fwd
+    assert a.bd_read_carry() == b.bd_read_carry()
+    k = a.bd_speculative_step(8, out)
+    assert 1 <= k <= 8 and a.bd_cache_len() == 40 + B + k
+    a.bd_read_carry()
+    with pytest.raises(binding.BdError):
+        a.bd_quad_step(3, out, tok)
+    a.bd_status()
+    a.close()
+    b.close()
+
+
 @pytest.mark.parametrize("B", [4, 16, 32])
 def test_fp8_3b_shaped_two_layers(B):
     _say(f"3B-shaped x2 layers, e4m3 decoder linears, B={B}")
