@@ -249,9 +249,11 @@ __global__ void pf_clear_ssq_kernel(float* __restrict__ ssq, int parts, int Mp) 
 }
 
 // Causal attention of a chunk against the packed cache (which already holds the chunk's own keys and values):
-// one wavefront per (head, tile of 16 query rows), walking the 32-key blocks up to its last visible key with the
-// decode path's block routine and two register buffers.  Four consecutive items (heads of one kv head first) share
-// a workgroup, so their key/value blocks meet in the caches.
+// NW (2 or 4) wavefronts per (head, tile of 16 query rows) share out the 32-key blocks up to the last visible key
+// round-robin, each with the decode path's block routine and two register buffers, and merge through LDS; the items of
+// a workgroup are heads of one kv head, so their key/value blocks meet in the caches; two workgroups fit a CU.
+// (Measured: two and four wavefronts per item are equal, also at 8192 keys; a variant that stages every block once in
+// LDS for four heads of a kv head, one barrier per block, is slower than these register-buffered walks.)
 struct PfAttnArgs {
   const u16* q;           // [Mc][n_q][D], rotated, dims in rotary-pair order
   const u16* Kc; const u16* Vc;
@@ -261,55 +263,87 @@ struct PfAttnArgs {
   int MTc;
 };
 
-template <int D>
-__global__ __launch_bounds__(kPfThreads) void pf_attn_kernel(PfAttnArgs a) {
+template <int D, int NW>
+__global__ __launch_bounds__(kPfThreads, 2) void pf_attn_kernel(PfAttnArgs a) {
   constexpr int DS = D / 32, DT = D / 16;
+  constexpr int IPW = 4 / NW;                                  // items per workgroup, NW wavefronts per item
+  __shared__ f32x4 sO[IPW][NW - 1][DT][64];
+  __shared__ float sm[IPW][NW - 1][64], sl[IPW][NW - 1][64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int sub = wave / NW, half = wave % NW;                 // wavefront `half` of item `sub` takes blocks half, half + NW, ..
   const int col = lane & 15, g = lane >> 4;
   const int G = a.n_q / a.n_kv, QT = a.Mc >> 4;
-  const int item = blockIdx.x * (kPfThreads / 64) + wave;
-  if (item >= a.n_kv * QT * G) return;
-  const int hq = item % G, qt = (item / G) % QT, kvh = item / (G * QT);
+  const int item = blockIdx.x * IPW + sub;
+  const bool valid = item < a.n_kv * QT * G;
+  const int hq = item % G, qt = (item / G) % QT, kvh = valid ? item / (G * QT) : 0;
   const int head = kvh * G + hq;
   const int row = qt * 16 + col;
   const size_t kv_block = (size_t)32 * D / 8;
   const bf16x8* Kh = reinterpret_cast<const bf16x8*>(a.Kc) + (size_t)kvh * a.max_kb * kv_block;
   const bf16x8* Vh = reinterpret_cast<const bf16x8*>(a.Vc) + (size_t)kvh * a.max_kb * kv_block;
-  bf16x8 qf[DS];
-  {
-    const u16* qp = a.q + ((size_t)row * a.n_q + head) * D + 8 * g;
-#pragma unroll
-    for (int ds = 0; ds < DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8*>(qp + ds * 32);
-  }
   f32x4 O[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   float mrun = kNegBig, lrun = 0.f;
-  const int kb_end = (a.n0 + qt * 16 + 15) / 32 + 1;            // blocks holding a key some row of the tile may see
-  const float c = a.scale_log2e;
-  KvBlock<D> b0, b1;
-  kv_load<D>(b0, Kh, Vh, 0, lane);
-  asm volatile("" ::: "memory");
-  for (int kb = 0; kb < kb_end; kb += 2) {
-    if (kb + 1 < kb_end) kv_load<D>(b1, Kh, Vh, kb + 1, lane);
+  if (valid) {
+    bf16x8 qf[DS];
+    {
+      const u16* qp = a.q + ((size_t)row * a.n_q + head) * D + 8 * g;
+#pragma unroll
+      for (int ds = 0; ds < DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8*>(qp + ds * 32);
+    }
+    const int kb_end = (a.n0 + qt * 16 + 15) / 32 + 1;          // blocks holding a key some row of the tile may see
+    const int cnt = (kb_end - half + NW - 1) / NW;              // this wavefront's blocks: half, half + NW, ..
+    const float c = a.scale_log2e;
+    KvBlock<D> b0, b1;
+    if (cnt > 0) kv_load<D>(b0, Kh, Vh, half, lane);
     asm volatile("" ::: "memory");
-    if (kb * 32 + 31 >= a.n0) attn_block<D, true>(b0, qf, O, mrun, lrun, kb, a.n0, a.Mc, 1, row, g, c);
-    else attn_block<D, false>(b0, qf, O, mrun, lrun, kb, a.n0, a.Mc, 1, row, g, c);
-    if (kb + 1 < kb_end) {
-      if (kb + 2 < kb_end) kv_load<D>(b0, Kh, Vh, kb + 2, lane);
+    for (int j = 0; j < cnt; j += 2) {
+      const int kbA = half + NW * j, kbB = kbA + NW;
+      if (j + 1 < cnt) kv_load<D>(b1, Kh, Vh, kbB, lane);
       asm volatile("" ::: "memory");
-      if ((kb + 1) * 32 + 31 >= a.n0) attn_block<D, true>(b1, qf, O, mrun, lrun, kb + 1, a.n0, a.Mc, 1, row, g, c);
-      else attn_block<D, false>(b1, qf, O, mrun, lrun, kb + 1, a.n0, a.Mc, 1, row, g, c);
+      if (kbA * 32 + 31 >= a.n0) attn_block<D, true>(b0, qf, O, mrun, lrun, kbA, a.n0, a.Mc, 1, row, g, c);
+      else attn_block<D, false>(b0, qf, O, mrun, lrun, kbA, a.n0, a.Mc, 1, row, g, c);
+      if (j + 1 < cnt) {
+        if (j + 2 < cnt) kv_load<D>(b0, Kh, Vh, kbB + NW, lane);
+        asm volatile("" ::: "memory");
+        if (kbB * 32 + 31 >= a.n0) attn_block<D, true>(b1, qf, O, mrun, lrun, kbB, a.n0, a.Mc, 1, row, g, c);
+        else attn_block<D, false>(b1, qf, O, mrun, lrun, kbB, a.n0, a.Mc, 1, row, g, c);
+      }
     }
   }
-  const float inv = 1.f / lrun;
+  // wavefronts 1.. of an item hand their (max, sum, O) to wavefront 0 through LDS
+  if (half > 0) {
+    sm[sub][half - 1][lane] = mrun;
+    sl[sub][half - 1][lane] = lrun;
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt) {
-    const f32x4 o = O[dt] * inv;
-    const int fo = head * D + dt * 16 + 4 * g;
-    const uint32_t lo = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
-    const uint32_t hi = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
-    *reinterpret_cast<uint64_t*>(a.out + xp_index(row, fo, a.MTc)) = (uint64_t)lo | ((uint64_t)hi << 32);
+    for (int dt = 0; dt < DT; ++dt) sO[sub][half - 1][dt][lane] = O[dt];
+  }
+  __syncthreads();
+  if (half == 0 && valid) {
+    float m = mrun;
+#pragma unroll
+    for (int w = 0; w < NW - 1; ++w) m = fmaxf(m, sm[sub][w][lane]);
+    const float f0 = __builtin_amdgcn_exp2f(mrun - m);
+    float fw[NW - 1];
+    float l = lrun * f0;
+#pragma unroll
+    for (int w = 0; w < NW - 1; ++w) {
+      fw[w] = __builtin_amdgcn_exp2f(sm[sub][w][lane] - m);
+      l += sl[sub][w][lane] * fw[w];
+    }
+    const float inv = 1.f / l;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      f32x4 o = O[dt] * f0;
+#pragma unroll
+      for (int w = 0; w < NW - 1; ++w) o += sO[sub][w][dt][lane] * fw[w];
+      o *= inv;
+      const int fo = head * D + dt * 16 + 4 * g;
+      const uint32_t lo = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
+      const uint32_t hi = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
+      *reinterpret_cast<uint64_t*>(a.out + xp_index(row, fo, a.MTc)) = (uint64_t)lo | ((uint64_t)hi << 32);
+    }
   }
 }
 
