@@ -130,7 +130,11 @@ class Context:
             lib().bd_destroy(self._h)
             self._h = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:       # interpreter shutdown: the module globals may already be gone
+            pass
 
     # -- weights ------------------------------------------------------------------------------------------
     def bd_load_weight(self, name: str, arr: np.ndarray, scales: Optional[np.ndarray] = None):
