@@ -79,10 +79,10 @@ int bd_load_weight(bd_ctx* ctx, const char* name, const void* host_ptr, size_t b
 
 /* Alg. 1 prefill: causal forward over the prompt = n_embed continuous embeddings (dev fp32
  * [n_embed, hidden], may be NULL when n_embed is 0) followed by n_ids token ids (dev int32).  Resets
- * the cache, fills it with the prompt's K/V, sets the carry from the last prompt row.  With bf16
- * weights, a prompt of at least 129 rows goes through large-M kernels in chunks of up to 1024 rows and only
- * the final norm + LM head of its last row through the decode path; shorter prompts and contexts with e4m3
- * weights are processed by the decode kernels in chunks of at most max_block rows. */
+ * the cache, fills it with the prompt's K/V, sets the carry from the last prompt row.  A prompt of at
+ * least 129 rows goes through large-M kernels in chunks of up to 1024 rows and only the final norm + LM
+ * head of its last row through the decode path; shorter prompts are processed by the decode kernels in
+ * chunks of at most max_block rows. */
 int bd_prefill(bd_ctx* ctx, const float* dev_embeds, int n_embed, const int32_t* dev_ids, int n_ids);
 
 /* One denoising step on the current block (Sec. 3.4; Alg. 1 draft step; "Decoding threshold").

@@ -441,10 +441,14 @@ int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t
     const u16* wl = c->pf_w + (size_t)l * c->pf_layer_elems;
     g.Kc = c->Kc + (size_t)l * c->kv_layer_elems;
     g.Vc = c->Vc + (size_t)l * c->kv_layer_elems;
-    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs);
+    // e4m3 weights: the norm gains go into the activation copy and the row scales onto the accumulators (as in decode)
+    const float* ws = c->fp8 ? c->wscale + (size_t)l * c->wscale_layer : nullptr;
+    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
+                       c->fp8 ? c->gains + (size_t)(2 * l) * c->H : nullptr);
     BD_TRY(check_launch());
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[0]); g.KS = ceil_div(c->H, 32);
     g.xin = reinterpret_cast<const bf16x8*>(c->pf_xb);
+    g.wscale = ws ? ws + c->wscale_off[0] : nullptr;
     BD_TRY((launch_pf_gemm<PH_QKV, 2, 2, 2>(c, g, c->NQKV)));
     {
       PfAttnArgs t{};
@@ -458,14 +462,18 @@ int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t
     }
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[1]); g.KS = ceil_div(c->QD, 32);
     g.xin = reinterpret_cast<const bf16x8*>(c->pf_ap);
+    g.wscale = ws ? ws + c->wscale_off[1] : nullptr;
     BD_TRY((launch_pf_gemm<PH_O, 2, 4, 2>(c, g, c->H)));
-    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs);
+    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
+                       c->fp8 ? c->gains + (size_t)(2 * l + 1) * c->H : nullptr);
     BD_TRY(check_launch());
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[2]); g.KS = ceil_div(c->H, 32);
     g.xin = reinterpret_cast<const bf16x8*>(c->pf_xb);
+    g.wscale = ws ? ws + c->wscale_off[2] : nullptr;
     BD_TRY((launch_pf_gemm<PH_GU, 4, 2, 4>(c, g, 2 * c->F)));
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[3]); g.KS = ceil_div(c->F, 32);
     g.xin = reinterpret_cast<const bf16x8*>(c->pf_act);
+    g.wscale = ws ? ws + c->wscale_off[3] : nullptr;
     BD_TRY((launch_pf_gemm<PH_DOWN, 2, 4, 2>(c, g, c->H)));
   }
   return BD_OK;
@@ -591,9 +599,10 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   A(c->spec_k, 4);
   A(c->quad_ids, Mp * 4);
   {
-    // Large-M prefill for bf16 contexts whose cache can hold a chunk of 128 rows plus the prompt's last rows.
+    // Large-M prefill for contexts whose cache can hold a chunk of 128 rows plus the prompt's last rows.  (e4m3
+    // decoder linears are widened into the bf16 copy, exactly; their row scales stay in the epilogue.)
     const char* e = getenv("BD_PREFILL");
-    c->pf_on = !c->fp8 && k.max_seq > kPfTokens && !(e != nullptr && strcmp(e, "chunked") == 0);
+    c->pf_on = k.max_seq > kPfTokens && !(e != nullptr && strcmp(e, "chunked") == 0);
     if (c->pf_on) {
       c->pf_rows = std::min(1024, (k.max_seq - 1) / kPfTokens * kPfTokens);
       const size_t R = (size_t)c->pf_rows;
@@ -692,6 +701,10 @@ int bd_load_weight(bd_ctx* c, const char* name, const void* host_ptr, size_t byt
                          ph, layer, row_base, row_map, c->D, reinterpret_cast<uint8_t*>(c->wstream));
       hipLaunchKernelGGL(scatter_scales_kernel, dim3(64), dim3(256), 0, c->stream, sc, rows, row_base, row_map, c->D,
                          c->wscale + (size_t)layer * c->wscale_layer + c->wscale_off[ph]);
+      if (c->pf_on)
+        hipLaunchKernelGGL(pack_tiles_kernel<uint8_t>, dim3(4096), dim3(256), 0, c->stream, (const uint8_t*)stage, rows, K,
+                           ceil_div(K, 32), row_base, row_map, c->D, (const float*)nullptr,
+                           c->pf_w + (size_t)layer * c->pf_layer_elems + c->pf_off[ph]);
       e = hipGetLastError();
       if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     }

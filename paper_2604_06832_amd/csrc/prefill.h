@@ -27,6 +27,7 @@ struct PfGemmArgs {
   int Mvalid;             // rows of the chunk; the rows that pad its last tile write no Q, K or V
   int RG, TG;             // workgroup grid: row groups x token groups
   const float* rs;        // [Mc] 1/rms of the rows of the residual stream (QKV, gate/up)
+  const float* wscale;    // e4m3 weights: one scale per phase row, applied to the accumulators; else nullptr
   const float2* rope;     // [Mc][D/2] (QKV)
   float* x;               // [Mc][H] residual stream, updated in place (O, down)
   u16* q;                 // [Mc][n_q][D] (QKV)
@@ -141,6 +142,7 @@ __global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 2 * TW * BKS 
       if (mt0 + wm * TW + j >= a.MTc) continue;
       const int token = (mt0 + wm * TW + j) * 16 + col;
       f32x4 v = acc[i][j];
+      if (a.wscale != nullptr) v *= *reinterpret_cast<const f32x4*>(a.wscale + r);
       if constexpr (PH == PH_QKV) {
         if (token >= a.Mvalid) continue;
         const int D = a.D, half = D >> 1;
@@ -191,7 +193,7 @@ template <int WN, int BKS, int TW> constexpr int pf_gemm_lds() { return 2 * (2 *
 // One workgroup per row: 1/rms of the fp32 residual row and its bf16 copy in packed order (the norm gain lives in
 // the weights, the factor is applied by the GEMM epilogue: same arithmetic as the decode path).
 __global__ __launch_bounds__(kPfThreads) void pf_norm_kernel(const float* __restrict__ x, int H, float eps, u16* __restrict__ xb,
-                                                             int MTc, float* __restrict__ rs) {
+                                                             int MTc, float* __restrict__ rs, const float* __restrict__ gain) {
   __shared__ float part[kPfThreads / 64];
   const int token = blockIdx.x;
   const float* row = x + (size_t)token * H;
@@ -199,7 +201,7 @@ __global__ __launch_bounds__(kPfThreads) void pf_norm_kernel(const float* __rest
   for (int c = threadIdx.x; c < H; c += kPfThreads) {
     const float v = row[c];
     ss += v * v;
-    xb[xp_index(token, c, MTc)] = f32_to_bf16_bits(v);
+    xb[xp_index(token, c, MTc)] = f32_to_bf16_bits(gain != nullptr ? v * gain[c] : v);
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
@@ -348,7 +350,8 @@ __global__ __launch_bounds__(kPfThreads, 2) void pf_attn_kernel(PfAttnArgs a) {
 }
 
 // One matrix into the tile-major fragment order of the prefill GEMMs (same row maps and column gains as the
-// weight stream of the decode kernels).
+// weight stream of the decode kernels).  One-byte sources are e4m3 codes: every code is a bf16 value, so the copy is
+// exact; its row scales and the norm gains stay outside (accumulator epilogue, activation copy).
 template <typename SrcT>
 __global__ void pack_tiles_kernel(const SrcT* __restrict__ src, int n_rows, int K, int KS, int row_base, int row_map, int D,
                                   const float* __restrict__ col_gain, u16* __restrict__ dst) {
@@ -374,6 +377,7 @@ __global__ void pack_tiles_kernel(const SrcT* __restrict__ src, int n_rows, int 
       if (k < K) {
         float f;
         if constexpr (sizeof(SrcT) == 4) f = ((const float*)src)[(size_t)rs * K + k];
+        else if constexpr (sizeof(SrcT) == 1) f = __builtin_amdgcn_cvt_f32_fp8((int)((const uint8_t*)src)[(size_t)rs * K + k], 0);
         else f = bf16_bits_to_f32(((const u16*)src)[(size_t)rs * K + k]);
         if (col_gain != nullptr) f *= col_gain[k];
         v = f32_to_bf16_bits(f);

@@ -587,6 +587,24 @@ def test_fp8_tiny_block_decode():
     p.close()
 
 
+@pytest.mark.parametrize("n_embed,n_ids", [(0, 129), (150, 150), (0, 400)])
+def test_fp8_large_m_prefill(n_embed, n_ids):
+    """Prompts of more than 128 rows on a context with e4m3 weights go through the large-M kernels (codes widened into
+    the tile-major bf16 copy, row scales on the accumulators, norm gains in the activation copy): cache, carry and a
+    decode step on top against the oracle."""
+    _say(f"tiny config, e4m3 weights, jittered gains, large-M prefill of {n_embed}+{n_ids} rows")
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 2, "fp8", norm_gain_jitter=0.1, threads=1)
+    emb, ids = inputs.make_prompt(shape, n_embed, n_ids, seed=106)
+    p = Pair(shape, w, max_seq=n_embed + n_ids + 64)
+    p.prefill(emb, ids)
+    p.check_carry(logit_err=0.05)
+    p.check_kv(0, n_embed + n_ids, frac=6e-2)
+    tok, msk = fresh_block(shape, 8)
+    p.denoise_step(tok, msk, 0.9, fixed_k=3, frac=FP8_LOGIT_TOL)
+    p.close()
+
+
 def test_fp8_whole_block_and_speculative_calls():
     """The calls that chain forwards on the device, on a context with e4m3 weights: a whole block per call equals the
     step-by-step loop bit for bit, a speculative iteration accepts between 1 and B tokens and leaves a valid carry, and
