@@ -167,10 +167,15 @@ int make_plan(bd_ctx* c) {
   // Gate/up rows dealt out per XCD so that the SwiGLU output never leaves the XCD that produced it: needs the K slices
   // of the down projection to coincide with XCDs (workgroup b holds K slice b mod ksplit and runs on XCD b mod xcds).
   P.xcd_gu = 0;
-  if (c->xcds > 0 && !fp8 && P.nwg % c->xcds == 0 && P.ph[PH_DOWN].ksplit == c->xcds && P.ph[PH_GU].ksplit == 1 &&
-      (P.ph[PH_GU].N / 16) % c->xcds == 0 && P.ph[PH_DOWN].KS % c->xcds == 0 &&
-      (P.ph[PH_GU].N / 2 / c->xcds) == (P.ph[PH_DOWN].KS / c->xcds) * 32)
+  // (F a whole number of K units, so that every K slice of the down projection is a whole number of gate/up tiles.)
+  if (c->xcds > 0 && P.nwg % c->xcds == 0 && P.ph[PH_DOWN].ksplit == c->xcds && P.ph[PH_GU].ksplit == 1 &&
+      c->F == P.ph[PH_DOWN].KS * 32 && P.ph[PH_DOWN].KS % P.ph[PH_DOWN].kgran == 0 &&
+      P.ph[PH_DOWN].KS / P.ph[PH_DOWN].kgran >= c->xcds) {
     P.xcd_gu = c->xcds;
+    int most = 0;
+    for (int g = 0; g < P.nwg; ++g) most = std::max(most, phase_tile0(P, PH_GU, g + 1) - phase_tile0(P, PH_GU, g));
+    P.ph[PH_GU].RW = 16 * most;
+  }
   long long mx = 0;
   for (int wg = 0; wg < P.nwg; ++wg)
     for (int w = 0; w < kWavesPerWG; ++w) {

@@ -58,6 +58,37 @@ struct MegaPlan {
                            // workgroups of XCD x (workgroup id mod xcd_gu) produce exactly the features that K slice x of
                            // the down projection (also held by the workgroups of XCD x) consumes
 };
+// Tiles of a phase's row groups.  With xcd_gu the gate/up tiles are first cut where the K slices of the down
+// projection are cut (a K unit of kgran k-steps = 4*kgran gate/up tiles), then each XCD's share is spread over its
+// workgroups; for slices of equal size that is the plain even spread.
+__host__ __device__ inline int gu_slice_tile0(const MegaPlan& P, int x) {
+  const PhasePlan& d = P.ph[PH_DOWN];
+  const int KU = (d.KS + d.kgran - 1) / d.kgran;
+  return min((int)((long long)KU * x / P.xcd_gu) * 4 * d.kgran, P.ph[PH_GU].N >> 4);
+}
+__host__ __device__ inline int phase_tile0(const MegaPlan& P, int p, int ng) {
+  const PhasePlan& ph = P.ph[p];
+  const int T = ph.N >> 4, G = P.nwg / ph.ksplit;
+  if (p == PH_GU && P.xcd_gu > 0) {
+    if (ng >= G) return T;
+    const int per = G / P.xcd_gu, x = ng / per;
+    const int b0 = gu_slice_tile0(P, x), b1 = gu_slice_tile0(P, x + 1);
+    return b0 + tile0_of_group(b1 - b0, per, ng % per);
+  }
+  return tile0_of_group(T, G, ng);
+}
+__host__ __device__ inline int phase_group_of_tile(const MegaPlan& P, int p, int tile) {
+  const PhasePlan& ph = P.ph[p];
+  const int T = ph.N >> 4, G = P.nwg / ph.ksplit;
+  if (p == PH_GU && P.xcd_gu > 0) {
+    const int per = G / P.xcd_gu;
+    int x = 0;
+    while (x + 1 < P.xcd_gu && gu_slice_tile0(P, x + 1) <= tile) ++x;
+    const int b0 = gu_slice_tile0(P, x), b1 = gu_slice_tile0(P, x + 1);
+    return x * per + group_of_tile(b1 - b0, per, tile - b0);
+  }
+  return group_of_tile(T, G, tile);
+}
 // Row group of workgroup `wg` in phase p, and the inverse.
 __host__ __device__ inline int row_group_of_wg(const MegaPlan& P, int p, int wg) {
   if (p == PH_GU && P.xcd_gu > 0) return (wg % P.xcd_gu) * (P.nwg / P.xcd_gu) + wg / P.xcd_gu;
@@ -83,8 +114,7 @@ __host__ __device__ inline WavePhase wave_phase(const MegaPlan& P, int p, int wg
   r.ng = ng;
   r.kg = wg % ph.ksplit;
   {
-    const int T = ph.N >> 4, G = P.nwg / ph.ksplit;
-    const int t0 = tile0_of_group(T, G, ng), t1 = tile0_of_group(T, G, ng + 1);
+    const int t0 = phase_tile0(P, p, ng), t1 = phase_tile0(P, p, ng + 1);
     r.row0 = t0 << 4;
     r.rows = (t1 - t0) << 4;
   }
@@ -1216,8 +1246,8 @@ __global__ void pack_stream_kernel(const SrcT* __restrict__ src, int n_rows, int
       r = row_base + rs;
     }
     const PhasePlan& pp = P.ph[ph];
-    const int ng = group_of_tile(pp.N >> 4, P.nwg / pp.ksplit, r >> 4);
-    const int lr = r - (tile0_of_group(pp.N >> 4, P.nwg / pp.ksplit, ng) << 4);
+    const int ng = phase_group_of_tile(P, ph, r >> 4);
+    const int lr = r - (phase_tile0(P, ph, ng) << 4);
     // which K group / wavefront holds k-step ks
     int kg = 0;
     while ((int)((long long)pp.KS * (kg + 1) / pp.ksplit) <= ks) ++kg;
@@ -1266,8 +1296,8 @@ __global__ void pack_stream_fp8_kernel(const uint8_t* __restrict__ src, int n_ro
     } else {
       r = row_base + rs;
     }
-    const int ng = group_of_tile(pp.N >> 4, P.nwg / pp.ksplit, r >> 4);
-    const int lr = r - (tile0_of_group(pp.N >> 4, P.nwg / pp.ksplit, ng) << 4);
+    const int ng = phase_group_of_tile(P, ph, r >> 4);
+    const int lr = r - (phase_tile0(P, ph, ng) << 4);
     const int ks = 2 * kp;
     int kg = 0;
     while ((int)((long long)KP * (kg + 1) / pp.ksplit) <= kp) ++kg;

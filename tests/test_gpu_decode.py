@@ -511,14 +511,15 @@ def test_3b_shaped_two_layers_block_sizes(B):
 
 
 
-def test_xcd_local_handover_is_bit_identical_to_the_chip_wide_one(monkeypatch):
+@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+def test_xcd_local_handover_is_bit_identical_to_the_chip_wide_one(monkeypatch, dtype):
     """The gate/up -> down hand-over inside each XCD moves the same values through other caches: logits, K/V and
     the revealed ids of a whole block must not change by a bit against the chip-wide path, and a forward repeated
     many times (alternating with forwards of another block size, which rewrite the same buffers) must repeat
     exactly.  A stale line anywhere in the hand-over would show up as a difference."""
-    _say("3B-shaped x2 layers: XCD-local vs chip-wide hand-over, B=32 and B=8 interleaved")
+    _say(f"3B-shaped x2 layers, {dtype} weights: XCD-local vs chip-wide hand-over, B=32 and B=8 interleaved")
     shape = _wide(2, vocab=8192)
-    w = inputs.make_weights(shape, 5, "bf16", threads=8)
+    w = inputs.make_weights(shape, 5, dtype, threads=8)
     emb, ids = inputs.make_prompt(shape, 96, 37, seed=11)
 
     def run(local):
@@ -526,7 +527,8 @@ def test_xcd_local_handover_is_bit_identical_to_the_chip_wide_one(monkeypatch):
             monkeypatch.delenv("BD_XCD_LOCAL", raising=False)
         else:
             monkeypatch.setenv("BD_XCD_LOCAL", "0")
-        ctx = binding.Context(shape, max_seq=133 + 64, max_block=32)
+        ctx = binding.Context(shape, max_seq=133 + 64, max_block=32,
+                              weight_dtype=binding.BD_FP8_E4M3 if dtype == "fp8" else binding.BD_BF16)
         ctx.load_model(w, as_bf16_bits=True)
         ctx.bd_debug_logits(True)
         ctx.bd_prefill(torch.from_numpy(emb).cuda(), torch.from_numpy(ids).cuda())
