@@ -84,6 +84,8 @@ struct bd_ctx {
   u16* pf_w = nullptr; size_t pf_layer_elems = 0; size_t pf_off[4] = {0, 0, 0, 0};
   float* pf_x = nullptr; u16* pf_xb = nullptr; float* pf_rs = nullptr; float2* pf_rope = nullptr;
   u16* pf_q = nullptr; u16* pf_ap = nullptr; u16* pf_act = nullptr;
+  bool pf_staged = false;
+  float* pf_part = nullptr;        // [kPfSplit][pf_rows][H] K splits of the down projection
   int32_t* spec_tokens = nullptr; uint8_t* spec_mask = nullptr; int32_t* spec_k = nullptr;   // bd_speculative_step, bd_decode_block, bd_quad_*
   int32_t* quad_ids = nullptr;     // rows of the quadratic forward
   DevState* st = nullptr;
@@ -167,11 +169,14 @@ int make_plan(bd_ctx* c) {
   // Gate/up rows dealt out per XCD so that the SwiGLU output never leaves the XCD that produced it: needs the K slices
   // of the down projection to coincide with XCDs (workgroup b holds K slice b mod ksplit and runs on XCD b mod xcds).
   P.xcd_gu = 0;
-  // (F a whole number of K units, so that every K slice of the down projection is a whole number of gate/up tiles.)
+  // (F a whole number of K units, so that every K slice of the down projection is a whole number of gate/up tiles;
+  // bf16: slices of equal size, so that the even spread of the tiles is also the spread per XCD.)
+  P.gu_cut = 0;
   if (c->xcds > 0 && P.nwg % c->xcds == 0 && P.ph[PH_DOWN].ksplit == c->xcds && P.ph[PH_GU].ksplit == 1 &&
       c->F == P.ph[PH_DOWN].KS * 32 && P.ph[PH_DOWN].KS % P.ph[PH_DOWN].kgran == 0 &&
-      P.ph[PH_DOWN].KS / P.ph[PH_DOWN].kgran >= c->xcds) {
+      P.ph[PH_DOWN].KS / P.ph[PH_DOWN].kgran >= c->xcds && (fp8 || P.ph[PH_DOWN].KS % c->xcds == 0)) {
     P.xcd_gu = c->xcds;
+    P.gu_cut = fp8 ? 1 : 0;
     int most = 0;
     for (int g = 0; g < P.nwg; ++g) most = std::max(most, phase_tile0(P, PH_GU, g + 1) - phase_tile0(P, PH_GU, g));
     P.ph[PH_GU].RW = 16 * most;
@@ -423,6 +428,26 @@ int launch_pf_gemm(bd_ctx* c, PfGemmArgs a, int n_rows) {
   return check_launch();
 }
 
+template <int PH, int WN, int BKS, int TW, int NST, int OCC>
+int launch_pf_gemm_direct(bd_ctx* c, PfGemmArgs a, int n_rows) {
+  static bool attr_set = false;
+  constexpr int lds = pf_gemm_direct_lds<WN, BKS, TW, NST>();
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_direct_kernel<PH, WN, BKS, TW, NST, OCC>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    attr_set = true;
+  }
+  static_assert(OCC * lds <= 160 * 1024, "workgroups per CU bounded by LDS");
+  if (a.KS % BKS != 0) return BD_E_ARG;
+  a.NT = n_rows / 16;
+  a.RG = ceil_div(a.NT, 2 * WN);
+  a.TG = ceil_div(a.MTc, 2 * TW);
+  if (a.SK < 1 || (a.KS / BKS) % a.SK != 0) return BD_E_ARG;
+  const int grid = ceil_div(a.RG, 8) * 8 * a.TG * a.SK;
+  hipLaunchKernelGGL((pf_gemm_direct_kernel<PH, WN, BKS, TW, NST, OCC>), dim3(grid), dim3(kPfThreads), lds, c->stream, a);
+  return check_launch();
+}
+
 // One chunk of `rows` prompt rows starting at prompt row `off` = cache position c->n: all layers, K/V into the cache,
 // no LM head.  The kernels work on whole tiles of 16 rows: the rows that pad the last tile are zero on entry, take part
 // in every product and write nothing to the cache.  The device-side length is advanced by the caller.
@@ -442,6 +467,8 @@ int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t
   PfGemmArgs g{};
   g.MTc = MTc; g.Mvalid = rows; g.rs = c->pf_rs; g.rope = c->pf_rope; g.x = c->pf_x; g.q = c->pf_q; g.max_kb = c->max_kb; g.n0 = c->n;
   g.act = c->pf_act; g.H = c->H; g.QD = c->QD; g.KVD = c->KVD; g.D = c->D; g.n_q = c->cfg.n_q_heads;
+  g.SK = 1;
+  int parts = 0;                                   // K splits of the last down projection still to be added to pf_x
   for (int l = 0; l < c->L; ++l) {
     const u16* wl = c->pf_w + (size_t)l * c->pf_layer_elems;
     g.Kc = c->Kc + (size_t)l * c->kv_layer_elems;
@@ -449,12 +476,15 @@ int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t
     // e4m3 weights: the norm gains go into the activation copy and the row scales onto the accumulators (as in decode)
     const float* ws = c->fp8 ? c->wscale + (size_t)l * c->wscale_layer : nullptr;
     hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
-                       c->fp8 ? c->gains + (size_t)(2 * l) * c->H : nullptr);
+                       c->fp8 ? c->gains + (size_t)(2 * l) * c->H : nullptr, c->pf_part, parts);
+    parts = 0;
     BD_TRY(check_launch());
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[0]); g.KS = ceil_div(c->H, 32);
     g.xin = reinterpret_cast<const bf16x8*>(c->pf_xb);
     g.wscale = ws ? ws + c->wscale_off[0] : nullptr;
-    BD_TRY((launch_pf_gemm<PH_QKV, 2, 2, 2>(c, g, c->NQKV)));
+    // (every phase: the direct-to-LDS kernel when K is a whole number of stages, else the register-staged one)
+    if (!c->pf_staged && g.KS % 2 == 0) BD_TRY((launch_pf_gemm_direct<PH_QKV, 2, 2, 2, 2, 4>(c, g, c->NQKV)));
+    else BD_TRY((launch_pf_gemm<PH_QKV, 2, 2, 2>(c, g, c->NQKV)));
     {
       PfAttnArgs t{};
       t.q = c->pf_q; t.Kc = g.Kc; t.Vc = g.Vc; t.max_kb = c->max_kb; t.n0 = c->n; t.Mc = mc; t.n_q = c->cfg.n_q_heads;
@@ -468,18 +498,35 @@ int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[1]); g.KS = ceil_div(c->QD, 32);
     g.xin = reinterpret_cast<const bf16x8*>(c->pf_ap);
     g.wscale = ws ? ws + c->wscale_off[1] : nullptr;
-    BD_TRY((launch_pf_gemm<PH_O, 2, 4, 2>(c, g, c->H)));
+    if (!c->pf_staged && g.KS % 4 == 0) BD_TRY((launch_pf_gemm_direct<PH_O, 2, 4, 2, 2, 2>(c, g, c->H)));
+    else BD_TRY((launch_pf_gemm<PH_O, 2, 4, 2>(c, g, c->H)));
     hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
-                       c->fp8 ? c->gains + (size_t)(2 * l + 1) * c->H : nullptr);
+                       c->fp8 ? c->gains + (size_t)(2 * l + 1) * c->H : nullptr, (const float*)nullptr, 0);
     BD_TRY(check_launch());
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[2]); g.KS = ceil_div(c->H, 32);
     g.xin = reinterpret_cast<const bf16x8*>(c->pf_xb);
     g.wscale = ws ? ws + c->wscale_off[2] : nullptr;
-    BD_TRY((launch_pf_gemm<PH_GU, 4, 2, 4>(c, g, 2 * c->F)));
+    // gate/up: 110 us against 136 us of the register-staged kernel for the 3B shape (the narrower phases gain 1-2 us)
+    if (!c->pf_staged && g.KS % 2 == 0) BD_TRY((launch_pf_gemm_direct<PH_GU, 4, 2, 4, 2, 2>(c, g, 2 * c->F)));
+    else BD_TRY((launch_pf_gemm<PH_GU, 4, 2, 4>(c, g, 2 * c->F)));
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[3]); g.KS = ceil_div(c->F, 32);
     g.xin = reinterpret_cast<const bf16x8*>(c->pf_act);
     g.wscale = ws ? ws + c->wscale_off[3] : nullptr;
-    BD_TRY((launch_pf_gemm<PH_DOWN, 2, 4, 2>(c, g, c->H)));
+    // down: K split four ways over workgroups with 128 x 128 tiles when K divides; the next norm adds the splits
+    if (!c->pf_staged && g.KS % (2 * kPfSplit) == 0) {
+      g.SK = kPfSplit; g.part = c->pf_part;
+      BD_TRY((launch_pf_gemm_direct<PH_DOWN, 4, 2, 4, 2, 2>(c, g, c->H)));
+      g.SK = 1; g.part = nullptr;
+      parts = kPfSplit;
+    } else {
+      BD_TRY((launch_pf_gemm<PH_DOWN, 2, 4, 2>(c, g, c->H)));
+    }
+  }
+  if (parts > 0) {
+    // the last layer's splits: the same kernel completes the residual stream (its other outputs are not used)
+    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
+                       (const float*)nullptr, c->pf_part, parts);
+    BD_TRY(check_launch());
   }
   return BD_OK;
 }
@@ -608,6 +655,7 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
     // decoder linears are widened into the bf16 copy, exactly; their row scales stay in the epilogue.)
     const char* e = getenv("BD_PREFILL");
     c->pf_on = k.max_seq > kPfTokens && !(e != nullptr && strcmp(e, "chunked") == 0);
+    c->pf_staged = e != nullptr && strcmp(e, "staged") == 0;   // register-staged GEMMs only (else: the fallback for K tails)
     if (c->pf_on) {
       c->pf_rows = std::min(1024, (k.max_seq - 1) / kPfTokens * kPfTokens);
       const size_t R = (size_t)c->pf_rows;
@@ -624,6 +672,7 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
       A(c->pf_q, R * c->QD * 2);
       A(c->pf_ap, R * (size_t)ceil_div(c->QD, 32) * 32 * 2);
       A(c->pf_act, R * (size_t)ceil_div(c->F, 32) * 32 * 2);
+      A(c->pf_part, (size_t)kPfSplit * R * c->H * 4);
     }
   }
   A(c->st, sizeof(DevState));

@@ -57,30 +57,39 @@ struct MegaPlan {
   int xcd_gu;              // > 0: number of XCDs; the row groups of the gate/up phase are dealt out so that the
                            // workgroups of XCD x (workgroup id mod xcd_gu) produce exactly the features that K slice x of
                            // the down projection (also held by the workgroups of XCD x) consumes
+  int gu_cut;              // 1: K slices of unequal size (e4m3 contexts), see phase_tile0_t
 };
-// Tiles of a phase's row groups.  With xcd_gu the gate/up tiles are first cut where the K slices of the down
-// projection are cut (a K unit of kgran k-steps = 4*kgran gate/up tiles), then each XCD's share is spread over its
-// workgroups; for slices of equal size that is the plain even spread.
+// Tiles of a phase's row groups.  With xcd_gu the gate/up tiles belong to the XCD whose K slice of the down
+// projection they feed.  For slices of equal size (bf16 weights: required for xcd_gu) that is the plain even
+// spread; with e4m3 weights the slices are whole units of two k-steps and differ by one unit, so the gate/up tiles
+// are first cut where the slices are cut (a K unit of kgran k-steps = 4*kgran tiles) and each XCD's share is spread
+// over its workgroups (gu_cut).  CUT is a compile-time switch so that the bf16 kernels carry none of this.
 __host__ __device__ inline int gu_slice_tile0(const MegaPlan& P, int x) {
   const PhasePlan& d = P.ph[PH_DOWN];
   const int KU = (d.KS + d.kgran - 1) / d.kgran;
   return min((int)((long long)KU * x / P.xcd_gu) * 4 * d.kgran, P.ph[PH_GU].N >> 4);
 }
-__host__ __device__ inline int phase_tile0(const MegaPlan& P, int p, int ng) {
+template <bool CUT>
+__host__ __device__ inline int phase_tile0_t(const MegaPlan& P, int p, int ng) {
   const PhasePlan& ph = P.ph[p];
   const int T = ph.N >> 4, G = P.nwg / ph.ksplit;
-  if (p == PH_GU && P.xcd_gu > 0) {
-    if (ng >= G) return T;
-    const int per = G / P.xcd_gu, x = ng / per;
-    const int b0 = gu_slice_tile0(P, x), b1 = gu_slice_tile0(P, x + 1);
-    return b0 + tile0_of_group(b1 - b0, per, ng % per);
+  if constexpr (CUT) {
+    if (p == PH_GU && P.gu_cut) {
+      if (ng >= G) return T;
+      const int per = G / P.xcd_gu, x = ng / per;
+      const int b0 = gu_slice_tile0(P, x), b1 = gu_slice_tile0(P, x + 1);
+      return b0 + tile0_of_group(b1 - b0, per, ng % per);
+    }
   }
   return tile0_of_group(T, G, ng);
+}
+__host__ __device__ inline int phase_tile0(const MegaPlan& P, int p, int ng) {
+  return P.gu_cut ? phase_tile0_t<true>(P, p, ng) : phase_tile0_t<false>(P, p, ng);
 }
 __host__ __device__ inline int phase_group_of_tile(const MegaPlan& P, int p, int tile) {
   const PhasePlan& ph = P.ph[p];
   const int T = ph.N >> 4, G = P.nwg / ph.ksplit;
-  if (p == PH_GU && P.xcd_gu > 0) {
+  if (p == PH_GU && P.gu_cut) {
     const int per = G / P.xcd_gu;
     int x = 0;
     while (x + 1 < P.xcd_gu && gu_slice_tile0(P, x + 1) <= tile) ++x;
@@ -107,14 +116,15 @@ __host__ __device__ inline int phase_tile_slots(const MegaPlan& P, int p) {
   return (P.nwg / P.ph[p].ksplit) * phase_tpg(P.ph[p]);
 }
 
-__host__ __device__ inline WavePhase wave_phase(const MegaPlan& P, int p, int wg, int w) {
+template <bool CUT>
+__host__ __device__ inline WavePhase wave_phase_t(const MegaPlan& P, int p, int wg, int w) {
   const PhasePlan& ph = P.ph[p];
   WavePhase r;
   const int ng = row_group_of_wg(P, p, wg);
   r.ng = ng;
   r.kg = wg % ph.ksplit;
   {
-    const int t0 = phase_tile0(P, p, ng), t1 = phase_tile0(P, p, ng + 1);
+    const int t0 = phase_tile0_t<CUT>(P, p, ng), t1 = phase_tile0_t<CUT>(P, p, ng + 1);
     r.row0 = t0 << 4;
     r.rows = (t1 - t0) << 4;
   }
@@ -127,14 +137,21 @@ __host__ __device__ inline WavePhase wave_phase(const MegaPlan& P, int p, int wg
   r.KW = (u1 - u0) * ph.kgran;
   return r;
 }
+__host__ __device__ inline WavePhase wave_phase(const MegaPlan& P, int p, int wg, int w) {
+  return P.gu_cut ? wave_phase_t<true>(P, p, wg, w) : wave_phase_t<false>(P, p, wg, w);
+}
 // 16-byte units one wavefront streams in a phase: per row and k-step 32 weights of wbytes each
 __host__ __device__ inline long long wave_phase_units(const PhasePlan& ph, const WavePhase& wp) {
   return (long long)wp.rows * 2 * ph.wbytes * wp.KW;
 }
-__host__ __device__ inline long long wave_layer_units(const MegaPlan& P, int wg, int w) {
+template <bool CUT>
+__host__ __device__ inline long long wave_layer_units_t(const MegaPlan& P, int wg, int w) {
   long long s = 0;
-  for (int p = 0; p < PH_LM; ++p) s += wave_phase_units(P.ph[p], wave_phase(P, p, wg, w));
+  for (int p = 0; p < PH_LM; ++p) s += wave_phase_units(P.ph[p], wave_phase_t<CUT>(P, p, wg, w));
   return s;
+}
+__host__ __device__ inline long long wave_layer_units(const MegaPlan& P, int wg, int w) {
+  return P.gu_cut ? wave_layer_units_t<true>(P, wg, w) : wave_layer_units_t<false>(P, wg, w);
 }
 // Position (16-byte units from the wavefront's phase start) of row `lr` (local to the row range),
 // k-step `ksl` (local to the wavefront), k-quarter kq: tiles of 16 rows go in chunks of two.
@@ -302,7 +319,8 @@ struct Cursor {
     ChunkRef r;
     r.off = 0; r.KW = 0; r.R0 = 0; r.R1 = 0;
     while (p != PH_END) {
-      const WavePhase wp = wave_phase(P, p, wg, w);
+      // (the cursor serves the bf16 layers kernel and the LM head: neither sees cut gate/up tiles)
+      const WavePhase wp = wave_phase_t<false>(P, p, wg, w);
       const int n_tiles = (wp.rows + 15) >> 4;
       const int n_chunks = (n_tiles + 1) >> 1;
       if (c < n_chunks && wp.KW > 0) {
@@ -617,7 +635,7 @@ __device__ inline void gemm_phase(const MegaArgs& a, const PhaseCtx& pc, bf16x8 
   constexpr int XH = (MT <= 2) ? kMaxKW : 4;          // k-steps of activation fragments staged at a time
   bf16x8* xs = pc.xstage + (size_t)wave * (XH * MT * 64);
   const MegaPlan& P = a.P;
-  const WavePhase wp = wave_phase(P, PH, blockIdx.x, wave);
+  const WavePhase wp = wave_phase_t<false>(P, PH, blockIdx.x, wave);
   const int n_tiles = (wp.rows + 15) >> 4;
   const int n_chunks = (n_tiles + 1) >> 1;
   float rmax[MT], rsum[MT];

@@ -18,6 +18,7 @@ namespace bd {
 
 constexpr int kPfTokens = 128;        // tokens per workgroup tile (8 token tiles of 16)
 constexpr int kPfThreads = 256;       // four wavefronts, 2 (rows) x 2 (tokens)
+constexpr int kPfSplit = 4;           // K splits of the down projection over workgroups
 
 struct PfGemmArgs {
   const bf16x8* w;        // fragments of this layer's phase, tile-major
@@ -30,12 +31,80 @@ struct PfGemmArgs {
   const float* wscale;    // e4m3 weights: one scale per phase row, applied to the accumulators; else nullptr
   const float2* rope;     // [Mc][D/2] (QKV)
   float* x;               // [Mc][H] residual stream, updated in place (O, down)
+  int SK;                 // K split over workgroups (direct kernel; 1 = none)
+  float* part;            // SK > 1: [SK][Mc][H] partial products of the splits, added to x by the next norm kernel
   u16* q;                 // [Mc][n_q][D] (QKV)
   u16* Kc; u16* Vc;       // this layer's packed cache (QKV)
   int max_kb, n0;         // key blocks per kv head; position of the chunk's first row
   u16* act;               // packed SwiGLU output (gate/up)
   int H, QD, KVD, D, n_q;
 };
+
+// Epilogue of both GEMM kernels: lane (token column col, row quad g) of a 16 x 16 accumulator tile holds rows
+// r .. r+3 of one token.
+template <int PH, int WN, int TW>
+__device__ inline void pf_epilogue(const PfGemmArgs& a, const f32x4 (&acc)[WN][TW], int T0, int mt0, int wn, int wm, int lane,
+                                   int kz = 0) {
+  const int col = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < WN; ++i) {
+    const int T = T0 + wn * WN + i;
+    if (T >= a.NT) continue;
+    const int r = T * 16 + 4 * g;
+#pragma unroll
+    for (int j = 0; j < TW; ++j) {
+      if (mt0 + wm * TW + j >= a.MTc) continue;
+      const int token = (mt0 + wm * TW + j) * 16 + col;
+      f32x4 v = acc[i][j];
+      if (a.wscale != nullptr) v *= *reinterpret_cast<const f32x4*>(a.wscale + r);
+      if constexpr (PH == PH_QKV) {
+        if (token >= a.Mvalid) continue;
+        const int D = a.D, half = D >> 1;
+        v *= a.rs[token];
+        const int key = a.n0 + token;
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+          const int rp = r + 2 * pr;
+          if (rp < a.QD + a.KVD) {
+            // rotary pair: phase rows (2i, 2i+1) of a head hold dims (i, i + D/2)
+            const int dp = rp % D;
+            const float2 cs = a.rope[(size_t)token * half + (dp >> 1)];
+            const float lo = v[2 * pr] * cs.x - v[2 * pr + 1] * cs.y;
+            const float hi = v[2 * pr + 1] * cs.x + v[2 * pr] * cs.y;
+            const uint32_t pk = (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+            u16* dst;
+            if (rp < a.QD) {
+              dst = a.q + ((size_t)token * a.n_q + rp / D) * D + dp;
+            } else {
+              const int rk = rp - a.QD;
+              dst = a.Kc + (size_t)(rk / D) * a.max_kb * 32 * D + kp_index(key, dp, D / 32);
+            }
+            *reinterpret_cast<uint32_t*>(dst) = pk;
+          } else {
+            const int rv = rp - a.QD - a.KVD;
+            u16* vc = a.Vc + (size_t)(rv / D) * a.max_kb * 32 * D;
+            vc[vp_index(key, rv % D, D / 16)] = f32_to_bf16_bits(v[2 * pr]);
+            vc[vp_index(key, (rv + 1) % D, D / 16)] = f32_to_bf16_bits(v[2 * pr + 1]);
+          }
+        }
+      } else if constexpr (PH == PH_O || PH == PH_DOWN) {
+        if (a.part != nullptr) {
+          *reinterpret_cast<f32x4*>(a.part + ((size_t)kz * a.MTc * 16 + token) * a.H + r) = v;
+        } else {
+          f32x4* xp = reinterpret_cast<f32x4*>(a.x + (size_t)token * a.H + r);
+          *xp = *xp + v;
+        }
+      } else {
+        v *= a.rs[token];
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+          const float gt = v[2 * pr], up = v[2 * pr + 1];
+          a.act[xp_index(token, (r >> 1) + pr, a.MTc)] = f32_to_bf16_bits(gt / (1.f + __expf(-gt)) * up);
+        }
+      }
+    }
+  }
+}
 
 // C[rows of the phase][tokens] = W * X^T, fp32 accumulation, epilogue per phase.  A workgroup computes
 // (2*WN*16) rows x (2*TW*16) tokens; each wavefront WN x TW tiles of 16 x 16.  K advances by BKS k-steps per iteration
@@ -130,76 +199,108 @@ __global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 2 * TW * BKS 
     __syncthreads();
   }
 
-  // ---- epilogue: lane (token column col, row quad g) holds rows r .. r+3 of one token ----
-  const int col = lane & 15, g = lane >> 4;
-#pragma unroll
-  for (int i = 0; i < WN; ++i) {
-    const int T = T0 + wn * WN + i;
-    if (T >= a.NT) continue;
-    const int r = T * 16 + 4 * g;
-#pragma unroll
-    for (int j = 0; j < TW; ++j) {
-      if (mt0 + wm * TW + j >= a.MTc) continue;
-      const int token = (mt0 + wm * TW + j) * 16 + col;
-      f32x4 v = acc[i][j];
-      if (a.wscale != nullptr) v *= *reinterpret_cast<const f32x4*>(a.wscale + r);
-      if constexpr (PH == PH_QKV) {
-        if (token >= a.Mvalid) continue;
-        const int D = a.D, half = D >> 1;
-        v *= a.rs[token];
-        const int key = a.n0 + token;
-#pragma unroll
-        for (int pr = 0; pr < 2; ++pr) {
-          const int rp = r + 2 * pr;
-          if (rp < a.QD + a.KVD) {
-            // rotary pair: phase rows (2i, 2i+1) of a head hold dims (i, i + D/2)
-            const int dp = rp % D;
-            const float2 cs = a.rope[(size_t)token * half + (dp >> 1)];
-            const float lo = v[2 * pr] * cs.x - v[2 * pr + 1] * cs.y;
-            const float hi = v[2 * pr + 1] * cs.x + v[2 * pr] * cs.y;
-            const uint32_t pk = (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
-            u16* dst;
-            if (rp < a.QD) {
-              dst = a.q + ((size_t)token * a.n_q + rp / D) * D + dp;
-            } else {
-              const int rk = rp - a.QD;
-              dst = a.Kc + (size_t)(rk / D) * a.max_kb * 32 * D + kp_index(key, dp, D / 32);
-            }
-            *reinterpret_cast<uint32_t*>(dst) = pk;
-          } else {
-            const int rv = rp - a.QD - a.KVD;
-            u16* vc = a.Vc + (size_t)(rv / D) * a.max_kb * 32 * D;
-            vc[vp_index(key, rv % D, D / 16)] = f32_to_bf16_bits(v[2 * pr]);
-            vc[vp_index(key, (rv + 1) % D, D / 16)] = f32_to_bf16_bits(v[2 * pr + 1]);
-          }
-        }
-      } else if constexpr (PH == PH_O || PH == PH_DOWN) {
-        f32x4* xp = reinterpret_cast<f32x4*>(a.x + (size_t)token * a.H + r);
-        *xp = *xp + v;
-      } else {
-        v *= a.rs[token];
-#pragma unroll
-        for (int pr = 0; pr < 2; ++pr) {
-          const float gt = v[2 * pr], up = v[2 * pr + 1];
-          a.act[xp_index(token, (r >> 1) + pr, a.MTc)] = f32_to_bf16_bits(gt / (1.f + __expf(-gt)) * up);
-        }
-      }
-    }
-  }
+  pf_epilogue<PH, WN, TW>(a, acc, T0, mt0, wn, wm, lane);
 }
+
+// The same product with the operands loaded straight into LDS (no registers in between) through NST stages: the loads
+// of iteration i + NST - 1 are issued, one 1-KiB fragment per instruction and wavefront, before the MFMAs of
+// iteration i, and one barrier per iteration both publishes the stage that has landed and frees the one just read.
+// (Measured on the gate/up shape: two stages with two workgroups per CU beat deeper pipelines with one.)  Needs KS to
+// be a multiple of BKS (no K tail); tiles past the end of the rows or tokens re-read the last valid tile and are
+// dropped by the epilogue.  With SK > 1 the workgroups of an output tile split K among them and each leaves its
+// product in its own slice of `part` (O and down phases: a 128 x 128 tile then fetches half the operand bytes per
+// MFMA of the 64 x 64 tile that the same number of workgroups would otherwise need).
+template <int PH, int WN, int BKS, int TW, int NST, int OCC>
+__global__ __launch_bounds__(kPfThreads, OCC) void pf_gemm_direct_kernel(PfGemmArgs a) {
+  constexpr int AT = 2 * WN, BT = 2 * TW;
+  constexpr int AF = AT * BKS, BF = BT * BKS;                       // fragments per stage
+  constexpr int PER = (AF + BF) / 4;                                // loads per wavefront and stage
+  static_assert(AF % 4 == 0 && BF % 4 == 0, "fragments are dealt to four wavefronts");
+  static_assert((NST - 2) * PER <= 63, "outstanding loads must fit the counter");
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+  const int per = a.TG * a.SK;                                      // workgroups of a row group: token groups x K splits
+  const int rg = (slot / per) * 8 + xcd, tg = (slot % per) / a.SK, kz = slot % a.SK;
+  if (rg >= a.RG) return;
+  const int T0 = rg * AT, mt0 = tg * BT;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wn = wave >> 1, wm = wave & 1;
+  const rsrc_t wr = make_rsrc(a.w, (unsigned)((size_t)a.NT * a.KS * 1024));
+  const rsrc_t xr = make_rsrc(a.xin, (unsigned)((size_t)a.KS * a.MTc * 1024));
+
+  const int n_it = a.KS / BKS / a.SK, it0 = kz * n_it;             // this workgroup's share of K
+  auto issue = [&](int it) {
+    char* base = lds + (it % NST) * ((AF + BF) * 1024);
+    const int ks0 = (it0 + it) * BKS;
+#pragma unroll
+    for (int i = 0; i < AF / 4; ++i) {
+      const int f = i * 4 + wave, tile = f / BKS, ksl = f % BKS;
+      const int off = ((min(T0 + tile, a.NT - 1) * a.KS) + ks0 + ksl) * 1024 + lane * 16;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (lds_void_t*)(base + f * 1024), 16, off, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < BF / 4; ++i) {
+      const int f = i * 4 + wave, ksl = f / BT, tile = f % BT;
+      const int off = ((ks0 + ksl) * a.MTc + min(mt0 + tile, a.MTc - 1)) * 1024 + lane * 16;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (lds_void_t*)(base + (AF + f) * 1024), 16, off, 0, 0, 0);
+    }
+  };
+
+  f32x4 acc[WN][TW];
+#pragma unroll
+  for (int i = 0; i < WN; ++i)
+#pragma unroll
+    for (int j = 0; j < TW; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  auto compute = [&](int stage) {
+    const bf16x8* A = reinterpret_cast<const bf16x8*>(lds + stage * ((AF + BF) * 1024));
+    const bf16x8* Bm = A + AF * 64;
+#pragma unroll
+    for (int ksl = 0; ksl < BKS; ++ksl) {
+      bf16x8 af[WN], bfr[TW];
+#pragma unroll
+      for (int i = 0; i < WN; ++i) af[i] = A[((wn * WN + i) * BKS + ksl) * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < TW; ++j) bfr[j] = Bm[(ksl * BT + wm * TW + j) * 64 + lane];
+#pragma unroll
+      for (int i = 0; i < WN; ++i)
+#pragma unroll
+        for (int j = 0; j < TW; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  for (int it = 0; it < NST - 1 && it < n_it; ++it) issue(it);
+  for (int it = 0; it < n_it; ++it) {
+    // the loads of iteration `it` are this wavefront's oldest: in the steady state NST - 2 later stages may stay in flight
+    if (it + NST - 2 < n_it) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NST - 2) * PER) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (it + NST - 1 < n_it) issue(it + NST - 1);
+    compute(it % NST);
+  }
+  pf_epilogue<PH, WN, TW>(a, acc, T0, mt0, wn, wm, lane, kz);
+}
+
+template <int WN, int BKS, int TW, int NST> constexpr int pf_gemm_direct_lds() { return NST * (2 * WN * BKS + 2 * TW * BKS) * 1024; }
 
 template <int WN, int BKS, int TW> constexpr int pf_gemm_lds() { return 2 * (2 * WN * BKS * 64 + 2 * TW * BKS * 64) * 16; }
 
-// One workgroup per row: 1/rms of the fp32 residual row and its bf16 copy in packed order (the norm gain lives in
+// One workgroup per row: 1/rms of the fp32 residual row and its bf16 copy in packed order; completes the residual
+// row first when the projection before it left its product in K splits (the norm gain lives in
 // the weights, the factor is applied by the GEMM epilogue: same arithmetic as the decode path).
-__global__ __launch_bounds__(kPfThreads) void pf_norm_kernel(const float* __restrict__ x, int H, float eps, u16* __restrict__ xb,
-                                                             int MTc, float* __restrict__ rs, const float* __restrict__ gain) {
+__global__ __launch_bounds__(kPfThreads) void pf_norm_kernel(float* __restrict__ x, int H, float eps, u16* __restrict__ xb,
+                                                             int MTc, float* __restrict__ rs, const float* __restrict__ gain,
+                                                             const float* __restrict__ kparts, int n_kparts) {
   __shared__ float part[kPfThreads / 64];
   const int token = blockIdx.x;
-  const float* row = x + (size_t)token * H;
+  float* row = x + (size_t)token * H;
   float ss = 0.f;
   for (int c = threadIdx.x; c < H; c += kPfThreads) {
-    const float v = row[c];
+    float v = row[c];
+    if (n_kparts > 0) {
+      // the K splits of the projection before this norm, added in split order
+      for (int p = 0; p < n_kparts; ++p) v += kparts[((size_t)p * MTc * 16 + token) * H + c];
+      row[c] = v;
+    }
     ss += v * v;
     xb[xp_index(token, c, MTc)] = f32_to_bf16_bits(gain != nullptr ? v * gain[c] : v);
   }

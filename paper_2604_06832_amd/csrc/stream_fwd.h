@@ -100,13 +100,15 @@ __device__ inline void cbar(FwdSync& sy, int lane, DevState* st) {
 // ---- producer ----------------------------------------------------------------------------------------------
 // Row ranges are whole tiles, so a consumer's stream is a plain sequence of 1-KiB fragments: fragment q of the
 // forward sits at byte q*1024 of the wavefront's stream, lane l's 16 bytes at l*16.
+template <bool CUT>
 __device__ inline unsigned stream_fragments(const MegaPlan& P, int cw) {
-  return (unsigned)((long long)P.L * wave_layer_units(P, blockIdx.x, cw) / 64);
+  return (unsigned)((long long)P.L * wave_layer_units_t<CUT>(P, blockIdx.x, cw) / 64);
 }
 
+template <bool CUT>
 __device__ inline void producer_loop(const MegaArgs& a, int cw, char* ring, unsigned sync_base, int lane) {
   const MegaPlan& P = a.P;
-  const unsigned total = stream_fragments(P, cw);
+  const unsigned total = stream_fragments<CUT>(P, cw);
   const rsrc_t wr = make_rsrc(a.wstream + (size_t)(blockIdx.x * kWavesPerWG + cw) * P.wave_stride, total * 1024u);
   const unsigned landed_addr = sync_base + (SY_LANDED + cw) * 4;
   const unsigned consumed_addr = sync_base + (SY_CONSUMED + cw) * 4;
@@ -327,7 +329,7 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
   asm volatile("" : "+v"(lane));
   const MegaPlan& P = a.P;
   PhaseCtx& pc = fc.pc;
-  const WavePhase wp = wave_phase(P, PH, blockIdx.x, wave);
+  const WavePhase wp = wave_phase_t<FP8>(P, PH, blockIdx.x, wave);
   const int n_tiles = (wp.rows + 15) >> 4;
   const int n_chunks = (n_tiles + 1) >> 1;
   float rmax[MT], rsum[MT];
@@ -990,7 +992,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
 
   if (wave >= kWavesPerWG) {
     const int cw = wave - kWavesPerWG;
-    producer_loop(a, cw, lds + cw * kSlots * 1024, sync_base, lane);
+    producer_loop<FP8>(a, cw, lds + cw * kSlots * 1024, sync_base, lane);
     return;
   }
 

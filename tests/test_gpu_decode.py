@@ -690,7 +690,11 @@ def test_headline_config_first_block_full_depth():
     _say("uploading + oracle prefill of 1024 tokens")
     p = Pair(shape, w, max_seq=1024 + 256 + 32, oracle_dtype=np.float32)
     p.prefill(emb, ids, oracle_chunk=256)
-    p.check_carry()
+    # the last prompt row's logits (row 0 of the LM-head pass that ends a large-M prefill) against the oracle's, to the
+    # bar of every other logits row; the carry's probability is then held to the bound that this measured error implies
+    glog = p.ctx.bd_read_logits(1).cpu().numpy()[0]
+    assert_logits_close(glog, p.o.carry, what="carry logits")
+    p.check_carry(logit_err=float(np.abs(glog.astype(np.float64) - p.o.carry).max()))
     tok, msk = fresh_block(shape, 32)
     fwd = 0
     while msk.any():
@@ -768,6 +772,21 @@ def test_prefill_edge_lengths(n_embed, n_ids):
     p.close()
 
 
+@pytest.mark.parametrize("n_embed,n_ids", [(130, 126), (700, 400)])
+def test_prefill_with_the_register_staged_gemms(monkeypatch, n_embed, n_ids):
+    """The large-M GEMM kernel that stages its operands through registers (the fallback for K tails, forced here
+    for every phase, without the K split of the down projection) against the oracle."""
+    monkeypatch.setenv("BD_PREFILL", "staged")
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, "bf16", threads=1)
+    emb, ids = inputs.make_prompt(shape, n_embed, n_ids, seed=7)
+    p = Pair(shape, w, max_seq=max(256, n_embed + n_ids + 32))
+    p.prefill(emb, ids)
+    p.check_carry()
+    p.check_kv(0, n_embed + n_ids)
+    p.close()
+
+
 def test_large_m_prefill_agrees_with_the_chunked_one(monkeypatch):
     """The same prompt through the large-M kernels and through 64-row decode forwards: same cache and carry up to
     bf16 rounding of a different summation order (each path is also held against the oracle elsewhere)."""
@@ -776,9 +795,9 @@ def test_large_m_prefill_agrees_with_the_chunked_one(monkeypatch):
     w = inputs.make_weights(shape, 4, "bf16", threads=8)
     emb, ids = inputs.make_prompt(shape, 500, 200, seed=12)
     res = []
-    for mode in ("large", "chunked"):
-        if mode == "chunked":
-            monkeypatch.setenv("BD_PREFILL", "chunked")
+    for mode in ("large", "chunked", "staged"):
+        if mode != "large":
+            monkeypatch.setenv("BD_PREFILL", mode)
         else:
             monkeypatch.delenv("BD_PREFILL", raising=False)
         ctx = binding.Context(shape, max_seq=768, max_block=64)
@@ -789,7 +808,12 @@ def test_large_m_prefill_agrees_with_the_chunked_one(monkeypatch):
         res.append((k.clone(), v.clone(), ctx.bd_read_carry()))
         ctx.bd_status()
         ctx.close()
-    (k0, v0, c0), (k1, v1, c1) = res
+    (k0, v0, c0), (k1, v1, c1), (k2, v2, c2) = res
     for a, b in ((k0, k1), (v0, v1)):
         assert float((a - b).abs().max()) <= 2e-2 * float(b.abs().max())
     assert c0[0] == c1[0] and abs(c0[1] - c1[1]) <= 0.05 * c1[1]
+    # direct-to-LDS GEMMs with the K split of the down projection vs the register-staged ones: the same products, the
+    # down projection summed in another order
+    for a, b in ((k0, k2), (v0, v2)):
+        assert float((a - b).abs().max()) <= 1e-2 * float(b.abs().max())
+    assert c0[0] == c2[0] and abs(c0[1] - c2[1]) <= 0.02 * c2[1]
