@@ -294,15 +294,27 @@ __global__ __launch_bounds__(kPfThreads) void pf_norm_kernel(float* __restrict__
   const int token = blockIdx.x;
   float* row = x + (size_t)token * H;
   float ss = 0.f;
-  for (int c = threadIdx.x; c < H; c += kPfThreads) {
-    float v = row[c];
+  // eight consecutive columns per thread: two 16-byte loads per source, one 16-byte store of the packed copy
+  for (int c = threadIdx.x * 8; c < H; c += kPfThreads * 8) {
+    f32x4 v0 = *reinterpret_cast<const f32x4*>(row + c), v1 = *reinterpret_cast<const f32x4*>(row + c + 4);
     if (n_kparts > 0) {
       // the K splits of the projection before this norm, added in split order
-      for (int p = 0; p < n_kparts; ++p) v += kparts[((size_t)p * MTc * 16 + token) * H + c];
-      row[c] = v;
+      for (int p = 0; p < n_kparts; ++p) {
+        const float* src = kparts + ((size_t)p * MTc * 16 + token) * H + c;
+        v0 += *reinterpret_cast<const f32x4*>(src);
+        v1 += *reinterpret_cast<const f32x4*>(src + 4);
+      }
+      *reinterpret_cast<f32x4*>(row + c) = v0;
+      *reinterpret_cast<f32x4*>(row + c + 4) = v1;
     }
-    ss += v * v;
-    xb[xp_index(token, c, MTc)] = f32_to_bf16_bits(gain != nullptr ? v * gain[c] : v);
+    union { u16 h[8]; u32x4 q; } o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      ss += v0[e] * v0[e] + v1[e] * v1[e];
+      o.h[e] = f32_to_bf16_bits(gain != nullptr ? v0[e] * gain[c + e] : v0[e]);
+      o.h[4 + e] = f32_to_bf16_bits(gain != nullptr ? v1[e] * gain[c + 4 + e] : v1[e]);
+    }
+    *reinterpret_cast<u32x4*>(xb + xp_index(token, c, MTc)) = o.q;
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
