@@ -787,6 +787,22 @@ def test_prefill_with_the_register_staged_gemms(monkeypatch, n_embed, n_ids):
     p.close()
 
 
+@pytest.mark.parametrize("n_embed,n_ids", [(130, 126), (0, 144), (700, 400)])
+def test_prefill_with_the_k_split_down_projection(n_embed, n_ids):
+    """A small model whose FFN width lets the down projection of the large-M path split K over workgroups (the
+    tiny config's 688 has a K tail and takes the unsplit kernel): cache, carry and a decode step against the oracle."""
+    shape = inputs.ModelShape(n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=768, vocab=1024)
+    w = inputs.make_weights(shape, 3, "bf16", threads=1)
+    emb, ids = inputs.make_prompt(shape, n_embed, n_ids, seed=8)
+    p = Pair(shape, w, max_seq=max(256, n_embed + n_ids + 32))
+    p.prefill(emb, ids)
+    p.check_carry()
+    p.check_kv(0, n_embed + n_ids)
+    tok, msk = fresh_block(shape, 8)
+    p.denoise_step(tok, msk, 0.9, fixed_k=3)
+    p.close()
+
+
 def test_large_m_prefill_agrees_with_the_chunked_one(monkeypatch):
     """The same prompt through the large-M kernels and through 64-row decode forwards: same cache and carry up to
     bf16 rounding of a different summation order (each path is also held against the oracle elsewhere)."""
