@@ -489,10 +489,9 @@ int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t
       PfAttnArgs t{};
       t.q = c->pf_q; t.Kc = g.Kc; t.Vc = g.Vc; t.max_kb = c->max_kb; t.n0 = c->n; t.Mc = mc; t.n_q = c->cfg.n_q_heads;
       t.n_kv = c->cfg.n_kv_heads; t.scale_log2e = 1.4426950408889634f / std::sqrt((float)c->D); t.out = c->pf_ap; t.MTc = MTc;
-      const int items = t.n_q * (mc / 16);
-      const int grid = ceil_div(items, 2);
-      if (c->D == 128) hipLaunchKernelGGL((pf_attn_kernel<128, 2>), dim3(grid), dim3(kPfThreads), 0, s, t);
-      else hipLaunchKernelGGL((pf_attn_kernel<64, 2>), dim3(grid), dim3(kPfThreads), 0, s, t);
+      const int items = t.n_q * (mc / 16);                    // one item per workgroup, its four wavefronts share the blocks
+      if (c->D == 128) hipLaunchKernelGGL((pf_attn_kernel<128, 4>), dim3(items), dim3(kPfThreads), 0, s, t);
+      else hipLaunchKernelGGL((pf_attn_kernel<64, 4>), dim3(items), dim3(kPfThreads), 0, s, t);
       BD_TRY(check_launch());
     }
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[1]); g.KS = ceil_div(c->QD, 32);

@@ -365,10 +365,9 @@ __global__ void pf_clear_ssq_kernel(float* __restrict__ ssq, int parts, int Mp) 
 
 // Causal attention of a chunk against the packed cache (which already holds the chunk's own keys and values):
 // NW (2 or 4) wavefronts per (head, tile of 16 query rows) share out the 32-key blocks up to the last visible key
-// round-robin, each with the decode path's block routine and two register buffers, and merge through LDS; the items of
-// a workgroup are heads of one kv head, so their key/value blocks meet in the caches; two workgroups fit a CU.
-// (Measured: two and four wavefronts per item are equal, also at 8192 keys; a variant that stages every block once in
-// LDS for four heads of a kv head, one barrier per block, is slower than these register-buffered walks.)
+// round-robin, each with the decode path's block routine, and merge through LDS; with two wavefronts per item the items
+// of a workgroup are heads of one kv head; two workgroups fit a CU.  (Measured: a variant that stages every block once
+// in LDS for four heads of a kv head, one barrier per block, is slower than these register-buffered walks.)
 struct PfAttnArgs {
   const u16* q;           // [Mc][n_q][D], rotated, dims in rotary-pair order
   const u16* Kc; const u16* Vc;
@@ -410,21 +409,15 @@ __global__ __launch_bounds__(kPfThreads, 2) void pf_attn_kernel(PfAttnArgs a) {
     const int kb_end = (a.n0 + qt * 16 + 15) / 32 + 1;          // blocks holding a key some row of the tile may see
     const int cnt = (kb_end - half + NW - 1) / NW;              // this wavefront's blocks: half, half + NW, ..
     const float c = a.scale_log2e;
-    KvBlock<D> b0, b1;
-    if (cnt > 0) kv_load<D>(b0, Kh, Vh, half, lane);
-    asm volatile("" ::: "memory");
-    for (int j = 0; j < cnt; j += 2) {
-      const int kbA = half + NW * j, kbB = kbA + NW;
-      if (j + 1 < cnt) kv_load<D>(b1, Kh, Vh, kbB, lane);
+    // one register buffer: the other wavefronts of the CU cover the load (a second buffer, loaded one block ahead,
+    // costs more in registers than it hides: 25.6 us against 19.3 us per layer at 1024 rows)
+    KvBlock<D> b0;
+    for (int j = 0; j < cnt; ++j) {
+      const int kb = half + NW * j;
+      kv_load<D>(b0, Kh, Vh, kb, lane);
       asm volatile("" ::: "memory");
-      if (kbA * 32 + 31 >= a.n0) attn_block<D, true>(b0, qf, O, mrun, lrun, kbA, a.n0, a.Mc, 1, row, g, c);
-      else attn_block<D, false>(b0, qf, O, mrun, lrun, kbA, a.n0, a.Mc, 1, row, g, c);
-      if (j + 1 < cnt) {
-        if (j + 2 < cnt) kv_load<D>(b0, Kh, Vh, kbB + NW, lane);
-        asm volatile("" ::: "memory");
-        if (kbB * 32 + 31 >= a.n0) attn_block<D, true>(b1, qf, O, mrun, lrun, kbB, a.n0, a.Mc, 1, row, g, c);
-        else attn_block<D, false>(b1, qf, O, mrun, lrun, kbB, a.n0, a.Mc, 1, row, g, c);
-      }
+      if (kb * 32 + 31 >= a.n0) attn_block<D, true>(b0, qf, O, mrun, lrun, kb, a.n0, a.Mc, 1, row, g, c);
+      else attn_block<D, false>(b0, qf, O, mrun, lrun, kb, a.n0, a.Mc, 1, row, g, c);
     }
   }
   // wavefronts 1.. of an item hand their (max, sum, O) to wavefront 0 through LDS
