@@ -475,7 +475,7 @@ int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t
     g.Vc = c->Vc + (size_t)l * c->kv_layer_elems;
     // e4m3 weights: the norm gains go into the activation copy and the row scales onto the accumulators (as in decode)
     const float* ws = c->fp8 ? c->wscale + (size_t)l * c->wscale_layer : nullptr;
-    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
+    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc / 4), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
                        c->fp8 ? c->gains + (size_t)(2 * l) * c->H : nullptr, c->pf_part, parts);
     parts = 0;
     BD_TRY(check_launch());
@@ -499,7 +499,7 @@ int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t
     g.wscale = ws ? ws + c->wscale_off[1] : nullptr;
     if (!c->pf_staged && g.KS % 4 == 0) BD_TRY((launch_pf_gemm_direct<PH_O, 2, 4, 2, 2, 2>(c, g, c->H)));
     else BD_TRY((launch_pf_gemm<PH_O, 2, 4, 2>(c, g, c->H)));
-    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
+    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc / 4), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
                        c->fp8 ? c->gains + (size_t)(2 * l + 1) * c->H : nullptr, (const float*)nullptr, 0);
     BD_TRY(check_launch());
     g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[2]); g.KS = ceil_div(c->H, 32);
@@ -524,7 +524,7 @@ int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t
   }
   if (parts > 0) {
     // the last layer's splits: the same kernel completes the residual stream (its other outputs are not used)
-    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
+    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc / 4), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
                        (const float*)nullptr, c->pf_part, parts);
     BD_TRY(check_launch());
   }

@@ -284,18 +284,19 @@ template <int WN, int BKS, int TW, int NST> constexpr int pf_gemm_direct_lds() {
 
 template <int WN, int BKS, int TW> constexpr int pf_gemm_lds() { return 2 * (2 * WN * BKS * 64 + 2 * TW * BKS * 64) * 16; }
 
-// One workgroup per row: 1/rms of the fp32 residual row and its bf16 copy in packed order; completes the residual
+// One wavefront per row: 1/rms of the fp32 residual row and its bf16 copy in packed order; completes the residual
 // row first when the projection before it left its product in K splits (the norm gain lives in
 // the weights, the factor is applied by the GEMM epilogue: same arithmetic as the decode path).
 __global__ __launch_bounds__(kPfThreads) void pf_norm_kernel(float* __restrict__ x, int H, float eps, u16* __restrict__ xb,
                                                              int MTc, float* __restrict__ rs, const float* __restrict__ gain,
                                                              const float* __restrict__ kparts, int n_kparts) {
-  __shared__ float part[kPfThreads / 64];
-  const int token = blockIdx.x;
+  // one wavefront per row, four rows per workgroup
+  const int token = blockIdx.x * (kPfThreads / 64) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (token >= MTc * 16) return;
   float* row = x + (size_t)token * H;
   float ss = 0.f;
-  // eight consecutive columns per thread: two 16-byte loads per source, one 16-byte store of the packed copy
-  for (int c = threadIdx.x * 8; c < H; c += kPfThreads * 8) {
+  // eight consecutive columns per lane: two 16-byte loads per source, one 16-byte store of the packed copy
+  for (int c = lane * 8; c < H; c += 64 * 8) {
     f32x4 v0 = *reinterpret_cast<const f32x4*>(row + c), v1 = *reinterpret_cast<const f32x4*>(row + c + 4);
     if (n_kparts > 0) {
       // the K splits of the projection before this norm, added in split order
@@ -318,13 +319,7 @@ __global__ __launch_bounds__(kPfThreads) void pf_norm_kernel(float* __restrict__
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    float t = 0.f;
-    for (int w = 0; w < kPfThreads / 64; ++w) t += part[w];
-    rs[token] = rsqrtf(t / (float)H + eps);
-  }
+  if (lane == 0) rs[token] = rsqrtf(ss / (float)H + eps);
 }
 
 __global__ __launch_bounds__(kPfThreads) void zero_rows_kernel(float* __restrict__ x, int H) {
