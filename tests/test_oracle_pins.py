@@ -403,6 +403,92 @@ def test_quadratic_groups_do_not_leak_into_each_other():
     np.testing.assert_allclose(r["logits"][:W], lg, atol=TOL)
 
 
+def _quad_group_rollout(w, xp, d, i, B):
+    """Logits of group i of an Alg. 2 step from the dense full-sequence model alone: the sequence
+    [prompt, d_0 .. d_{i-1}, d_i, MASK x B] at positions 0, 1, .. (so group i sits at L+i .. L+i+B, the rollout
+    from the acceptance point i of the appendix's 'Quadratic' paragraph) under the literally built mask: prompt
+    and first tokens token-causal (rule b), the B mask rows see the prompt (rule a) and the B+1 tokens of their
+    own group (rule c) and none of d_0 .. d_{i-1} (rule d)."""
+    L = xp.shape[0]
+    W = B + 1
+    ids = np.concatenate([np.asarray(d[:i + 1], np.int64), np.full(B, SMALL.mask_token_id, np.int64)])
+    x = torch.cat([xp, ref.embed_rows(w, ids)], 0)
+    T = L + i + W
+    A = torch.zeros(T, T, dtype=torch.bool)
+    for r in range(T):
+        for c in range(T):
+            if r <= L + i:
+                A[r, c] = c <= r
+            else:
+                A[r, c] = c < L or c >= L + i
+    return ref.full_forward(SMALL, w, x, A)[L + i:].numpy()
+
+
+@pytest.mark.parametrize("B", [2, 3, 5])
+def test_quadratic_step_groups_are_rollouts_from_each_acceptance_point(B):
+    """Every row of the B(B+1)-row forward, mask rows of the later groups included, against the dense model: this
+    fixes the position ids n+i+j of group i, the four mask rules, and with them every proposal P[i][j]."""
+    o, w, xp = _prefilled()
+    W = B + 1
+    d = copy.deepcopy(o).greedy_ar(B)
+    if B > 2:
+        d[B - 1] = (d[B - 1] + 3) % (SMALL.vocab - 1)      # the last draft is wrong: k = B - 1
+    r = copy.deepcopy(o).quad_step(d)
+    want_P = np.empty((B, W), np.int64)
+    for i in range(B):
+        want = _quad_group_rollout(w, xp, d, i, B)
+        np.testing.assert_allclose(r["logits"][i * W:(i + 1) * W], want, atol=TOL, rtol=1e-9)
+        want_P[i] = want.argmax(-1)
+    assert np.array_equal(r["P"], want_P)
+    k = 1
+    while k < B and want_P[k - 1, 0] == d[k]:
+        k += 1
+    assert r["k"] == k == (B - 1 if B > 2 else B)
+    assert list(r["next_draft"]) == list(want_P[k - 1, :B])
+
+
+@pytest.mark.parametrize("B", [1, 2, 4, 6])
+def test_quadratic_first_draft_is_the_dense_model_over_prompt_and_masks(B):
+    """Alg. 2 step 1: z = [prompt, MASK x B], prompt rows causal, mask rows see everything; draft i is the argmax of
+    row L-1+i (draft 0 comes from the last prompt row), and the cache keeps the prompt only."""
+    o, w, xp = _prefilled()
+    L = xp.shape[0]
+    x = torch.cat([xp, ref.embed_rows(w, np.full(B, SMALL.mask_token_id, np.int64))], 0)
+    lg = ref.full_forward(SMALL, w, x, ref.dense_mask(L, B, bidir=True)).numpy()
+    oo = copy.deepcopy(o)
+    got = oo.quad_draft(B)
+    assert list(got) == list(lg[L - 1:L - 1 + B].argmax(-1))
+    assert oo.n == L
+
+
+def test_quadratic_pins_catch_same_positions_for_every_group(monkeypatch):
+    """Planted mistake: positions n+j in every group (instead of n+i+j).  The first-token and greedy-equivalence pins
+    cannot see it in group 0; the rollout pin must."""
+    o, w, xp = _prefilled()
+    B, W = 3, 4
+    d = copy.deepcopy(o).greedy_ar(B)
+    bad = copy.deepcopy(o)
+    orig = bad.forward
+
+    def forward_same_pos(x, mode, want_logits_rows=None, pos=None, vis_block=None):
+        if pos is not None:
+            r = np.arange(len(pos))
+            pos = bad.n + r % W
+        return orig(x, mode, want_logits_rows, pos, vis_block)
+
+    monkeypatch.setattr(bad, "forward", forward_same_pos)
+    r = bad.quad_step(d)
+    np.testing.assert_allclose(r["logits"][:W], _quad_group_rollout(w, xp, d, 0, B), atol=TOL)   # group 0 unaffected
+    assert np.abs(r["logits"][W:2 * W] - _quad_group_rollout(w, xp, d, 1, B)).max() > 1e-4
+    # and a mask row that wrongly sees an earlier group's first token is caught too
+    leaky = copy.deepcopy(o)
+    vis = BlockDiffusionOracle.quad_mask(B).copy()
+    vis[W + 1, 0] = True
+    monkeypatch.setattr(BlockDiffusionOracle, "quad_mask", staticmethod(lambda b: vis))
+    r2 = leaky.quad_step(d)
+    assert np.abs(r2["logits"][W:2 * W] - _quad_group_rollout(w, xp, d, 1, B)).max() > 1e-6
+
+
 def test_crop_restores_earlier_state():
     o, _, _ = _prefilled()
     a = copy.deepcopy(o); a.commit_block(np.array([1, 2, 3, 4])); a.crop(o.n + 2); a.commit_block(np.array([9]))
