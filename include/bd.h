@@ -9,8 +9,11 @@
  * block is committed to the cache by a causal forward.
  *
  * Conventions
- *   - Every function returns 0 (BD_OK) or a negative BD_E_* code; nothing aborts or throws.  On error
- *     no output argument is written and the context state is unchanged.
+ *   - Every function returns 0 (BD_OK) or a negative BD_E_* code; nothing aborts or throws.  A call
+ *     refused for its arguments or its place in the call order (BD_E_ARG, BD_E_STATE, BD_E_CAPACITY,
+ *     BD_E_DTYPE) writes no output argument and leaves the context as it was.  After BD_E_HIP (a launch
+ *     or runtime call failed, or a bounded wait inside a kernel timed out) the cache and the carry are
+ *     undefined: prefill again, or destroy the context if bd_status() reports the time-out.
  *   - "dev" pointers are device memory owned by the caller (for instance PyTorch tensors); "host"
  *     pointers are ordinary host memory.  The library never frees or keeps caller pointers beyond
  *     the call, except that work enqueued on the stream reads/writes dev buffers asynchronously:
@@ -56,7 +59,16 @@ typedef struct {
   int32_t max_block;     /* largest B of any call (<= 64; <= 32 with BD_FP8_E4M3 weights)            */
   int32_t mask_token_id; /* id embedded at masked positions; negative = vocab-1                       */
   int32_t weight_dtype;  /* device storage of the seven decoder linears: BD_BF16 or BD_FP8_E4M3       */
+  int32_t flags;         /* 0, or BD_FLAG_* bits: alternative code paths, kept for the tests that compare them */
 } bd_config;
+
+/* bd_config.flags (0 is the product path; results are the same to rounding, see each flag): */
+enum {
+  BD_FLAG_CHIP_WIDE_HANDOVER = 1,  /* gate/up -> down hand-over through the chip-wide barrier instead of per XCD (bit-identical) */
+  BD_FLAG_REGISTER_RING = 2,       /* forwards of <= 32 rows on the register-ring kernel that serves 33..64 rows (bf16 weights)   */
+  BD_FLAG_PREFILL_DECODE = 4,      /* prompts through the decode kernels in chunks of max_block rows, no large-M kernels          */
+  BD_FLAG_PREFILL_STAGED = 8       /* large-M GEMMs stage their operands through registers instead of loading straight into LDS  */
+};
 
 /* Shape limits: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads; hidden, ffn, vocab and the
  * projection widths multiples of 16; hidden a multiple of 32. */

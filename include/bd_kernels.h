@@ -1,11 +1,10 @@
 /*
  * bd_kernels.h - kernel-level entry points of the block-denoising library.
  *
- * These expose single kernels of the forward (the skinny weight-streaming GEMM, the block-causal
- * attention) on caller-provided tensors, and per-kernel-class timing of a context, so that tests can
- * check one kernel against the oracle and the benchmark can price one kernel against its roofline.
- * They allocate temporary device memory and synchronise the stream; they are not part of the decode
- * path.  Return codes as in bd.h.
+ * These expose block-causal attention on caller-provided tensors, per-kernel-class timing of a context and
+ * the in-kernel phase trace, so that tests can check one operation against the oracle and the benchmark
+ * can price one kernel against its roofline.  They are not part of the decode path.  Return codes as in
+ * bd.h.
  */
 #ifndef BD_KERNELS_H_
 #define BD_KERNELS_H_
@@ -18,17 +17,12 @@
 extern "C" {
 #endif
 
-/* Y[M,N] (dev fp32) = bf16(X[M,K]) * W[N,K]^T with W given as bf16 bit patterns (dev), fp32
- * accumulation; the same kernel and split-K plan the decoder linears use (Sec. 3.4 forward; the
- * paper delegates its linears to library kernels).  M <= 64, N % 16 == 0.
- * iters > 1 repeats the GEMM launch and *avg_ms (host, may be NULL) receives the mean kernel time. */
-int bd_k_gemm(void* hip_stream, const uint16_t* dev_w, const float* dev_x, int M, int N, int K, float* dev_y,
-              int iters, float* avg_ms);
-
 /* Block-causal grouped-query attention (Sec. 3.3 mask rules; Alg. 1 draft / verify masks) on explicit
  * operands: dev_q fp32 [M, n_q, D] (already rotated), dev_k / dev_v fp32 [n_prefix + M, n_kv, D] (prefix
  * keys first, then the block's own); all rounded to bf16 inside.  dev_out fp32 [M, n_q*D].
- * mode BD_MODE_BIDIR / BD_MODE_CAUSAL.  M <= 64, D in {64, 128}. */
+ * mode BD_MODE_BIDIR / BD_MODE_CAUSAL.  M <= 64, D in {64, 128}.  Allocates its working buffers per call
+ * and synchronises the stream.  iters > 1 repeats the kernels and *avg_ms (host, may be NULL) receives the
+ * mean time of one run. */
 int bd_k_attention(void* hip_stream, const float* dev_q, const float* dev_k, const float* dev_v, int n_prefix, int M,
                    int n_q, int n_kv, int D, int mode, float* dev_out, int iters, float* avg_ms);
 

@@ -18,13 +18,14 @@ LIB_PATH = os.path.join(_HERE, "libbd.so")
 BD_OK, BD_E_ARG, BD_E_STATE, BD_E_CAPACITY, BD_E_DTYPE, BD_E_HIP = 0, -1, -2, -3, -4, -5
 BD_F32, BD_BF16, BD_FP8_E4M3 = 0, 1, 2
 BD_MODE_BIDIR, BD_MODE_CAUSAL = 0, 1
+BD_FLAG_CHIP_WIDE_HANDOVER, BD_FLAG_REGISTER_RING, BD_FLAG_PREFILL_DECODE, BD_FLAG_PREFILL_STAGED = 1, 2, 4, 8
 
 # every symbol the two headers declare
 EXPORTS = [
     "bd_create", "bd_destroy", "bd_load_weight", "bd_prefill", "bd_denoise_step", "bd_commit_block",
     "bd_verify_block", "bd_decode_block", "bd_speculative_step", "bd_quad_draft", "bd_quad_step", "bd_crop", "bd_cache_len", "bd_status", "bd_debug_logits", "bd_read_logits", "bd_read_kv",
     "bd_read_carry", "bd_read_rows", "bd_forward_bytes", "bd_strerror", "bd_last_error",
-    "bd_k_gemm", "bd_k_attention", "bd_k_profile", "bd_k_profile_read", "bd_k_class_count", "bd_k_class_name",
+    "bd_k_attention", "bd_k_profile", "bd_k_profile_read", "bd_k_class_count", "bd_k_class_name",
     "bd_k_class_bytes", "bd_k_trace", "bd_k_trace_read",
 ]
 
@@ -32,7 +33,7 @@ EXPORTS = [
 class bd_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab")] + \
                [("rope_theta", C.c_float), ("rms_eps", C.c_float)] + \
-               [(n, C.c_int32) for n in ("max_seq", "max_block", "mask_token_id", "weight_dtype")]
+               [(n, C.c_int32) for n in ("max_seq", "max_block", "mask_token_id", "weight_dtype", "flags")]
 
 
 _lib = None
@@ -72,7 +73,6 @@ def lib() -> C.CDLL:
     L.bd_strerror.restype = C.c_char_p
     L.bd_last_error.argtypes = []
     L.bd_last_error.restype = C.c_char_p
-    L.bd_k_gemm.argtypes = [vp, vp, vp, i32, i32, i32, vp, i32, C.POINTER(f32)]
     L.bd_k_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, i32, C.POINTER(f32)]
     L.bd_k_profile.argtypes = [vp, i32]
     L.bd_k_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i32)]
@@ -114,12 +114,12 @@ def _ptr(t) -> Optional[int]:
 class Context:
     """One decode context = one bd_ctx.  Methods carry the names of the C calls they wrap."""
 
-    def __init__(self, shape, max_seq: int, max_block: int, weight_dtype: int = BD_BF16, stream=None):
+    def __init__(self, shape, max_seq: int, max_block: int, weight_dtype: int = BD_BF16, stream=None, flags: int = 0):
         import torch
         self.shape = shape
         cfg = bd_config(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn,
                         shape.vocab, shape.rope_theta, shape.rms_eps, max_seq, max_block, shape.mask_token_id,
-                        weight_dtype)
+                        weight_dtype, flags)
         self._stream = stream if stream is not None else torch.cuda.current_stream()
         h = C.c_void_p()
         _check(lib().bd_create(C.byref(cfg), C.c_void_p(self._stream.cuda_stream), C.byref(h)))
@@ -274,19 +274,6 @@ def _trace_methods():
 _trace_methods()
 
 
-def bd_k_gemm(w_bits, x, iters: int = 1):
-    """Y = bf16(x) @ W^T through the library's skinny GEMM.  w_bits: uint16 [N,K] (cuda, viewed as int16),
-    x: fp32 [M,K] (cuda).  Returns (Y fp32 [M,N], mean kernel ms or 0)."""
-    import torch
-    N, K = w_bits.shape
-    M = x.shape[0]
-    y = torch.empty((M, N), dtype=torch.float32, device="cuda")
-    ms = C.c_float(0)
-    _check(lib().bd_k_gemm(C.c_void_p(torch.cuda.current_stream().cuda_stream), _ptr(w_bits), _ptr(x), M, N, K, _ptr(y),
-                           iters, C.byref(ms)))
-    return y, ms.value
-
-
 def bd_k_attention(q, k, v, n_prefix: int, mode: int, iters: int = 1):
     """Block-causal GQA attention on explicit fp32 cuda operands (see include/bd_kernels.h)."""
     import torch
@@ -297,3 +284,4 @@ def bd_k_attention(q, k, v, n_prefix: int, mode: int, iters: int = 1):
     _check(lib().bd_k_attention(C.c_void_p(torch.cuda.current_stream().cuda_stream), _ptr(q), _ptr(k), _ptr(v), n_prefix,
                                 M, n_q, n_kv, D, mode, _ptr(out), iters, C.byref(ms)))
     return out, ms.value
+

@@ -22,23 +22,6 @@
 
 namespace bd {
 
-// ---- packed cache layouts (per layer, per kv head; key blocks of 32 keys) --------------------------
-// K: block kb, half t (0/1), d-step ds (32 dims):  lane l holds key kb*32 + 8*(i/4) + 4*t + (i%4) with
-//    i = l & 15, dims ds*32 + 8*(l>>4) .. +7.            index ((kb*2 + t)*DS + ds)*64 + l   (bf16x8)
-// V: block kb, d-tile dt (16 dims): lane l holds dim dt*16 + (l & 15), keys kb*32 + 8*(l>>4) .. +7.
-//                                                        index (kb*DT + dt)*64 + l           (bf16x8)
-__device__ inline size_t kp_index(int key, int d, int DS) {   // element index of K[key][d]
-  const int kb = key >> 5, kk = key & 31;
-  const int g = kk >> 3, e = kk & 7, t = e >> 2, r = e & 3, i = 4 * g + r;
-  const int ds = d >> 5, kq = (d >> 3) & 3;
-  return ((((size_t)kb * 2 + t) * DS + ds) * 64 + kq * 16 + i) * 8 + (d & 7);
-}
-__device__ inline size_t vp_index(int key, int d, int DT) {   // element index of V[key][d]
-  const int kb = key >> 5, kk = key & 31;
-  const int g = kk >> 3, e = kk & 7;
-  return ((((size_t)kb * DT + (d >> 4)) * 64) + g * 16 + (d & 15)) * 8 + e;
-}
-
 struct AttnArgs {
   const u16* Q;            // [MT*16][n_q][D] bf16, rotary applied
   const bf16x8* Kc;        // this layer's packed K cache: [n_kv][max_kb] blocks
@@ -52,16 +35,6 @@ struct AttnArgs {
   float* pl;               // partial sums     [item][JT*16]
   u16* out;                // combine: packed bf16 activation [M][n_q*D] with MT row tiles
 };
-
-// Chunk geometry shared by both kernels: n_kb key blocks are cut into chunks of chunk_len blocks.
-__device__ inline void attn_chunks(int n_keys, int max_chunks, int& n_kb, int& chunk_len, int& n_chunks) {
-  n_kb = (n_keys + 31) >> 5;
-  chunk_len = (n_kb + max_chunks - 1) / max_chunks;
-  if (chunk_len < kWavesPerWG) chunk_len = kWavesPerWG;
-  n_chunks = (n_kb + chunk_len - 1) / chunk_len;
-}
-
-constexpr float kNegBig = -1.0e30f;
 
 template <int D, int JT>
 __global__ __launch_bounds__(kWGThreads) void attn_partial_kernel(AttnArgs a) {
@@ -278,6 +251,29 @@ __global__ __launch_bounds__(kWGThreads) void attn_combine_kernel(AttnArgs a) {
       }
     }
     __syncthreads();
+  }
+}
+
+// ---- operand conversion of the stand-alone entry point ----
+__global__ void unpack_x_kernel(const u16* __restrict__ xp, int M, int K, float* __restrict__ x, int MT) {
+  const size_t total = (size_t)M * K;
+  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total;
+       idx += (size_t)gridDim.x * blockDim.x) {
+    const int m = (int)(idx / K), k = (int)(idx % K);
+    x[idx] = bf16_bits_to_f32(xp[xp_index(m, k, MT)]);
+  }
+}
+
+// fp32 [T][n_kv][D] keys and values -> packed bf16 caches of one layer
+__global__ void pack_kv_kernel(const float* __restrict__ k, const float* __restrict__ v, int T, int n_kv, int D,
+                               int max_kb, u16* __restrict__ Kc, u16* __restrict__ Vc) {
+  const size_t total = (size_t)T * n_kv * D;
+  const size_t kv_head_elems = (size_t)max_kb * 32 * D;
+  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total;
+       idx += (size_t)gridDim.x * blockDim.x) {
+    const int d = idx % D, h = (idx / D) % n_kv, p = (int)(idx / ((size_t)D * n_kv));
+    Kc[h * kv_head_elems + kp_index(p, d, D / 32)] = f32_to_bf16_bits(k[idx]);
+    Vc[h * kv_head_elems + vp_index(p, d, D / 16)] = f32_to_bf16_bits(v[idx]);
   }
 }
 

@@ -13,39 +13,31 @@
 #include <string>
 #include <vector>
 
-#include "attention.h"
+#include <cstdarg>
+
 #include "common.h"
-#include "gemm.h"
-#include "mega.h"
+#include "launch.h"
 #include "misc.h"
-#include "stream_fwd.h"
-#include "prefill.h"
+#include "pack.h"
+#include "plan.h"
+#include "prefill_args.h"
 
 using namespace bd;
 
 static char g_last_error[512] = "";
 
-#define HIP_TRY(expr)                                                                                   \
-  do {                                                                                                  \
-    hipError_t e__ = (expr);                                                                            \
-    if (e__ != hipSuccess) {                                                                            \
-      snprintf(g_last_error, sizeof g_last_error, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), \
-               __FILE__, __LINE__);                                                                     \
-      return BD_E_HIP;                                                                                  \
-    }                                                                                                   \
-  } while (0)
-
-#define BD_TRY(expr)            \
-  do {                          \
-    int rc__ = (expr);          \
-    if (rc__ != BD_OK) return rc__; \
-  } while (0)
+namespace bd {
+void set_last_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_last_error, sizeof g_last_error, fmt, ap);
+  va_end(ap);
+}
+}  // namespace bd
 
 namespace {
 
 enum KClass { KC_PROLOGUE = 0, KC_LAYERS, KC_LMHEAD, KC_FINISH, KC_COUNT };
-
-struct GemmPlan { int NT, ksplit, grid; };   // launch plan of the stand-alone GEMM entry point
 
 }  // namespace
 
@@ -75,7 +67,6 @@ struct bd_ctx {
   unsigned* counters = nullptr; int n_cntD = 0, n_cntA = 0;
   float* pO = nullptr; float* pm = nullptr; float* pl = nullptr;
   size_t pO_layer_floats = 0, pml_layer_floats = 0;
-  int attn_items_max = 0;          // stand-alone attention entry point only
   float* lm_max = nullptr; int* lm_idx = nullptr; float* lm_sum = nullptr;
   float* logits = nullptr; int logits_on = 0; int last_rows = 0; int last_had_logits = 0;
   int* row_cand = nullptr; float* row_conf = nullptr;
@@ -131,17 +122,6 @@ struct Prof {
   }
 };
 
-int check_launch() {
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) {
-    snprintf(g_last_error, sizeof g_last_error, "kernel launch failed: %s", hipGetErrorString(e));
-    return BD_E_HIP;
-  }
-  return BD_OK;
-}
-
-int ceil_even(int v) { return (v + 1) & ~1; }
-
 // Row ranges and K splits of every GEMM phase; fails if a wavefront would have to hold more than
 // kMaxKW k-steps of activations.
 int make_plan(bd_ctx* c) {
@@ -191,77 +171,29 @@ int make_plan(bd_ctx* c) {
   return BD_OK;
 }
 
-// Column tiles per attention item: the stand-alone kernels take up to 4; inside the forward kernel the
-// register budget is shared with the prefetched weights, so it works on pairs.
-int attn_jt(const bd_ctx* c, int MT, bool in_forward = false) {
-  const int jt_total = c->G * MT;
-  if (in_forward) return 2;
-  return (jt_total % 4 == 0) ? 4 : ((jt_total % 2 == 0) ? 2 : 1);
-}
+// Column tiles per attention item of the register-ring kernel: its register budget is shared with the prefetched
+// weights, so it works on pairs.
+int attn_jt(const bd_ctx*, int) { return 2; }
 
-int attn_max_chunks(const bd_ctx* c, int MT, bool in_forward = false) {
-  const int JT = attn_jt(c, MT, in_forward);
+int attn_max_chunks(const bd_ctx* c, int MT) {
+  const int JT = attn_jt(c, MT);
   const int groups = c->cfg.n_kv_heads * (c->G * MT / JT);
   int mc = (2 * c->num_cus) / groups;
   return std::max(1, std::min(mc, 64));
 }
 
-// Dynamic LDS the forward kernel needs: GEMM staging, or the attention phase's buffers if larger.
-template <int MT>
-constexpr int mega_lds_total() { return mega_lds_bytes<MT>() > 56 * 1024 ? mega_lds_bytes<MT>() : 56 * 1024; }
-
-template <int MT, int D, int JT, bool QUAD = false>
-int launch_mega_inst(bd_ctx* c, const MegaArgs& a) {
-  static bool attr_set = false;
-  constexpr int lds = mega_lds_total<MT>();
-  if (!attr_set) {
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&mega_kernel<MT, D, JT, QUAD>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    attr_set = true;
-  }
-  hipLaunchKernelGGL((mega_kernel<MT, D, JT, QUAD>), dim3(c->plan.nwg), dim3(kWGThreads), lds, c->stream, a);
-  return check_launch();
-}
-
-template <int MT>
-int launch_lm(bd_ctx* c, const MegaArgs& a) {
-  static bool attr_set = false;
-  constexpr int lds = mega_lds_total<MT>();
-  if (!attr_set) {
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&lm_kernel<MT>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    attr_set = true;
-  }
-  hipLaunchKernelGGL((lm_kernel<MT>), dim3(c->plan.nwg), dim3(kWGThreads), lds, c->stream, a);
-  return check_launch();
-}
-
-// The forward kernel with decoupled weight streaming (stream_fwd.h): block sizes up to 32.
-template <int MT, int D, bool FP8, bool QUAD = false>
-int launch_stream_inst(bd_ctx* c, const MegaArgs& a) {
-  static bool attr_set = false;
-  constexpr int lds = stream_lds_bytes<MT>();
-  if (!attr_set) {
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_fwd_kernel<MT, D, FP8, QUAD>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    attr_set = true;
-  }
-  hipLaunchKernelGGL((stream_fwd_kernel<MT, D, FP8, QUAD>), dim3(c->plan.nwg), dim3(kFwdThreads), lds, c->stream, a);
-  return check_launch();
-}
-
 // Does workgroup b of a launch shaped like the streaming forward kernel's run on XCD b mod 8?  Returns 8 if so, else 0.
 int probe_xcds(bd_ctx* c) {
-  if (const char* e = getenv("BD_XCD_LOCAL")) if (strcmp(e, "0") == 0) return 0;
+  if (c->cfg.flags & BD_FLAG_CHIP_WIDE_HANDOVER) return 0;
   const int nwg = c->num_cus, nx = 8;
   if (nwg % nx != 0) return 0;
   unsigned* d = nullptr;
   if (hipMalloc(reinterpret_cast<void**>(&d), (size_t)nwg * 4) != hipSuccess) { (void)hipGetLastError(); return 0; }
-  constexpr int lds = stream_lds_bytes<2>();
   std::vector<unsigned> h((size_t)nwg, ~0u);
-  bool ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&xcc_probe_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds) == hipSuccess;
+  bool ok = true;
   for (int rep = 0; rep < 2 && ok; ++rep) {
-    hipLaunchKernelGGL(xcc_probe_kernel, dim3(nwg), dim3(kFwdThreads), lds, c->stream, d);
-    ok = hipGetLastError() == hipSuccess && hipMemcpyAsync(h.data(), d, (size_t)nwg * 4, hipMemcpyDeviceToHost, c->stream) == hipSuccess &&
+    ok = launch_xcc_probe(c->stream, nwg, d) == BD_OK &&
+         hipMemcpyAsync(h.data(), d, (size_t)nwg * 4, hipMemcpyDeviceToHost, c->stream) == hipSuccess &&
          hipStreamSynchronize(c->stream) == hipSuccess;
     for (int b = 0; b < nwg && ok; ++b) ok = h[(size_t)b] == (unsigned)(b % nx);
   }
@@ -275,46 +207,30 @@ int stream_attn_max_chunks(const bd_ctx* c, int MT) {
   return std::max(1, std::min(c->num_cus / groups, 64));
 }
 
-template <int MT>
-int launch_mega_mt(bd_ctx* c, MegaArgs& a, bool lm_only = false) {
-  bool streamed = false;
-  if constexpr (MT <= 2) streamed = c->use_stream;
+// The layers kernel (streaming kernel for forwards of up to 32 rows, register-ring kernel beyond) and the LM head.
+int launch_forward_kernels(bd_ctx* c, int MT, MegaArgs& a, bool lm_only = false) {
+  const bool streamed = MT <= 2 && c->use_stream;
   if (!lm_only) {
-  Prof pr(c, KC_LAYERS);
-  if (streamed) {
-    if constexpr (MT <= 2) {
+    Prof pr(c, KC_LAYERS);
+    const bool quad = a.mode >= 2;                           // quadratic mask (Alg. 2): its own instantiations
+    if (streamed) {
       a.attn_max_chunks = stream_attn_max_chunks(c, MT);
       a.local_gu = c->plan.xcd_gu > 0 ? 1 : 0;
       a.xbar = c->xbar; a.xbar_epoch = c->xbar_epoch;
-      if (a.mode >= 2) {                                     // quadratic mask (Alg. 2): its own instantiations
-        if (c->fp8) return BD_E_ARG;
-        if (c->D == 128) BD_TRY((launch_stream_inst<MT, 128, false, true>(c, a)));
-        else BD_TRY((launch_stream_inst<MT, 64, false, true>(c, a)));
-      } else if (c->fp8) {
-        if (c->D == 128) BD_TRY((launch_stream_inst<MT, 128, true>(c, a)));
-        else BD_TRY((launch_stream_inst<MT, 64, true>(c, a)));
-      } else {
-        if (c->D == 128) BD_TRY((launch_stream_inst<MT, 128, false>(c, a)));
-        else BD_TRY((launch_stream_inst<MT, 64, false>(c, a)));
-      }
+      BD_TRY(launch_stream_fwd(c->stream, MT, c->D, c->fp8, quad, a));
       c->bar_epoch += (a.local_gu ? 4u : 5u) * (unsigned)c->L;
       if (a.local_gu) c->xbar_epoch += (unsigned)c->L;
       a.local_gu = 0;
+    } else {
+      if (c->fp8) return BD_E_ARG;                           // e4m3 weights are only streamed by the kernel above
+      BD_TRY(launch_mega_fwd(c->stream, MT, c->D, quad, a));
+      c->bar_epoch += 5u * (unsigned)c->L;
     }
-  } else {
-    if (c->fp8) return BD_E_ARG;                            // e4m3 weights are only streamed by the kernel above
-    if (a.mode >= 2) {
-      if (c->D == 128) BD_TRY((launch_mega_inst<MT, 128, 2, true>(c, a)));
-      else BD_TRY((launch_mega_inst<MT, 64, 2, true>(c, a)));
-    } else if (c->D == 128) BD_TRY((launch_mega_inst<MT, 128, 2>(c, a)));
-    else BD_TRY((launch_mega_inst<MT, 64, 2>(c, a)));
-    c->bar_epoch += 5u * (unsigned)c->L;
-  }
   }
   if (a.want_lm) {
     Prof pr(c, KC_LMHEAD);
     a.bar_epoch = c->bar_epoch;
-    BD_TRY(launch_lm<MT>(c, a));
+    BD_TRY(launch_lm_head(c->stream, MT, a));
     c->bar_epoch += 1u;
   }
   return BD_OK;
@@ -359,26 +275,14 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
   a.wsD = c->wsD; a.wsD_layer_floats = c->wsD_layer_floats; a.cntD = c->counters;
   a.pO = c->pO; a.pm = c->pm; a.pl = c->pl; a.pO_layer_floats = c->pO_layer_floats; a.pml_layer_floats = c->pml_layer_floats;
   a.cntA = c->counters + c->n_cntD;
-  a.attn_max_chunks = attn_max_chunks(c, MT, true);
+  a.attn_max_chunks = attn_max_chunks(c, MT);
   a.scale_log2e = 1.4426950408889634f / std::sqrt((float)c->D);
   a.lm_max = c->lm_max; a.lm_idx = c->lm_idx; a.lm_sum = c->lm_sum;
   a.logits = (want_lm && c->logits_on) ? c->logits : nullptr;
   a.row_cand = c->row_cand; a.row_conf = c->row_conf;
   a.trace = c->trace_on ? c->trace : nullptr;
   a.trace2 = c->trace_on ? c->trace + (size_t)c->plan.nwg * (10 * c->L + 4) : nullptr;
-  {
-#ifdef BD_DEV_FAST   /* development builds: one instantiation only, to shorten compile time */
-    if (MT != 2) return BD_E_ARG;
-    BD_TRY(launch_mega_mt<2>(c, a, lm_only));
-#else
-    switch (MT) {
-      case 1: BD_TRY(launch_mega_mt<1>(c, a, lm_only)); break;
-      case 2: BD_TRY(launch_mega_mt<2>(c, a, lm_only)); break;
-      case 3: BD_TRY(launch_mega_mt<3>(c, a, lm_only)); break;
-      default: BD_TRY(launch_mega_mt<4>(c, a, lm_only)); break;
-    }
-#endif
-  }
+  BD_TRY(launch_forward_kernels(c, MT, a, lm_only));
   c->last_rows = M;
   c->last_had_logits = (want_lm && c->logits_on) ? 1 : 0;
   return BD_OK;
@@ -406,129 +310,26 @@ FinishArgs finish_args(bd_ctx* c, int B) {
 
 }  // namespace
 
-// ---------------------------------------------------------------------------------------------------------
 namespace {
 
-// Tile shapes per phase (rows per workgroup = 32*WN, k-steps per stage BKS, tokens per workgroup = 32*TW), picked by
-// measurement at 1024 rows: gate/up 128 rows x 128 tokens x 2 k-steps, down and O 64 x 64 x 4, QKV 64 x 64 x 2 (the
-// phases with 2048-2560 output rows need the smaller token tile to put two workgroups on every CU).
-template <int PH, int WN, int BKS, int TW>
-int launch_pf_gemm(bd_ctx* c, PfGemmArgs a, int n_rows) {
-  static bool attr_set = false;
-  constexpr int lds = pf_gemm_lds<WN, BKS, TW>();
-  if (!attr_set) {
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<PH, WN, BKS, TW>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    attr_set = true;
-  }
-  a.NT = n_rows / 16;
-  a.RG = ceil_div(a.NT, 2 * WN);
-  a.TG = ceil_div(a.MTc, 2 * TW);
-  const int grid = ceil_div(a.RG, 8) * 8 * a.TG;
-  hipLaunchKernelGGL((pf_gemm_kernel<PH, WN, BKS, TW>), dim3(grid), dim3(kPfThreads), lds, c->stream, a);
-  return check_launch();
-}
-
-template <int PH, int WN, int BKS, int TW, int NST, int OCC>
-int launch_pf_gemm_direct(bd_ctx* c, PfGemmArgs a, int n_rows) {
-  static bool attr_set = false;
-  constexpr int lds = pf_gemm_direct_lds<WN, BKS, TW, NST>();
-  if (!attr_set) {
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_direct_kernel<PH, WN, BKS, TW, NST, OCC>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-    attr_set = true;
-  }
-  static_assert(OCC * lds <= 160 * 1024, "workgroups per CU bounded by LDS");
-  if (a.KS % BKS != 0) return BD_E_ARG;
-  a.NT = n_rows / 16;
-  a.RG = ceil_div(a.NT, 2 * WN);
-  a.TG = ceil_div(a.MTc, 2 * TW);
-  if (a.SK < 1 || (a.KS / BKS) % a.SK != 0) return BD_E_ARG;
-  const int grid = ceil_div(a.RG, 8) * 8 * a.TG * a.SK;
-  hipLaunchKernelGGL((pf_gemm_direct_kernel<PH, WN, BKS, TW, NST, OCC>), dim3(grid), dim3(kPfThreads), lds, c->stream, a);
-  return check_launch();
-}
-
-// One chunk of `rows` prompt rows starting at prompt row `off` = cache position c->n: all layers, K/V into the cache,
-// no LM head.  The kernels work on whole tiles of 16 rows: the rows that pad the last tile are zero on entry, take part
-// in every product and write nothing to the cache.  The device-side length is advanced by the caller.
+// One chunk of `rows` prompt rows starting at prompt row `off` = cache position c->n through the large-M kernels.
 int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* dev_ids, int off, int rows) {
-  hipStream_t s = c->stream;
-  const int MTc = ceil_div(rows, 16);
-  const int mc = MTc * 16;
-  hipLaunchKernelGGL(embed_kernel, dim3(rows), dim3(kWGThreads), 0, s, c->pf_x, c->H, dev_embeds, n_embed, dev_ids, off,
-                     (const uint8_t*)nullptr, c->cfg.mask_token_id, c->embed, c->V);
-  BD_TRY(check_launch());
-  if (mc > rows) {
-    hipLaunchKernelGGL(zero_rows_kernel, dim3(mc - rows), dim3(kWGThreads), 0, s, c->pf_x + (size_t)rows * c->H, c->H);
-    BD_TRY(check_launch());
-  }
-  hipLaunchKernelGGL(rope_table_kernel, dim3(mc), dim3(64), 0, s, c->pf_rope, c->st, c->D / 2, c->cfg.rope_theta);
-  BD_TRY(check_launch());
-  PfGemmArgs g{};
-  g.MTc = MTc; g.Mvalid = rows; g.rs = c->pf_rs; g.rope = c->pf_rope; g.x = c->pf_x; g.q = c->pf_q; g.max_kb = c->max_kb; g.n0 = c->n;
-  g.act = c->pf_act; g.H = c->H; g.QD = c->QD; g.KVD = c->KVD; g.D = c->D; g.n_q = c->cfg.n_q_heads;
-  g.SK = 1;
-  int parts = 0;                                   // K splits of the last down projection still to be added to pf_x
-  for (int l = 0; l < c->L; ++l) {
-    const u16* wl = c->pf_w + (size_t)l * c->pf_layer_elems;
-    g.Kc = c->Kc + (size_t)l * c->kv_layer_elems;
-    g.Vc = c->Vc + (size_t)l * c->kv_layer_elems;
-    // e4m3 weights: the norm gains go into the activation copy and the row scales onto the accumulators (as in decode)
-    const float* ws = c->fp8 ? c->wscale + (size_t)l * c->wscale_layer : nullptr;
-    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc / 4), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
-                       c->fp8 ? c->gains + (size_t)(2 * l) * c->H : nullptr, c->pf_part, parts);
-    parts = 0;
-    BD_TRY(check_launch());
-    g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[0]); g.KS = ceil_div(c->H, 32);
-    g.xin = reinterpret_cast<const bf16x8*>(c->pf_xb);
-    g.wscale = ws ? ws + c->wscale_off[0] : nullptr;
-    // (every phase: the direct-to-LDS kernel when K is a whole number of stages, else the register-staged one)
-    if (!c->pf_staged && g.KS % 2 == 0) BD_TRY((launch_pf_gemm_direct<PH_QKV, 2, 2, 2, 2, 4>(c, g, c->NQKV)));
-    else BD_TRY((launch_pf_gemm<PH_QKV, 2, 2, 2>(c, g, c->NQKV)));
-    {
-      PfAttnArgs t{};
-      t.q = c->pf_q; t.Kc = g.Kc; t.Vc = g.Vc; t.max_kb = c->max_kb; t.n0 = c->n; t.Mc = mc; t.n_q = c->cfg.n_q_heads;
-      t.n_kv = c->cfg.n_kv_heads; t.scale_log2e = 1.4426950408889634f / std::sqrt((float)c->D); t.out = c->pf_ap; t.MTc = MTc;
-      const int items = t.n_q * (mc / 16);                    // one item per workgroup, its four wavefronts share the blocks
-      if (c->D == 128) hipLaunchKernelGGL((pf_attn_kernel<128, 4>), dim3(items), dim3(kPfThreads), 0, s, t);
-      else hipLaunchKernelGGL((pf_attn_kernel<64, 4>), dim3(items), dim3(kPfThreads), 0, s, t);
-      BD_TRY(check_launch());
-    }
-    g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[1]); g.KS = ceil_div(c->QD, 32);
-    g.xin = reinterpret_cast<const bf16x8*>(c->pf_ap);
-    g.wscale = ws ? ws + c->wscale_off[1] : nullptr;
-    if (!c->pf_staged && g.KS % 4 == 0) BD_TRY((launch_pf_gemm_direct<PH_O, 2, 4, 2, 2, 2>(c, g, c->H)));
-    else BD_TRY((launch_pf_gemm<PH_O, 2, 4, 2>(c, g, c->H)));
-    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc / 4), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
-                       c->fp8 ? c->gains + (size_t)(2 * l + 1) * c->H : nullptr, (const float*)nullptr, 0);
-    BD_TRY(check_launch());
-    g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[2]); g.KS = ceil_div(c->H, 32);
-    g.xin = reinterpret_cast<const bf16x8*>(c->pf_xb);
-    g.wscale = ws ? ws + c->wscale_off[2] : nullptr;
-    // gate/up: 256 rows x 128 tokens per workgroup (a 128 x 64 tile per wavefront), one k-step per stage: 97 us for the
-    // 3B shape against 110 us with 128 x 128 tiles and 136 us with the register-staged kernel
-    if (!c->pf_staged) BD_TRY((launch_pf_gemm_direct<PH_GU, 8, 1, 4, 2, 2>(c, g, 2 * c->F)));
-    else BD_TRY((launch_pf_gemm<PH_GU, 4, 2, 4>(c, g, 2 * c->F)));
-    g.w = reinterpret_cast<const bf16x8*>(wl + c->pf_off[3]); g.KS = ceil_div(c->F, 32);
-    g.xin = reinterpret_cast<const bf16x8*>(c->pf_act);
-    g.wscale = ws ? ws + c->wscale_off[3] : nullptr;
-    // down: K split four ways over workgroups with 128 x 128 tiles when K divides; the next norm adds the splits
-    if (!c->pf_staged && g.KS % (2 * kPfSplit) == 0) {
-      g.SK = kPfSplit; g.part = c->pf_part;
-      BD_TRY((launch_pf_gemm_direct<PH_DOWN, 4, 2, 4, 2, 2>(c, g, c->H)));
-      g.SK = 1; g.part = nullptr;
-      parts = kPfSplit;
-    } else {
-      BD_TRY((launch_pf_gemm<PH_DOWN, 2, 4, 2>(c, g, c->H)));
-    }
-  }
-  if (parts > 0) {
-    // the last layer's splits: the same kernel completes the residual stream (its other outputs are not used)
-    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc / 4), dim3(kPfThreads), 0, s, c->pf_x, c->H, c->cfg.rms_eps, c->pf_xb, MTc, c->pf_rs,
-                       (const float*)nullptr, c->pf_part, parts);
-    BD_TRY(check_launch());
-  }
-  return BD_OK;
+  PfChunk p{};
+  p.rows = rows; p.off = off; p.n0 = c->n;
+  p.embeds = dev_embeds; p.n_embed = n_embed; p.ids = dev_ids;
+  p.table = c->embed; p.vocab = c->V; p.mask_id = c->cfg.mask_token_id;
+  p.L = c->L; p.H = c->H; p.QD = c->QD; p.KVD = c->KVD; p.NQKV = c->NQKV; p.F = c->F; p.D = c->D;
+  p.n_q = c->cfg.n_q_heads; p.n_kv = c->cfg.n_kv_heads; p.max_kb = c->max_kb;
+  p.rms_eps = c->cfg.rms_eps; p.rope_theta = c->cfg.rope_theta;
+  p.st = c->st;
+  p.fp8 = c->fp8; p.staged = c->pf_staged;
+  p.gains = c->gains; p.wscale = c->wscale; p.wscale_layer = c->wscale_layer;
+  for (int i = 0; i < 4; ++i) { p.wscale_off[i] = c->wscale_off[i]; p.w_off[i] = c->pf_off[i]; }
+  p.w = c->pf_w; p.layer_elems = c->pf_layer_elems;
+  p.Kc = c->Kc; p.Vc = c->Vc; p.kv_layer_elems = c->kv_layer_elems;
+  p.x = c->pf_x; p.xb = c->pf_xb; p.rs = c->pf_rs; p.rope = c->pf_rope; p.q = c->pf_q; p.ap = c->pf_ap; p.act = c->pf_act;
+  p.part = c->pf_part;
+  return launch_prefill_chunk(c->stream, p);
 }
 
 }  // namespace
@@ -567,6 +368,7 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
     if (G % 2 != 0) return BD_E_ARG;
   }
   if (k.weight_dtype != BD_BF16 && k.weight_dtype != BD_FP8_E4M3) return BD_E_DTYPE;
+  if (k.flags & ~(BD_FLAG_CHIP_WIDE_HANDOVER | BD_FLAG_REGISTER_RING | BD_FLAG_PREFILL_DECODE | BD_FLAG_PREFILL_STAGED)) return BD_E_ARG;
   if (k.weight_dtype == BD_FP8_E4M3 && k.max_block > 32) return BD_E_ARG;   // e4m3 weights: forwards of up to 32 rows
 
   int dev = 0;
@@ -581,7 +383,7 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   c->device = dev;
   c->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   c->fp8 = k.weight_dtype == BD_FP8_E4M3;
-  if (const char* e = getenv("BD_FORWARD_KERNEL")) c->use_stream = c->fp8 || strcmp(e, "ring") != 0;
+  c->use_stream = c->fp8 || !(k.flags & BD_FLAG_REGISTER_RING);
   c->H = k.hidden; c->D = k.head_dim; c->QD = k.n_q_heads * k.head_dim; c->KVD = k.n_kv_heads * k.head_dim;
   c->NQKV = c->QD + 2 * c->KVD; c->F = k.ffn; c->V = k.vocab; c->L = k.n_layers; c->G = k.n_q_heads / k.n_kv_heads;
   c->Mp_max = ceil_div(k.max_block, 16) * 16;
@@ -622,9 +424,9 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
     // attention partials of one layer: sized for the largest item count any (M, n) can produce
     size_t tiles = 0; int groups_max = 0;
     for (int MT = 1; MT <= (int)Mp / 16; ++MT) {
-      const int JT = attn_jt(c, MT, true);
+      const int JT = attn_jt(c, MT);
       const int groups = k.n_kv_heads * (c->G * MT / JT);
-      tiles = std::max(tiles, (size_t)groups * attn_max_chunks(c, MT, true) * JT);
+      tiles = std::max(tiles, (size_t)groups * attn_max_chunks(c, MT) * JT);
       groups_max = std::max(groups_max, groups);
       if (MT <= 2) {   // the streaming kernel works on single column tiles
         const int sg = k.n_kv_heads * c->G * MT;
@@ -653,9 +455,8 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   {
     // Large-M prefill for contexts whose cache can hold a chunk of 128 rows plus the prompt's last rows.  (e4m3
     // decoder linears are widened into the bf16 copy, exactly; their row scales stay in the epilogue.)
-    const char* e = getenv("BD_PREFILL");
-    c->pf_on = k.max_seq > kPfTokens && !(e != nullptr && strcmp(e, "chunked") == 0);
-    c->pf_staged = e != nullptr && strcmp(e, "staged") == 0;   // register-staged GEMMs only (else: the fallback for K tails)
+    c->pf_on = k.max_seq > kPfTokens && !(k.flags & BD_FLAG_PREFILL_DECODE);
+    c->pf_staged = (k.flags & BD_FLAG_PREFILL_STAGED) != 0;     // register-staged GEMMs only (else: the fallback for K tails)
     if (c->pf_on) {
       c->pf_rows = std::min(1024, (k.max_seq - 1) / kPfTokens * kPfTokens);
       const size_t R = (size_t)c->pf_rows;
@@ -1195,172 +996,3 @@ int64_t bd_k_class_bytes(const bd_ctx* c, int kclass) {
 
 }  // extern "C"
 
-namespace {
-// ---- launch helpers of the stand-alone GEMM / attention entry points -----------------------------------
-GemmPlan plan_gemm(int num_cus, int n_tiles, int KS) {
-  GemmPlan p;
-  p.NT = (n_tiles % 2 == 0) ? 2 : 1;
-  const int groups = n_tiles / p.NT;
-  int ks = (3 * num_cus / 2 + groups - 1) / groups;
-  ks = std::max(1, std::min(ks, std::max(1, KS / 8)));
-  p.ksplit = std::min(ks, 16);
-  p.grid = groups * p.ksplit;
-  return p;
-}
-
-int launch_gemm_partial(const GemmArgs& a, int MT, int NT, int grid, hipStream_t s) {
-#define BD_CASE(mt, nt) \
-  if (MT == mt && NT == nt) { hipLaunchKernelGGL((gemm_kernel<mt, nt, EPI_PARTIAL>), dim3(grid), dim3(kWGThreads), 0, s, a); return check_launch(); }
-  BD_CASE(1, 1) BD_CASE(2, 1) BD_CASE(3, 1) BD_CASE(4, 1) BD_CASE(1, 2) BD_CASE(2, 2) BD_CASE(3, 2) BD_CASE(4, 2)
-#undef BD_CASE
-  return BD_E_ARG;
-}
-
-template <int D>
-int launch_attention_d(hipStream_t s, const AttnArgs& a, int JT, int grid_p, int grid_c) {
-#define BD_ATT(jt)                                                                                      \
-  if (JT == jt) {                                                                                       \
-    hipLaunchKernelGGL((attn_partial_kernel<D, jt>), dim3(grid_p), dim3(kWGThreads), 0, s, a);           \
-    BD_TRY(check_launch());                                                                             \
-    hipLaunchKernelGGL((attn_combine_kernel<D, jt>), dim3(grid_c), dim3(kWGThreads), 0, s, a);           \
-    return check_launch();                                                                              \
-  }
-  BD_ATT(1) BD_ATT(2) BD_ATT(4)
-#undef BD_ATT
-  return BD_E_ARG;
-}
-
-int attention(bd_ctx* c, int layer, int M, int mode) {
-  const int MT = ceil_div(M, 16);
-  const int JT = attn_jt(c, MT);
-  const int groups = c->cfg.n_kv_heads * (c->G * MT / JT);
-  AttnArgs a{};
-  a.Q = c->q;
-  a.Kc = reinterpret_cast<const bf16x8*>(c->Kc + (size_t)layer * c->kv_layer_elems);
-  a.Vc = reinterpret_cast<const bf16x8*>(c->Vc + (size_t)layer * c->kv_layer_elems);
-  a.st = c->st;
-  a.M = M; a.MT = MT; a.n_q = c->cfg.n_q_heads; a.n_kv = c->cfg.n_kv_heads; a.mode = mode; a.max_kb = c->max_kb;
-  a.max_chunks = attn_max_chunks(c, MT);
-  a.scale_log2e = 1.4426950408889634f / std::sqrt((float)c->D);
-  a.pO = c->pO; a.pm = c->pm; a.pl = c->pl; a.out = c->ap;
-  const int n_kb = ceil_div(c->n + M, 32);
-  const int chunk_len = std::max(kWavesPerWG, ceil_div(n_kb, a.max_chunks));
-  const int n_chunks = ceil_div(n_kb, chunk_len);
-  const int grid_p = groups * n_chunks;
-  if (grid_p > c->attn_items_max) return BD_E_ARG;
-  if (c->D == 128) return launch_attention_d<128>(c->stream, a, JT, grid_p, groups);
-  return launch_attention_d<64>(c->stream, a, JT, grid_p, groups);
-}
-}  // namespace
-
-namespace {
-struct TmpBufs {
-  std::vector<void*> p;
-  ~TmpBufs() { for (void* q : p) hipFree(q); }
-  template <typename T> int get(T** out, size_t bytes) {
-    void* q = nullptr;
-    HIP_TRY(hipMalloc(&q, bytes));
-    HIP_TRY(hipMemset(q, 0, bytes));
-    p.push_back(q);
-    *out = static_cast<T*>(q);
-    return BD_OK;
-  }
-};
-
-int timed_loop(hipStream_t s, int iters, float* avg_ms, const std::function<int()>& body) {
-  hipEvent_t e0, e1;
-  HIP_TRY(hipEventCreate(&e0));
-  HIP_TRY(hipEventCreate(&e1));
-  int rc = body();                                   // first launch also serves as warm-up
-  if (rc == BD_OK && iters > 1) {
-    hipEventRecord(e0, s);
-    for (int i = 0; i < iters && rc == BD_OK; ++i) rc = body();
-    hipEventRecord(e1, s);
-  }
-  hipError_t e = hipStreamSynchronize(s);
-  if (rc == BD_OK && e != hipSuccess) {
-    snprintf(g_last_error, sizeof g_last_error, "kernel failed: %s", hipGetErrorString(e));
-    rc = BD_E_HIP;
-  }
-  if (rc == BD_OK && avg_ms != nullptr) {
-    float ms = 0.f;
-    if (iters > 1) { hipEventElapsedTime(&ms, e0, e1); ms /= (float)iters; }
-    *avg_ms = ms;
-  }
-  hipEventDestroy(e0);
-  hipEventDestroy(e1);
-  return rc;
-}
-}  // namespace
-
-extern "C" int bd_k_gemm(void* hip_stream, const uint16_t* dev_w, const float* dev_x, int M, int N, int K,
-                         float* dev_y, int iters, float* avg_ms) {
-  if (dev_w == nullptr || dev_x == nullptr || dev_y == nullptr) return BD_E_ARG;
-  if (M < 1 || M > 64 || N < 16 || N % 16 != 0 || K < 1 || iters < 1) return BD_E_ARG;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const int MT = ceil_div(M, 16), KS = ceil_div(K, 32);
-  int dev = 0;
-  HIP_TRY(hipGetDevice(&dev));
-  hipDeviceProp_t prop;
-  HIP_TRY(hipGetDeviceProperties(&prop, dev));
-  GemmPlan p = plan_gemm(prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256, N / 16, KS);
-  TmpBufs t;
-  u16 *wp, *xp; float* ws;
-  BD_TRY(t.get(&wp, (size_t)N * KS * 32 * 2));
-  BD_TRY(t.get(&xp, (size_t)KS * 32 * MT * 16 * 2));
-  BD_TRY(t.get(&ws, (size_t)p.ksplit * MT * 16 * N * 4));
-  hipLaunchKernelGGL(pack_weight_kernel<u16>, dim3(2048), dim3(256), 0, s, dev_w, (const float*)nullptr, N, K, KS, wp, 0, 1);
-  hipLaunchKernelGGL(pack_x_kernel, dim3(256), dim3(256), 0, s, dev_x, M, K, xp, MT);
-  BD_TRY(check_launch());
-  GemmArgs a{};
-  a.Wp = reinterpret_cast<const bf16x8*>(wp); a.Xp = reinterpret_cast<const bf16x8*>(xp);
-  a.n_tiles = N / 16; a.KS = KS; a.ksplit = p.ksplit; a.M = M; a.N = N; a.partial = ws;
-  BD_TRY(timed_loop(s, iters, avg_ms, [&]() { return launch_gemm_partial(a, MT, p.NT, p.grid, s); }));
-  hipLaunchKernelGGL(reduce_partial_kernel, dim3(512), dim3(256), 0, s, ws, p.ksplit, MT * 16, N, M, dev_y);
-  BD_TRY(check_launch());
-  HIP_TRY(hipStreamSynchronize(s));
-  return BD_OK;
-}
-
-extern "C" int bd_k_attention(void* hip_stream, const float* dev_q, const float* dev_k, const float* dev_v,
-                              int n_prefix, int M, int n_q, int n_kv, int D, int mode, float* dev_out, int iters,
-                              float* avg_ms) {
-  if (dev_q == nullptr || dev_k == nullptr || dev_v == nullptr || dev_out == nullptr) return BD_E_ARG;
-  if (M < 1 || M > 64 || n_prefix < 0 || n_q < 1 || n_kv < 1 || n_q % n_kv != 0 || (D != 64 && D != 128)) return BD_E_ARG;
-  if ((mode != BD_MODE_BIDIR && mode != BD_MODE_CAUSAL) || iters < 1) return BD_E_ARG;
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  int dev = 0;
-  HIP_TRY(hipGetDevice(&dev));
-  hipDeviceProp_t prop;
-  HIP_TRY(hipGetDeviceProperties(&prop, dev));
-  bd_ctx c;                                          // a context shell holding just the attention state
-  c.stream = s;
-  c.num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-  c.cfg.n_q_heads = n_q; c.cfg.n_kv_heads = n_kv; c.D = D; c.G = n_q / n_kv; c.QD = n_q * D;
-  const int T = n_prefix + M, MT = ceil_div(M, 16), Mp = MT * 16;
-  c.max_kb = ceil_div(T, 32);
-  c.kv_layer_elems = (size_t)n_kv * c.max_kb * 32 * D;
-  c.n = n_prefix;
-  TmpBufs t;
-  const int JT = attn_jt(&c, MT);
-  const int groups = n_kv * (c.G * MT / JT);
-  const int mc = attn_max_chunks(&c, MT);
-  c.attn_items_max = groups * mc;
-  BD_TRY(t.get(&c.Kc, c.kv_layer_elems * 2));
-  BD_TRY(t.get(&c.Vc, c.kv_layer_elems * 2));
-  BD_TRY(t.get(&c.q, (size_t)Mp * n_q * D * 2));
-  BD_TRY(t.get(&c.ap, (size_t)ceil_div(c.QD, 32) * 32 * Mp * 2));
-  BD_TRY(t.get(&c.pO, (size_t)c.attn_items_max * JT * (D / 16) * 64 * 16));
-  BD_TRY(t.get(&c.pm, (size_t)c.attn_items_max * JT * 16 * 4));
-  BD_TRY(t.get(&c.pl, (size_t)c.attn_items_max * JT * 16 * 4));
-  BD_TRY(t.get(&c.st, sizeof(DevState)));
-  hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, s, c.st, n_prefix, 1);
-  hipLaunchKernelGGL(pack_kv_kernel, dim3(1024), dim3(256), 0, s, dev_k, dev_v, T, n_kv, D, c.max_kb, c.Kc, c.Vc);
-  hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(64), dim3(256), 0, s, dev_q, c.q, (size_t)M * n_q * D);
-  BD_TRY(check_launch());
-  BD_TRY(timed_loop(s, iters, avg_ms, [&]() { return attention(&c, 0, M, mode); }));
-  hipLaunchKernelGGL(unpack_x_kernel, dim3(256), dim3(256), 0, s, c.ap, M, c.QD, dev_out, MT);
-  BD_TRY(check_launch());
-  HIP_TRY(hipStreamSynchronize(s));
-  return BD_OK;
-}

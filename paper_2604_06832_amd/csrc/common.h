@@ -41,6 +41,48 @@ __device__ inline size_t xp_index(int m, int k, int MT) {
   return (((size_t)ks * MT + mt) * 64 + lane) * 8 + e;
 }
 
+// ---- packed cache layouts (per layer, per kv head; key blocks of 32 keys) --------------------------
+// K: block kb, half t (0/1), d-step ds (32 dims):  lane l holds key kb*32 + 8*(i/4) + 4*t + (i%4) with
+//    i = l & 15, dims ds*32 + 8*(l>>4) .. +7.            index ((kb*2 + t)*DS + ds)*64 + l   (bf16x8)
+// V: block kb, d-tile dt (16 dims): lane l holds dim dt*16 + (l & 15), keys kb*32 + 8*(l>>4) .. +7.
+//                                                        index (kb*DT + dt)*64 + l           (bf16x8)
+// The K cache stores the 32 keys of a block in the row order that makes the two S^T accumulator tiles of a lane
+// (S^T[key, col] = K[key, :] . Q[col, :]) line up with the k-order of the P fragment of O^T = V^T . P^T.
+__device__ inline size_t kp_index(int key, int d, int DS) {   // element index of K[key][d]
+  const int kb = key >> 5, kk = key & 31;
+  const int g = kk >> 3, e = kk & 7, t = e >> 2, r = e & 3, i = 4 * g + r;
+  const int ds = d >> 5, kq = (d >> 3) & 3;
+  return ((((size_t)kb * 2 + t) * DS + ds) * 64 + kq * 16 + i) * 8 + (d & 7);
+}
+__device__ inline size_t vp_index(int key, int d, int DT) {   // element index of V[key][d]
+  const int kb = key >> 5, kk = key & 31;
+  const int g = kk >> 3, e = kk & 7;
+  return ((((size_t)kb * DT + (d >> 4)) * 64) + g * 16 + (d & 15)) * 8 + e;
+}
+
+constexpr float kNegBig = -1.0e30f;
+
+// Merge two (max, argmax, sum of exp(. - max)) triples; equal maxima keep the lower index.
+// A triple with s == 0 is the empty set (its max is -inf) and merges as the identity.
+__device__ inline void stat_merge(float& m, int& i, float& s, float m2, int i2, float s2) {
+  if (s2 == 0.f) return;
+  if (s == 0.f || m2 > m || (m2 == m && i2 < i)) {
+    s = s * __expf(m - m2) + s2;
+    m = m2;
+    i = i2;
+  } else {
+    s = s + s2 * __expf(m2 - m);
+  }
+}
+
+// Chunk geometry of the key-split attention: n_kb key blocks are cut into chunks of chunk_len blocks.
+__device__ inline void attn_chunks(int n_keys, int max_chunks, int& n_kb, int& chunk_len, int& n_chunks) {
+  n_kb = (n_keys + 31) >> 5;
+  chunk_len = (n_kb + max_chunks - 1) / max_chunks;
+  if (chunk_len < kWavesPerWG) chunk_len = kWavesPerWG;
+  n_chunks = (n_kb + chunk_len - 1) / chunk_len;
+}
+
 // In-block visibility of the block's key jb (0-based index inside the block) for the block's query row `row`
 // (Sec. 3.3 mask rules; Alg. 1 draft / verify masks; Alg. 2 quadratic mask).  mode 0: all visible; 1: causal;
 // 2 + (B << 8): B groups of B+1 rows, a group's first row sees the first rows of the groups up to its own, every other

@@ -1,0 +1,135 @@
+// Translation unit of the large-M prefill kernels (prefill.h) and the host sequence that runs one chunk of prompt
+// rows through all layers.
+#include <cmath>
+
+#include "launch.h"
+#include "prefill.h"
+
+namespace bd {
+namespace {
+
+// Tile shapes per phase (rows per workgroup = 32*WN, k-steps per stage BKS, tokens per workgroup = 32*TW), picked by
+// measurement at 1024 rows: gate/up 128 rows x 128 tokens x 2 k-steps, down and O 64 x 64 x 4, QKV 64 x 64 x 2 (the
+// phases with 2048-2560 output rows need the smaller token tile to put two workgroups on every CU).
+template <int PH, int WN, int BKS, int TW>
+int launch_pf_gemm(hipStream_t s, PfGemmArgs a, int n_rows) {
+  static bool attr_set = false;
+  constexpr int lds = pf_gemm_lds<WN, BKS, TW>();
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_kernel<PH, WN, BKS, TW>), hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    attr_set = true;
+  }
+  a.NT = n_rows / 16;
+  a.RG = ceil_div(a.NT, 2 * WN);
+  a.TG = ceil_div(a.MTc, 2 * TW);
+  const int grid = ceil_div(a.RG, 8) * 8 * a.TG;
+  hipLaunchKernelGGL((pf_gemm_kernel<PH, WN, BKS, TW>), dim3(grid), dim3(kPfThreads), lds, s, a);
+  return check_launch();
+}
+
+template <int PH, int WN, int BKS, int TW, int NST, int OCC>
+int launch_pf_gemm_direct(hipStream_t s, PfGemmArgs a, int n_rows) {
+  static bool attr_set = false;
+  constexpr int lds = pf_gemm_direct_lds<WN, BKS, TW, NST>();
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&pf_gemm_direct_kernel<PH, WN, BKS, TW, NST, OCC>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    attr_set = true;
+  }
+  static_assert(OCC * lds <= 160 * 1024, "workgroups per CU bounded by LDS");
+  if (a.KS % BKS != 0) return BD_E_ARG;
+  a.NT = n_rows / 16;
+  a.RG = ceil_div(a.NT, 2 * WN);
+  a.TG = ceil_div(a.MTc, 2 * TW);
+  if (a.SK < 1 || (a.KS / BKS) % a.SK != 0) return BD_E_ARG;
+  const int grid = ceil_div(a.RG, 8) * 8 * a.TG * a.SK;
+  hipLaunchKernelGGL((pf_gemm_direct_kernel<PH, WN, BKS, TW, NST, OCC>), dim3(grid), dim3(kPfThreads), lds, s, a);
+  return check_launch();
+}
+
+}  // namespace
+
+// One chunk of c.rows prompt rows starting at prompt row c.off = cache position c.n0: all layers, K/V into the cache,
+// no LM head.  The kernels work on whole tiles of 16 rows: the rows that pad the last tile are zero on entry, take part
+// in every product and write nothing to the cache.  The device-side length is advanced by the caller.
+int launch_prefill_chunk(hipStream_t s, const PfChunk& c) {
+  const int rows = c.rows;
+  const int MTc = ceil_div(rows, 16);
+  const int mc = MTc * 16;
+  hipLaunchKernelGGL(embed_kernel, dim3(rows), dim3(kWGThreads), 0, s, c.x, c.H, c.embeds, c.n_embed, c.ids, c.off,
+                     (const uint8_t*)nullptr, c.mask_id, c.table, c.vocab);
+  BD_TRY(check_launch());
+  if (mc > rows) {
+    hipLaunchKernelGGL(zero_rows_kernel, dim3(mc - rows), dim3(kWGThreads), 0, s, c.x + (size_t)rows * c.H, c.H);
+    BD_TRY(check_launch());
+  }
+  hipLaunchKernelGGL(rope_table_kernel, dim3(mc), dim3(64), 0, s, c.rope, c.st, c.D / 2, c.rope_theta);
+  BD_TRY(check_launch());
+  PfGemmArgs g{};
+  g.MTc = MTc; g.Mvalid = rows; g.rs = c.rs; g.rope = c.rope; g.x = c.x; g.q = c.q; g.max_kb = c.max_kb; g.n0 = c.n0;
+  g.act = c.act; g.H = c.H; g.QD = c.QD; g.KVD = c.KVD; g.D = c.D; g.n_q = c.n_q;
+  g.SK = 1;
+  int parts = 0;                                   // K splits of the last down projection still to be added to x
+  for (int l = 0; l < c.L; ++l) {
+    const u16* wl = c.w + (size_t)l * c.layer_elems;
+    g.Kc = c.Kc + (size_t)l * c.kv_layer_elems;
+    g.Vc = c.Vc + (size_t)l * c.kv_layer_elems;
+    // e4m3 weights: the norm gains go into the activation copy and the row scales onto the accumulators (as in decode)
+    const float* ws = c.fp8 ? c.wscale + (size_t)l * c.wscale_layer : nullptr;
+    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc / 4), dim3(kPfThreads), 0, s, c.x, c.H, c.rms_eps, c.xb, MTc, c.rs,
+                       c.fp8 ? c.gains + (size_t)(2 * l) * c.H : nullptr, c.part, parts);
+    parts = 0;
+    BD_TRY(check_launch());
+    g.w = reinterpret_cast<const bf16x8*>(wl + c.w_off[0]); g.KS = ceil_div(c.H, 32);
+    g.xin = reinterpret_cast<const bf16x8*>(c.xb);
+    g.wscale = ws ? ws + c.wscale_off[0] : nullptr;
+    // (every phase: the direct-to-LDS kernel when K is a whole number of stages, else the register-staged one)
+    if (!c.staged && g.KS % 2 == 0) BD_TRY((launch_pf_gemm_direct<PH_QKV, 2, 2, 2, 2, 4>(s, g, c.NQKV)));
+    else BD_TRY((launch_pf_gemm<PH_QKV, 2, 2, 2>(s, g, c.NQKV)));
+    {
+      PfAttnArgs t{};
+      t.q = c.q; t.Kc = g.Kc; t.Vc = g.Vc; t.max_kb = c.max_kb; t.n0 = c.n0; t.Mc = mc; t.n_q = c.n_q;
+      t.n_kv = c.n_kv; t.scale_log2e = 1.4426950408889634f / std::sqrt((float)c.D); t.out = c.ap; t.MTc = MTc;
+      const int items = t.n_q * (mc / 16);                    // one item per workgroup, its four wavefronts share the blocks
+      if (c.D == 128) hipLaunchKernelGGL((pf_attn_kernel<128, 4>), dim3(items), dim3(kPfThreads), 0, s, t);
+      else hipLaunchKernelGGL((pf_attn_kernel<64, 4>), dim3(items), dim3(kPfThreads), 0, s, t);
+      BD_TRY(check_launch());
+    }
+    g.w = reinterpret_cast<const bf16x8*>(wl + c.w_off[1]); g.KS = ceil_div(c.QD, 32);
+    g.xin = reinterpret_cast<const bf16x8*>(c.ap);
+    g.wscale = ws ? ws + c.wscale_off[1] : nullptr;
+    if (!c.staged && g.KS % 4 == 0) BD_TRY((launch_pf_gemm_direct<PH_O, 2, 4, 2, 2, 2>(s, g, c.H)));
+    else BD_TRY((launch_pf_gemm<PH_O, 2, 4, 2>(s, g, c.H)));
+    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc / 4), dim3(kPfThreads), 0, s, c.x, c.H, c.rms_eps, c.xb, MTc, c.rs,
+                       c.fp8 ? c.gains + (size_t)(2 * l + 1) * c.H : nullptr, (const float*)nullptr, 0);
+    BD_TRY(check_launch());
+    g.w = reinterpret_cast<const bf16x8*>(wl + c.w_off[2]); g.KS = ceil_div(c.H, 32);
+    g.xin = reinterpret_cast<const bf16x8*>(c.xb);
+    g.wscale = ws ? ws + c.wscale_off[2] : nullptr;
+    // gate/up: 256 rows x 128 tokens per workgroup (a 128 x 64 tile per wavefront), one k-step per stage: 97 us for the
+    // 3B shape against 110 us with 128 x 128 tiles and 136 us with the register-staged kernel
+    if (!c.staged) BD_TRY((launch_pf_gemm_direct<PH_GU, 8, 1, 4, 2, 2>(s, g, 2 * c.F)));
+    else BD_TRY((launch_pf_gemm<PH_GU, 4, 2, 4>(s, g, 2 * c.F)));
+    g.w = reinterpret_cast<const bf16x8*>(wl + c.w_off[3]); g.KS = ceil_div(c.F, 32);
+    g.xin = reinterpret_cast<const bf16x8*>(c.act);
+    g.wscale = ws ? ws + c.wscale_off[3] : nullptr;
+    // down: K split four ways over workgroups with 128 x 128 tiles when K divides; the next norm adds the splits
+    if (!c.staged && g.KS % (2 * kPfSplit) == 0) {
+      g.SK = kPfSplit; g.part = c.part;
+      BD_TRY((launch_pf_gemm_direct<PH_DOWN, 4, 2, 4, 2, 2>(s, g, c.H)));
+      g.SK = 1; g.part = nullptr;
+      parts = kPfSplit;
+    } else {
+      BD_TRY((launch_pf_gemm<PH_DOWN, 2, 4, 2>(s, g, c.H)));
+    }
+  }
+  if (parts > 0) {
+    // the last layer's splits: the same kernel completes the residual stream (its other outputs are not used)
+    hipLaunchKernelGGL(pf_norm_kernel, dim3(mc / 4), dim3(kPfThreads), 0, s, c.x, c.H, c.rms_eps, c.xb, MTc, c.rs,
+                       (const float*)nullptr, c.part, parts);
+    BD_TRY(check_launch());
+  }
+  return BD_OK;
+}
+
+}  // namespace bd

@@ -23,200 +23,10 @@
 //   * a workgroup signals (barrier arrival, split-K counters) only after its stores have completed
 //     (s_waitcnt on the in-order vector-memory counter).
 #pragma once
-#include "attention.h"
 #include "common.h"
-#include "gemm.h"
+#include "plan.h"
 
 namespace bd {
-
-constexpr int kMaxKW = 16;   // k-steps (of 32) one wavefront covers in a GEMM phase
-constexpr int kT = 2;        // 16-row tiles a wavefront accumulates side by side (one chunk of its stream)
-constexpr int kBarGroup = 16;
-constexpr int kSpinLimit = 1 << 19;
-
-enum { PH_QKV = 0, PH_O = 1, PH_GU = 2, PH_DOWN = 3, PH_LM = 4, PH_COUNT = 5, PH_END = 6 };
-
-struct PhasePlan {
-  int N;        // output rows of the phase (after fusing / interleaving); a multiple of 16
-  int KS;       // k-steps
-  int ksplit;   // workgroups that share an output row range and split K
-  int RW;       // rows of the largest row range (a multiple of 16)
-  int kgran;    // k-steps per unit of the K split: 1 (bf16 weights) or 2 (fp8 weights: a 1-KiB fragment of 16 rows
-                // x 64 k holds two k-steps, so wavefront ranges start and end on even k-steps)
-  int wbytes;   // bytes per streamed weight element: 2 (bf16) or 1 (e4m3)
-};
-// Row ranges are whole 16-row tiles, spread over the nwg/ksplit row groups as evenly as whole tiles allow
-// (group g holds tiles [T*g/G, T*(g+1)/G)).  So every weight fragment of the stream is a full 1 KiB.
-__host__ __device__ inline int tile0_of_group(int T, int G, int g) { return (int)((long long)T * g / G); }
-__host__ __device__ inline int group_of_tile(int T, int G, int tile) { return (int)((((long long)tile + 1) * G - 1) / T); }
-
-struct MegaPlan {
-  int nwg, L, H, QD, KVD, F, V, D, n_q, n_kv;
-  PhasePlan ph[PH_COUNT];
-  long long wave_stride;   // 16-byte units reserved per wavefront in the weight stream
-  int xcd_gu;              // > 0: number of XCDs; the row groups of the gate/up phase are dealt out so that the
-                           // workgroups of XCD x (workgroup id mod xcd_gu) produce exactly the features that K slice x of
-                           // the down projection (also held by the workgroups of XCD x) consumes
-  int gu_cut;              // 1: K slices of unequal size (e4m3 contexts), see phase_tile0_t
-};
-// Tiles of a phase's row groups.  With xcd_gu the gate/up tiles belong to the XCD whose K slice of the down
-// projection they feed.  For slices of equal size (bf16 weights: required for xcd_gu) that is the plain even
-// spread; with e4m3 weights the slices are whole units of two k-steps and differ by one unit, so the gate/up tiles
-// are first cut where the slices are cut (a K unit of kgran k-steps = 4*kgran tiles) and each XCD's share is spread
-// over its workgroups (gu_cut).  CUT is a compile-time switch so that the bf16 kernels carry none of this.
-__host__ __device__ inline int gu_slice_tile0(const MegaPlan& P, int x) {
-  const PhasePlan& d = P.ph[PH_DOWN];
-  const int KU = (d.KS + d.kgran - 1) / d.kgran;
-  return min((int)((long long)KU * x / P.xcd_gu) * 4 * d.kgran, P.ph[PH_GU].N >> 4);
-}
-template <bool CUT>
-__host__ __device__ inline int phase_tile0_t(const MegaPlan& P, int p, int ng) {
-  const PhasePlan& ph = P.ph[p];
-  const int T = ph.N >> 4, G = P.nwg / ph.ksplit;
-  if constexpr (CUT) {
-    if (p == PH_GU && P.gu_cut) {
-      if (ng >= G) return T;
-      const int per = G / P.xcd_gu, x = ng / per;
-      const int b0 = gu_slice_tile0(P, x), b1 = gu_slice_tile0(P, x + 1);
-      return b0 + tile0_of_group(b1 - b0, per, ng % per);
-    }
-  }
-  return tile0_of_group(T, G, ng);
-}
-__host__ __device__ inline int phase_tile0(const MegaPlan& P, int p, int ng) {
-  return P.gu_cut ? phase_tile0_t<true>(P, p, ng) : phase_tile0_t<false>(P, p, ng);
-}
-__host__ __device__ inline int phase_group_of_tile(const MegaPlan& P, int p, int tile) {
-  const PhasePlan& ph = P.ph[p];
-  const int T = ph.N >> 4, G = P.nwg / ph.ksplit;
-  if (p == PH_GU && P.gu_cut) {
-    const int per = G / P.xcd_gu;
-    int x = 0;
-    while (x + 1 < P.xcd_gu && gu_slice_tile0(P, x + 1) <= tile) ++x;
-    const int b0 = gu_slice_tile0(P, x), b1 = gu_slice_tile0(P, x + 1);
-    return x * per + group_of_tile(b1 - b0, per, tile - b0);
-  }
-  return group_of_tile(T, G, tile);
-}
-// Row group of workgroup `wg` in phase p, and the inverse.
-__host__ __device__ inline int row_group_of_wg(const MegaPlan& P, int p, int wg) {
-  if (p == PH_GU && P.xcd_gu > 0) return (wg % P.xcd_gu) * (P.nwg / P.xcd_gu) + wg / P.xcd_gu;
-  return wg / P.ph[p].ksplit;
-}
-__host__ __device__ inline int wg_of_row_group(const MegaPlan& P, int p, int ng, int kg) {
-  if (p == PH_GU && P.xcd_gu > 0) return (ng % (P.nwg / P.xcd_gu)) * P.xcd_gu + ng / (P.nwg / P.xcd_gu);
-  return ng * P.ph[p].ksplit + kg;
-}
-
-struct WavePhase { int rows, row0, ng, kg, w0, KW; };
-
-// 16-row tiles per row range of a phase, and (row range, tile) pairs of the whole phase
-__host__ __device__ inline int phase_tpg(const PhasePlan& ph) { return (ph.RW + 15) >> 4; }
-__host__ __device__ inline int phase_tile_slots(const MegaPlan& P, int p) {
-  return (P.nwg / P.ph[p].ksplit) * phase_tpg(P.ph[p]);
-}
-
-template <bool CUT>
-__host__ __device__ inline WavePhase wave_phase_t(const MegaPlan& P, int p, int wg, int w) {
-  const PhasePlan& ph = P.ph[p];
-  WavePhase r;
-  const int ng = row_group_of_wg(P, p, wg);
-  r.ng = ng;
-  r.kg = wg % ph.ksplit;
-  {
-    const int t0 = phase_tile0_t<CUT>(P, p, ng), t1 = phase_tile0_t<CUT>(P, p, ng + 1);
-    r.row0 = t0 << 4;
-    r.rows = (t1 - t0) << 4;
-  }
-  // the K split works on units of kgran k-steps (the last unit may reach past KS: zero weights, zero activations)
-  const int KU = (ph.KS + ph.kgran - 1) / ph.kgran;
-  const int k0 = (int)((long long)KU * r.kg / ph.ksplit), k1 = (int)((long long)KU * (r.kg + 1) / ph.ksplit);
-  const int len = k1 - k0;
-  const int u0 = k0 + len * w / kWavesPerWG, u1 = k0 + len * (w + 1) / kWavesPerWG;
-  r.w0 = u0 * ph.kgran;
-  r.KW = (u1 - u0) * ph.kgran;
-  return r;
-}
-__host__ __device__ inline WavePhase wave_phase(const MegaPlan& P, int p, int wg, int w) {
-  return P.gu_cut ? wave_phase_t<true>(P, p, wg, w) : wave_phase_t<false>(P, p, wg, w);
-}
-// 16-byte units one wavefront streams in a phase: per row and k-step 32 weights of wbytes each
-__host__ __device__ inline long long wave_phase_units(const PhasePlan& ph, const WavePhase& wp) {
-  return (long long)wp.rows * 2 * ph.wbytes * wp.KW;
-}
-template <bool CUT>
-__host__ __device__ inline long long wave_layer_units_t(const MegaPlan& P, int wg, int w) {
-  long long s = 0;
-  for (int p = 0; p < PH_LM; ++p) s += wave_phase_units(P.ph[p], wave_phase_t<CUT>(P, p, wg, w));
-  return s;
-}
-__host__ __device__ inline long long wave_layer_units(const MegaPlan& P, int wg, int w) {
-  return P.gu_cut ? wave_layer_units_t<true>(P, wg, w) : wave_layer_units_t<false>(P, wg, w);
-}
-// Position (16-byte units from the wavefront's phase start) of row `lr` (local to the row range),
-// k-step `ksl` (local to the wavefront), k-quarter kq: tiles of 16 rows go in chunks of two.
-__host__ __device__ inline long long stream_pos(int rows, int KW, int lr, int ksl, int kq) {
-  const int tile = lr >> 4, i = lr & 15, c = tile >> 1, t = tile & 1;
-  const int n_tiles = (rows + 15) >> 4;
-  const int R0 = min(16, rows - 32 * c);
-  const int R1 = (2 * c + 1 < n_tiles) ? min(16, rows - 32 * c - 16) : 0;
-  const int R = t ? R1 : R0;
-  return (long long)c * 32 * 4 * KW + (long long)ksl * (R0 + R1) * 4 + (t ? R0 * 4 : 0) + kq * R + i;
-}
-
-struct MegaArgs {
-  MegaPlan P;
-  const bf16x8* wstream;
-  DevState* st;
-  unsigned* bar;              // barrier words (see grid_barrier)
-  unsigned bar_epoch;         // epoch of the last barrier of the previous forward
-  int M, MT, mode, want_lm;
-  // activations (all write-once per forward)
-  float* xv;                  // [2L+1][Mp][H] residual stream versions (fp32: the accumulation chain)
-  u16* xb;                    // [2L+1] the same versions rounded to bf16 in packed activation order (K = H): what
-                              // the norm-on-load GEMM phases read
-  size_t xb_elems;
-  float* ssq;                 // [2L+1][parts][Mp] partial sums of squares of each version
-  int ssq_parts;              // stride (parts) per version; version 0 has one part, odd versions one per
-                              // tile slot of the O phase, even versions one per tile slot of the DOWN phase
-  int Mp;
-  const float* gains;         // [2L+1][H]: attn_norm l, ffn_norm l, ..., final_norm
-  int skippable;              // this launch belongs to a step that does nothing once the block is complete (DevState::skip)
-  int local_gu;               // the gate/up -> down hand-over stays inside each XCD (stream_fwd.h): plain stores, XCD barrier
-  unsigned* xbar;             // [xcd][32 words] arrival counters of the XCD barriers
-  unsigned xbar_epoch;        // XCD barriers run before this launch
-  int fp8;                    // the decoder linears are e4m3 codes with one scale per output row: the scale multiplies
-                              // the accumulators, and the norm gains (which cannot be folded into the codes) multiply
-                              // the bf16 copies of the residual versions that feed them
-  const float* wscale;        // [L][wscale_layer] scales in phase-row order: QKV | O | gate/up | down
-  int wscale_layer;
-  int wscale_off[4];
-  float rms_eps;
-  const float2* rope;         // [Mp][D/2]
-  u16* Q;                     // [L][Mp][n_q][D]  (dims in rotary-pair order)
-  u16* Kc; u16* Vc;           // packed caches, [L][n_kv][max_kb] blocks
-  size_t kv_layer_elems;
-  int max_kb;
-  u16* ap;                    // [L] packed attention output (K = QD)
-  size_t ap_elems;
-  u16* act;                   // [L] packed SwiGLU output (K = F)
-  size_t act_elems;
-  float* wsD;                 // [L][ksplit][tiles][MT][64] f32x4 partials of the down projection
-  size_t wsD_layer_floats;
-  unsigned* cntD;             // [L][H/16] arrival counters (zeroed by the prologue kernel)
-  // attention
-  float* pO; float* pm; float* pl;   // per layer partials
-  size_t pO_layer_floats, pml_layer_floats;
-  unsigned* cntA;             // [L][groups]
-  int attn_max_chunks;
-  float scale_log2e;
-  // LM head
-  float* lm_max; int* lm_idx; float* lm_sum;   // [nwg][Mp]
-  float* logits;
-  int* row_cand; float* row_conf;
-  unsigned long long* trace;  // optional [nwg][10L+4] timestamps of phase boundaries (nullptr = off)
-  unsigned long long* trace2; // optional [nwg][64] timestamps inside the GEMM phases of layer 1
-};
 
 // ---- write-through stores and ordered waits ---------------------------------------------------------------
 __device__ inline void st_wt_u32(void* p, uint32_t v) {
@@ -1170,190 +980,6 @@ __global__ __launch_bounds__(kWGThreads, 1) void lm_kernel(MegaArgs a) {
       a.row_cand[r] = i;
       a.row_conf[r] = 1.f / s;
     }
-  }
-}
-
-// ---- prologue: block assembly (seed, embedding gather), first sum of squares, rotary table, counters ------------
-struct PrologueArgs {
-  float* x0; float* ssq0; int H, Mp;
-  u16* xb0; int MT;
-  const float* embeds; int n_embed; const int* ids; int off;
-  int* seed_tokens; uint8_t* seed_mask;       // denoise only: position 0 takes the carry if still masked
-  const uint8_t* mask; int mask_id; const u16* table; int vocab;
-  DevState* st;
-  float2* rope; int half; float theta;
-  unsigned* counters; int n_counters;
-  int skippable;                              // nothing to do once the block is complete (DevState::skip)
-  int quad_W;                                 // > 0: rows are groups of quad_W tokens, row r sits at position n + r / W + r % W (Alg. 2)
-  const float* gain0;                         // fp8 weights: gain of the first norm, applied to the bf16 copy (else nullptr)
-};
-
-__global__ __launch_bounds__(kWGThreads) void prologue_kernel(PrologueArgs a) {
-  __shared__ float wsum[kWavesPerWG];
-  __shared__ int s_id;
-  const int r = blockIdx.x;
-  if (a.skippable && a.st->skip) return;
-  for (int i = blockIdx.x * kWGThreads + threadIdx.x; i < a.n_counters; i += gridDim.x * kWGThreads) a.counters[i] = 0u;
-  {
-    const double pos = (double)(a.st->n + (a.quad_W > 0 ? r / a.quad_W + r % a.quad_W : r));
-    for (int i = threadIdx.x; i < a.half; i += kWGThreads) {
-      const double inv = exp2(-log2((double)a.theta) * (double)i / (double)a.half);
-      const double ang = pos * inv;
-      a.rope[(size_t)r * a.half + i] = make_float2((float)cos(ang), (float)sin(ang));
-    }
-  }
-  const int p = a.off + r;
-  if (threadIdx.x == 0) {
-    int id = -1;
-    if (p >= a.n_embed) {
-      const int j = p - a.n_embed;
-      if (r == 0 && a.seed_mask != nullptr) {
-        a.st->seeded = 0;
-        if (a.seed_mask[0]) {
-          a.seed_tokens[0] = a.st->carry_cand;
-          a.seed_mask[0] = 0;
-          a.st->seeded = 1;
-        }
-      }
-      id = a.ids[j];
-      if (a.mask != nullptr && a.mask[j]) id = a.mask_id;
-      id = min(max(id, 0), a.vocab - 1);
-    }
-    s_id = id;
-  }
-  __syncthreads();
-  const int id = s_id;
-  float ss = 0.f;
-  for (int c = threadIdx.x; c < a.H; c += kWGThreads) {
-    const float v = id < 0 ? a.embeds[(size_t)p * a.H + c] : bf16_bits_to_f32(a.table[(size_t)id * a.H + c]);
-    a.x0[(size_t)r * a.H + c] = v;
-    a.xb0[xp_index(r, c, a.MT)] = f32_to_bf16_bits(a.gain0 != nullptr ? v * a.gain0[c] : v);
-    ss += v * v;
-  }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
-  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = ss;
-  __syncthreads();
-  if (threadIdx.x == 0) a.ssq0[r] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
-}
-
-// ---- weight stream packing ----------------------------------------------------------------------------------
-// One source matrix (row-major [n_rows][K], fp32 or bf16 bits) goes into the stream of phase `ph` of
-// layer `layer`; `row_map` says where source row r sits among the phase's output rows:
-//   0: row_base + r                       (plain)
-//   1: rotary pairing inside heads of D   (Q and K: dim i -> 2i, dim i + D/2 -> 2i + 1)
-//   2: row_base + 2*r                     (gate: even rows, up: odd rows with row_base = 1)
-template <typename SrcT>
-__global__ void pack_stream_kernel(const SrcT* __restrict__ src, int n_rows, int K, MegaPlan P, int ph, int layer,
-                                   int row_base, int row_map, int D, const float* __restrict__ col_gain,
-                                   u16* __restrict__ stream) {
-  const int KS = P.ph[ph].KS;
-  const size_t total = (size_t)n_rows * KS * 4;             // one thread per (row, k-step, k-quarter)
-  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total;
-       idx += (size_t)gridDim.x * blockDim.x) {
-    const int kq = idx & 3;
-    const int ks = (int)((idx >> 2) % KS);
-    const int rs = (int)(idx / ((size_t)KS * 4));
-    int r;
-    if (row_map == 1) {
-      const int h = rs / D, d = rs % D, half = D >> 1;
-      r = row_base + h * D + (d < half ? 2 * d : 2 * (d - half) + 1);
-    } else if (row_map == 2) {
-      r = row_base + 2 * rs;
-    } else {
-      r = row_base + rs;
-    }
-    const PhasePlan& pp = P.ph[ph];
-    const int ng = phase_group_of_tile(P, ph, r >> 4);
-    const int lr = r - (phase_tile0(P, ph, ng) << 4);
-    // which K group / wavefront holds k-step ks
-    int kg = 0;
-    while ((int)((long long)pp.KS * (kg + 1) / pp.ksplit) <= ks) ++kg;
-    const int wg = wg_of_row_group(P, ph, ng, kg);
-    int w = 0;
-    WavePhase wp = wave_phase(P, ph, wg, 0);
-    while (ks >= wp.w0 + wp.KW) { ++w; wp = wave_phase(P, ph, wg, w); }
-    long long pos = (long long)(wg * kWavesPerWG + w) * P.wave_stride;
-    pos += (ph == PH_LM) ? (long long)P.L * wave_layer_units(P, wg, w) : (long long)layer * wave_layer_units(P, wg, w);
-    for (int q = 0; q < ph && ph != PH_LM; ++q) pos += wave_phase_units(P.ph[q], wave_phase(P, q, wg, w));
-    pos += stream_pos(wp.rows, wp.KW, lr, ks - wp.w0, kq);
-    u16* dst = stream + (size_t)pos * 8;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int k = ks * 32 + kq * 8 + e;
-      u16 o = 0;
-      if (k < K) {
-        float f;
-        if constexpr (sizeof(SrcT) == 4) f = ((const float*)src)[(size_t)rs * K + k];
-        else f = bf16_bits_to_f32(((const u16*)src)[(size_t)rs * K + k]);
-        if (col_gain != nullptr) f *= col_gain[k];        // gain of the RMSNorm that feeds this matrix
-        o = f32_to_bf16_bits(f);
-      }
-      dst[e] = o;
-    }
-  }
-}
-
-// e4m3 codes of one matrix into the stream: a fragment is 16 rows x 64 k (two k-steps); lane (row i, k-quarter kq)
-// holds 8 codes of the even k-step (k = 64j + 8kq ..) followed by 8 codes of the odd one (k = 64j + 32 + 8kq ..).
-__global__ void pack_stream_fp8_kernel(const uint8_t* __restrict__ src, int n_rows, int K, MegaPlan P, int ph, int layer,
-                                       int row_base, int row_map, int D, uint8_t* __restrict__ stream) {
-  const PhasePlan& pp = P.ph[ph];
-  const int KP = (pp.KS + 1) / 2;                            // k-step pairs
-  const size_t total = (size_t)n_rows * KP * 4;              // one thread per (row, pair, k-quarter)
-  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
-    const int kq = idx & 3;
-    const int kp = (int)((idx >> 2) % KP);
-    const int rs = (int)(idx / ((size_t)KP * 4));
-    int r;
-    if (row_map == 1) {
-      const int h = rs / D, d = rs % D, half = D >> 1;
-      r = row_base + h * D + (d < half ? 2 * d : 2 * (d - half) + 1);
-    } else if (row_map == 2) {
-      r = row_base + 2 * rs;
-    } else {
-      r = row_base + rs;
-    }
-    const int ng = phase_group_of_tile(P, ph, r >> 4);
-    const int lr = r - (phase_tile0(P, ph, ng) << 4);
-    const int ks = 2 * kp;
-    int kg = 0;
-    while ((int)((long long)KP * (kg + 1) / pp.ksplit) <= kp) ++kg;
-    const int wg = wg_of_row_group(P, ph, ng, kg);
-    int w = 0;
-    WavePhase wp = wave_phase(P, ph, wg, 0);
-    while (ks >= wp.w0 + wp.KW) { ++w; wp = wave_phase(P, ph, wg, w); }
-    long long pos = (long long)(wg * kWavesPerWG + w) * P.wave_stride + (long long)layer * wave_layer_units(P, wg, w);
-    for (int q = 0; q < ph; ++q) pos += wave_phase_units(P.ph[q], wave_phase(P, q, wg, w));
-    // fragment index inside the phase: chunks of two tiles, pairs in order, tiles side by side
-    const int tile = lr >> 4, c = tile >> 1, t = tile & 1;
-    const int n_tiles = wp.rows >> 4;
-    const int nt = (2 * c + 1 < n_tiles) ? 2 : 1;
-    const int KWP = wp.KW >> 1;
-    const long long frag = (long long)c * 2 * KWP + (long long)((ks - wp.w0) >> 1) * nt + t;
-    uint8_t* dst = stream + ((size_t)pos + (size_t)frag * 64 + kq * 16 + (lr & 15)) * 16;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int k = ks * 32 + (e >> 3) * 32 + kq * 8 + (e & 7);
-      dst[e] = k < K ? src[(size_t)rs * K + k] : (uint8_t)0;
-    }
-  }
-}
-
-// Per-output-row scales of one fp8 matrix into phase-row order.
-__global__ void scatter_scales_kernel(const float* __restrict__ src, int n_rows, int row_base, int row_map, int D,
-                                      float* __restrict__ dst) {
-  for (int rs = blockIdx.x * blockDim.x + threadIdx.x; rs < n_rows; rs += gridDim.x * blockDim.x) {
-    int r;
-    if (row_map == 1) {
-      const int h = rs / D, d = rs % D, half = D >> 1;
-      r = row_base + h * D + (d < half ? 2 * d : 2 * (d - half) + 1);
-    } else if (row_map == 2) {
-      r = row_base + 2 * rs;
-    } else {
-      r = row_base + rs;
-    }
-    dst[r] = src[rs];
   }
 }
 

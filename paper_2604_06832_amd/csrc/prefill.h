@@ -12,33 +12,10 @@
 // ((T*KS + ks)*64 + lane) 16-byte units, rows in the decode path's phase-row order (rotary pairs of q/k adjacent,
 // (gate f, up f) adjacent, norm gains folded into the columns).  Activations: the packed order of xp_index().
 #pragma once
+#include "prefill_args.h"
 #include "stream_fwd.h"
 
 namespace bd {
-
-constexpr int kPfTokens = 128;        // tokens per workgroup tile (8 token tiles of 16)
-constexpr int kPfThreads = 256;       // four wavefronts, 2 (rows) x 2 (tokens)
-constexpr int kPfSplit = 4;           // K splits of the down projection over workgroups
-
-struct PfGemmArgs {
-  const bf16x8* w;        // fragments of this layer's phase, tile-major
-  int NT, KS;             // 16-row tiles and k-steps of the phase
-  const bf16x8* xin;      // packed activations of the chunk
-  int MTc;                // token tiles of the chunk (any number: a workgroup's eight may reach past the end)
-  int Mvalid;             // rows of the chunk; the rows that pad its last tile write no Q, K or V
-  int RG, TG;             // workgroup grid: row groups x token groups
-  const float* rs;        // [Mc] 1/rms of the rows of the residual stream (QKV, gate/up)
-  const float* wscale;    // e4m3 weights: one scale per phase row, applied to the accumulators; else nullptr
-  const float2* rope;     // [Mc][D/2] (QKV)
-  float* x;               // [Mc][H] residual stream, updated in place (O, down)
-  int SK;                 // K split over workgroups (direct kernel; 1 = none)
-  float* part;            // SK > 1: [SK][Mc][H] partial products of the splits, added to x by the next norm kernel
-  u16* q;                 // [Mc][n_q][D] (QKV)
-  u16* Kc; u16* Vc;       // this layer's packed cache (QKV)
-  int max_kb, n0;         // key blocks per kv head; position of the chunk's first row
-  u16* act;               // packed SwiGLU output (gate/up)
-  int H, QD, KVD, D, n_q;
-};
 
 // Epilogue of both GEMM kernels: lane (token column col, row quad g) of a 16 x 16 accumulator tile holds rows
 // r .. r+3 of one token.
@@ -284,6 +261,35 @@ template <int WN, int BKS, int TW, int NST> constexpr int pf_gemm_direct_lds() {
 
 template <int WN, int BKS, int TW> constexpr int pf_gemm_lds() { return 2 * (2 * WN * BKS * 64 + 2 * TW * BKS * 64) * 16; }
 
+// ---- block assembly: embedding gather into the fp32 residual stream ---------------------------------
+// Row r takes embeds[off + r] while off + r < n_embed, else table[id] with id = ids[off + r - n_embed];
+// with a mask array, masked rows take the mask token's embedding instead.
+__global__ void embed_kernel(float* __restrict__ x, int H, const float* __restrict__ embeds, int n_embed,
+                             const int* __restrict__ ids, int off, const uint8_t* __restrict__ mask,
+                             int mask_id, const u16* __restrict__ table, int vocab) {
+  const int r = blockIdx.x;
+  const int p = off + r;
+  if (p < n_embed) {
+    for (int c = threadIdx.x; c < H; c += blockDim.x) x[(size_t)r * H + c] = embeds[(size_t)p * H + c];
+    return;
+  }
+  int id = ids[p - n_embed];
+  if (mask != nullptr && mask[p - n_embed]) id = mask_id;
+  id = min(max(id, 0), vocab - 1);
+  for (int c = threadIdx.x; c < H; c += blockDim.x) x[(size_t)r * H + c] = bf16_bits_to_f32(table[(size_t)id * H + c]);
+}
+
+// ---- rotary table for positions n .. n+M-1: (cos, sin) of pos * theta^(-2i/d), i < d/2 ------------------
+__global__ void rope_table_kernel(float2* __restrict__ tab, const DevState* st, int half, float theta) {
+  const int m = blockIdx.x;
+  const double pos = (double)(st->n + m);
+  for (int i = threadIdx.x; i < half; i += blockDim.x) {
+    const double inv = exp2(-log2((double)theta) * (double)i / (double)half);
+    const double ang = pos * inv;
+    tab[(size_t)m * half + i] = make_float2((float)cos(ang), (float)sin(ang));
+  }
+}
+
 // One wavefront per row: 1/rms of the fp32 residual row and its bf16 copy in packed order; completes the residual
 // row first when the projection before it left its product in K splits (the norm gain lives in
 // the weights, the factor is applied by the GEMM epilogue: same arithmetic as the decode path).
@@ -326,52 +332,11 @@ __global__ __launch_bounds__(kPfThreads) void zero_rows_kernel(float* __restrict
   for (int c = threadIdx.x; c < H; c += kPfThreads) x[(size_t)blockIdx.x * H + c] = 0.f;
 }
 
-// Hand-over of the prompt's last row to the final norm + LM head of the decode path: its bf16 copy becomes row 0 of the
-// last residual version (packed order of a 16-row tile, the other rows zero) and its sum of squares part 0 of that
-// version's partial sums (the other parts zero; rows 1..15 get a harmless 1).
-__global__ __launch_bounds__(kPfThreads) void pf_last_row_kernel(const float* __restrict__ xrow, int H, u16* __restrict__ xb,
-                                                                 float* __restrict__ ssq, int parts, int Mp) {
-  __shared__ float part[kPfThreads / 64];
-  float ss = 0.f;
-  for (int c = threadIdx.x; c < H; c += kPfThreads) {
-    const float v = xrow[c];
-    ss += v * v;
-    xb[xp_index(0, c, 1)] = f32_to_bf16_bits(v);
-    for (int m = 1; m < 16; ++m) xb[xp_index(m, c, 1)] = 0;
-  }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
-  __syncthreads();
-  float t = 0.f;
-  for (int w = 0; w < kPfThreads / 64; ++w) t += part[w];
-  for (int i = threadIdx.x; i < parts * 16; i += kPfThreads) {
-    const int p = i / 16, m = i % 16;
-    ssq[(size_t)p * Mp + m] = p == 0 ? (m == 0 ? t : 1.f) : 0.f;
-  }
-}
-
-// The decode kernels rely on the slots of the partial sums that no tile owns staying zero: clear what the hand-over
-// wrote once the LM head has read it.
-__global__ void pf_clear_ssq_kernel(float* __restrict__ ssq, int parts, int Mp) {
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < parts * 16; i += gridDim.x * blockDim.x)
-    ssq[(size_t)(i / 16) * Mp + i % 16] = 0.f;
-}
-
 // Causal attention of a chunk against the packed cache (which already holds the chunk's own keys and values):
 // NW (2 or 4) wavefronts per (head, tile of 16 query rows) share out the 32-key blocks up to the last visible key
 // round-robin, each with the decode path's block routine, and merge through LDS; with two wavefronts per item the items
 // of a workgroup are heads of one kv head; two workgroups fit a CU.  (Measured: a variant that stages every block once
 // in LDS for four heads of a kv head, one barrier per block, is slower than these register-buffered walks.)
-struct PfAttnArgs {
-  const u16* q;           // [Mc][n_q][D], rotated, dims in rotary-pair order
-  const u16* Kc; const u16* Vc;
-  int max_kb, n0, Mc, n_q, n_kv;
-  float scale_log2e;
-  u16* out;               // packed attention output (K = n_q*D)
-  int MTc;
-};
-
 template <int D, int NW>
 __global__ __launch_bounds__(kPfThreads, 2) void pf_attn_kernel(PfAttnArgs a) {
   constexpr int DS = D / 32, DT = D / 16;
@@ -446,44 +411,6 @@ __global__ __launch_bounds__(kPfThreads, 2) void pf_attn_kernel(PfAttnArgs a) {
       const uint32_t lo = (uint32_t)f32_to_bf16_bits(o[0]) | ((uint32_t)f32_to_bf16_bits(o[1]) << 16);
       const uint32_t hi = (uint32_t)f32_to_bf16_bits(o[2]) | ((uint32_t)f32_to_bf16_bits(o[3]) << 16);
       *reinterpret_cast<uint64_t*>(a.out + xp_index(row, fo, a.MTc)) = (uint64_t)lo | ((uint64_t)hi << 32);
-    }
-  }
-}
-
-// One matrix into the tile-major fragment order of the prefill GEMMs (same row maps and column gains as the
-// weight stream of the decode kernels).  One-byte sources are e4m3 codes: every code is a bf16 value, so the copy is
-// exact; its row scales and the norm gains stay outside (accumulator epilogue, activation copy).
-template <typename SrcT>
-__global__ void pack_tiles_kernel(const SrcT* __restrict__ src, int n_rows, int K, int KS, int row_base, int row_map, int D,
-                                  const float* __restrict__ col_gain, u16* __restrict__ dst) {
-  const size_t total = (size_t)n_rows * KS * 4;             // one thread per (row, k-step, k-quarter)
-  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total; idx += (size_t)gridDim.x * blockDim.x) {
-    const int kq = idx & 3;
-    const int ks = (int)((idx >> 2) % KS);
-    const int rs = (int)(idx / ((size_t)KS * 4));
-    int r;
-    if (row_map == 1) {
-      const int h = rs / D, d = rs % D, half = D >> 1;
-      r = row_base + h * D + (d < half ? 2 * d : 2 * (d - half) + 1);
-    } else if (row_map == 2) {
-      r = row_base + 2 * rs;
-    } else {
-      r = row_base + rs;
-    }
-    u16* o = dst + ((((size_t)(r >> 4) * KS + ks) * 64) + kq * 16 + (r & 15)) * 8;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int k = ks * 32 + kq * 8 + e;
-      u16 v = 0;
-      if (k < K) {
-        float f;
-        if constexpr (sizeof(SrcT) == 4) f = ((const float*)src)[(size_t)rs * K + k];
-        else if constexpr (sizeof(SrcT) == 1) f = __builtin_amdgcn_cvt_f32_fp8((int)((const uint8_t*)src)[(size_t)rs * K + k], 0);
-        else f = bf16_bits_to_f32(((const u16*)src)[(size_t)rs * K + k]);
-        if (col_gain != nullptr) f *= col_gain[k];
-        v = f32_to_bf16_bits(f);
-      }
-      o[e] = v;
     }
   }
 }

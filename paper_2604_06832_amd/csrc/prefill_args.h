@@ -1,0 +1,57 @@
+// Argument blocks of the large-M prefill kernels (prefill.h) and of the host call that runs one chunk through them.
+#pragma once
+#include "common.h"
+
+namespace bd {
+
+constexpr int kPfTokens = 128;        // tokens per workgroup tile (8 token tiles of 16)
+constexpr int kPfThreads = 256;       // four wavefronts, 2 (rows) x 2 (tokens)
+constexpr int kPfSplit = 4;           // K splits of the down projection over workgroups
+
+struct PfGemmArgs {
+  const bf16x8* w;        // fragments of this layer's phase, tile-major
+  int NT, KS;             // 16-row tiles and k-steps of the phase
+  const bf16x8* xin;      // packed activations of the chunk
+  int MTc;                // token tiles of the chunk (any number: a workgroup's eight may reach past the end)
+  int Mvalid;             // rows of the chunk; the rows that pad its last tile write no Q, K or V
+  int RG, TG;             // workgroup grid: row groups x token groups
+  const float* rs;        // [Mc] 1/rms of the rows of the residual stream (QKV, gate/up)
+  const float* wscale;    // e4m3 weights: one scale per phase row, applied to the accumulators; else nullptr
+  const float2* rope;     // [Mc][D/2] (QKV)
+  float* x;               // [Mc][H] residual stream, updated in place (O, down)
+  int SK;                 // K split over workgroups (direct kernel; 1 = none)
+  float* part;            // SK > 1: [SK][Mc][H] partial products of the splits, added to x by the next norm kernel
+  u16* q;                 // [Mc][n_q][D] (QKV)
+  u16* Kc; u16* Vc;       // this layer's packed cache (QKV)
+  int max_kb, n0;         // key blocks per kv head; position of the chunk's first row
+  u16* act;               // packed SwiGLU output (gate/up)
+  int H, QD, KVD, D, n_q;
+};
+
+struct PfAttnArgs {
+  const u16* q;           // [Mc][n_q][D], rotated, dims in rotary-pair order
+  const u16* Kc; const u16* Vc;
+  int max_kb, n0, Mc, n_q, n_kv;
+  float scale_log2e;
+  u16* out;               // packed attention output (K = n_q*D)
+  int MTc;
+};
+
+
+// One chunk of prompt rows through all layers (k_prefill.hip): plain pointers and sizes of the context.
+struct PfChunk {
+  int rows, off;                  // rows of the chunk; prompt row of its first row
+  int n0;                         // cache position of its first row
+  const float* embeds; int n_embed; const int32_t* ids;
+  const u16* table; int vocab, mask_id;
+  int L, H, QD, KVD, NQKV, F, D, n_q, n_kv, max_kb;
+  float rms_eps, rope_theta;
+  const DevState* st;
+  bool fp8, staged;
+  const float* gains; const float* wscale; int wscale_layer; int wscale_off[4];
+  const u16* w; size_t layer_elems; size_t w_off[4];
+  u16* Kc; u16* Vc; size_t kv_layer_elems;
+  float* x; u16* xb; float* rs; float2* rope; u16* q; u16* ap; u16* act; float* part;
+};
+
+}  // namespace bd

@@ -953,13 +953,6 @@ __device__ inline bool stream_xcd_barrier(const MegaArgs& a, FwdSync& sy, unsign
   return ok;
 }
 
-// Writes the XCD id of every workgroup of a launch shaped like the forward kernel's (host-side check of the
-// workgroup -> XCD rule before a plan relies on it).
-__global__ __launch_bounds__(kFwdThreads, 1) void xcc_probe_kernel(unsigned* out) {
-  extern __shared__ __attribute__((aligned(16))) char lds[];
-  if (threadIdx.x == 0) { lds[0] = 1; out[blockIdx.x] = xcc_id(); }
-}
-
 // ---- the kernel ------------------------------------------------------------------------------------------------
 template <int MT> constexpr int stream_lds_bytes() { return kWavesPerWG * kSlots * 1024 + kShareBytes; }
 

@@ -26,3 +26,43 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _parity_report(request):
+    """After every GPU test: one line saying what its comparisons with the oracle really covered."""
+    try:
+        from tests import gpu_util
+    except Exception:
+        yield
+        return
+    gpu_util.REPORT.clear()
+    yield
+    if not gpu_util.REPORT:
+        return
+    import json
+    kinds = {}
+    for k, rec in gpu_util.REPORT:
+        kinds.setdefault(k, []).append(rec)
+    parts = []
+    if "logits" in kinds:
+        L = kinds["logits"]
+        parts.append(f"logit checks {len(L)}: max abs err {max(r['err'] for r in L):.3g}, max err/range "
+                     f"{max(r['err'] / max(r['range'], 1e-30) for r in L):.3g}")
+    if "ids" in kinds:
+        I = kinds["ids"]
+        parts.append(f"argmax rows compared {sum(r['compared'] for r in I)}/{sum(r['rows'] for r in I)} "
+                     f"(fixed 1e-2 rule: {sum(r['fixed_rule'] for r in I)}, mismatches under it {sum(r['mismatch_fixed'] for r in I)})")
+    if "step" in kinds:
+        S = kinds["step"]
+        parts.append(f"steps {len(S)}: revealed set compared in {sum(r['unique'] for r in S)}, equal in {sum(r['set_equal'] for r in S)}; "
+                     f"max conf rel err {max(r['cerr'] for r in S):.3g}; id mismatches under the fixed rule {sum(r['id_mismatch_fixed'] for r in S)}"
+                     f" of {sum(r['rows_margin'] for r in S)} rows")
+    line = f"[parity] {request.node.name}: " + "; ".join(parts)
+    print(line, flush=True)
+    try:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "parity_report.jsonl"), "a") as f:
+            f.write(json.dumps({"test": request.node.name, "records": gpu_util.REPORT}) + "\n")
+    except OSError:
+        pass

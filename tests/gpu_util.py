@@ -9,6 +9,14 @@ BF16_LOGIT_TOL = 3e-2      # max-abs logit error as a fraction of the oracle's l
 FP8_LOGIT_TOL = 1e-1       # the same bar for the path with e4m3 decoder weights
 MARGIN = 1e-2              # ids are compared where the oracle's top-2 logit margin exceeds this
 
+# What every comparison of the current test really covered (filled by the helpers below, summarised per test by
+# tests/conftest.py): kind -> list of records.
+REPORT = []
+
+
+def note(kind, **kw):
+    REPORT.append((kind, kw))
+
 
 def top2_margin(logits):
     part = np.partition(logits, -2, axis=-1)
@@ -20,6 +28,7 @@ def assert_logits_close(got, want, frac=BF16_LOGIT_TOL, what="logits"):
     want = np.asarray(want, np.float64)
     rng = float(want.max() - want.min())
     err = float(np.abs(got - want).max())
+    note("logits", err=err, range=rng, rows=int(got.shape[0]) if got.ndim > 1 else 1)
     assert np.isfinite(got).all(), f"{what}: non-finite values"
     assert err <= frac * rng, f"{what}: max-abs error {err:.4g} > {frac} * range {rng:.4g}"
     return err / rng
@@ -34,6 +43,8 @@ def check_argmax_ids(got_ids, got_logits, want_logits):
     err = float(np.abs(np.asarray(got_logits, np.float64) - want_logits).max())
     ok = top2_margin(want_logits) > max(MARGIN, 2.0 * err)
     want = np.argmax(want_logits, axis=-1)
+    note("ids", compared=int(ok.sum()), rows=int(ok.size), fixed_rule=int((top2_margin(want_logits) > MARGIN).sum()),
+         mismatch_fixed=int((got_ids != want)[top2_margin(want_logits) > MARGIN].sum()))
     assert np.array_equal(got_ids[ok], want[ok]), (got_ids[ok], want[ok])
     return ok
 
@@ -41,12 +52,12 @@ def check_argmax_ids(got_ids, got_logits, want_logits):
 class Pair:
     """A HIP context and an oracle holding the same model and prompt."""
 
-    def __init__(self, shape, weights, max_seq, max_block=64, oracle_dtype=np.float64, gpu_weights=None):
+    def __init__(self, shape, weights, max_seq, max_block=64, oracle_dtype=np.float64, gpu_weights=None, flags=0):
         self.shape = shape
         self.o = BlockDiffusionOracle(shape, weights, dtype=oracle_dtype)
         fp8 = weights["l0.wq"].dtype == np.uint8
         self.ctx = binding.Context(shape, max_seq=max_seq, max_block=min(max_block, 32) if fp8 else max_block,
-                                   weight_dtype=binding.BD_FP8_E4M3 if fp8 else binding.BD_BF16)
+                                   weight_dtype=binding.BD_FP8_E4M3 if fp8 else binding.BD_BF16, flags=flags)
         self.ctx.load_model(gpu_weights if gpu_weights is not None else weights,
                             as_bf16_bits=gpu_weights is None and _is_bf16(weights))
         self.ctx.bd_debug_logits(True)
@@ -120,6 +131,7 @@ class Pair:
         cerr = float(np.max(np.abs(gconf - oconf) / np.maximum(oconf, 1e-30)))
         tol = 2.5 * cerr + rank_tol
         unique = True
+        gaps = None
         srt = np.sort(cm)[::-1]
         if fixed_k > 0:
             k = min(fixed_k, len(masked))
@@ -136,6 +148,13 @@ class Pair:
             if i > 0:
                 assert gtok[i] == gam[i - 1], (i, gtok[i], gam[i - 1])
         assert np.array_equal(gtok[~mask], tokens[~mask])          # already revealed positions untouched
+        if fixed_k > 0 and min(fixed_k, len(masked)) < len(masked):
+            k = min(fixed_k, len(masked))
+            gaps = float((srt[k - 1] - srt[k]) / srt[k - 1])
+        mg = top2_margin(r["logits"])
+        note("step", cerr=cerr, unique=bool(unique), lerr=lerr_all, gap=gaps, set_equal=bool(np.array_equal(gmask, om)),
+             rows_margin=int((mg[:-1] > MARGIN).sum()), rows=int(B - 1),
+             id_mismatch_fixed=int(sum(1 for i in range(1, B) if mg[i - 1] > MARGIN and gam[i - 1] != int(np.argmax(r["logits"][i - 1])))))
         if unique:
             assert np.array_equal(gmask, om), (gmask, om)
             assert int(nun.item()) == r["n_unmasked"]

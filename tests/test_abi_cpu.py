@@ -46,14 +46,14 @@ def _cfg(**kw):
     s = inputs.TINY
     base = dict(n_layers=s.n_layers, hidden=s.hidden, n_q_heads=s.n_q_heads, n_kv_heads=s.n_kv_heads,
                 head_dim=s.head_dim, ffn=s.ffn, vocab=s.vocab, rope_theta=s.rope_theta, rms_eps=s.rms_eps,
-                max_seq=256, max_block=32, mask_token_id=-1, weight_dtype=binding.BD_BF16)
+                max_seq=256, max_block=32, mask_token_id=-1, weight_dtype=binding.BD_BF16, flags=0)
     base.update(kw)
     return binding.bd_config(**base)
 
 
 @pytest.mark.parametrize("bad", [dict(head_dim=48), dict(n_q_heads=3), dict(n_q_heads=2, n_kv_heads=2), dict(hidden=250), dict(max_block=0),
                                  dict(max_block=65), dict(max_seq=8), dict(vocab=1000), dict(ffn=100),
-                                 dict(mask_token_id=1024), dict(n_layers=0), dict(rope_theta=0.0)])
+                                 dict(mask_token_id=1024), dict(n_layers=0), dict(rope_theta=0.0), dict(flags=1 << 20)])
 def test_create_rejects_bad_shapes_before_any_device_call(L, bad):
     h = C.c_void_p()
     cfg = _cfg(**bad)
@@ -79,7 +79,7 @@ def test_null_context_is_an_argument_error(L):
     assert L.bd_cache_len(None) == binding.BD_E_ARG
     assert L.bd_status(None) == binding.BD_E_ARG
     assert L.bd_load_weight(None, b"embed", None, 0, 0, None) == binding.BD_E_ARG
-    assert L.bd_k_gemm(None, None, None, 4, 16, 32, None, 1, None) == binding.BD_E_ARG
+    assert L.bd_k_attention(None, None, None, None, 0, 4, 4, 2, 64, 0, None, 1, None) == binding.BD_E_ARG
     L.bd_destroy(None)
 
 

@@ -512,7 +512,7 @@ def test_3b_shaped_two_layers_block_sizes(B):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp8"])
-def test_xcd_local_handover_is_bit_identical_to_the_chip_wide_one(monkeypatch, dtype):
+def test_xcd_local_handover_is_bit_identical_to_the_chip_wide_one(dtype):
     """The gate/up -> down hand-over inside each XCD moves the same values through other caches: logits, K/V and
     the revealed ids of a whole block must not change by a bit against the chip-wide path, and a forward repeated
     many times (alternating with forwards of another block size, which rewrite the same buffers) must repeat
@@ -523,12 +523,9 @@ def test_xcd_local_handover_is_bit_identical_to_the_chip_wide_one(monkeypatch, d
     emb, ids = inputs.make_prompt(shape, 96, 37, seed=11)
 
     def run(local):
-        if local:
-            monkeypatch.delenv("BD_XCD_LOCAL", raising=False)
-        else:
-            monkeypatch.setenv("BD_XCD_LOCAL", "0")
         ctx = binding.Context(shape, max_seq=133 + 64, max_block=32,
-                              weight_dtype=binding.BD_FP8_E4M3 if dtype == "fp8" else binding.BD_BF16)
+                              weight_dtype=binding.BD_FP8_E4M3 if dtype == "fp8" else binding.BD_BF16,
+                              flags=0 if local else binding.BD_FLAG_CHIP_WIDE_HANDOVER)
         ctx.load_model(w, as_bf16_bits=True)
         ctx.bd_debug_logits(True)
         ctx.bd_prefill(torch.from_numpy(emb).cuda(), torch.from_numpy(ids).cuda())
@@ -773,14 +770,13 @@ def test_prefill_edge_lengths(n_embed, n_ids):
 
 
 @pytest.mark.parametrize("n_embed,n_ids", [(130, 126), (700, 400)])
-def test_prefill_with_the_register_staged_gemms(monkeypatch, n_embed, n_ids):
+def test_prefill_with_the_register_staged_gemms(n_embed, n_ids):
     """The large-M GEMM kernel that stages its operands through registers (the fallback for K tails, forced here
     for every phase, without the K split of the down projection) against the oracle."""
-    monkeypatch.setenv("BD_PREFILL", "staged")
     shape = inputs.TINY
     w = inputs.make_weights(shape, 0, "bf16", threads=1)
     emb, ids = inputs.make_prompt(shape, n_embed, n_ids, seed=7)
-    p = Pair(shape, w, max_seq=max(256, n_embed + n_ids + 32))
+    p = Pair(shape, w, max_seq=max(256, n_embed + n_ids + 32), flags=binding.BD_FLAG_PREFILL_STAGED)
     p.prefill(emb, ids)
     p.check_carry()
     p.check_kv(0, n_embed + n_ids)
@@ -803,7 +799,7 @@ def test_prefill_with_the_k_split_down_projection(n_embed, n_ids):
     p.close()
 
 
-def test_large_m_prefill_agrees_with_the_chunked_one(monkeypatch):
+def test_large_m_prefill_agrees_with_the_chunked_one():
     """The same prompt through the large-M kernels and through 64-row decode forwards: same cache and carry up to
     bf16 rounding of a different summation order (each path is also held against the oracle elsewhere)."""
     _say("3B-shaped x2 layers: large-M prefill vs chunked prefill, 700 rows")
@@ -811,12 +807,8 @@ def test_large_m_prefill_agrees_with_the_chunked_one(monkeypatch):
     w = inputs.make_weights(shape, 4, "bf16", threads=8)
     emb, ids = inputs.make_prompt(shape, 500, 200, seed=12)
     res = []
-    for mode in ("large", "chunked", "staged"):
-        if mode != "large":
-            monkeypatch.setenv("BD_PREFILL", mode)
-        else:
-            monkeypatch.delenv("BD_PREFILL", raising=False)
-        ctx = binding.Context(shape, max_seq=768, max_block=64)
+    for flags in (0, binding.BD_FLAG_PREFILL_DECODE, binding.BD_FLAG_PREFILL_STAGED):
+        ctx = binding.Context(shape, max_seq=768, max_block=64, flags=flags)
         ctx.load_model(w, as_bf16_bits=True)
         ctx.bd_prefill(torch.from_numpy(emb).cuda(), torch.from_numpy(ids).cuda())
         assert ctx.bd_cache_len() == 700

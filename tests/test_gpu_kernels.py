@@ -1,5 +1,5 @@
-"""Kernel-level parity on the GPU: the skinny GEMM and the block-causal attention against the oracle's
-definitions on seeded operands, through the C ABI (include/bd_kernels.h)."""
+"""Kernel-level parity on the GPU: block-causal attention on caller tensors against the oracle's dense-softmax
+definition on seeded operands, through the C ABI (include/bd_kernels.h)."""
 import numpy as np
 import pytest
 import torch
@@ -8,39 +8,6 @@ from oracle.bd_oracle import BIDIR, CAUSAL, BlockDiffusionOracle
 from paper_2604_06832_amd import binding, inputs
 
 pytestmark = pytest.mark.gpu
-
-
-def _bits_cuda(w):
-    return torch.from_numpy(inputs.bf16_bits(w).view(np.int16)).cuda()
-
-
-# shapes: every 3B projection (some with fewer output rows to keep the host matmul short), ragged K,
-# the tiny model's shapes, M from 1 to 64 including non-multiples of 16
-@pytest.mark.parametrize("M,N,K", [
-    (32, 2560, 2048), (32, 2048, 2048), (32, 2048, 11008), (32, 4096, 2048), (64, 2560, 2048),
-    (1, 2048, 2048), (4, 512, 256), (4, 256, 688), (7, 1376, 256), (33, 1024, 256), (48, 2048, 2048),
-    (17, 16, 32), (64, 2048, 11008),
-])
-def test_gemm_matches_matmul(M, N, K):
-    print(f"gemm M={M} N={N} K={K}", flush=True)
-    rng = np.random.default_rng(M * 1000003 + N * 101 + K)
-    w = inputs.round_to_bf16(rng.standard_normal((N, K), dtype=np.float32) * 0.02)
-    x = inputs.round_to_bf16(rng.standard_normal((M, K), dtype=np.float32))
-    y, _ = binding.bd_k_gemm(_bits_cuda(w), torch.from_numpy(x).cuda())
-    want = x.astype(np.float64) @ w.astype(np.float64).T
-    err = np.abs(y.cpu().numpy() - want).max()
-    assert err <= 2e-5 * np.sqrt(K) * 0.02 * 4 + 1e-6, err       # fp32 accumulation of exact bf16 products
-
-
-def test_gemm_identity_pattern_pins_operand_layout():
-    # W = [I | 0]: row r of W picks x[:, r]; any mix-up of the packed row/k order or of the accumulator
-    # layout moves values to the wrong place
-    K, N, M = 96, 64, 20
-    w = np.zeros((N, K), np.float32)
-    w[np.arange(N), np.arange(N)] = 1.0
-    x = inputs.round_to_bf16(np.arange(M * K, dtype=np.float32).reshape(M, K) % 251)
-    y, _ = binding.bd_k_gemm(_bits_cuda(w), torch.from_numpy(x).cuda())
-    np.testing.assert_array_equal(y.cpu().numpy(), x[:, :N])
 
 
 @pytest.mark.parametrize("n_prefix,M,n_q,n_kv,D,mode", [
