@@ -26,6 +26,18 @@ extern "C" {
 int bd_k_attention(void* hip_stream, const float* dev_q, const float* dev_k, const float* dev_v, int n_prefix, int M,
                    int n_q, int n_kv, int D, int mode, float* dev_out, int iters, float* avg_ms);
 
+/* The same operation for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, layouts and result as bd_k_attention with
+ * iters = 1, but every working buffer (packed K/V, bf16 Q, per-chunk partials) lives in one static device
+ * array of BD_K_ATTENTION_STATIC_BYTES bytes that each GPU the library runs on holds until the process
+ * ends.  The call allocates and frees nothing, records no memset node, only enqueues on hip_stream and
+ * does not synchronise.  A shape whose working buffers exceed the array returns BD_E_CAPACITY (the text
+ * from bd_last_error() names both sizes); bad arguments return BD_E_ARG as for bd_k_attention.  All calls
+ * on one GPU share the array: calls that overlap in time on one GPU race, even on different streams. */
+#define BD_K_ATTENTION_STATIC_BYTES (32u << 20)
+int bd_k_attention_static(void* hip_stream, const float* dev_q, const float* dev_k, const float* dev_v, int n_prefix,
+                          int M, int n_q, int n_kv, int D, int mode, float* dev_out);
+
 /* Per-kernel-class timing of a context's forwards: enable brackets every launch with HIP events on
  * the context's stream (and drops earlier samples); read sums the elapsed time of one class. */
 int bd_k_profile(bd_ctx* ctx, int enable);

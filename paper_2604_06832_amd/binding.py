@@ -25,7 +25,7 @@ EXPORTS = [
     "bd_create", "bd_destroy", "bd_load_weight", "bd_prefill", "bd_denoise_step", "bd_commit_block",
     "bd_verify_block", "bd_decode_block", "bd_speculative_step", "bd_quad_draft", "bd_quad_step", "bd_crop", "bd_cache_len", "bd_status", "bd_debug_logits", "bd_read_logits", "bd_read_kv",
     "bd_read_carry", "bd_read_rows", "bd_forward_bytes", "bd_strerror", "bd_last_error",
-    "bd_k_attention", "bd_k_profile", "bd_k_profile_read", "bd_k_class_count", "bd_k_class_name",
+    "bd_k_attention", "bd_k_attention_static", "bd_k_profile", "bd_k_profile_read", "bd_k_class_count", "bd_k_class_name",
     "bd_k_class_bytes", "bd_k_trace", "bd_k_trace_read",
 ]
 
@@ -74,6 +74,7 @@ def lib() -> C.CDLL:
     L.bd_last_error.argtypes = []
     L.bd_last_error.restype = C.c_char_p
     L.bd_k_attention.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, i32, C.POINTER(f32)]
+    L.bd_k_attention_static.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]
     L.bd_k_profile.argtypes = [vp, i32]
     L.bd_k_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i32)]
     L.bd_k_class_count.argtypes = []
@@ -285,3 +286,15 @@ def bd_k_attention(q, k, v, n_prefix: int, mode: int, iters: int = 1):
                                 M, n_q, n_kv, D, mode, _ptr(out), iters, C.byref(ms)))
     return out, ms.value
 
+
+def bd_k_attention_static(q, k, v, n_prefix: int, mode: int, out=None):
+    """The same operation through the entry point that allocates nothing (its working buffers are a static device
+    array).  `out` (fp32 [M, n_q*D], cuda) is allocated here when not given; the call only enqueues."""
+    import torch
+    M, n_q, D = q.shape
+    n_kv = k.shape[1]
+    if out is None:
+        out = torch.empty((M, n_q * D), dtype=torch.float32, device="cuda")
+    _check(lib().bd_k_attention_static(C.c_void_p(torch.cuda.current_stream().cuda_stream), _ptr(q), _ptr(k), _ptr(v),
+                                       n_prefix, M, n_q, n_kv, D, mode, _ptr(out)))
+    return out

@@ -1,5 +1,5 @@
 // Stand-alone block-causal attention on caller tensors (include/bd_kernels.h): bd_k_attention allocates its working
-// buffers per call.
+// buffers per call; bd_k_attention_static runs the same kernels on a file-scope device array and allocates nothing.
 #include <algorithm>
 #include <cmath>
 #include <vector>
@@ -46,6 +46,9 @@ int attn_shape(int num_cus, int n_prefix, int M, int n_q, int n_kv, int D, int m
   return BD_OK;
 }
 
+__global__ void fill_zero_kernel(uint32_t* p, size_t n_words) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n_words; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
 __global__ void attn_state_kernel(DevState* st, int n) {
   if (threadIdx.x == 0 && blockIdx.x == 0) { st->n = n; st->error = 0; }
 }
@@ -122,6 +125,25 @@ int num_cus_of_current_device(int* out) {
   return BD_OK;
 }
 
+// ---- the working buffers of bd_k_attention_static ------------------------------------------------------------------
+constexpr size_t kScratchBytes = (size_t)BD_K_ATTENTION_STATIC_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, resolved on first use
+
+int scratch_of_current_device(unsigned char** out) {
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) { set_last_error("device index %d out of range", dev); return BD_E_ARG; }
+  if (g_scratch_ptr[dev] == nullptr) {
+    unsigned char* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return BD_OK;
+}
+
 }  // namespace
 }  // namespace bd
 
@@ -171,4 +193,38 @@ extern "C" int bd_k_attention(void* hip_stream, const float* dev_q, const float*
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
   return rc;
+}
+
+extern "C" int bd_k_attention_static(void* hip_stream, const float* dev_q, const float* dev_k, const float* dev_v,
+                                     int n_prefix, int M, int n_q, int n_kv, int D, int mode, float* dev_out) {
+  if (dev_q == nullptr || dev_k == nullptr || dev_v == nullptr || dev_out == nullptr) return BD_E_ARG;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  int cus = 0;
+  BD_TRY(num_cus_of_current_device(&cus));
+  AttnShape sh;
+  BD_TRY(attn_shape(cus, n_prefix, M, n_q, n_kv, D, mode, &sh));
+  // carve the working buffers out of the static array, each on a 256-byte boundary
+  unsigned char* base = nullptr;
+  BD_TRY(scratch_of_current_device(&base));
+  size_t off = 0;
+  auto carve = [&](size_t bytes) { const size_t o = off; off = (off + bytes + 255) & ~(size_t)255; return o; };
+  const size_t oK = carve(sh.kv_elems * 2), oV = carve(sh.kv_elems * 2), oq = carve(sh.q_elems * 2), oa = carve(sh.ap_elems * 2);
+  const size_t clear_end = off;                        // everything up to here must start at zero (padding rows and keys)
+  const size_t oO = carve(sh.pO_floats * 4), om = carve(sh.pml_floats * 4), ol = carve(sh.pml_floats * 4), os = carve(sizeof(DevState));
+  if (off > kScratchBytes) {
+    set_last_error("bd_k_attention_static: this shape needs %zu bytes of working memory, the static buffer holds %zu", off,
+                   kScratchBytes);
+    return BD_E_CAPACITY;
+  }
+  AttnBufs b{};
+  b.Kc = reinterpret_cast<u16*>(base + oK); b.Vc = reinterpret_cast<u16*>(base + oV);
+  b.q = reinterpret_cast<u16*>(base + oq); b.ap = reinterpret_cast<u16*>(base + oa);
+  b.pO = reinterpret_cast<float*>(base + oO); b.pm = reinterpret_cast<float*>(base + om); b.pl = reinterpret_cast<float*>(base + ol);
+  b.st = reinterpret_cast<DevState*>(base + os);
+  // the array keeps the last call's contents: clear the operand buffers with a fill kernel (no memset node, so the call
+  // can be captured into a graph); the partials are fully written by the first kernel before the second reads them
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(512), dim3(256), 0, s, reinterpret_cast<uint32_t*>(base), clear_end / 4);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(base + os), sizeof(DevState) / 4);
+  BD_TRY(check_launch());
+  return attention_enqueue(s, sh, b, dev_q, dev_k, dev_v, dev_out, [](auto&& body) { return body(); });
 }
