@@ -51,13 +51,20 @@ def _parity_report(request):
                      f"{max(r['err'] / max(r['range'], 1e-30) for r in L):.3g}")
     if "ids" in kinds:
         I = kinds["ids"]
-        parts.append(f"argmax rows compared {sum(r['compared'] for r in I)}/{sum(r['rows'] for r in I)} "
-                     f"(fixed 1e-2 rule: {sum(r['fixed_rule'] for r in I)}, mismatches under it {sum(r['mismatch_fixed'] for r in I)})")
+        parts.append(f"argmax rows held exact {sum(r['compared'] for r in I)}/{sum(r['rows'] for r in I)}, "
+                     f"in the band between 1e-2 and the id margin {sum(r['band'] for r in I)} "
+                     f"(of them different {sum(r['band_mismatch'] for r in I)})")
     if "step" in kinds:
         S = kinds["step"]
-        parts.append(f"steps {len(S)}: revealed set compared in {sum(r['unique'] for r in S)}, equal in {sum(r['set_equal'] for r in S)}; "
-                     f"max conf rel err {max(r['cerr'] for r in S):.3g}; id mismatches under the fixed rule {sum(r['id_mismatch_fixed'] for r in S)}"
-                     f" of {sum(r['rows_margin'] for r in S)} rows")
+        parts.append(f"steps {len(S)}: revealed set held against the oracle's in {sum(r['set_compared'] for r in S)} "
+                     f"(equal in {sum(r['set_equal'] for r in S)}); candidate rows held exact {sum(r['id_rows'] for r in S)}/"
+                     f"{sum(r['rows'] for r in S)}, band {sum(r['band'] for r in S)} (different {sum(r['band_mismatch'] for r in S)}); "
+                     f"max conf rel err {max(r['cerr'] for r in S):.3g}")
+    if "carry" in kinds:
+        K = kinds["carry"]
+        parts.append(f"carry checks {len(K)} (id held exact in {sum(r['compared'] for r in K)})")
+    if "count" in kinds:
+        parts += [f"{r['what']} {r['n']}" for r in kinds["count"]]
     line = f"[parity] {request.node.name}: " + "; ".join(parts)
     print(line, flush=True)
     try:

@@ -18,12 +18,44 @@ def note(kind, **kw):
     REPORT.append((kind, kw))
 
 
+BAND_MISMATCH = 0.15       # share of the rows between the 1e-2 margin and the derived id margin that may differ
+
+
+def assert_band(n_band, n_diff, what):
+    assert n_diff <= BAND_MISMATCH * n_band + 1, f"{what}: {n_diff} of {n_band} rows inside the error band differ"
+
+
 def top2_margin(logits):
     part = np.partition(logits, -2, axis=-1)
     return part[..., -1] - part[..., -2]
 
 
-def assert_logits_close(got, want, frac=BF16_LOGIT_TOL, what="logits"):
+def bars(want_logits, n_layers):
+    """The fixed bars of one comparison, from the oracle's side alone (nothing measured on the GPU enters):
+
+    E  bound on the absolute logit error that the GPU path's arithmetic can cause.  The path hands eight tensors per
+       layer from kernel to kernel in bf16 (the two normalised copies of the residual stream, Q, K, V, the attention
+       probabilities, the attention output, the SwiGLU output), each rounding with relative error <= 2^-9; the
+       errors are independent, add in quadrature through the 8 L hand-overs and reach the logits scaled like the
+       logits themselves (standard deviation sigma of the oracle's logits): rms 2^-9 sqrt(8 L) sigma.  E is 8 times
+       that (the largest of ~10^6 logits of a forward): E = 2^-6 sqrt(8 L) sigma.
+    id margin  an argmax can differ between two logit rows that agree within E only where the top-2 margin is below
+       2 E; ids are held bit-exact wherever the oracle's margin exceeds max(1e-2, 2 E).  At 3B scale E > 5e-3, so
+       the 1e-2 margin alone cannot be met by any bf16 path (the design notes list this reading); the rows in the
+       band between 1e-2 and 2 E are counted, reported and held statistically: at most BAND_MISMATCH of them (plus
+       one) may differ, which a wrong mask, index or operand (every row off) cannot pass.
+    C  bound on the relative error of a confidence: log conf = max logit - log sum exp; for V >> 1 the error of the
+       sum averages out, leaving the error of single logits, for which 4 sigma (C = E / 2) covers the <= 64 rows of
+       a forward.  A ranking of two confidences can differ only where they are closer than 2 C.
+    """
+    sigma = float(np.std(np.asarray(want_logits, np.float64)))
+    E = 2.0 ** -6 * float(np.sqrt(8.0 * n_layers)) * sigma
+    return E, max(MARGIN, 2.0 * E), 0.5 * E
+
+
+def assert_logits_close(got, want, frac=BF16_LOGIT_TOL, what="logits", n_layers=None):
+    """The stated bar (max-abs error within frac of the oracle's logit range) and, when the depth is given, the
+    bound E derived from the arithmetic (see bars()), which is the tighter of the two in every configuration here."""
     got = np.asarray(got, np.float64)
     want = np.asarray(want, np.float64)
     rng = float(want.max() - want.min())
@@ -31,21 +63,27 @@ def assert_logits_close(got, want, frac=BF16_LOGIT_TOL, what="logits"):
     note("logits", err=err, range=rng, rows=int(got.shape[0]) if got.ndim > 1 else 1)
     assert np.isfinite(got).all(), f"{what}: non-finite values"
     assert err <= frac * rng, f"{what}: max-abs error {err:.4g} > {frac} * range {rng:.4g}"
+    if n_layers is not None:
+        E = bars(want, n_layers)[0]
+        assert err <= E, f"{what}: max-abs error {err:.4g} > derived bound {E:.4g}"
     return err / rng
 
 
-def check_argmax_ids(got_ids, got_logits, want_logits):
+def check_argmax_ids(got_ids, got_logits, want_logits, n_layers):
     """Fused argmax: (a) bit-exact against the argmax (lowest id on ties) of the GPU's own stored logits;
-    (b) equal to the oracle's wherever the oracle's top-2 margin exceeds 1e-2 and twice the measured
-    logit error (with N(0,0.02) weights the error is far below 1e-2 and (b) is the plain 1e-2 rule)."""
+    (b) equal to the oracle's wherever the oracle's top-2 margin exceeds the fixed id margin of bars().
+    Returns the rows that were compared."""
     got_ids = np.asarray(got_ids)
     assert np.array_equal(got_ids, np.argmax(got_logits, axis=-1)), "fused argmax != argmax of own logits"
-    err = float(np.abs(np.asarray(got_logits, np.float64) - want_logits).max())
-    ok = top2_margin(want_logits) > max(MARGIN, 2.0 * err)
+    _, idm, _ = bars(want_logits, n_layers)
+    marg = top2_margin(want_logits)
+    ok = marg > idm
+    band = (marg > MARGIN) & ~ok
     want = np.argmax(want_logits, axis=-1)
-    note("ids", compared=int(ok.sum()), rows=int(ok.size), fixed_rule=int((top2_margin(want_logits) > MARGIN).sum()),
-         mismatch_fixed=int((got_ids != want)[top2_margin(want_logits) > MARGIN].sum()))
+    note("ids", compared=int(ok.sum()), rows=int(ok.size), band=int(band.sum()),
+         band_mismatch=int((got_ids != want)[band].sum()))
     assert np.array_equal(got_ids[ok], want[ok]), (got_ids[ok], want[ok])
+    assert_band(int(band.sum()), int((got_ids != want)[band].sum()), "argmax ids")
     return ok
 
 
@@ -54,6 +92,7 @@ class Pair:
 
     def __init__(self, shape, weights, max_seq, max_block=64, oracle_dtype=np.float64, gpu_weights=None, flags=0):
         self.shape = shape
+        self.L = shape.n_layers
         self.o = BlockDiffusionOracle(shape, weights, dtype=oracle_dtype)
         fp8 = weights["l0.wq"].dtype == np.uint8
         self.ctx = binding.Context(shape, max_seq=max_seq, max_block=min(max_block, 32) if fp8 else max_block,
@@ -73,15 +112,20 @@ class Pair:
         self.ctx.bd_status()
         assert self.ctx.bd_cache_len() == self.o.n
 
-    def check_carry(self, logit_err=0.0):
-        """Carry = (argmax id, its softmax probability) of the last causal row.  A logit error e moves the
-        probability by at most a factor exp(2e), so the bound follows the measured logit error."""
+    def carry_is_robust(self):
+        """The oracle's carry decides its argmax by more than the fixed id margin."""
+        return top2_margin(self.o.carry) > bars(self.o.carry, self.L)[1]
+
+    def check_carry(self):
+        """Carry = (argmax id, its softmax probability) of the last causal row, to the fixed bars of bars()."""
         cand, conf = self.ctx.bd_read_carry()
         ocand, oconf = self.o.cand_conf(self.o.carry[None, :])
-        if top2_margin(self.o.carry) > max(MARGIN, 2 * logit_err):
+        E, idm, C = bars(self.o.carry, self.L)
+        robust = top2_margin(self.o.carry) > idm
+        note("carry", compared=bool(robust), cerr=abs(conf - float(oconf[0])) / float(oconf[0]))
+        if robust:
             assert cand == int(ocand[0]), (cand, int(ocand[0]))
-        tol = max(0.02, float(np.expm1(2.0 * logit_err)))
-        assert abs(conf - float(oconf[0])) <= tol * float(oconf[0]) + 1e-6, (conf, float(oconf[0]), logit_err)
+        assert abs(conf - float(oconf[0])) <= 2.0 * C * float(oconf[0]) + 1e-7, (conf, float(oconf[0]), C)
 
     def check_kv(self, pos0, count, frac=2e-2):
         for l in range(self.shape.n_layers):
@@ -93,9 +137,9 @@ class Pair:
                 err = float(np.abs(g - w).max())
                 assert err <= frac * scale, f"layer {l} {nm}: err {err:.4g} > {frac} * {scale:.4g}"
 
-    def denoise_step(self, tokens, mask, tau, fixed_k=0, frac=BF16_LOGIT_TOL, rank_tol=1e-3):
+    def denoise_step(self, tokens, mask, tau, fixed_k=0, frac=BF16_LOGIT_TOL):
         """One step on both sides from the same (tokens, mask); returns the oracle's new state.
-        Compares logits, confidences, revealed set and ids, with the near-tie exemptions."""
+        Compares logits, confidences, revealed set and ids to the fixed bars of bars()."""
         B = len(tokens)
         ot, om = tokens.copy(), mask.copy()
         r = self.o.denoise_step(ot, om, tau, fixed_k)
@@ -111,12 +155,12 @@ class Pair:
             assert int(nun.item()) == r["n_unmasked"]
             return ot, om, r
         glog = self.ctx.bd_read_logits(B).cpu().numpy()
-        assert_logits_close(glog, r["logits"], frac)
+        assert_logits_close(glog, r["logits"], frac, n_layers=self.L)
+        E, idm, C = bars(r["logits"], self.L)
         oconf = r["conf"]
         gconf = conf.cpu().numpy()
-        # a logit error e moves a softmax probability by at most a factor exp(2e)
-        lerr_all = float(np.abs(glog.astype(np.float64) - r["logits"]).max())
-        np.testing.assert_allclose(gconf, oconf, rtol=max(0.02, float(np.expm1(2.0 * lerr_all))), atol=1e-7)
+        cerr = float(np.max(np.abs(gconf - oconf) / np.maximum(oconf, 1e-30)))
+        assert cerr <= 2.0 * C, f"confidence relative error {cerr:.4g} > {2 * C:.4g}"
         # (a) integer work: the GPU's revealed set must be exactly what the rule gives on the GPU's own
         #     confidences (both sides decide in the same precision)
         masked = [i for i in range(1, B) if mask[i]]
@@ -126,12 +170,10 @@ class Pair:
         want_mask[sel] = False
         assert np.array_equal(gmask, want_mask), (gmask, want_mask)
         assert int(nun.item()) == int(mask[0]) + len(sel)
-        # (b) against the oracle's set, whenever that set is robust to the measured confidence error
+        # (b) against the oracle's set, wherever that set is not decided by two confidences closer than 2 C + 1e-3
         cm = np.array([oconf[i] for i in masked])
-        cerr = float(np.max(np.abs(gconf - oconf) / np.maximum(oconf, 1e-30)))
-        tol = 2.5 * cerr + rank_tol
+        tol = 2.0 * C + 1e-3
         unique = True
-        gaps = None
         srt = np.sort(cm)[::-1]
         if fixed_k > 0:
             k = min(fixed_k, len(masked))
@@ -148,23 +190,23 @@ class Pair:
             if i > 0:
                 assert gtok[i] == gam[i - 1], (i, gtok[i], gam[i - 1])
         assert np.array_equal(gtok[~mask], tokens[~mask])          # already revealed positions untouched
-        if fixed_k > 0 and min(fixed_k, len(masked)) < len(masked):
-            k = min(fixed_k, len(masked))
-            gaps = float((srt[k - 1] - srt[k]) / srt[k - 1])
-        mg = top2_margin(r["logits"])
-        note("step", cerr=cerr, unique=bool(unique), lerr=lerr_all, gap=gaps, set_equal=bool(np.array_equal(gmask, om)),
-             rows_margin=int((mg[:-1] > MARGIN).sum()), rows=int(B - 1),
-             id_mismatch_fixed=int(sum(1 for i in range(1, B) if mg[i - 1] > MARGIN and gam[i - 1] != int(np.argmax(r["logits"][i - 1])))))
+        # candidate ids of every row against the oracle's, wherever its margin exceeds the fixed id margin
+        marg = top2_margin(r["logits"])
+        oam = np.argmax(r["logits"], axis=-1)
+        rows_ok = marg > idm
+        band = (marg > MARGIN) & ~rows_ok
+        assert np.array_equal(gam[rows_ok], oam[rows_ok]), (gam[rows_ok], oam[rows_ok])
+        note("step", cerr=cerr, set_compared=bool(unique), set_equal=bool(np.array_equal(gmask, om)),
+             id_rows=int(rows_ok.sum()), band=int(band.sum()), band_mismatch=int((gam != oam)[band].sum()), rows=int(B))
+        assert_band(int(band.sum()), int((gam != oam)[band].sum()), "candidate ids")
         if unique:
             assert np.array_equal(gmask, om), (gmask, om)
             assert int(nun.item()) == r["n_unmasked"]
-            lerr = float(np.abs(glog.astype(np.float64) - r["logits"]).max())
-            marg = top2_margin(r["logits"])
             for i in np.flatnonzero(mask & ~om):
                 if i == 0:
-                    if top2_margin(self.o.carry) > max(MARGIN, 2 * lerr):
+                    if self.carry_is_robust():
                         assert gtok[0] == ot[0]
-                elif marg[i - 1] > max(MARGIN, 2 * lerr):
+                elif rows_ok[i - 1]:
                     assert gtok[i] == ot[i], (i, gtok[i], ot[i])
         return ot, om, r
 
@@ -175,8 +217,8 @@ class Pair:
         self.ctx.bd_status()
         assert self.ctx.bd_cache_len() == self.o.n == n0 + len(tokens)
         glog = self.ctx.bd_read_logits(len(tokens)).cpu().numpy()
-        assert_logits_close(glog, ol, frac, "commit logits")
-        self.check_carry(float(np.abs(glog[-1].astype(np.float64) - ol[-1]).max()))
+        assert_logits_close(glog, ol, frac, "commit logits", n_layers=self.L)
+        self.check_carry()
         return ol
 
 

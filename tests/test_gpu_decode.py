@@ -1,8 +1,10 @@
 """End-to-end parity of the HIP decode path against the CPU oracle, through the C ABI.
 
-Bars: unmask masks and token ids bit-exact wherever the oracle's top-2 logit margin exceeds 1e-2 and the
-revealed set is not decided by a near-tie; logits within 3e-2 of the oracle's logit range (bf16 path);
-cached K/V within bf16 rounding of the oracle's.
+Bars (tests/gpu_util.bars): logits within 3e-2 of the oracle's logit range (bf16 path; 1e-1 with e4m3 weights) and
+within the bound E that the bf16 hand-overs of the path can cause; unmask masks and token ids bit-exact wherever the
+oracle's top-2 logit margin exceeds max(1e-2, 2 E) and the revealed set is not decided by two confidences closer than
+the fixed confidence bound; cached K/V within bf16 rounding of the oracle's.  Every test prints what its comparisons
+covered (tests/conftest.py).
 """
 import ctypes as C
 
@@ -12,7 +14,7 @@ import torch
 
 from oracle.bd_oracle import BlockDiffusionOracle
 from paper_2604_06832_amd import binding, inputs
-from tests.gpu_util import FP8_LOGIT_TOL, MARGIN, Pair, check_argmax_ids, assert_logits_close, fresh_block, top2_margin
+from tests.gpu_util import FP8_LOGIT_TOL, MARGIN, Pair, assert_logits_close, bars, check_argmax_ids, fresh_block, note, top2_margin
 
 pytestmark = pytest.mark.gpu
 
@@ -53,13 +55,17 @@ def test_block_size_one_is_autoregressive_decoding():
     want = BlockDiffusionOracle(shape, w)
     want.prefill(emb, ids)
     ar = want.greedy_ar(6)
+    held = 0
     for t in range(6):
         tok, msk = fresh_block(shape, 1)
         tok, msk, _ = p.denoise_step(tok, msk, 0.9)
         assert not msk.any()
-        if top2_margin(p.o.carry) > MARGIN:
+        if p.carry_is_robust():
             assert tok[0] == ar[t]
+            held += 1
         p.commit(tok)
+    note("count", what="autoregressive tokens held against the oracle's", n=held)
+    assert held >= 1
     p.close()
 
 
@@ -128,10 +134,20 @@ def test_verify_accept_and_crop(B):
     torch.cuda.synchronize()
     assert p.ctx.bd_cache_len() == 48
     glog = p.ctx.bd_read_logits(B).cpu().numpy()
-    assert_logits_close(glog, r["logits"])
-    ok = check_argmax_ids(pred.cpu().numpy(), glog, r["logits"])
-    if ok[:max(r["n_accept"], 1)].all() and top2_margin(p.o.carry) > MARGIN:
+    assert_logits_close(glog, r["logits"], n_layers=shape.n_layers)
+    ok = check_argmax_ids(pred.cpu().numpy(), glog, r["logits"], shape.n_layers)
+    # the accept length is decided by the carry and rows 0 .. n_accept-1: held exact when all of those are robust
+    decided = bool(ok[:max(r["n_accept"], 1)].all() and p.carry_is_robust())
+    note("count", what="accept length held against the oracle's", n=int(decided))
+    if decided:
         assert int(nacc.item()) == r["n_accept"]
+    else:
+        # integer work on the GPU's own predictions: the accept rule itself is still checked bit-exactly
+        gp = np.concatenate([[p.ctx.bd_read_carry()[0]], pred.cpu().numpy()[:-1]])
+        k = 0
+        while k < B and gp[k] == draft[k]:
+            k += 1
+        assert int(nacc.item()) == k
     # commit, then crop to the accepted prefix and continue: same state as committing only that prefix
     k = max(1, r["n_accept"])
     p.ctx.bd_verify_block(d, True, None, None)
@@ -283,43 +299,51 @@ def test_speculative_step_accept_lengths_on_a_token_cycle(B, flip):
 @pytest.mark.parametrize("B", [4, 16])
 def test_speculative_steps_emit_the_greedy_sequence(B):
     """Alg. 1 emits exactly the greedy autoregressive continuation, whatever the drafts are worth: with random
-    weights nearly every draft is rejected, so every iteration exercises reject + crop."""
+    weights nearly every draft is rejected, so every iteration exercises reject + crop.  Iterations are compared as
+    long as every decision of the oracle clears the fixed id margin; when one does not, both sides start again from
+    another prompt, until at least three iterations have been held against the oracle."""
     _say(f"speculative steps vs greedy decoding, tiny config, B={B}")
     shape = inputs.TINY
     w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, threads=1)
-    emb, ids = inputs.make_prompt(shape, 24, 24, seed=6)
     p = Pair(shape, w, max_seq=48 + 12 * B, max_block=B)
-    p.prefill(emb, ids)
     import copy
-    greedy = copy.deepcopy(p.o).greedy_ar(12)
-    x_n = int(np.argmax(p.o.carry))
-    if top2_margin(p.o.carry) <= MARGIN:
-        pytest.skip("near-tie in the carry of this seed")
-    emitted = [x_n]
     out = torch.zeros(B, dtype=torch.int32, device="cuda")
-    while len(emitted) < 12:
-        r = _oracle_spec_iteration(p.o, x_n, B)
-        k = p.ctx.bd_speculative_step(B, out)
-        got = out.cpu().numpy()
-        glog = p.ctx.bd_read_logits(B).cpu().numpy()              # logits of the verify pass
-        # row 0 of the verify pass has the same input on both sides whatever the drafts are: its error measures the
-        # numerical noise, and decisions count only where the oracle's margins are clear of it
-        rng = float(r["verify_logits"].max() - r["verify_logits"].min())
-        e0 = float(np.abs(glog[0] - r["verify_logits"][0]).max())
-        assert e0 <= 3e-2 * rng, (e0, rng)
-        thr = max(MARGIN, 2.5 * e0)
-        robust = top2_margin(r["verify_logits"])[:r["k"]].min() > thr and \
-            (r["draft_logits"] is None or top2_margin(r["draft_logits"])[:B - 1].min() > thr)
-        if not robust:
-            break                                                  # a near-tie decides from here on: stop comparing
-        assert_logits_close(glog, r["verify_logits"])
-        assert k == r["k"] and np.array_equal(got[:k], r["a"][:k])
-        emitted += [int(t) for t in got[:k]]
-        x_n = int(r["a"][k - 1])
-        assert p.ctx.bd_cache_len() == p.o.n
-    n = min(len(emitted), 12)
-    assert n >= 4
-    assert np.array_equal(np.array(emitted[:n]), greedy[:n])
+    compared, prompts = 0, 0
+    for seed in range(6, 30):
+        if compared >= 3:
+            break
+        emb, ids = inputs.make_prompt(shape, 24, 24, seed=seed)
+        p.prefill(emb, ids)
+        prompts += 1
+        if not p.carry_is_robust():
+            continue
+        greedy = copy.deepcopy(p.o).greedy_ar(12)
+        x_n = int(np.argmax(p.o.carry))
+        emitted = [x_n]
+        while len(emitted) < 12:
+            r = _oracle_spec_iteration(p.o, x_n, B)
+            k = p.ctx.bd_speculative_step(B, out)
+            got = out.cpu().numpy()
+            glog = p.ctx.bd_read_logits(B).cpu().numpy()              # logits of the verify pass
+            # row 0 of the verify pass has the same input on both sides whatever the drafts are
+            assert_logits_close(glog[:1], r["verify_logits"][:1], n_layers=shape.n_layers)
+            # decisions count only where the oracle's margins exceed the fixed id margin
+            thr = bars(r["verify_logits"], shape.n_layers)[1]
+            robust = top2_margin(r["verify_logits"])[:r["k"]].min() > thr and \
+                (r["draft_logits"] is None or
+                 top2_margin(r["draft_logits"])[:B - 1].min() > bars(r["draft_logits"], shape.n_layers)[1])
+            if not robust:
+                break                                                  # a near-tie decides from here on: next prompt
+            assert_logits_close(glog, r["verify_logits"], n_layers=shape.n_layers)
+            assert k == r["k"] and np.array_equal(got[:k], r["a"][:k])
+            compared += 1
+            emitted += [int(t) for t in got[:k]]
+            x_n = int(r["a"][k - 1])
+            assert p.ctx.bd_cache_len() == p.o.n
+        n = min(len(emitted), 12)
+        assert np.array_equal(np.array(emitted[:n]), greedy[:n])
+    note("count", what=f"speculative iterations held against the oracle's (over {prompts} prompts)", n=compared)
+    assert compared >= 3, compared
     p.close()
 
 
@@ -363,23 +387,30 @@ def test_quadratic_step_against_the_oracle(B):
     nxt = torch.zeros(B, dtype=torch.int32, device="cuda")
     p.ctx.bd_quad_draft(B, d_gpu)
     d = p.o.quad_draft(B)
-    thr0 = MARGIN
     if B > 1:
         glog = p.ctx.bd_read_logits(B).cpu().numpy()
         from oracle.bd_oracle import BIDIR
         olog, _, _ = p.o.forward(p.o.embed(np.full(B, p.o.mask_id, np.int32)), BIDIR)
-        err = assert_logits_close(glog, olog) * float(olog.max() - olog.min())
-        thr0 = max(MARGIN, 2.5 * err)
-        if top2_margin(olog)[:B - 1].min() <= thr0 or top2_margin(p.o.carry) <= thr0:
-            pytest.skip("near-tie in the first draft of this seed")
-    assert np.array_equal(d_gpu.cpu().numpy(), d)
+        assert_logits_close(glog, olog, n_layers=shape.n_layers)
+        thr0 = bars(olog, shape.n_layers)[1]
+        draft_robust = bool(top2_margin(olog)[:B - 1].min() > thr0 and p.carry_is_robust())
+    else:
+        draft_robust = bool(p.carry_is_robust())
+    note("count", what="first draft held against the oracle's", n=int(draft_robust))
+    if draft_robust:
+        assert np.array_equal(d_gpu.cpu().numpy(), d)
+    else:
+        d = d_gpu.cpu().numpy().copy()            # the oracle follows the device's draft: the steps are what is compared
+        d[0] = int(np.argmax(p.o.carry))
+        d_gpu.copy_(torch.from_numpy(d))
     emitted = []
+    compared = 0
     for it in range(6):
         r = p.o.quad_step(d)
         k = p.ctx.bd_quad_step(B, d_gpu, nxt)
         glog = p.ctx.bd_read_logits(M).cpu().numpy()
-        e = assert_logits_close(glog, r["logits"]) * float(r["logits"].max() - r["logits"].min())
-        thr = max(MARGIN, 2.5 * e)
+        assert_logits_close(glog, r["logits"], n_layers=shape.n_layers)
+        thr = bars(r["logits"], shape.n_layers)[1]
         W = B + 1
         firsts = top2_margin(r["logits"])[::W]
         robust = firsts[:r["k"]].min() > thr and top2_margin(r["logits"])[(r["k"] - 1) * W:(r["k"] - 1) * W + B].min() > thr
@@ -391,12 +422,15 @@ def test_quadratic_step_against_the_oracle(B):
         cand, _ = p.ctx.bd_read_carry()
         assert cand == int(np.argmax(p.o.carry))
         p.check_kv(max(0, p.o.n - k - 2), min(k + 2, p.o.n))
+        compared += 1
         emitted += [int(t) for t in r["accepted"]]
         d = r["next_draft"]
         d_gpu.copy_(nxt)
-    assert len(emitted) >= 2
-    n = min(len(emitted), 6)
-    assert emitted[:n] == [int(t) for t in greedy[:n]]
+    note("count", what="quadratic iterations held against the oracle's", n=compared)
+    assert compared >= 1 and len(emitted) >= 1, compared
+    if draft_robust:
+        n = min(len(emitted), 6)
+        assert emitted[:n] == [int(t) for t in greedy[:n]]
     p.check_kv(0, p.o.n)
     p.close()
 
@@ -461,20 +495,23 @@ def test_quadratic_step_3b_shaped_two_layers():
     nxt = torch.zeros(B, dtype=torch.int32, device="cuda")
     p.ctx.bd_quad_draft(B, d_gpu)
     d = d_gpu.cpu().numpy()                       # the oracle follows the device's draft: the step is what is compared
+    compared = 0
     for it in range(2):
         r = p.o.quad_step(d)
         k = p.ctx.bd_quad_step(B, d_gpu, nxt)
         glog = p.ctx.bd_read_logits(M).cpu().numpy()
-        e = assert_logits_close(glog, r["logits"]) * float(r["logits"].max() - r["logits"].min())
-        thr = max(MARGIN, 2.5 * e)
+        assert_logits_close(glog, r["logits"], n_layers=shape.n_layers)
+        thr = bars(r["logits"], shape.n_layers)[1]
         W = B + 1
         if top2_margin(r["logits"])[::W][:r["k"]].min() <= thr or \
                 top2_margin(r["logits"])[(r["k"] - 1) * W:(r["k"] - 1) * W + B].min() <= thr:
             break
         assert k == r["k"] and np.array_equal(nxt.cpu().numpy(), r["next_draft"])
         p.check_kv(p.o.n - k, k)
+        compared += 1
         d = r["next_draft"]
         d_gpu.copy_(nxt)
+    note("count", what="quadratic iterations held against the oracle's (logits of every iteration run are held)", n=compared)
     p.close()
 
 # ---- 3B-shaped layers at reduced depth: every block size, ragged prefix, both masks -------------------
@@ -577,7 +614,7 @@ def test_fp8_tiny_block_decode():
     emb, ids = inputs.make_prompt(shape, 40, 37, seed=104)
     p = Pair(shape, w, max_seq=256)
     p.prefill(emb, ids)
-    p.check_carry(logit_err=0.05)
+    p.check_carry()
     p.check_kv(0, 77, frac=6e-2)
     tok, msk = fresh_block(shape, 8)
     while msk.any():
@@ -597,7 +634,7 @@ def test_fp8_large_m_prefill(n_embed, n_ids):
     emb, ids = inputs.make_prompt(shape, n_embed, n_ids, seed=106)
     p = Pair(shape, w, max_seq=n_embed + n_ids + 64)
     p.prefill(emb, ids)
-    p.check_carry(logit_err=0.05)
+    p.check_carry()
     p.check_kv(0, n_embed + n_ids, frac=6e-2)
     tok, msk = fresh_block(shape, 8)
     p.denoise_step(tok, msk, 0.9, fixed_k=3, frac=FP8_LOGIT_TOL)
@@ -688,10 +725,10 @@ def test_headline_config_first_block_full_depth():
     p = Pair(shape, w, max_seq=1024 + 256 + 32, oracle_dtype=np.float32)
     p.prefill(emb, ids, oracle_chunk=256)
     # the last prompt row's logits (row 0 of the LM-head pass that ends a large-M prefill) against the oracle's, to the
-    # bar of every other logits row; the carry's probability is then held to the bound that this measured error implies
+    # bars of every other logits row
     glog = p.ctx.bd_read_logits(1).cpu().numpy()[0]
-    assert_logits_close(glog, p.o.carry, what="carry logits")
-    p.check_carry(logit_err=float(np.abs(glog.astype(np.float64) - p.o.carry).max()))
+    assert_logits_close(glog, p.o.carry, what="carry logits", n_layers=shape.n_layers)
+    p.check_carry()
     tok, msk = fresh_block(shape, 32)
     fwd = 0
     while msk.any():
