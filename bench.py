@@ -21,9 +21,42 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes one launch of the layers kernel moves on the default workload, from hardware counters
-# (profiles/streaming_forward_config1_hbm_traffic.txt: FETCH_SIZE and WRITE_SIZE, scaled by a reference copy)
-MEASURED_TRAFFIC_BYTES = {("bf16", 36, 1024, 32): 6.333e9}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "streaming_forward_config1_hbm_traffic.txt")
+
+
+def measured_traffic(weights, layers, prefix, block):
+    """HBM bytes one launch of the layers kernel moves on the default workload, from the hardware counters summarised in
+    profiles/streaming_forward_config1_hbm_traffic.txt (FETCH_SIZE and WRITE_SIZE, scaled by a reference copy): its line
+    'traffic_bytes_per_launch layers <bytes>'.  None for any other workload, or when the file is not there."""
+    if (weights, layers, prefix, block) != ("bf16", 36, 1024, 32):
+        return None
+    try:
+        for line in open(TRAFFIC_FILE):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == "layers":
+                return float(f[2])
+    except OSError:
+        pass
+    return None
+
+
+def phase_timeline(ctx, n_layers):
+    """Per-phase time line of the last forward from the kernel's own 100 MHz stamps (bd_k_trace): for every phase the
+    time from the first workgroup's start to the last arrival at the barrier that ends it, the median workgroup's time
+    in the phase, and the barrier's cost from the last arrival to the last release; averaged over layers 1..L-1."""
+    import numpy as np
+    t = ctx.bd_k_trace_read().astype(np.int64)
+    t = (t - t[:, 0].min()) / 100.0                      # microseconds
+    rows = []
+    for e, name in enumerate(["qkv", "attention", "o", "gate/up", "down"]):
+        span, med, bar = [], [], []
+        for l in range(1, n_layers):
+            start, arrive, release = t[:, l * 10 + 2 * e], t[:, 1 + l * 10 + 2 * e], t[:, 2 + l * 10 + 2 * e]
+            span.append(arrive.max() - start.min())
+            med.append(np.median(arrive - start))
+            bar.append(release.max() - arrive.max())
+        rows.append((name, float(np.mean(span)), float(np.mean(med)), float(np.mean(bar))))
+    return rows, float(t.max())
 
 
 def main():
@@ -48,6 +81,9 @@ def main():
     ap.add_argument("--quadratic", type=int, default=0, metavar="B",
                     help="also time 8 iterations of the quadratic speculative loop (Alg. 2) with block size B "
                          "(B*(B+1) <= 64 rows, one forward per iteration)")
+    ap.add_argument("--timeline", action="store_true",
+                    help="instead of the benchmark: print the per-phase time line of one denoising forward (in-kernel "
+                         "timestamps) at this prefix, as text")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -97,6 +133,7 @@ def main():
         ctx.bd_commit_block(tok)
 
     prefill_s = []
+    block_ms = []                                # per-block latency of the last run, from events on the stream
 
     def run(n_blocks, after_prefill=None):
         tp = time.perf_counter()
@@ -105,11 +142,16 @@ def main():
         prefill_s.append(time.perf_counter() - tp)
         if after_prefill is not None:
             after_prefill()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_blocks + 1)]
         t = time.perf_counter()
-        for _ in range(n_blocks):
+        ev[0].record()
+        for i in range(n_blocks):
             decode_block()
+            ev[i + 1].record()
         torch.cuda.synchronize()
-        return time.perf_counter() - t
+        dt = time.perf_counter() - t
+        block_ms[:] = [ev[i].elapsed_time(ev[i + 1]) for i in range(n_blocks)]
+        return dt
 
     if args.calibrate_copy:
         # a plain copy of known size: 2^28 fp32 read + written once (1 GiB each way), for scaling FETCH_SIZE / WRITE_SIZE
@@ -119,8 +161,40 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.timeline:
+        ctx.bd_prefill(d_emb, d_ids)
+        tok.fill_(shape.mask_token_id)
+        msk.fill_(1)
+        for _ in range(3):
+            ctx.bd_denoise_step(tok, msk, 0.9, 1)
+        ctx.bd_status()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            ctx.bd_denoise_step(tok, msk, 0.9, 1)
+        e1.record()
+        torch.cuda.synchronize()
+        ctx.bd_k_trace(True)
+        ctx.bd_denoise_step(tok, msk, 0.9, 1)
+        ctx.bd_status()
+        rows, span = phase_timeline(ctx, shape.n_layers)
+        ctx.bd_k_trace(False)
+        print(f"phase time line of one denoising forward: {args.weights} weights, {shape.n_layers} layers, prefix {args.prefix}, B={B}")
+        print(f"forward (layers kernel + LM head + unmask), mean of 10 untraced: {e0.elapsed_time(e1) * 100:.0f} us; "
+              f"traced layers kernel: {span:.0f} us")
+        print(f"{'phase':10s} {'first start -> last arrival':>28s} {'median workgroup':>18s} {'barrier (last arrival -> last release)':>40s}   [us, mean over layers 1..L-1]")
+        for name, sp, md, br in rows:
+            print(f"{name:10s} {sp:28.2f} {md:18.2f} {br:40.2f}")
+        print(f"{'sum':10s} {sum(r[1] for r in rows):28.2f} {'':18s} {sum(r[3] for r in rows):40.2f}   -> {sum(r[1] + r[3] for r in rows):.1f} us per layer")
+        ctx.close()
+        return
+
     run(args.warmup)                              # untimed warm-up blocks, then the prompt is prefilled afresh
     elapsed = run(args.steps)
+    lat = sorted(block_ms)
+    pct = lambda q: lat[min(len(lat) - 1, int(round(q * (len(lat) - 1))))] if lat else None
+    step_latency = {"unit": "ms per block", "median": round(pct(0.5), 4), "p10": round(pct(0.1), 4), "p90": round(pct(0.9), 4),
+                    "per_forward_median": round(pct(0.5) / (n_den + 1), 4)}
     assert int(msk.sum().item()) == 0 and ctx.bd_cache_len() == args.prefix + args.steps * B
     tokens = args.steps * B
     forwards = args.steps * (n_den + 1)
@@ -199,7 +273,7 @@ def main():
         achieved = nbytes / (ms / cnt * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.weights, args.layers, args.prefix, B)) if dom == "layers" else None,
+                    "traffic": measured_traffic(args.weights, args.layers, args.prefix, B) if dom == "layers" else None,
                     "avg_kernel_us": round(ms / cnt * 1e3, 2), "launches": cnt,
                     "classes": {k: {"avg_us": round(v[0] / v[1] * 1e3, 2), "launches": v[1],
                                     "GBps": round(v[2] / (v[0] / v[1] * 1e-3) / 1e9, 1) if v[2] else None}
@@ -207,22 +281,37 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
+        # the oracle as it stands, in float32, on the workload itself: the prompt is prefilled (not timed, as for the
+        # GPU), then three denoising forwards and the commit forward of the first block are timed and extrapolated over
+        # the block's schedule (n_den denoising forwards + 1 commit)
         from oracle.bd_oracle import BlockDiffusionOracle
-        o = BlockDiffusionOracle(shape, w)
-        o.prefill(emb[:64], None)                  # a short prefix: K/V are <1% of a forward's bytes
+        ctx.close()
+        del ctx
+        torch.cuda.empty_cache()
+        o = BlockDiffusionOracle(shape, w, dtype=np.float32)
+        tp = time.perf_counter()
+        o.prefill(emb, ids, chunk=256)
+        t_prefill = time.perf_counter() - tp
         t = np.full(B, shape.mask_token_id, np.int32)
         m = np.ones(B, bool)
+        n_f = min(3, n_den)
         t1 = time.perf_counter()
-        n_f = 2
         for _ in range(n_f):
             o.denoise_step(t, m, 0.9, K)
-        dt = (time.perf_counter() - t1) / n_f
-        cpu = {"value": round(B / ((n_den + 1) * dt), 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
-               "sample": f"{n_f} denoising forwards at B={B} (fp64 numpy oracle, prefix 64), {dt:.2f}s each, "
-                         f"extrapolated over the {n_den + 1}-forward block schedule"}
+        t_den = (time.perf_counter() - t1) / max(n_f, 1)
+        t[m] = 0                                   # (a block is committed complete: the timing does not depend on the ids)
+        t1 = time.perf_counter()
+        o.commit_block(t)
+        t_com = time.perf_counter() - t1
+        cpu = {"value": round(B / (n_den * t_den + t_com), 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+               "sample": f"float32 numpy oracle on {threads} host threads, same workload (prefix {args.prefix}, B={B}, {K} reveals/step): "
+                         f"{n_f} denoising forwards ({t_den:.2f} s each) + the commit forward ({t_com:.2f} s) of the first block, "
+                         f"extrapolated over its {n_den}+1 forwards; prompt pass {t_prefill:.1f} s, not counted"}
+        ctx = None
 
     out = {
-        "metric": "decoded tokens/s at batch 1, 3B-shaped bf16, B=32; % HBM roofline per step",
+        "metric": "decoded tokens/s at batch 1, 3B-shaped bf16, B=32; % HBM roofline per step" if not fp8 else
+                  "decoded tokens/s at batch 1, 3B-shaped e4m3 weights (bf16 arithmetic), B=32; % HBM roofline per step",
         "value": round(tokens / elapsed, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
@@ -230,7 +319,7 @@ def main():
                                f"({n_embed} visual embeddings + {args.prefix - n_embed} ids), B={B}, "
                                f"fixed {K} unmasks/step, {tokens} tokens",
                    "block": B, "fixed_k": K, "prefix": args.prefix, "forwards_per_block": n_den + 1},
-        "ms_per_forward": round(ms_fwd, 4), "hbm_roofline_frac_step": round(step_frac, 4),
+        "ms_per_forward": round(ms_fwd, 4), "hbm_roofline_frac_step": round(step_frac, 4), "step_latency": step_latency,
         **({"speculative": spec} if spec is not None else {}),
         **({"quadratic": quad} if quad is not None else {}),
         # the prompt pass (not part of `value`): large-M kernels for all but its last rows; linears only in the flop count
@@ -243,7 +332,8 @@ def main():
     if verify_ms is not None:
         out["verify_pass_ms"] = round(verify_ms, 4)
     print(json.dumps(out), flush=True)
-    ctx.close()
+    if ctx is not None:
+        ctx.close()
 
 
 if __name__ == "__main__":

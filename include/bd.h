@@ -67,7 +67,8 @@ enum {
   BD_FLAG_CHIP_WIDE_HANDOVER = 1,  /* gate/up -> down hand-over through the chip-wide barrier instead of per XCD (bit-identical) */
   BD_FLAG_REGISTER_RING = 2,       /* forwards of <= 32 rows on the register-ring kernel that serves 33..64 rows (bf16 weights)   */
   BD_FLAG_PREFILL_DECODE = 4,      /* prompts through the decode kernels in chunks of max_block rows, no large-M kernels          */
-  BD_FLAG_PREFILL_STAGED = 8       /* large-M GEMMs stage their operands through registers instead of loading straight into LDS  */
+  BD_FLAG_PREFILL_STAGED = 8,      /* large-M GEMMs stage their operands through registers instead of loading straight into LDS  */
+  BD_FLAG_ATTENTION_KEY_SPLIT = 16 /* attention of forwards of <= 32 rows by the chip-wide key split instead of per XCD           */
 };
 
 /* Shape limits: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads; hidden, ffn, vocab and the

@@ -19,6 +19,7 @@ BD_OK, BD_E_ARG, BD_E_STATE, BD_E_CAPACITY, BD_E_DTYPE, BD_E_HIP = 0, -1, -2, -3
 BD_F32, BD_BF16, BD_FP8_E4M3 = 0, 1, 2
 BD_MODE_BIDIR, BD_MODE_CAUSAL = 0, 1
 BD_FLAG_CHIP_WIDE_HANDOVER, BD_FLAG_REGISTER_RING, BD_FLAG_PREFILL_DECODE, BD_FLAG_PREFILL_STAGED = 1, 2, 4, 8
+BD_FLAG_ATTENTION_KEY_SPLIT = 16
 
 # every symbol the two headers declare
 EXPORTS = [

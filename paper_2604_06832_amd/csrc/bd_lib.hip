@@ -17,6 +17,7 @@
 
 #include "common.h"
 #include "launch.h"
+#include "attn_plan.h"
 #include "misc.h"
 #include "pack.h"
 #include "plan.h"
@@ -146,6 +147,10 @@ int make_plan(bd_ctx* c) {
   if (!set(PH_QKV, c->NQKV, c->H, false) || !set(PH_O, c->H, c->QD, false) || !set(PH_GU, 2 * c->F, c->H, false) ||
       !set(PH_DOWN, c->H, c->F, true) || !set(PH_LM, c->V, c->H, false))
     return BD_E_ARG;
+  // QKV and O: at most one tile per workgroup -> tile j on workgroup j / nwg-1-j (see MegaPlan::single)
+  P.single = 0;
+  for (int p : {PH_QKV, PH_O})
+    if (P.ph[p].ksplit == 1 && P.ph[p].N / 16 <= P.nwg) { P.single |= 1 << p; P.ph[p].RW = 16; }
   // Gate/up rows dealt out per XCD so that the SwiGLU output never leaves the XCD that produced it: needs the K slices
   // of the down projection to coincide with XCDs (workgroup b holds K slice b mod ksplit and runs on XCD b mod xcds).
   P.xcd_gu = 0;
@@ -216,11 +221,15 @@ int launch_forward_kernels(bd_ctx* c, int MT, MegaArgs& a, bool lm_only = false)
     if (streamed) {
       a.attn_max_chunks = stream_attn_max_chunks(c, MT);
       a.local_gu = c->plan.xcd_gu > 0 ? 1 : 0;
+      a.n_xcd = c->xcds;
+      AttnLocalPlan lp;
+      a.attn_local = (!(c->cfg.flags & BD_FLAG_ATTENTION_KEY_SPLIT) &&
+                      attn_local_plan(c->plan.nwg, c->xcds, c->cfg.n_kv_heads, c->G * MT, lp)) ? 1 : 0;
       a.xbar = c->xbar; a.xbar_epoch = c->xbar_epoch;
       BD_TRY(launch_stream_fwd(c->stream, MT, c->D, c->fp8, quad, a));
       c->bar_epoch += (a.local_gu ? 4u : 5u) * (unsigned)c->L;
-      if (a.local_gu) c->xbar_epoch += (unsigned)c->L;
-      a.local_gu = 0;
+      c->xbar_epoch += (unsigned)((a.local_gu ? 1 : 0) + (a.attn_local ? 1 : 0)) * (unsigned)c->L;
+      a.local_gu = 0; a.attn_local = 0;
     } else {
       if (c->fp8) return BD_E_ARG;                           // e4m3 weights are only streamed by the kernel above
       BD_TRY(launch_mega_fwd(c->stream, MT, c->D, quad, a));
@@ -368,7 +377,7 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
     if (G % 2 != 0) return BD_E_ARG;
   }
   if (k.weight_dtype != BD_BF16 && k.weight_dtype != BD_FP8_E4M3) return BD_E_DTYPE;
-  if (k.flags & ~(BD_FLAG_CHIP_WIDE_HANDOVER | BD_FLAG_REGISTER_RING | BD_FLAG_PREFILL_DECODE | BD_FLAG_PREFILL_STAGED)) return BD_E_ARG;
+  if (k.flags & ~(BD_FLAG_CHIP_WIDE_HANDOVER | BD_FLAG_REGISTER_RING | BD_FLAG_PREFILL_DECODE | BD_FLAG_PREFILL_STAGED | BD_FLAG_ATTENTION_KEY_SPLIT)) return BD_E_ARG;
   if (k.weight_dtype == BD_FP8_E4M3 && k.max_block > 32) return BD_E_ARG;   // e4m3 weights: forwards of up to 32 rows
 
   int dev = 0;
@@ -428,8 +437,9 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
       const int groups = k.n_kv_heads * (c->G * MT / JT);
       tiles = std::max(tiles, (size_t)groups * attn_max_chunks(c, MT) * JT);
       groups_max = std::max(groups_max, groups);
-      if (MT <= 2) {   // the streaming kernel works on single column tiles
+      if (MT <= 2) {   // the streaming kernel works on single column tiles (one partial per workgroup when it keeps the phase inside the XCDs)
         const int sg = k.n_kv_heads * c->G * MT;
+        tiles = std::max(tiles, (size_t)P.nwg);
         tiles = std::max(tiles, (size_t)sg * stream_attn_max_chunks(c, MT));
         groups_max = std::max(groups_max, sg);
       }

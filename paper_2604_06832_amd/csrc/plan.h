@@ -37,7 +37,13 @@ struct MegaPlan {
                            // workgroups of XCD x (workgroup id mod xcd_gu) produce exactly the features that K slice x of
                            // the down projection (also held by the workgroups of XCD x) consumes
   int gu_cut;              // 1: K slices of unequal size (e4m3 contexts), see phase_tile0_t
+  int single;              // bit p set: phase p (QKV, O) has at most one tile per workgroup and no K split; tile j then
+                           // belongs to workgroup j (QKV) or nwg-1-j (O).  With consecutive workgroups on consecutive
+                           // XCDs this spreads each phase's tiles evenly over the XCDs and stacks both on as few
+                           // workgroups as possible; the even spread of T < nwg tiles over nwg groups would put the
+                           // tiles of both phases on the same (odd) workgroups, i.e. on half of the XCDs
 };
+__host__ __device__ inline bool phase_single(const MegaPlan& P, int p) { return ((P.single >> p) & 1) != 0; }
 // Tiles of a phase's row groups.  With xcd_gu the gate/up tiles belong to the XCD whose K slice of the down
 // projection they feed.  For slices of equal size (bf16 weights: required for xcd_gu) that is the plain even
 // spread; with e4m3 weights the slices are whole units of two k-steps and differ by one unit, so the gate/up tiles
@@ -60,6 +66,7 @@ __host__ __device__ inline int phase_tile0_t(const MegaPlan& P, int p, int ng) {
       return b0 + tile0_of_group(b1 - b0, per, ng % per);
     }
   }
+  if (phase_single(P, p)) return min(ng, T);
   return tile0_of_group(T, G, ng);
 }
 __host__ __device__ inline int phase_tile0(const MegaPlan& P, int p, int ng) {
@@ -75,15 +82,18 @@ __host__ __device__ inline int phase_group_of_tile(const MegaPlan& P, int p, int
     const int b0 = gu_slice_tile0(P, x), b1 = gu_slice_tile0(P, x + 1);
     return x * per + group_of_tile(b1 - b0, per, tile - b0);
   }
+  if (phase_single(P, p)) return tile;
   return group_of_tile(T, G, tile);
 }
 // Row group of workgroup `wg` in phase p, and the inverse.
 __host__ __device__ inline int row_group_of_wg(const MegaPlan& P, int p, int wg) {
   if (p == PH_GU && P.xcd_gu > 0) return (wg % P.xcd_gu) * (P.nwg / P.xcd_gu) + wg / P.xcd_gu;
+  if (phase_single(P, p)) return p == PH_O ? P.nwg - 1 - wg : wg;
   return wg / P.ph[p].ksplit;
 }
 __host__ __device__ inline int wg_of_row_group(const MegaPlan& P, int p, int ng, int kg) {
   if (p == PH_GU && P.xcd_gu > 0) return (ng % (P.nwg / P.xcd_gu)) * P.xcd_gu + ng / (P.nwg / P.xcd_gu);
+  if (phase_single(P, p)) return p == PH_O ? P.nwg - 1 - ng : ng;
   return ng * P.ph[p].ksplit + kg;
 }
 
@@ -162,6 +172,8 @@ struct MegaArgs {
   const float* gains;         // [2L+1][H]: attn_norm l, ffn_norm l, ..., final_norm
   int skippable;              // this launch belongs to a step that does nothing once the block is complete (DevState::skip)
   int local_gu;               // the gate/up -> down hand-over stays inside each XCD (stream_fwd.h): plain stores, XCD barrier
+  int attn_local;             // the attention phase stays inside each XCD (stream_fwd.h): partials in the XCD's L2, XCD barrier
+  int n_xcd;                  // XCDs (8) when workgroup b runs on XCD b mod n_xcd, else 0
   unsigned* xbar;             // [xcd][32 words] arrival counters of the XCD barriers
   unsigned xbar_epoch;        // XCD barriers run before this launch
   int fp8;                    // the decoder linears are e4m3 codes with one scale per output row: the scale multiplies

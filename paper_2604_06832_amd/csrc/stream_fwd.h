@@ -21,6 +21,7 @@
 // buffers, write-through stores, no cache maintenance inside the kernel) are those of mega.h; the two
 // kernels are interchangeable on the same context.
 #pragma once
+#include "attn_plan.h"
 #include "mega.h"
 
 namespace bd {
@@ -147,6 +148,126 @@ __device__ inline void producer_loop(const MegaArgs& a, int cw, char* ring, unsi
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   lds_st32(landed_addr, issued);
+}
+
+// ---- producer with a register stash behind the ring -------------------------------------------------------------
+// The ring alone holds 28 KiB per consumer; the phases that stream almost nothing (QKV, attention, O and their
+// hand-overs, a third of a layer's time) would leave HBM idle once it is full.  A producer wavefront owns as many
+// registers as a consumer and needs none, so it keeps NS further fragments there: every fragment travels
+// HBM -> stash register -> ring slot, the stash being a circular buffer of NS / 4 groups of four fragments between the
+// two (fragment f in entry f mod NS).  Filling and draining advance independently: a group is moved to the ring as
+// soon as the ring has room (at LDS speed, whatever is in flight), and groups are re-loaded at a bounded rate (a token
+// bucket on the 100 MHz clock: kStashTicks per fragment, bursts of up to kStashBurst), so that the deep look-ahead
+// never shows up as a deep queue in front of the latency-critical loads of the hand-overs.
+// Stash entries are registers and can only be named statically, so the loop sweeps over the groups: at group k it
+// moves group k if that is the next to move, then re-loads it if it is the next to load.  The loads are issued from
+// inline assembly so that the waits stay in our hands (a compiler-placed wait in front of a conditionally loaded
+// register can only be a wait for everything): vector-memory loads return in order, hence the group with y younger
+// loads behind it has landed once at most y are outstanding.  The build checks that the compiler keeps the entries in
+// place (no copy or spill of a register whose load may still be in flight) between the two markers below.
+#ifndef BD_STASH
+#define BD_STASH 48
+#endif
+#ifndef BD_STASH_TICKS
+#define BD_STASH_TICKS 30
+#endif
+constexpr int kStash = BD_STASH;                 // fragments a producer keeps in registers (4 registers each); 0: ring only
+constexpr int kStashGroup = 4;                   // fragments moved or requested per step
+constexpr unsigned kStashTicks = BD_STASH_TICKS; // 10-ns ticks per fragment of the background pace (1 KiB / 300 ns = 3.4 GB/s a wavefront: a layer needs 2.5)
+#ifndef BD_STASH_TICKS_FAST
+#define BD_STASH_TICKS_FAST 10
+#endif
+#ifndef BD_STASH_LOW
+#define BD_STASH_LOW 24
+#endif
+constexpr unsigned kStashTicksFast = BD_STASH_TICKS_FAST;   // pace while the consumer is about to run dry
+constexpr int kStashLow = BD_STASH_LOW;          // "about to run dry": at most this many fragments requested and not yet consumed
+#ifndef BD_STASH_BURST
+#define BD_STASH_BURST 16
+#endif
+constexpr unsigned kStashBurst = BD_STASH_BURST;  // fragments that may be requested back to back
+static_assert(kStash % kStashGroup == 0 && kSlots % kStashGroup == 0, "whole groups");
+
+__device__ inline unsigned clock_ticks() { return (unsigned)wall_clock64(); }
+
+// The loads that have `younger` loads issued after them have landed once this returns.
+__device__ inline void wait_for_loads(unsigned younger) {
+  if (younger >= 32u) asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+  else if (younger >= 16u) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  else if (younger >= 8u) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else if (younger >= 4u) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+template <bool CUT, int NS>
+__device__ inline void producer_loop_stash(const MegaArgs& a, int cw, char* ring, unsigned sync_base, int lane) {
+  constexpr int NG = NS / kStashGroup;
+  const MegaPlan& P = a.P;
+  // (everything the inline assembly takes in scalar registers is made uniform explicitly)
+  const unsigned total = (unsigned)__builtin_amdgcn_readfirstlane((int)stream_fragments<CUT>(P, cw));
+  const unsigned total_up = (total + kStashGroup - 1) / kStashGroup * kStashGroup;   // (loads past the end read zeros and move no data)
+  const size_t wbase = (size_t)(a.wstream + (size_t)(blockIdx.x * kWavesPerWG + cw) * P.wave_stride);
+  const unsigned wlo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)wbase);
+  const unsigned whi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(wbase >> 32));
+  const rsrc_t wr = make_rsrc(reinterpret_cast<const void*>(((size_t)whi << 32) | wlo), total * 1024u);
+  const unsigned landed_addr = sync_base + (SY_LANDED + cw) * 4;
+  const unsigned consumed_addr = sync_base + (SY_CONSUMED + cw) * 4;
+  const unsigned dead_addr = sync_base + SY_DEAD * 4;
+  bf16x8 st[NS];
+#pragma unroll
+  for (int i = 0; i < NS; ++i) st[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+  unsigned issued = 0, moved = 0, consumed = 0;     // fragments (multiples of the group size)
+  int fill_g = 0, move_g = 0;                       // stash groups of fragment `issued` / fragment `moved`
+  int slot = 0, spins = 0;
+  unsigned t_mark = clock_ticks() - kStashBurst * kStashTicksFast;   // start with a full bucket
+  asm volatile("; BD_STASH_BEGIN" ::: "memory");
+  while (moved < total_up) {
+    // pace of the requests: the background pace while the consumer has plenty buffered, the demand pace once it is
+    // about to run dry (what is buffered is what was requested and not yet consumed)
+    const unsigned now = clock_ticks();
+    consumed = lds_ld32(consumed_addr);
+    const unsigned ticks = (issued - consumed <= (unsigned)kStashLow) ? kStashTicksFast : kStashTicks;
+    unsigned tokens = (now - t_mark) / ticks;
+    if (tokens > kStashBurst) { tokens = kStashBurst; t_mark = now - kStashBurst * ticks; }
+    bool progress = false;
+#pragma unroll
+    for (int k = 0; k < NG; ++k) {
+      if (move_g == k && moved < issued) {
+        if (moved + kStashGroup - consumed > (unsigned)kSlots) consumed = lds_ld32(consumed_addr);
+        if (moved + kStashGroup - consumed <= (unsigned)kSlots) {
+          wait_for_loads(issued - moved - kStashGroup);
+          bf16x8* dst = reinterpret_cast<bf16x8*>(ring + slot * 1024 + lane * 16);
+#pragma unroll
+          for (int j = 0; j < kStashGroup; ++j) dst[j * 64] = st[kStashGroup * k + j];
+          asm volatile("" ::: "memory");
+          moved += kStashGroup;
+          lds_st32(landed_addr, min(moved, total));   // LDS executes a wavefront's operations in order
+          slot = (slot + kStashGroup == kSlots) ? 0 : slot + kStashGroup;
+          move_g = (k + 1 == NG) ? 0 : k + 1;
+          progress = true;
+        }
+      }
+      if (fill_g == k && issued < total_up && issued - moved < (unsigned)NS && tokens >= (unsigned)kStashGroup) {
+        const int off = (int)(issued * 1024u) + lane * 16;
+#pragma unroll
+        for (int j = 0; j < kStashGroup; ++j)
+          asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:%3 nt"
+                       : "+v"(st[kStashGroup * k + j]) : "v"(off), "s"(wr), "n"(j * 1024) : "memory");
+        issued += kStashGroup;
+        tokens -= kStashGroup;
+        t_mark += kStashGroup * ticks;
+        fill_g = (k + 1 == NG) ? 0 : k + 1;
+        progress = true;
+      }
+    }
+    if (progress) {
+      spins = 0;
+    } else {
+      __builtin_amdgcn_s_sleep(1);
+      if ((++spins & 31) == 0 && (lds_ld32(dead_addr) != 0u || spins > kLdsSpin)) break;
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)\n\t; BD_STASH_END" ::: "memory");
 }
 
 // ---- consumer side of the ring -------------------------------------------------------------------------------
@@ -448,6 +569,10 @@ __device__ inline void stream_gemm_phase(const MegaArgs& a, FwdCtx& fc, Ring& rg
         }
       }
       if (c < 3) BD_SUBTS2(3 + 2 * c);
+      // The operands fetched for the epilogue are taken here, before its first store: the vector-memory counter is
+      // in order, so a wait for them placed behind a write-through store would also wait for that store's
+      // acknowledgement (and after a branch that may have stored, the compiler can only wait for everything).
+      asm volatile("" ::"v"(pre.cs[0].x), "v"(pre.cs[0].y), "v"(pre.cs[1].x), "v"(pre.cs[1].y), "v"(pre.xo), "v"(pre.gn), "v"(wsc));
       // the four consumers hold disjoint K ranges: sum them through LDS in fixed order
       f32x4* red = (c & 1) ? fc.red2 : pc.red;
 #pragma unroll
@@ -869,6 +994,170 @@ __device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, Fwd
 #undef BD_ATS
 }
 
+// ---- attention phase kept inside each XCD ------------------------------------------------------------------------
+// The split over key chunks above pays only for long contexts, because its merge is a chain of far-memory round trips
+// (write-through partials, counter, reload by the last arriver).  When workgroup b runs on XCD b mod 8 (the rule the
+// gate/up hand-over already relies on) the whole chip can work on a short context instead: the column tiles
+// ((head, token) columns, 16 per tile) are dealt out to the XCDs, CT tiles each, all of one kv head; inside an XCD the
+// tile's keys are spread over NCH = (workgroups per XCD) / CT workgroups and their four wavefronts (key block kb goes
+// to chunk kb mod NCH, wavefront (kb / NCH) mod 4: every wavefront holds one or two blocks of a 1024-token context).
+// Partials go to the XCD's L2 with plain stores, the workgroups of the XCD meet at their own barrier, and the merge is
+// shared out again: (column tile, 16-dim slice) items over the XCD's wavefronts, each summing the NCH partials of its
+// slice in chunk order.  Only the merged bf16 output is written through, for the O projection of all XCDs.
+__device__ inline bool stream_xcd_barrier(const MegaArgs& a, FwdSync& sy, unsigned xepoch, int wave, int lane);
+
+template <int D, bool QUAD>
+__device__ inline bool stream_attention_local(const MegaArgs& a, FwdCtx& fc, FwdSync& sy, unsigned xepoch, int wave, int lane_in) {
+  constexpr int DS = D / 32, DT = D / 16;
+  int lane = lane_in;
+  asm volatile("" : "+v"(lane));
+  const MegaPlan& P = a.P;
+  const PhaseCtx& pc = fc.pc;
+  f32x4* sO = reinterpret_cast<f32x4*>(fc.share);                        // [4][DT][64]
+  float* sm = reinterpret_cast<float*>(fc.share + kWavesPerWG * DT * 1024);   // [4][16]
+  float* sl = sm + kWavesPerWG * 16;                                     // [4][16]
+  float* wgt = sl + kWavesPerWG * 16;                                    // [64 chunks][16]
+  float* s_inv = wgt + 64 * 16;                                          // [16]
+
+  const int col = lane & 15, g = lane >> 4;
+  const int n = pc.n;
+  const int G = P.n_q / P.n_kv;
+  const int Mp = a.MT * 16;
+  const int n_ct = G * a.MT;                                             // column tiles per kv head
+  AttnLocalPlan lp;
+  attn_local_plan(P.nwg, a.n_xcd, P.n_kv, n_ct, lp);
+  const int x = blockIdx.x % a.n_xcd, w = blockIdx.x / a.n_xcd;          // XCD, workgroup inside it
+  const int n_kb = (n + a.M + 31) >> 5;
+  const size_t kv_block = (size_t)32 * D / 8;
+  const u16* Qb = a.Q + (size_t)pc.layer * a.Mp * P.n_q * D;
+  float* pO = a.pO + (size_t)pc.layer * a.pO_layer_floats;
+  float* pm = a.pm + (size_t)pc.layer * a.pml_layer_floats;
+  float* pl = a.pl + (size_t)pc.layer * a.pml_layer_floats;
+  u16* out = a.ap + (size_t)pc.layer * a.ap_elems;
+  const float c = a.scale_log2e;
+
+#define BD_ATS(k)                                                                                     \
+  do {                                                                                                \
+    if (a.trace2 != nullptr && pc.layer == 1 && threadIdx.x == 0) a.trace2[(size_t)blockIdx.x * 64 + 48 + (k)] = wall_clock64(); \
+  } while (0)
+  BD_ATS(0);
+  {
+    const int ctl = w % lp.CT, chunk = w / lp.CT;
+    const int ct = x * lp.CT + ctl;                                      // column tile of this workgroup
+    const int kvh = ct / n_ct, ctk = ct - kvh * n_ct;
+    const bf16x8* Kh = reinterpret_cast<const bf16x8*>(a.Kc + (size_t)pc.layer * a.kv_layer_elems) + (size_t)kvh * a.max_kb * kv_block;
+    const bf16x8* Vh = reinterpret_cast<const bf16x8*>(a.Vc + (size_t)pc.layer * a.kv_layer_elems) + (size_t)kvh * a.max_kb * kv_block;
+    const int cidx = ctk * 16 + col;
+    const int hq = cidx / Mp, row = cidx - hq * Mp;
+    bf16x8 qf[DS];
+    {
+      const u16* qp = Qb + ((size_t)row * P.n_q + kvh * G + hq) * D + 8 * g;
+#pragma unroll
+      for (int ds = 0; ds < DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8*>(qp + ds * 32);
+    }
+    f32x4 O[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mrun = kNegBig, lrun = 0.f;
+    const int stride = kWavesPerWG * lp.NCH;
+    const int kb0 = chunk + lp.NCH * wave;
+    KvBlock<D> b0, b1;
+    if (kb0 < n_kb) kv_load<D>(b0, Kh, Vh, kb0, lane);
+    asm volatile("" ::: "memory");
+    for (int kb = kb0; kb < n_kb; kb += 2 * stride) {
+      const int kb1 = kb + stride, kb2 = kb + 2 * stride;
+      if (kb1 < n_kb) kv_load<D>(b1, Kh, Vh, kb1, lane);
+      asm volatile("" ::: "memory");
+      if (kb * 32 + 31 >= n) attn_block<D, true, QUAD>(b0, qf, O, mrun, lrun, kb, n, a.M, a.mode, row, g, c);
+      else attn_block<D, false>(b0, qf, O, mrun, lrun, kb, n, a.M, a.mode, row, g, c);
+      if (kb1 < n_kb) {
+        if (kb2 < n_kb) kv_load<D>(b0, Kh, Vh, kb2, lane);
+        asm volatile("" ::: "memory");
+        if (kb1 * 32 + 31 >= n) attn_block<D, true, QUAD>(b1, qf, O, mrun, lrun, kb1, n, a.M, a.mode, row, g, c);
+        else attn_block<D, false>(b1, qf, O, mrun, lrun, kb1, n, a.M, a.mode, row, g, c);
+      }
+    }
+    BD_ATS(2);
+    // merge the four consumers through LDS, each folding a share of the d tiles; the result is this workgroup's partial
+    if (g == 0) {
+      sm[wave * 16 + col] = mrun;
+      sl[wave * 16 + col] = lrun;
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) sO[(wave * DT + dt) * 64 + lane] = O[dt];
+    cbar(sy, lane, a.st);
+    float mm = sm[col];
+#pragma unroll
+    for (int wv = 1; wv < kWavesPerWG; ++wv) mm = fmaxf(mm, sm[wv * 16 + col]);
+    float f[kWavesPerWG];
+    float ll = 0.f;
+#pragma unroll
+    for (int wv = 0; wv < kWavesPerWG; ++wv) {
+      f[wv] = exp2f(sm[wv * 16 + col] - mm);
+      ll += sl[wv * 16 + col] * f[wv];
+    }
+    float* po = pO + (size_t)blockIdx.x * DT * 64 * 4;
+    for (int dt = wave; dt < DT; dt += kWavesPerWG) {
+      f32x4 acc = sO[(0 * DT + dt) * 64 + lane] * f[0];
+#pragma unroll
+      for (int wv = 1; wv < kWavesPerWG; ++wv) acc += sO[(wv * DT + dt) * 64 + lane] * f[wv];
+      *reinterpret_cast<f32x4*>(po + ((size_t)dt * 64 + lane) * 4) = acc;   // read only inside this XCD: its L2 is coherent
+    }
+    if (wave == 0 && g == 0) {
+      pm[(size_t)blockIdx.x * 16 + col] = mm;
+      pl[(size_t)blockIdx.x * 16 + col] = ll;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    BD_ATS(3);
+  }
+  if (!stream_xcd_barrier(a, sy, xepoch, wave, lane)) return false;
+  BD_ATS(4);
+  // merge: item (column tile ctl, d tile dt) -> workgroup item mod WX, wavefront item / WX
+  for (int item = w + lp.WX * wave; item < lp.CT * DT; item += lp.WX * kWavesPerWG) {
+    const int ctl = item / DT, dt = item - ctl * DT;
+    const int ct = x * lp.CT + ctl;
+    const int kvh = ct / n_ct, ctk = ct - kvh * n_ct;
+    const int cidx = ctk * 16 + col;
+    const int hq = cidx / Mp, row = cidx - hq * Mp;
+    // partial of chunk ch of this tile: the workgroup with w = ch * CT + ctl of this XCD
+    float mx = kNegBig;
+    for (int ch = 0; ch < lp.NCH; ++ch) mx = fmaxf(mx, pm[(size_t)((ch * lp.CT + ctl) * a.n_xcd + x) * 16 + col]);
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    float lsum = 0.f;
+    for (int ch0 = 0; ch0 < lp.NCH; ch0 += 8) {
+      f32x4 pv[8];
+      float pmv[8], plv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int chc = min(ch0 + u, lp.NCH - 1);
+        const size_t it = (size_t)((chc * lp.CT + ctl) * a.n_xcd + x);
+        pv[u] = *reinterpret_cast<const f32x4*>(pO + (it * DT + dt) * 64 * 4 + (size_t)lane * 4);
+        pmv[u] = pm[it * 16 + col];
+        plv[u] = pl[it * 16 + col];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (ch0 + u < lp.NCH) {
+          const float wq = exp2f(pmv[u] - mx);
+          acc += pv[u] * wq;
+          lsum += plv[u] * wq;
+        }
+    }
+    acc *= 1.f / lsum;
+    if (row < a.M) {
+      const int fo = (kvh * G + hq) * D + dt * 16 + 4 * g;
+      const uint32_t lo = (uint32_t)f32_to_bf16_bits(acc[0]) | ((uint32_t)f32_to_bf16_bits(acc[1]) << 16);
+      const uint32_t hi = (uint32_t)f32_to_bf16_bits(acc[2]) | ((uint32_t)f32_to_bf16_bits(acc[3]) << 16);
+      st_wt_u64(out + xp_index(row, fo, a.MT), (uint64_t)lo | ((uint64_t)hi << 32));
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  BD_ATS(5);
+#undef BD_ATS
+  (void)wgt; (void)s_inv;
+  return true;
+}
+
 // ---- grid barrier of the consumer wavefronts ---------------------------------------------------------------------
 // Every consumer has waited for its own stores (each phase ends with that wait).  Consumer 0 collects the four
 // arrivals, takes part in the chip-wide barrier (two-level counters of mega.h) and hands the new epoch to the
@@ -932,7 +1221,7 @@ __device__ inline bool stream_xcd_barrier(const MegaArgs& a, FwdSync& sy, unsign
   if (wave == 0) {
     bool ok = lds_wait_ge(sy, sy.base + SY_ARRIVE * 4, sy.arrive_target, a.st);
     if (ok && lane == 0) {
-      const int nx = a.P.xcd_gu;
+      const int nx = a.n_xcd;
       unsigned* cnt = a.xbar + 32 * (blockIdx.x % nx);
       const unsigned target = xepoch * (unsigned)(a.P.nwg / nx);
       __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -970,10 +1259,10 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
   if (threadIdx.x == 0) {
     int go = (a.st->error == 0);
     if (go && a.skippable && a.st->skip) {
-      skip_barriers(a.bar, a.xbar, (a.local_gu ? 4u : 5u) * (unsigned)P.L, a.local_gu ? (unsigned)P.L : 0u);
+      skip_barriers(a.bar, a.xbar, (a.local_gu ? 4u : 5u) * (unsigned)P.L, ((a.local_gu ? 1u : 0u) + (a.attn_local ? 1u : 0u)) * (unsigned)P.L);
       go = 0;
     }
-    if (go && a.local_gu && xcc_id() != blockIdx.x % 8u) {   // the XCD-local hand-over would be unsafe
+    if (go && (a.local_gu || a.attn_local) && xcc_id() != blockIdx.x % 8u) {   // the XCD-local hand-overs would be unsafe
       __hip_atomic_store(&a.st->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       go = 0;
     }
@@ -985,7 +1274,8 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
 
   if (wave >= kWavesPerWG) {
     const int cw = wave - kWavesPerWG;
-    producer_loop<FP8>(a, cw, lds + cw * kSlots * 1024, sync_base, lane);
+    if constexpr (kStash > 0) producer_loop_stash<FP8, kStash>(a, cw, lds + cw * kSlots * 1024, sync_base, lane);
+    else producer_loop<FP8>(a, cw, lds + cw * kSlots * 1024, sync_base, lane);
     return;
   }
 
@@ -1021,7 +1311,12 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
     if (!alive) break;
-    stream_attention_phase<D, QUAD>(a, fc, sy, wave, lane);
+    if (a.attn_local) {
+      alive = stream_attention_local<D, QUAD>(a, fc, sy, ++xepoch, wave, lane);
+      if (!alive) break;
+    } else {
+      stream_attention_phase<D, QUAD>(a, fc, sy, wave, lane);
+    }
     BD_TS2();
     alive = stream_grid_barrier(a, sy, ++epoch, wave, lane);
     BD_TS2();
