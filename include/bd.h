@@ -56,7 +56,7 @@ typedef struct {
   float rope_theta;      /* rotary base, 1e6 in every configuration                                  */
   float rms_eps;         /* RMSNorm epsilon, 1e-6                                                     */
   int32_t max_seq;       /* KV-cache capacity in positions (committed context + one block)           */
-  int32_t max_block;     /* largest B of any call (<= 64; <= 32 with BD_FP8_E4M3 weights)            */
+  int32_t max_block;     /* largest B of any call (<= 64; <= 32 with BD_FP8_E4M3 weights unless max_seq > 128) */
   int32_t mask_token_id; /* id embedded at masked positions; negative = vocab-1                       */
   int32_t weight_dtype;  /* device storage of the seven decoder linears: BD_BF16 or BD_FP8_E4M3       */
   int32_t flags;         /* 0, or BD_FLAG_* bits: alternative code paths, kept for the tests that compare them */
@@ -65,8 +65,9 @@ typedef struct {
 /* bd_config.flags (0 is the product path; results are the same to rounding, see each flag): */
 enum {
   BD_FLAG_CHIP_WIDE_HANDOVER = 1,  /* gate/up -> down hand-over through the chip-wide barrier instead of per XCD (bit-identical) */
-  BD_FLAG_REGISTER_RING = 2,       /* forwards of <= 32 rows on the register-ring kernel that serves 33..64 rows (bf16 weights)   */
-  BD_FLAG_PREFILL_DECODE = 4,      /* prompts through the decode kernels in chunks of max_block rows, no large-M kernels          */
+  BD_FLAG_REGISTER_RING = 2,       /* forwards of <= 32 rows on the register-ring kernel instead of the streaming one (bf16)      */
+  BD_FLAG_PREFILL_DECODE = 4,      /* no large-M kernels: prompts in chunks of max_block rows through the decode kernels, forwards */
+                                   /* of 33..64 rows on the register-ring kernel (the only path when max_seq <= 128)              */
   BD_FLAG_PREFILL_STAGED = 8,      /* large-M GEMMs stage their operands through registers instead of loading straight into LDS  */
   BD_FLAG_ATTENTION_KEY_SPLIT = 16 /* attention of forwards of <= 32 rows by the chip-wide key split instead of per XCD           */
 };
@@ -146,8 +147,10 @@ int bd_decode_block(bd_ctx* ctx, int B, float threshold, int fixed_k, int32_t* d
  * cache_len + B > max_seq, BD_E_ARG for NULL pointers or B outside [1, max_block]. */
 int bd_speculative_step(bd_ctx* ctx, int B, int32_t* dev_tokens_out, int32_t* host_n_accepted);
 
-/* Quadratic speculative decoding (appendix "Details of Speculative Decoding", Alg. 2), for blocks with
- * B*(B+1) <= max_block rows.
+/* Quadratic speculative decoding (appendix "Details of Speculative Decoding", Alg. 2): B <= max_block and either
+ * B*(B+1) <= max_block rows (decode kernels) or, on a context with max_seq > 128 (large-M kernels, quadratic mask and
+ * per-row positions there), B <= 16 and B*(B+1) <= min(1024, 128 * floor((max_seq-1)/128)) rows; BD_E_ARG otherwise
+ * and for BD_FP8_E4M3 contexts.
  * bd_quad_draft: step 1, the first block's draft: B mask tokens after the context, one bidirectional forward without
  *   cache update; dev_draft_out[0] = the carry's argmax, dev_draft_out[i] = argmax of the row before position i.
  * bd_quad_step: one iteration: a single forward over the B groups [draft[i], MASK x B] (group i at positions

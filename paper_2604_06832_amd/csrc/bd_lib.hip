@@ -48,6 +48,7 @@ struct bd_ctx {
   int device = 0, num_cus = 256;
   int H, QD, KVD, NQKV, F, V, D, L, G;
   int Mp_max, max_kb;
+  int rows_max = 0;                // most rows any forward can have: Mp_max, or the rows of a quadratic forward through the large-M kernels
   MegaPlan plan;
   // weights
   u16* wstream = nullptr;          // all matrices, in per-wavefront streaming order
@@ -245,11 +246,90 @@ int launch_forward_kernels(bd_ctx* c, int MT, MegaArgs& a, bool lm_only = false)
   return BD_OK;
 }
 
+constexpr int kQuadMaxB = 16;      // largest block of a quadratic step: B (B + 1) = 272 rows
+constexpr int kStreamRows = 32;    // rows of a forward the decode kernels stream the weights against (two token tiles)
+
+// What every chunk through the large-M kernels shares: shapes, weights, cache and working buffers of the context.
+PfChunk chunk_args(bd_ctx* c) {
+  PfChunk p{};
+  p.n0 = c->n;
+  p.table = c->embed; p.vocab = c->V; p.mask_id = c->cfg.mask_token_id;
+  p.L = c->L; p.H = c->H; p.QD = c->QD; p.KVD = c->KVD; p.NQKV = c->NQKV; p.F = c->F; p.D = c->D;
+  p.n_q = c->cfg.n_q_heads; p.n_kv = c->cfg.n_kv_heads; p.max_kb = c->max_kb;
+  p.rms_eps = c->cfg.rms_eps; p.rope_theta = c->cfg.rope_theta;
+  p.st = c->st;
+  p.fp8 = c->fp8; p.staged = c->pf_staged;
+  p.gains = c->gains; p.wscale = c->wscale; p.wscale_layer = c->wscale_layer;
+  for (int i = 0; i < 4; ++i) { p.wscale_off[i] = c->wscale_off[i]; p.w_off[i] = c->pf_off[i]; }
+  p.w = c->pf_w; p.layer_elems = c->pf_layer_elems;
+  p.Kc = c->Kc; p.Vc = c->Vc; p.kv_layer_elems = c->kv_layer_elems;
+  p.x = c->pf_x; p.xb = c->pf_xb; p.rs = c->pf_rs; p.rope = c->pf_rope; p.q = c->pf_q; p.ap = c->pf_ap; p.act = c->pf_act;
+  p.part = c->pf_part;
+  p.mode = BD_MODE_CAUSAL;
+  return p;
+}
+
+// One chunk of `rows` prompt rows starting at prompt row `off` = cache position c->n through the large-M kernels.
+int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* dev_ids, int off, int rows) {
+  PfChunk p = chunk_args(c);
+  p.rows = rows; p.off = off;
+  p.embeds = dev_embeds; p.n_embed = n_embed; p.ids = dev_ids;
+  return launch_prefill_chunk(c->stream, p);
+}
+
+int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n_embed, const int32_t* ids, int off,
+            int32_t* seed_tokens, uint8_t* seed_mask, const uint8_t* mask, bool skippable = false, int quad_B = 0,
+            bool lm_only = false, int row0 = 0);
+
+// Rows of the large-M kernels' residual stream [0, M) to the final norm + LM head of the decode kernels (all of them,
+// or only the last one as row 0), and the clean-up afterwards.
+int lm_head_of_rows(bd_ctx* c, const float* xrows, int M, int mode, bool skippable, int quad_B) {
+  hipStream_t s = c->stream;
+  const int ver = 2 * c->L, parts = phase_tile_slots(c->plan, PH_DOWN);
+  const DevState* skip = skippable ? c->st : nullptr;
+  float* ssq = c->ssq + (size_t)ver * c->ssq_parts * c->Mp_max;
+  // (the LM head takes as many rows at a time as the decode kernels' buffers hold)
+  for (int r0 = 0; r0 < M; r0 += c->Mp_max) {
+    const int rows = std::min(c->Mp_max, M - r0), MT = ceil_div(rows, 16);
+    hipLaunchKernelGGL(pf_rows_to_lm_kernel, dim3(MT * 16), dim3(kPfThreads), 0, s, xrows + (size_t)r0 * c->H, c->H, rows, MT,
+                       c->xb + (size_t)ver * c->xb_elems, ssq, parts, c->Mp_max, skip);
+    BD_TRY(check_launch());
+    BD_TRY(forward(c, rows, mode, true, nullptr, 0, nullptr, 0, nullptr, nullptr, nullptr, skippable, quad_B, true, r0));
+    hipLaunchKernelGGL(pf_clear_ssq_kernel, dim3(4), dim3(256), 0, s, ssq, parts, c->Mp_max, MT * 16, skip);
+    BD_TRY(check_launch());
+  }
+  c->last_rows = M;
+  return BD_OK;
+}
+
+// A forward of more than 32 rows: the decode kernels stream the weights against at most two token tiles, so these go
+// through the large-M kernels (whole-chip tiled GEMMs per phase, attention with the forward's own visibility among the
+// new rows), then the decode path's LM head over all rows.
+int forward_large(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n_embed, const int32_t* ids, int off,
+                  int32_t* seed_tokens, uint8_t* seed_mask, const uint8_t* mask, bool skippable, int quad_B) {
+  PfChunk p = chunk_args(c);
+  p.rows = M; p.off = off;
+  p.embeds = embeds; p.n_embed = n_embed; p.ids = ids;
+  p.block = mask != nullptr || seed_mask != nullptr;
+  if (p.block && (embeds != nullptr || n_embed != 0 || off != 0)) return BD_E_ARG;
+  p.seed_tokens = seed_tokens; p.seed_mask = seed_mask; p.mask = mask;
+  p.mode = mode; p.quad_W = quad_B > 0 ? quad_B + 1 : 0; p.skippable = skippable ? 1 : 0;
+  {
+    Prof pr(c, KC_LAYERS);
+    BD_TRY(launch_prefill_chunk(c->stream, p));
+  }
+  c->last_rows = M;
+  c->last_had_logits = 0;
+  if (want_lm) BD_TRY(lm_head_of_rows(c, c->pf_x, M, mode, skippable, quad_B));
+  return BD_OK;
+}
+
 // One decoder forward over M rows: prologue (block assembly) + the persistent forward kernel.
 // Source of the rows: prompt rows [off, off+M) (embeds then ids), or block tokens with an optional mask.
 int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n_embed, const int32_t* ids, int off,
-            int32_t* seed_tokens, uint8_t* seed_mask, const uint8_t* mask, bool skippable = false, int quad_B = 0,
-            bool lm_only = false) {
+            int32_t* seed_tokens, uint8_t* seed_mask, const uint8_t* mask, bool skippable, int quad_B, bool lm_only, int row0) {
+  if (!lm_only && M > kStreamRows && c->pf_on && M <= std::max(c->Mp_max, c->rows_max))
+    return forward_large(c, M, mode, want_lm, embeds, n_embed, ids, off, seed_tokens, seed_mask, mask, skippable, quad_B);
   // lm_only: the last residual version of the rows (bf16 copy and sums of squares) is already in place; only the final
   // norm + LM head run (the large-M prefill hands its last row over this way)
   const int MT = ceil_div(M, 16);
@@ -287,8 +367,9 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
   a.attn_max_chunks = attn_max_chunks(c, MT);
   a.scale_log2e = 1.4426950408889634f / std::sqrt((float)c->D);
   a.lm_max = c->lm_max; a.lm_idx = c->lm_idx; a.lm_sum = c->lm_sum;
-  a.logits = (want_lm && c->logits_on) ? c->logits : nullptr;
-  a.row_cand = c->row_cand; a.row_conf = c->row_conf;
+  // (lm_only: the rows are rows row0 .. of a larger forward, and so are their results)
+  a.logits = (want_lm && c->logits_on) ? c->logits + (size_t)row0 * c->V : nullptr;
+  a.row_cand = c->row_cand + row0; a.row_conf = c->row_conf + row0;
   a.trace = c->trace_on ? c->trace : nullptr;
   a.trace2 = c->trace_on ? c->trace + (size_t)c->plan.nwg * (10 * c->L + 4) : nullptr;
   BD_TRY(launch_forward_kernels(c, MT, a, lm_only));
@@ -320,26 +401,6 @@ FinishArgs finish_args(bd_ctx* c, int B) {
 }  // namespace
 
 namespace {
-
-// One chunk of `rows` prompt rows starting at prompt row `off` = cache position c->n through the large-M kernels.
-int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* dev_ids, int off, int rows) {
-  PfChunk p{};
-  p.rows = rows; p.off = off; p.n0 = c->n;
-  p.embeds = dev_embeds; p.n_embed = n_embed; p.ids = dev_ids;
-  p.table = c->embed; p.vocab = c->V; p.mask_id = c->cfg.mask_token_id;
-  p.L = c->L; p.H = c->H; p.QD = c->QD; p.KVD = c->KVD; p.NQKV = c->NQKV; p.F = c->F; p.D = c->D;
-  p.n_q = c->cfg.n_q_heads; p.n_kv = c->cfg.n_kv_heads; p.max_kb = c->max_kb;
-  p.rms_eps = c->cfg.rms_eps; p.rope_theta = c->cfg.rope_theta;
-  p.st = c->st;
-  p.fp8 = c->fp8; p.staged = c->pf_staged;
-  p.gains = c->gains; p.wscale = c->wscale; p.wscale_layer = c->wscale_layer;
-  for (int i = 0; i < 4; ++i) { p.wscale_off[i] = c->wscale_off[i]; p.w_off[i] = c->pf_off[i]; }
-  p.w = c->pf_w; p.layer_elems = c->pf_layer_elems;
-  p.Kc = c->Kc; p.Vc = c->Vc; p.kv_layer_elems = c->kv_layer_elems;
-  p.x = c->pf_x; p.xb = c->pf_xb; p.rs = c->pf_rs; p.rope = c->pf_rope; p.q = c->pf_q; p.ap = c->pf_ap; p.act = c->pf_act;
-  p.part = c->pf_part;
-  return launch_prefill_chunk(c->stream, p);
-}
 
 }  // namespace
 
@@ -378,7 +439,8 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   }
   if (k.weight_dtype != BD_BF16 && k.weight_dtype != BD_FP8_E4M3) return BD_E_DTYPE;
   if (k.flags & ~(BD_FLAG_CHIP_WIDE_HANDOVER | BD_FLAG_REGISTER_RING | BD_FLAG_PREFILL_DECODE | BD_FLAG_PREFILL_STAGED | BD_FLAG_ATTENTION_KEY_SPLIT)) return BD_E_ARG;
-  if (k.weight_dtype == BD_FP8_E4M3 && k.max_block > 32) return BD_E_ARG;   // e4m3 weights: forwards of up to 32 rows
+  // e4m3 weights: the streaming kernel takes forwards of up to 32 rows, larger ones need the large-M kernels
+  if (k.weight_dtype == BD_FP8_E4M3 && k.max_block > 32 && !(k.max_seq > kPfTokens && !(k.flags & BD_FLAG_PREFILL_DECODE))) return BD_E_ARG;
 
   int dev = 0;
   HIP_TRY(hipGetDevice(&dev));
@@ -397,6 +459,10 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   c->NQKV = c->QD + 2 * c->KVD; c->F = k.ffn; c->V = k.vocab; c->L = k.n_layers; c->G = k.n_q_heads / k.n_kv_heads;
   c->Mp_max = ceil_div(k.max_block, 16) * 16;
   c->max_kb = ceil_div(k.max_seq, 32);
+  // Large-M kernels for contexts whose cache can hold a chunk of 128 rows plus the prompt's last rows.
+  c->pf_on = k.max_seq > kPfTokens && !(k.flags & BD_FLAG_PREFILL_DECODE);
+  c->pf_rows = c->pf_on ? std::min(1024, (k.max_seq - 1) / kPfTokens * kPfTokens) : 0;
+  c->rows_max = c->pf_on ? std::max(c->Mp_max, std::min(c->pf_rows, kQuadMaxB * (kQuadMaxB + 1))) : c->Mp_max;
   c->loaded.assign(c->L + 1, 0u);
   c->kv_layer_elems = (size_t)k.n_kv_heads * c->max_kb * 32 * c->D;
   c->xcds = c->use_stream ? probe_xcds(c) : 0;
@@ -456,19 +522,17 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   A(c->lm_max, (size_t)P.nwg * Mp * 4);
   A(c->lm_idx, (size_t)P.nwg * Mp * 4);
   A(c->lm_sum, (size_t)P.nwg * Mp * 4);
-  A(c->row_cand, Mp * 4);
-  A(c->row_conf, Mp * 4);
+  A(c->row_cand, (size_t)c->rows_max * 4);
+  A(c->row_conf, (size_t)c->rows_max * 4);
   A(c->spec_tokens, Mp * 4);
   A(c->spec_mask, Mp);
   A(c->spec_k, 4);
-  A(c->quad_ids, Mp * 4);
+  A(c->quad_ids, (size_t)c->rows_max * 4);
   {
     // Large-M prefill for contexts whose cache can hold a chunk of 128 rows plus the prompt's last rows.  (e4m3
     // decoder linears are widened into the bf16 copy, exactly; their row scales stay in the epilogue.)
-    c->pf_on = k.max_seq > kPfTokens && !(k.flags & BD_FLAG_PREFILL_DECODE);
     c->pf_staged = (k.flags & BD_FLAG_PREFILL_STAGED) != 0;     // register-staged GEMMs only (else: the fallback for K tails)
     if (c->pf_on) {
-      c->pf_rows = std::min(1024, (k.max_seq - 1) / kPfTokens * kPfTokens);
       const size_t R = (size_t)c->pf_rows;
       const int NP[4] = {c->NQKV, c->H, 2 * c->F, c->H};
       const int KP[4] = {c->H, c->QD, c->H, c->F};
@@ -652,19 +716,11 @@ int bd_prefill(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* d
       hipLaunchKernelGGL(advance_kernel, dim3(1), dim3(1), 0, s, c->st, last ? rows - 1 : rows);
       BD_TRY(check_launch());
       if (last) {
-        const int ver = 2 * c->L;
-        hipLaunchKernelGGL(pf_last_row_kernel, dim3(1), dim3(kPfThreads), 0, s, c->pf_x + (size_t)(rows - 1) * c->H, c->H,
-                           c->xb + (size_t)ver * c->xb_elems, c->ssq + (size_t)ver * c->ssq_parts * c->Mp_max,
-                           phase_tile_slots(c->plan, PH_DOWN), c->Mp_max);
-        BD_TRY(check_launch());
         c->n += rows - 1;
-        BD_TRY(forward(c, 1, BD_MODE_CAUSAL, true, nullptr, 0, nullptr, 0, nullptr, nullptr, nullptr, false, 0, true));
+        BD_TRY(lm_head_of_rows(c, c->pf_x + (size_t)(rows - 1) * c->H, 1, BD_MODE_CAUSAL, false, 0));
         FinishArgs f = finish_args(c, 1);
         f.commit = 1;
         hipLaunchKernelGGL(finish_causal_kernel, dim3(1), dim3(64), 0, s, f);
-        BD_TRY(check_launch());
-        hipLaunchKernelGGL(pf_clear_ssq_kernel, dim3(4), dim3(256), 0, s, c->ssq + (size_t)ver * c->ssq_parts * c->Mp_max,
-                           phase_tile_slots(c->plan, PH_DOWN), c->Mp_max);
         BD_TRY(check_launch());
         c->n += 1;
       } else {
@@ -798,8 +854,11 @@ int bd_quad_draft(bd_ctx* c, int B, int32_t* dev_draft_out) {
 int bd_quad_step(bd_ctx* c, int B, const int32_t* dev_draft, int32_t* dev_next_draft, int32_t* host_n_accepted) {
   if (c == nullptr || B < 1 || dev_draft == nullptr || dev_next_draft == nullptr || host_n_accepted == nullptr) return BD_E_ARG;
   const int M = B * (B + 1);
-  if (M > c->cfg.max_block || c->fp8) return BD_E_ARG;   // (bf16 contexts only)
-  BD_TRY(check_decode_call(c, M));                       // the forward parks its B(B+1) rows at [cache_len, cache_len + M)
+  if (B > c->cfg.max_block || B > kQuadMaxB || c->fp8) return BD_E_ARG;   // (bf16 contexts only)
+  // B (B + 1) rows: within max_block through the decode kernels, beyond (up to 272) through the large-M kernels
+  if (M > c->cfg.max_block && !(c->pf_on && M <= c->rows_max)) return BD_E_ARG;
+  if (!c->prefilled) return BD_E_STATE;
+  if (c->n + M > c->cfg.max_seq) return BD_E_CAPACITY;   // the forward parks its rows at [cache_len, cache_len + M)
   hipStream_t s = c->stream;
   hipLaunchKernelGGL(quad_assemble_kernel, dim3(ceil_div(M, 64)), dim3(64), 0, s, dev_draft, B, c->cfg.mask_token_id, c->quad_ids);
   BD_TRY(check_launch());
@@ -895,7 +954,7 @@ int bd_status(bd_ctx* c) {
 
 int bd_debug_logits(bd_ctx* c, int enable) {
   if (c == nullptr) return BD_E_ARG;
-  if (enable && c->logits == nullptr) HIP_TRY(hipMalloc(reinterpret_cast<void**>(&c->logits), (size_t)c->Mp_max * c->V * 4));
+  if (enable && c->logits == nullptr) HIP_TRY(hipMalloc(reinterpret_cast<void**>(&c->logits), (size_t)c->rows_max * c->V * 4));
   c->logits_on = enable ? 1 : 0;
   return BD_OK;
 }

@@ -191,18 +191,21 @@ __global__ void scatter_scales_kernel(const float* __restrict__ src, int n_rows,
   }
 }
 
-// Hand-over of the prompt's last row to the final norm + LM head of the decode path: its bf16 copy becomes row 0 of the
-// last residual version (packed order of a 16-row tile, the other rows zero) and its sum of squares part 0 of that
-// version's partial sums (the other parts zero; rows 1..15 get a harmless 1).
-__global__ __launch_bounds__(kPfThreads) void pf_last_row_kernel(const float* __restrict__ xrow, int H, u16* __restrict__ xb,
-                                                                 float* __restrict__ ssq, int parts, int Mp) {
+// Hand-over of rows of the large-M kernels' residual stream to the final norm + LM head of the decode path: the bf16
+// copies of rows [0, M) of `xrows` become the last residual version (packed order of MT 16-row tiles, the rows that pad
+// the last tile zero) and their sums of squares part 0 of that version's partial sums (the other parts zero; padding
+// rows get a harmless 1).  One workgroup per row of the MT tiles.
+__global__ __launch_bounds__(kPfThreads) void pf_rows_to_lm_kernel(const float* __restrict__ xrows, int H, int M, int MT,
+                                                                   u16* __restrict__ xb, float* __restrict__ ssq, int parts,
+                                                                   int Mp, const DevState* st) {
   __shared__ float part[kPfThreads / 64];
+  if (st != nullptr && st->skip) return;
+  const int m = blockIdx.x;
   float ss = 0.f;
   for (int c = threadIdx.x; c < H; c += kPfThreads) {
-    const float v = xrow[c];
+    const float v = m < M ? xrows[(size_t)m * H + c] : 0.f;
     ss += v * v;
-    xb[xp_index(0, c, 1)] = f32_to_bf16_bits(v);
-    for (int m = 1; m < 16; ++m) xb[xp_index(m, c, 1)] = 0;
+    xb[xp_index(m, c, MT)] = f32_to_bf16_bits(v);
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
@@ -210,17 +213,15 @@ __global__ __launch_bounds__(kPfThreads) void pf_last_row_kernel(const float* __
   __syncthreads();
   float t = 0.f;
   for (int w = 0; w < kPfThreads / 64; ++w) t += part[w];
-  for (int i = threadIdx.x; i < parts * 16; i += kPfThreads) {
-    const int p = i / 16, m = i % 16;
-    ssq[(size_t)p * Mp + m] = p == 0 ? (m == 0 ? t : 1.f) : 0.f;
-  }
+  for (int p = threadIdx.x; p < parts; p += kPfThreads) ssq[(size_t)p * Mp + m] = p == 0 ? (m < M ? t : 1.f) : 0.f;
 }
 
 // The decode kernels rely on the slots of the partial sums that no tile owns staying zero: clear what the hand-over
 // wrote once the LM head has read it.
-__global__ void pf_clear_ssq_kernel(float* __restrict__ ssq, int parts, int Mp) {
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < parts * 16; i += gridDim.x * blockDim.x)
-    ssq[(size_t)(i / 16) * Mp + i % 16] = 0.f;
+__global__ void pf_clear_ssq_kernel(float* __restrict__ ssq, int parts, int Mp, int rows, const DevState* st) {
+  if (st != nullptr && st->skip) return;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < parts * rows; i += gridDim.x * blockDim.x)
+    ssq[(size_t)(i / rows) * Mp + i % rows] = 0.f;
 }
 
 // One matrix into the tile-major fragment order of the prefill GEMMs (same row maps and column gains as the

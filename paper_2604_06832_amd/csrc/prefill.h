@@ -97,6 +97,7 @@ __global__ __launch_bounds__(kPfThreads, (2 * (2 * WN * BKS * 64 + 2 * TW * BKS 
   constexpr int A_PER = A_UNITS / kPfThreads, B_PER = B_UNITS / kPfThreads;
   extern __shared__ __attribute__((aligned(16))) char lds[];
   bf16x8* sm = reinterpret_cast<bf16x8*>(lds);
+  if (a.skippable && a.st->skip) return;
   // Row group rg runs on XCD rg mod 8 for all of its token groups, so that a weight tile is fetched into one L2.
   const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
   const int rg = (slot / a.TG) * 8 + xcd, tg = slot % a.TG;
@@ -195,6 +196,7 @@ __global__ __launch_bounds__(kPfThreads, OCC) void pf_gemm_direct_kernel(PfGemmA
   static_assert(AF % 4 == 0 && BF % 4 == 0, "fragments are dealt to four wavefronts");
   static_assert((NST - 2) * PER <= 63, "outstanding loads must fit the counter");
   extern __shared__ __attribute__((aligned(16))) char lds[];
+  if (a.skippable && a.st->skip) return;
   const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
   const int per = a.TG * a.SK;                                      // workgroups of a row group: token groups x K splits
   const int rg = (slot / per) * 8 + xcd, tg = (slot % per) / a.SK, kz = slot % a.SK;
@@ -206,9 +208,14 @@ __global__ __launch_bounds__(kPfThreads, OCC) void pf_gemm_direct_kernel(PfGemmA
   const rsrc_t xr = make_rsrc(a.xin, (unsigned)((size_t)a.KS * a.MTc * 1024));
 
   const int n_it = a.KS / BKS / a.SK, it0 = kz * n_it;             // this workgroup's share of K
+  // Every row group walks its K range from another starting point (fixed by its number: same sums on every run), so that
+  // the workgroups running at the same time do not all ask the same L2 channels for the same activation fragment.
+  const int rot = (rg * 5) % n_it;
   auto issue = [&](int it) {
     char* base = lds + (it % NST) * ((AF + BF) * 1024);
-    const int ks0 = (it0 + it) * BKS;
+    int itr = it + rot;
+    if (itr >= n_it) itr -= n_it;
+    const int ks0 = (it0 + itr) * BKS;
 #pragma unroll
     for (int i = 0; i < AF / 4; ++i) {
       const int f = i * 4 + wave, tile = f / BKS, ksl = f % BKS;
@@ -250,7 +257,10 @@ __global__ __launch_bounds__(kPfThreads, OCC) void pf_gemm_direct_kernel(PfGemmA
     // the loads of iteration `it` are this wavefront's oldest: in the steady state NST - 2 later stages may stay in flight
     if (it + NST - 2 < n_it) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NST - 2) * PER) : "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    // (the bare barrier: __syncthreads() is also a fence, which waits for every load in flight and so would empty
+    // the pipeline at every iteration; the waits that matter are the explicit one above and the LDS reads of the last
+    // iteration, which the MFMAs that used them have already waited for)
+    __builtin_amdgcn_s_barrier();
     if (it + NST - 1 < n_it) issue(it + NST - 1);
     compute(it % NST);
   }
@@ -279,10 +289,38 @@ __global__ void embed_kernel(float* __restrict__ x, int H, const float* __restri
   for (int c = threadIdx.x; c < H; c += blockDim.x) x[(size_t)r * H + c] = bf16_bits_to_f32(table[(size_t)id * H + c]);
 }
 
+// Rows of a decode block into the fp32 residual stream: row r takes the embedding of ids[r], or of the mask token
+// where mask[r] is set.  With seed arrays (denoising step), position 0 first takes the carried prediction if it is
+// still masked, exactly as the prologue of the decode kernels does.
+__global__ void pf_block_embed_kernel(float* __restrict__ x, int H, const int* ids, const uint8_t* mask,
+                                      int* seed_tokens, uint8_t* seed_mask, DevState* st,
+                                      int skippable, int mask_id, const u16* __restrict__ table, int vocab) {
+  __shared__ int s_id;
+  const int r = blockIdx.x;
+  if (skippable && st->skip) return;
+  if (threadIdx.x == 0) {
+    if (r == 0 && seed_mask != nullptr) {
+      st->seeded = 0;
+      if (seed_mask[0]) {
+        seed_tokens[0] = st->carry_cand;
+        seed_mask[0] = 0;
+        st->seeded = 1;
+      }
+    }
+    int id = ids[r];
+    if (mask != nullptr && mask[r]) id = mask_id;
+    s_id = min(max(id, 0), vocab - 1);
+  }
+  __syncthreads();
+  const int id = s_id;
+  for (int c = threadIdx.x; c < H; c += blockDim.x) x[(size_t)r * H + c] = bf16_bits_to_f32(table[(size_t)id * H + c]);
+}
+
 // ---- rotary table for positions n .. n+M-1: (cos, sin) of pos * theta^(-2i/d), i < d/2 ------------------
-__global__ void rope_table_kernel(float2* __restrict__ tab, const DevState* st, int half, float theta) {
+// (quad_W > 0: rows are groups of quad_W tokens, row m sits at position n + m / W + m % W, Alg. 2)
+__global__ void rope_table_kernel(float2* __restrict__ tab, const DevState* st, int half, float theta, int quad_W = 0) {
   const int m = blockIdx.x;
-  const double pos = (double)(st->n + m);
+  const double pos = (double)(st->n + (quad_W > 0 ? m / quad_W + m % quad_W : m));
   for (int i = threadIdx.x; i < half; i += blockDim.x) {
     const double inv = exp2(-log2((double)theta) * (double)i / (double)half);
     const double ang = pos * inv;
@@ -295,7 +333,9 @@ __global__ void rope_table_kernel(float2* __restrict__ tab, const DevState* st, 
 // the weights, the factor is applied by the GEMM epilogue: same arithmetic as the decode path).
 __global__ __launch_bounds__(kPfThreads) void pf_norm_kernel(float* __restrict__ x, int H, float eps, u16* __restrict__ xb,
                                                              int MTc, float* __restrict__ rs, const float* __restrict__ gain,
-                                                             const float* __restrict__ kparts, int n_kparts) {
+                                                             const float* __restrict__ kparts, int n_kparts,
+                                                             const DevState* st = nullptr) {
+  if (st != nullptr && st->skip) return;
   // one wavefront per row, four rows per workgroup
   const int token = blockIdx.x * (kPfThreads / 64) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (token >= MTc * 16) return;
@@ -328,21 +368,63 @@ __global__ __launch_bounds__(kPfThreads) void pf_norm_kernel(float* __restrict__
   if (lane == 0) rs[token] = rsqrtf(ss / (float)H + eps);
 }
 
-__global__ __launch_bounds__(kPfThreads) void zero_rows_kernel(float* __restrict__ x, int H) {
+// The same for chunks of few rows: one workgroup per row, so that the rows of a 64-row forward spread over 64 CUs
+// instead of 16 and every lane has one group of eight columns per pass.  Same sums in the same order per column; the sum
+// of squares is reduced over the workgroup's lanes in a fixed order.
+__global__ __launch_bounds__(kPfThreads) void pf_norm_row_kernel(float* __restrict__ x, int H, float eps, u16* __restrict__ xb,
+                                                                 int MTc, float* __restrict__ rs, const float* __restrict__ gain,
+                                                                 const float* __restrict__ kparts, int n_kparts,
+                                                                 const DevState* st = nullptr) {
+  __shared__ float wsum[kPfThreads / 64];
+  if (st != nullptr && st->skip) return;
+  const int token = blockIdx.x;
+  float* row = x + (size_t)token * H;
+  float ss = 0.f;
+  for (int c = threadIdx.x * 8; c < H; c += kPfThreads * 8) {
+    f32x4 v0 = *reinterpret_cast<const f32x4*>(row + c), v1 = *reinterpret_cast<const f32x4*>(row + c + 4);
+    if (n_kparts > 0) {
+      for (int p = 0; p < n_kparts; ++p) {
+        const float* src = kparts + ((size_t)p * MTc * 16 + token) * H + c;
+        v0 += *reinterpret_cast<const f32x4*>(src);
+        v1 += *reinterpret_cast<const f32x4*>(src + 4);
+      }
+      *reinterpret_cast<f32x4*>(row + c) = v0;
+      *reinterpret_cast<f32x4*>(row + c + 4) = v1;
+    }
+    union { u16 h[8]; u32x4 q; } o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      ss += v0[e] * v0[e] + v1[e] * v1[e];
+      o.h[e] = f32_to_bf16_bits(gain != nullptr ? v0[e] * gain[c + e] : v0[e]);
+      o.h[4 + e] = f32_to_bf16_bits(gain != nullptr ? v1[e] * gain[c + 4 + e] : v1[e]);
+    }
+    *reinterpret_cast<u32x4*>(xb + xp_index(token, c, MTc)) = o.q;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) rs[token] = rsqrtf((wsum[0] + wsum[1] + wsum[2] + wsum[3]) / (float)H + eps);
+}
+
+__global__ __launch_bounds__(kPfThreads) void zero_rows_kernel(float* __restrict__ x, int H, const DevState* st = nullptr) {
+  if (st != nullptr && st->skip) return;
   for (int c = threadIdx.x; c < H; c += kPfThreads) x[(size_t)blockIdx.x * H + c] = 0.f;
 }
 
-// Causal attention of a chunk against the packed cache (which already holds the chunk's own keys and values):
+// Attention of a chunk against the packed cache (which already holds the chunk's own keys and values; among them the
+// mode decides what a row sees: causal, all of the chunk, or the groups of a quadratic forward):
 // NW (2 or 4) wavefronts per (head, tile of 16 query rows) share out the 32-key blocks up to the last visible key
 // round-robin, each with the decode path's block routine, and merge through LDS; with two wavefronts per item the items
 // of a workgroup are heads of one kv head; two workgroups fit a CU.  (Measured: a variant that stages every block once
 // in LDS for four heads of a kv head, one barrier per block, is slower than these register-buffered walks.)
-template <int D, int NW>
-__global__ __launch_bounds__(kPfThreads, 2) void pf_attn_kernel(PfAttnArgs a) {
+template <int D, int NW, bool QUAD = false>
+__global__ __launch_bounds__(64 * (NW > 4 ? NW : 4), NW > 4 ? 1 : 2) void pf_attn_kernel(PfAttnArgs a) {
   constexpr int DS = D / 32, DT = D / 16;
-  constexpr int IPW = 4 / NW;                                  // items per workgroup, NW wavefronts per item
+  constexpr int IPW = NW > 4 ? 1 : 4 / NW;                     // items per workgroup, NW wavefronts per item
   __shared__ f32x4 sO[IPW][NW - 1][DT][64];
   __shared__ float sm[IPW][NW - 1][64], sl[IPW][NW - 1][64];
+  if (a.skippable && a.st->skip) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int sub = wave / NW, half = wave % NW;                 // wavefront `half` of item `sub` takes blocks half, half + NW, ..
   const int col = lane & 15, g = lane >> 4;
@@ -366,18 +448,22 @@ __global__ __launch_bounds__(kPfThreads, 2) void pf_attn_kernel(PfAttnArgs a) {
 #pragma unroll
       for (int ds = 0; ds < DS; ++ds) qf[ds] = *reinterpret_cast<const bf16x8*>(qp + ds * 32);
     }
-    const int kb_end = (a.n0 + qt * 16 + 15) / 32 + 1;          // blocks holding a key some row of the tile may see
+    // blocks holding a key some row of the tile may see: up to its own last row (causal), else all of the chunk
+    const int kb_end = ((a.mode == 1 ? min(a.n0 + qt * 16 + 15, a.n0 + a.Mvalid - 1) : a.n0 + a.Mvalid - 1)) / 32 + 1;
     const int cnt = (kb_end - half + NW - 1) / NW;              // this wavefront's blocks: half, half + NW, ..
     const float c = a.scale_log2e;
     // one register buffer: the other wavefronts of the CU cover the load (a second buffer, loaded one block ahead,
     // costs more in registers than it hides: 25.6 us against 19.3 us per layer at 1024 rows)
+    auto block = [&](const KvBlock<D>& b, int kb) {
+      if (kb * 32 + 31 >= a.n0) attn_block<D, true, QUAD>(b, qf, O, mrun, lrun, kb, a.n0, a.Mvalid, a.mode, row, g, c);
+      else attn_block<D, false>(b, qf, O, mrun, lrun, kb, a.n0, a.Mvalid, a.mode, row, g, c);
+    };
     KvBlock<D> b0;
     for (int j = 0; j < cnt; ++j) {
       const int kb = half + NW * j;
       kv_load<D>(b0, Kh, Vh, kb, lane);
       asm volatile("" ::: "memory");
-      if (kb * 32 + 31 >= a.n0) attn_block<D, true>(b0, qf, O, mrun, lrun, kb, a.n0, a.Mc, 1, row, g, c);
-      else attn_block<D, false>(b0, qf, O, mrun, lrun, kb, a.n0, a.Mc, 1, row, g, c);
+      block(b0, kb);
     }
   }
   // wavefronts 1.. of an item hand their (max, sum, O) to wavefront 0 through LDS

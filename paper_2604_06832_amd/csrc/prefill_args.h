@@ -26,6 +26,7 @@ struct PfGemmArgs {
   int max_kb, n0;         // key blocks per kv head; position of the chunk's first row
   u16* act;               // packed SwiGLU output (gate/up)
   int H, QD, KVD, D, n_q;
+  const DevState* st; int skippable;   // nothing to do once the block is complete (DevState::skip)
 };
 
 struct PfAttnArgs {
@@ -35,18 +36,28 @@ struct PfAttnArgs {
   float scale_log2e;
   u16* out;               // packed attention output (K = n_q*D)
   int MTc;
+  int mode;               // visibility among the chunk's own rows: BD_MODE_* (bits 8.. = B of a quadratic forward)
+  int Mvalid;             // rows of the chunk: keys n0 + Mvalid .. do not exist
+  const DevState* st; int skippable;   // nothing to do once the block is complete (DevState::skip)
 };
 
 
-// One chunk of prompt rows through all layers (k_prefill.hip): plain pointers and sizes of the context.
+// One chunk of rows through all layers (k_prefill.hip): plain pointers and sizes of the context.  The rows are prompt
+// rows (embeds / ids from row `off`), or, with `block` set, the tokens of a decode block (ids[0..rows), masked rows
+// taking the mask token, position 0 seeded from the carry like the prologue of the decode kernels does).
 struct PfChunk {
   int rows, off;                  // rows of the chunk; prompt row of its first row
   int n0;                         // cache position of its first row
   const float* embeds; int n_embed; const int32_t* ids;
+  bool block;                     // rows are a decode block
+  int32_t* seed_tokens; uint8_t* seed_mask; const uint8_t* mask;
+  int mode;                       // BD_MODE_* among the chunk's rows (prompt chunks: causal)
+  int quad_W;                     // > 0: rows are groups of quad_W tokens, row r at position n + r / W + r % W (Alg. 2)
+  int skippable;
   const u16* table; int vocab, mask_id;
   int L, H, QD, KVD, NQKV, F, D, n_q, n_kv, max_kb;
   float rms_eps, rope_theta;
-  const DevState* st;
+  DevState* st;                   // (a block forward writes its seed flag)
   bool fp8, staged;
   const float* gains; const float* wscale; int wscale_layer; int wscale_off[4];
   const u16* w; size_t layer_elems; size_t w_off[4];

@@ -90,12 +90,21 @@ def check_argmax_ids(got_ids, got_logits, want_logits, n_layers):
 class Pair:
     """A HIP context and an oracle holding the same model and prompt."""
 
-    def __init__(self, shape, weights, max_seq, max_block=64, oracle_dtype=np.float64, gpu_weights=None, flags=0):
+    def __init__(self, shape, weights, max_seq, max_block=64, oracle_dtype=np.float64, gpu_weights=None, flags=0,
+                 predecode=False):
         self.shape = shape
         self.L = shape.n_layers
-        self.o = BlockDiffusionOracle(shape, weights, dtype=oracle_dtype)
         fp8 = weights["l0.wq"].dtype == np.uint8
-        self.ctx = binding.Context(shape, max_seq=max_seq, max_block=min(max_block, 32) if fp8 else max_block,
+        if predecode and fp8:
+            # The oracle turns e4m3 codes and scales into real values every time it touches a matrix; at full depth
+            # that takes longer than the forwards.  Here it does so once, with its own routine, and then runs on the values.
+            dec = BlockDiffusionOracle(shape, weights, dtype=oracle_dtype)
+            if gpu_weights is None:
+                gpu_weights = weights
+            weights = {k: (dec._mat(k) if v.dtype == np.uint8 else v) for k, v in weights.items() if not k.endswith(".scale")}
+        self.o = BlockDiffusionOracle(shape, weights, dtype=oracle_dtype)
+        # (e4m3 contexts too small for the large-M kernels take forwards of up to 32 rows only)
+        self.ctx = binding.Context(shape, max_seq=max_seq, max_block=min(max_block, 32) if fp8 and max_seq <= 128 else max_block,
                                    weight_dtype=binding.BD_FP8_E4M3 if fp8 else binding.BD_BF16, flags=flags)
         self.ctx.load_model(gpu_weights if gpu_weights is not None else weights,
                             as_bf16_bits=gpu_weights is None and _is_bf16(weights))

@@ -20,7 +20,17 @@ pytestmark = pytest.mark.gpu
 
 
 def _say(msg):
+    """Progress line: printed, and appended to a file next to the other run outputs (a test that computes on the host
+    for minutes still shows that it is alive when pytest captures its output)."""
     print(msg, flush=True)
+    try:
+        import os
+        d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "test_progress.log"), "a") as f:
+            f.write(msg + "\n")
+    except OSError:
+        pass
 
 
 # ---- configs[0]: the tiny plumbing model ---------------------------------------------------------------
@@ -371,17 +381,19 @@ def test_speculative_step_needs_a_carry():
 
 # ---- quadratic speculative decoding (Alg. 2): one forward per iteration -----------------------------------------
 
-@pytest.mark.parametrize("B", [1, 2, 3, 5, 7])
+@pytest.mark.parametrize("B", [1, 2, 3, 5, 7, 8, 16])
 def test_quadratic_step_against_the_oracle(B):
     """Draft, then iterations of the quadratic step, each held against the oracle's on the same state: logits of all
     B(B+1) rows, accept length, next draft, carry, and the cache (keys and values of the accepted first tokens moved
-    into place).  B = 5 (30 rows) runs on the streaming kernel, B = 7 (56 rows) on the register-ring kernel."""
+    into place).  B = 5 (30 rows) runs on the streaming kernel, B = 7 (56 rows) on the register-ring kernel (the context
+    is too small for the large-M kernels), B = 8 (72 rows) and B = 16 (272 rows) on the large-M kernels with the quadratic
+    mask and the per-row positions, the LM head in slices of 64 rows."""
     _say(f"quadratic step vs oracle, tiny config, B={B}")
     shape = inputs.TINY
     w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, threads=1)
     emb, ids = inputs.make_prompt(shape, 24, 24, seed=6)
     M = B * (B + 1)
-    p = Pair(shape, w, max_seq=48 + 6 * B + M, max_block=max(M, 4))
+    p = Pair(shape, w, max_seq=48 + 6 * B + M, max_block=min(max(M, 4), 64))
     p.prefill(emb, ids)
     import copy
     greedy = copy.deepcopy(p.o).greedy_ar(6)
@@ -485,13 +497,14 @@ def test_quadratic_step_rejects_blocks_that_do_not_fit():
     ctx.close()
 
 
-def test_quadratic_step_3b_shaped_two_layers():
-    _say("quadratic step vs oracle, 3B-shaped x2 layers, B=5 (30 rows)")
+@pytest.mark.parametrize("B", [5, 8, 16])
+def test_quadratic_step_3b_shaped_two_layers(B):
+    M = B * (B + 1)
+    _say(f"quadratic step vs oracle, 3B-shaped x2 layers, B={B} ({M} rows)")
     shape = _wide(2, vocab=8192)
     w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, threads=8)
     emb, ids = inputs.make_prompt(shape, 100, 41, seed=13)
-    B, M = 5, 30
-    p = Pair(shape, w, max_seq=141 + 3 * B + M, max_block=32)
+    p = Pair(shape, w, max_seq=141 + 3 * B + M, max_block=32 if M <= 32 else 64)
     p.prefill(emb, ids)
     d_gpu = torch.zeros(B, dtype=torch.int32, device="cuda")
     nxt = torch.zeros(B, dtype=torch.int32, device="cuda")
@@ -523,7 +536,7 @@ def _wide(n_layers, vocab=32000):
                              vocab=vocab)
 
 
-@pytest.mark.parametrize("B", [4, 8, 16, 32, 64])
+@pytest.mark.parametrize("B", [4, 8, 16, 32, 33, 64])
 def test_3b_shaped_two_layers_block_sizes(B):
     _say(f"3B-shaped x2 layers, B={B}")
     shape = _wide(2)
@@ -609,9 +622,102 @@ def test_long_prefix_3b_shaped_two_layers():
     p.check_carry()
     p.check_kv(8000, 192)
     tok, msk = fresh_block(shape, 32)
-    for _ in range(2):
+    while msk.any():
         tok, msk, _ = p.denoise_step(tok, msk, 0.9, fixed_k=4)
+    p.commit(tok)
+    p.check_kv(8192, 32)
+    # a verify call on top of the 8224 tokens: logits of all rows and the predictions against the oracle's
+    import copy
+    draft = np.asarray(tok[:16], np.int32)
+    r = copy.deepcopy(p.o).verify_block(draft, commit=False)
+    pred = torch.zeros(16, dtype=torch.int32, device="cuda")
+    nacc = torch.zeros(1, dtype=torch.int32, device="cuda")
+    p.ctx.bd_verify_block(torch.from_numpy(draft).cuda(), False, pred, nacc)
+    glog = p.ctx.bd_read_logits(16).cpu().numpy()
+    assert_logits_close(glog, r["logits"], n_layers=shape.n_layers)
+    check_argmax_ids(pred.cpu().numpy(), glog, r["logits"], shape.n_layers)
+    assert p.ctx.bd_cache_len() == 8224
     p.close()
+
+
+# ---- configs[3] at 3B width: verification of drafts of every block size on a 2048-token prefix -----------------
+
+def test_verify_block_sizes_3b_shaped_prefix_2048():
+    """bd_verify_block on a 2048-token prefix (1536 embeddings + 512 ids), 3B-shaped x2 layers, drafts of 4 .. 64
+    tokens (the greedy continuation with a fifth of the tokens replaced): logits of every row, the predictions and the
+    accept length against the oracle; blocks of 64 run on the large-M kernels, the others on the streaming kernel."""
+    _say("3B-shaped x2 layers, prefix 2048, verify blocks of 4 .. 64 tokens")
+    shape = _wide(2, vocab=8192)
+    w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, threads=8)
+    p = Pair(shape, w, max_seq=2048 + 64, oracle_dtype=np.float32)
+    for seed in range(103, 111):                 # (a prompt whose last row decides its argmax beyond the id margin)
+        emb, ids = inputs.make_prompt(shape, 1536, 512, seed=seed)
+        p.prefill(emb, ids, oracle_chunk=512)
+        p.check_carry()
+        if p.carry_is_robust():
+            break
+    assert p.carry_is_robust()
+    import copy
+    clean = copy.deepcopy(p.o).greedy_ar(64)
+    held = 0
+    for B in (4, 8, 16, 32, 33, 64):
+        _say(f"  B={B}")
+        draft, _ = inputs.corrupt_draft(shape, clean[:B], seed=B, p=0.2)
+        r = copy.deepcopy(p.o).verify_block(draft, commit=False)
+        pred = torch.zeros(B, dtype=torch.int32, device="cuda")
+        nacc = torch.zeros(1, dtype=torch.int32, device="cuda")
+        p.ctx.bd_verify_block(torch.from_numpy(draft).cuda(), False, pred, nacc)
+        assert p.ctx.bd_cache_len() == 2048
+        glog = p.ctx.bd_read_logits(B).cpu().numpy()
+        assert_logits_close(glog, r["logits"], n_layers=shape.n_layers)
+        ok = check_argmax_ids(pred.cpu().numpy(), glog, r["logits"], shape.n_layers)
+        decided = bool(ok[:max(r["n_accept"], 1)].all() and p.carry_is_robust())
+        held += int(decided)
+        if decided:
+            assert int(nacc.item()) == r["n_accept"], (B, int(nacc.item()), r["n_accept"])
+        else:
+            gp = np.concatenate([[p.ctx.bd_read_carry()[0]], pred.cpu().numpy()[:-1]])
+            k = 0
+            while k < B and gp[k] == draft[k]:
+                k += 1
+            assert int(nacc.item()) == k
+    note("count", what="accept lengths held against the oracle's (of 6 block sizes)", n=held)
+    assert held >= 1, held
+    p.close()
+
+
+@pytest.mark.parametrize("B", [33, 64])
+def test_large_m_forward_agrees_with_the_register_ring_kernel(B):
+    """Forwards of 33 .. 64 rows run on the large-M kernels where the context has their buffers, else (or with
+    BD_FLAG_PREFILL_DECODE) on the register-ring kernel: two implementations of the same forward, written apart, must
+    agree to bf16 rounding on logits and cache, for the bidirectional and the causal mask."""
+    _say(f"3B-shaped x2 layers, B={B}: large-M kernels vs register-ring kernel")
+    shape = _wide(2, vocab=8192)
+    w = inputs.make_weights(shape, 4, "bf16", threads=8)
+    emb, ids = inputs.make_prompt(shape, 96, 37, seed=11)
+    outs = []
+    for flags in (0, binding.BD_FLAG_PREFILL_DECODE):
+        ctx = binding.Context(shape, max_seq=133 + 2 * 64, max_block=64, flags=flags)
+        ctx.load_model(w, as_bf16_bits=True)
+        ctx.bd_debug_logits(True)
+        ctx.bd_prefill(torch.from_numpy(emb).cuda(), torch.from_numpy(ids).cuda())
+        tok, msk = fresh_block(shape, B)
+        gt = torch.from_numpy(tok.astype(np.int32)).cuda()
+        gm = torch.from_numpy(msk.astype(np.uint8)).cuda()
+        ctx.bd_denoise_step(gt, gm, 0.9, 4, None, None)
+        res = [ctx.bd_read_logits(B).clone()]
+        ctx.bd_commit_block(torch.arange(7, 7 + B, dtype=torch.int32, device="cuda"))
+        res.append(ctx.bd_read_logits(B).clone())
+        k, v = ctx.bd_read_kv(1, 133, B)
+        res += [k.clone(), v.clone()]
+        ctx.bd_status()
+        ctx.close()
+        outs.append(res)
+    for i, (x, y) in enumerate(zip(*outs)):
+        scale = float(y.abs().max())
+        err = float((x - y).abs().max())
+        note("count", what=f"output {i}: max abs difference / range x 1e6", n=int(1e6 * err / scale))
+        assert err <= 2e-2 * scale, (i, err, scale)
 
 
 # ---- configs[4]: e4m3 decoder weights with per-output-channel scales ---------------------------------------
@@ -688,7 +794,7 @@ def test_fp8_whole_block_and_speculative_calls():
     b.close()
 
 
-@pytest.mark.parametrize("B", [4, 16, 32])
+@pytest.mark.parametrize("B", [4, 16, 32, 33, 64])
 def test_fp8_3b_shaped_two_layers(B):
     _say(f"3B-shaped x2 layers, e4m3 decoder linears, B={B}")
     shape = _wide(2)
@@ -747,6 +853,31 @@ def test_headline_config_first_block_full_depth():
     assert fwd == 8
     p.commit(tok)
     assert p.ctx.bd_forward_bytes() == 2 * shape.weight_elements() + 36864 * (1024 + 32)
+    p.close()
+
+
+@pytest.mark.slow
+def test_fp8_config_first_block_full_depth():
+    """configs[4] at full depth: e4m3 decoder linears, 36 layers, the first block of 32 tokens (8 denoising forwards +
+    commit) against the fp32 oracle on the same codes and scales, to the e4m3 bars.  The prefix is 1024 tokens here (the
+    oracle's prompt pass over 2048 takes minutes; the 2048-token prefix is held at reduced depth above)."""
+    shape = inputs.QWEN3B
+    _say("generating 3B-shaped e4m3 weights (seed 2)")
+    w = inputs.make_weights(shape, 2, "fp8", threads=16)
+    emb, ids = inputs.make_prompt(shape, 768, 256, seed=104)
+    _say("uploading + oracle prefill of 1024 tokens")
+    p = Pair(shape, w, max_seq=1024 + 64, oracle_dtype=np.float32, predecode=True)
+    p.prefill(emb, ids, oracle_chunk=256)
+    glog = p.ctx.bd_read_logits(1).cpu().numpy()[0]
+    assert_logits_close(glog, p.o.carry, FP8_LOGIT_TOL, what="carry logits", n_layers=shape.n_layers)
+    tok, msk = fresh_block(shape, 32)
+    fwd = 0
+    while msk.any():
+        tok, msk, r = p.denoise_step(tok, msk, 0.9, fixed_k=4, frac=FP8_LOGIT_TOL)
+        fwd += 1
+        _say(f"  denoise forward {fwd}: {int((~msk).sum())}/32 revealed")
+    assert fwd == 8
+    p.commit(tok, frac=FP8_LOGIT_TOL)
     p.close()
 
 
