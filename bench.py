@@ -84,6 +84,10 @@ def main():
     ap.add_argument("--timeline", action="store_true",
                     help="instead of the benchmark: print the per-phase time line of one denoising forward (in-kernel "
                          "timestamps) at this prefix, as text")
+    ap.add_argument("--flags", type=int, default=0, help="bd_config.flags of the context (alternative code paths, see include/bd.h)")
+    ap.add_argument("--floors", action="store_true",
+                    help="bound the layers kernel instead of benchmarking: its time with no weight requests (fixed cost of "
+                         "hand-overs, barriers and arithmetic) and the time of its weight stream alone")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel (reference for hardware byte counters)")
     args = ap.parse_args()
@@ -114,8 +118,8 @@ def main():
     print(f"[bench] weights generated in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
     blocks = args.warmup + args.steps
-    ctx = binding.Context(shape, max_seq=args.prefix + (max(blocks, args.steps) + 1) * B, max_block=32 if fp8 else 64,
-                          weight_dtype=binding.BD_FP8_E4M3 if fp8 else binding.BD_BF16)
+    ctx = binding.Context(shape, max_seq=args.prefix + (max(blocks, args.steps) + 1) * B, max_block=64,
+                          weight_dtype=binding.BD_FP8_E4M3 if fp8 else binding.BD_BF16, flags=args.flags)
     t0 = time.time()
     ctx.load_model(w)
     print(f"[bench] weights uploaded in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
@@ -160,6 +164,39 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.floors:
+        def layers_us(c):
+            c.bd_prefill(d_emb, d_ids)
+            tok.fill_(shape.mask_token_id)
+            msk.fill_(1)
+            for _ in range(3):
+                c.bd_denoise_step(tok, msk, 0.9, 1)
+            c.bd_status()
+            c.bd_k_profile(True)
+            for _ in range(10):
+                c.bd_denoise_step(tok, msk, 0.9, 1)
+            c.bd_status()
+            ms, cnt, _ = c.bd_k_profile_read()["layers"]
+            c.bd_k_profile(False)
+            return ms / cnt * 1e3
+        full = layers_us(ctx)
+        floor_ms, floor_bytes = ctx.bd_k_stream_floor(10)
+        ctx.close()
+        ctx2 = binding.Context(shape, max_seq=args.prefix + 2 * B, max_block=64,
+                               weight_dtype=binding.BD_FP8_E4M3 if fp8 else binding.BD_BF16,
+                               flags=binding.BD_FLAG_MEASURE_NO_WEIGHTS)
+        ctx2.load_model(w)
+        fixed = layers_us(ctx2)
+        ctx2.close()
+        L = shape.n_layers
+        print(f"bounds of the layers kernel: {args.weights} weights, {L} layers, prefix {args.prefix}, B={B} (mean of 10 forwards, HIP events)")
+        print(f"layers kernel as it runs                          {full:8.0f} us  {full / L:6.1f} us per layer")
+        print(f"no weight requests (hand-overs, barriers, MFMAs)  {fixed:8.0f} us  {fixed / L:6.1f} us per layer   [results are wrong by construction]")
+        print(f"weight stream alone ({floor_bytes / 1e9:.3f} GB, no consumer)       {floor_ms * 1e3:8.0f} us  {floor_ms * 1e3 / L:6.1f} us per layer   "
+              f"= {floor_bytes / floor_ms / 1e6:.0f} GB/s")
+        print(f"fixed + stream = {fixed + floor_ms * 1e3:.0f} us; the kernel overlaps {fixed + floor_ms * 1e3 - full:.0f} us of the two")
+        return
 
     if args.timeline:
         ctx.bd_prefill(d_emb, d_ids)

@@ -69,7 +69,9 @@ enum {
   BD_FLAG_PREFILL_DECODE = 4,      /* no large-M kernels: prompts in chunks of max_block rows through the decode kernels, forwards */
                                    /* of 33..64 rows on the register-ring kernel (the only path when max_seq <= 128)              */
   BD_FLAG_PREFILL_STAGED = 8,      /* large-M GEMMs stage their operands through registers instead of loading straight into LDS  */
-  BD_FLAG_ATTENTION_KEY_SPLIT = 16 /* attention of forwards of <= 32 rows by the chip-wide key split instead of per XCD           */
+  BD_FLAG_ATTENTION_KEY_SPLIT = 16,/* attention of forwards of <= 32 rows by the chip-wide key split instead of per XCD           */
+  BD_FLAG_MEASURE_NO_WEIGHTS = 32  /* MEASUREMENT ONLY, RESULTS ARE WRONG: the streaming kernel requests no weights, so a forward  */
+                                   /* takes what its hand-overs, barriers and arithmetic cost without the stream                  */
 };
 
 /* Shape limits: head_dim 64 or 128; n_q_heads a multiple of n_kv_heads; hidden, ffn, vocab and the

@@ -52,6 +52,11 @@ int64_t bd_k_class_bytes(const bd_ctx* ctx, int kclass);
  * phase boundary of the next forwards (start; then per layer: QKV done, barrier, attention done, barrier,
  * O done, barrier, gate/up done, barrier, down done, barrier; then LM head done, barrier).  read copies
  * the last forward's [n_wg][per_wg] table to host memory (capacity in entries). */
+/* Measurement: time of reading the decoder layers' weight stream of one forward with no consumer, hand-over or barrier
+ * (each wavefront its own contiguous share, as the streaming kernel's producers read it): mean of `repeats` launches
+ * in milliseconds to *host_ms, the bytes read per launch to *host_bytes.  Synchronises the stream. */
+int bd_k_stream_floor(bd_ctx* ctx, int repeats, double* host_ms, int64_t* host_bytes);
+
 int bd_k_trace(bd_ctx* ctx, int enable);
 int bd_k_trace_read(bd_ctx* ctx, unsigned long long* host_out, int capacity, int* n_wg, int* per_wg);
 

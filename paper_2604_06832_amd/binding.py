@@ -20,6 +20,7 @@ BD_F32, BD_BF16, BD_FP8_E4M3 = 0, 1, 2
 BD_MODE_BIDIR, BD_MODE_CAUSAL = 0, 1
 BD_FLAG_CHIP_WIDE_HANDOVER, BD_FLAG_REGISTER_RING, BD_FLAG_PREFILL_DECODE, BD_FLAG_PREFILL_STAGED = 1, 2, 4, 8
 BD_FLAG_ATTENTION_KEY_SPLIT = 16
+BD_FLAG_MEASURE_NO_WEIGHTS = 32
 
 # every symbol the two headers declare
 EXPORTS = [
@@ -27,7 +28,7 @@ EXPORTS = [
     "bd_verify_block", "bd_decode_block", "bd_speculative_step", "bd_quad_draft", "bd_quad_step", "bd_crop", "bd_cache_len", "bd_status", "bd_debug_logits", "bd_read_logits", "bd_read_kv",
     "bd_read_carry", "bd_read_rows", "bd_forward_bytes", "bd_strerror", "bd_last_error",
     "bd_k_attention", "bd_k_attention_static", "bd_k_profile", "bd_k_profile_read", "bd_k_class_count", "bd_k_class_name",
-    "bd_k_class_bytes", "bd_k_trace", "bd_k_trace_read",
+    "bd_k_class_bytes", "bd_k_trace", "bd_k_trace_read", "bd_k_stream_floor",
 ]
 
 
@@ -84,6 +85,7 @@ def lib() -> C.CDLL:
     L.bd_k_class_bytes.argtypes = [vp, i32]
     L.bd_k_class_bytes.restype = C.c_int64
     L.bd_k_trace.argtypes = [vp, i32]
+    L.bd_k_stream_floor.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     L.bd_k_trace_read.argtypes = [vp, vp, i32, C.POINTER(i32), C.POINTER(i32)]
     _lib = L
     return L
@@ -258,6 +260,12 @@ def _trace_methods():
     def bd_k_trace(self, enable: bool):
         _check(lib().bd_k_trace(self._h, int(enable)))
 
+    def bd_k_stream_floor(self, repeats: int = 10):
+        """(milliseconds, bytes) of reading one forward's layer weights with no consumer, hand-over or barrier."""
+        ms, nb = C.c_double(0), C.c_int64(0)
+        _check(lib().bd_k_stream_floor(self._h, repeats, C.byref(ms), C.byref(nb)))
+        return ms.value, nb.value
+
     def bd_k_trace_read(self):
         """Timestamps (100 MHz ticks) of the last forward, array [n_wg, per_wg]."""
         n_layers = self.shape.n_layers
@@ -270,6 +278,7 @@ def _trace_methods():
         return buf[:n1].reshape(n_wg.value, per.value)
 
     Context.bd_k_trace = bd_k_trace
+    Context.bd_k_stream_floor = bd_k_stream_floor
     Context.bd_k_trace_read = bd_k_trace_read
 
 

@@ -227,6 +227,7 @@ int launch_forward_kernels(bd_ctx* c, int MT, MegaArgs& a, bool lm_only = false)
       a.attn_local = (!(c->cfg.flags & BD_FLAG_ATTENTION_KEY_SPLIT) &&
                       attn_local_plan(c->plan.nwg, c->xcds, c->cfg.n_kv_heads, c->G * MT, lp)) ? 1 : 0;
       a.xbar = c->xbar; a.xbar_epoch = c->xbar_epoch;
+      a.no_weights = (c->cfg.flags & BD_FLAG_MEASURE_NO_WEIGHTS) ? 1 : 0;
       BD_TRY(launch_stream_fwd(c->stream, MT, c->D, c->fp8, quad, a));
       c->bar_epoch += (a.local_gu ? 4u : 5u) * (unsigned)c->L;
       c->xbar_epoch += (unsigned)((a.local_gu ? 1 : 0) + (a.attn_local ? 1 : 0)) * (unsigned)c->L;
@@ -438,7 +439,7 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
     if (G % 2 != 0) return BD_E_ARG;
   }
   if (k.weight_dtype != BD_BF16 && k.weight_dtype != BD_FP8_E4M3) return BD_E_DTYPE;
-  if (k.flags & ~(BD_FLAG_CHIP_WIDE_HANDOVER | BD_FLAG_REGISTER_RING | BD_FLAG_PREFILL_DECODE | BD_FLAG_PREFILL_STAGED | BD_FLAG_ATTENTION_KEY_SPLIT)) return BD_E_ARG;
+  if (k.flags & ~(BD_FLAG_CHIP_WIDE_HANDOVER | BD_FLAG_REGISTER_RING | BD_FLAG_PREFILL_DECODE | BD_FLAG_PREFILL_STAGED | BD_FLAG_ATTENTION_KEY_SPLIT | BD_FLAG_MEASURE_NO_WEIGHTS)) return BD_E_ARG;
   // e4m3 weights: the streaming kernel takes forwards of up to 32 rows, larger ones need the large-M kernels
   if (k.weight_dtype == BD_FP8_E4M3 && k.max_block > 32 && !(k.max_seq > kPfTokens && !(k.flags & BD_FLAG_PREFILL_DECODE))) return BD_E_ARG;
 
@@ -1022,6 +1023,48 @@ int bd_k_profile_read(bd_ctx* c, int kclass, double* total_ms, int* launches) {
   }
   if (total_ms) *total_ms = tot;
   if (launches) *launches = cnt;
+  return BD_OK;
+}
+
+int bd_k_stream_floor(bd_ctx* c, int repeats, double* host_ms, int64_t* host_bytes) {
+  if (c == nullptr || repeats < 1 || host_ms == nullptr || !c->use_stream) return BD_E_ARG;
+  const MegaPlan& P = c->plan;
+  const int nw = P.nwg * kWavesPerWG;
+  std::vector<unsigned> frags((size_t)nw);
+  int64_t bytes = 0;
+  for (int wg = 0; wg < P.nwg; ++wg)
+    for (int w = 0; w < kWavesPerWG; ++w) {
+      frags[(size_t)wg * kWavesPerWG + w] = (unsigned)((long long)P.L * wave_layer_units(P, wg, w) / 64);
+      bytes += (int64_t)frags[(size_t)wg * kWavesPerWG + w] * 1024;
+    }
+  unsigned* d = nullptr;
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&d), (size_t)nw * 8));
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = BD_OK;
+  float ms = 0.f;
+  auto run = [&]() -> int {
+    HIP_TRY(hipMemcpyAsync(d, frags.data(), (size_t)nw * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    HIP_TRY(hipEventCreate(&e0));
+    HIP_TRY(hipEventCreate(&e1));
+    for (int i = 0; i < repeats + 1; ++i) {
+      if (i == 1) HIP_TRY(hipEventRecord(e0, c->stream));      // (the first launch warms up)
+      hipLaunchKernelGGL(stream_floor_kernel, dim3(P.nwg), dim3(256), 0, c->stream, reinterpret_cast<const floor_u32x4*>(c->wstream),
+                         (long long)P.wave_stride, d, d + nw);
+      BD_TRY(check_launch());
+    }
+    HIP_TRY(hipEventRecord(e1, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+    return BD_OK;
+  };
+  rc = run();
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  (void)hipFree(d);
+  if (rc != BD_OK) return rc;
+  *host_ms = (double)ms / repeats;
+  if (host_bytes) *host_bytes = bytes;
   return BD_OK;
 }
 

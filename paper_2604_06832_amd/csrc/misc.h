@@ -5,6 +5,33 @@
 
 namespace bd {
 
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned floor_u32x4;
+
+// Measurement only: every wavefront reads the weight stream of one forward's layers exactly as the producers of the
+// streaming forward kernel lay it out (wavefront w of workgroup b: its own contiguous range, 1 KiB per load, sixteen
+// loads in flight), with no consumer, no hand-over and no barrier: the time the bytes alone take on this chip.
+__global__ __launch_bounds__(256) void stream_floor_kernel(const floor_u32x4* __restrict__ wstream, long long wave_stride_units,
+                                                            const unsigned* __restrict__ frags, unsigned* __restrict__ out) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int sw = blockIdx.x * 4 + wave;
+  const floor_u32x4* src = wstream + (size_t)sw * wave_stride_units + lane;
+  const unsigned total = frags[sw];
+  unsigned acc = 0;
+  unsigned f = 0;
+  for (; f + 16 <= total; f += 16) {
+    floor_u32x4 v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = __builtin_nontemporal_load(src + (size_t)(f + j) * 64);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc ^= v[j][0] ^ v[j][1] ^ v[j][2] ^ v[j][3];
+  }
+  for (; f < total; ++f) {
+    const floor_u32x4 v = __builtin_nontemporal_load(src + (size_t)f * 64);
+    acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+  }
+  if (acc == 0x9E3779B9u) out[sw] = acc;          // (keeps the loads alive; practically never taken)
+}
+
 __global__ void f32_to_bf16_kernel(const float* __restrict__ src, u16* __restrict__ dst, size_t n) {
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
     dst[i] = f32_to_bf16_bits(src[i]);

@@ -133,8 +133,9 @@ __device__ inline void producer_loop(const MegaArgs& a, int cw, char* ring, unsi
       }
       if (!ok) break;
     }
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (lds_void_t*)(ring + slot * 1024), 16, (int)(issued * 1024u) + lane * 16, 0, 0,
-                                             kAuxNt);
+    if (!a.no_weights)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (lds_void_t*)(ring + slot * 1024), 16, (int)(issued * 1024u) + lane * 16, 0, 0,
+                                               kAuxNt);
     ++issued;
     slot = (slot + 1 == kSlots) ? 0 : slot + 1;
     if (++since == kProdBatch) {
@@ -220,6 +221,7 @@ __device__ inline void producer_loop_stash(const MegaArgs& a, int cw, char* ring
   int fill_g = 0, move_g = 0;                       // stash groups of fragment `issued` / fragment `moved`
   int slot = 0, spins = 0;
   unsigned t_mark = clock_ticks() - kStashBurst * kStashTicksFast;   // start with a full bucket
+  const bool no_w = __builtin_amdgcn_readfirstlane(a.no_weights) != 0;   // measurement only: everything but the loads
   asm volatile("; BD_STASH_BEGIN" ::: "memory");
   while (moved < total_up) {
     // pace of the requests: the background pace while the consumer has plenty buffered, the demand pace once it is
@@ -228,7 +230,7 @@ __device__ inline void producer_loop_stash(const MegaArgs& a, int cw, char* ring
     consumed = lds_ld32(consumed_addr);
     const unsigned ticks = (issued - consumed <= (unsigned)kStashLow) ? kStashTicksFast : kStashTicks;
     unsigned tokens = (now - t_mark) / ticks;
-    if (tokens > kStashBurst) { tokens = kStashBurst; t_mark = now - kStashBurst * ticks; }
+    if (tokens > kStashBurst || no_w) { tokens = kStashBurst; t_mark = now - kStashBurst * ticks; }
     bool progress = false;
 #pragma unroll
     for (int k = 0; k < NG; ++k) {
@@ -249,10 +251,12 @@ __device__ inline void producer_loop_stash(const MegaArgs& a, int cw, char* ring
       }
       if (fill_g == k && issued < total_up && issued - moved < (unsigned)NS && tokens >= (unsigned)kStashGroup) {
         const int off = (int)(issued * 1024u) + lane * 16;
+        if (!no_w) {
 #pragma unroll
-        for (int j = 0; j < kStashGroup; ++j)
-          asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:%3 nt"
-                       : "+v"(st[kStashGroup * k + j]) : "v"(off), "s"(wr), "n"(j * 1024) : "memory");
+          for (int j = 0; j < kStashGroup; ++j)
+            asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen offset:%3 nt"
+                         : "+v"(st[kStashGroup * k + j]) : "v"(off), "s"(wr), "n"(j * 1024) : "memory");
+        }
         issued += kStashGroup;
         tokens -= kStashGroup;
         t_mark += kStashGroup * ticks;
