@@ -28,7 +28,7 @@ int bd_k_attention(void* hip_stream, const float* dev_q, const float* dev_k, con
 
 /* The same operation for callers that cannot allocate device memory (code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc): same arguments, layouts and result as bd_k_attention with
- * iters = 1, but every working buffer (packed K/V, bf16 Q, per-chunk partials) lives in one static device
+ * iters = 1, but every working buffer (packed K/V, bf16 Q, packed bf16 result) lives in one static device
  * array of BD_K_ATTENTION_STATIC_BYTES bytes that each GPU the library runs on holds until the process
  * ends.  The call allocates and frees nothing, records no memset node, only enqueues on hip_stream and
  * does not synchronise.  A shape whose working buffers exceed the array returns BD_E_CAPACITY (the text
