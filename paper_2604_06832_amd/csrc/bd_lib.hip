@@ -393,6 +393,28 @@ int check_decode_call(const bd_ctx* c, int B) {
   return BD_OK;
 }
 
+// The accept length of a speculative or quadratic step, read back together with the device state: a forward that
+// gave up at a barrier leaves the previous call's length behind, so the call fails unless the device reports no error
+// and its context length has advanced by exactly that many tokens.
+int read_accept_length(bd_ctx* c, int B, const char* what, int32_t* k_out) {
+  int32_t k = 0;
+  DevState h;
+  HIP_TRY(hipMemcpyAsync(&k, c->spec_k, 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(hipMemcpyAsync(&h, c->st, sizeof h, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(hipStreamSynchronize(c->stream));
+  if (h.error != 0) {
+    snprintf(g_last_error, sizeof g_last_error, "a grid barrier of the forward kernel timed out; the context is unusable");
+    return BD_E_HIP;
+  }
+  if (k < 1 || k > B || h.n != c->n + k) {
+    snprintf(g_last_error, sizeof g_last_error, "%s step returned an accept length of %d for a block of %d (device length %d, host length %d)",
+             what, (int)k, B, h.n, c->n);
+    return BD_E_HIP;
+  }
+  *k_out = k;
+  return BD_OK;
+}
+
 FinishArgs finish_args(bd_ctx* c, int B) {
   FinishArgs f{};
   f.B = B; f.st = c->st; f.row_cand = c->row_cand; f.row_conf = c->row_conf;
@@ -875,12 +897,7 @@ int bd_quad_step(bd_ctx* c, int B, const int32_t* dev_draft, int32_t* dev_next_d
     BD_TRY(check_launch());
   }
   int32_t k = 0;
-  HIP_TRY(hipMemcpyAsync(&k, c->spec_k, 4, hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipStreamSynchronize(s));
-  if (k < 1 || k > B) {
-    snprintf(g_last_error, sizeof g_last_error, "quadratic step returned an accept length of %d for a block of %d", (int)k, B);
-    return BD_E_HIP;
-  }
+  BD_TRY(read_accept_length(c, B, "quadratic", &k));
   c->n += k;
   c->carry_valid = true;
   *host_n_accepted = k;
@@ -916,12 +933,7 @@ int bd_speculative_step(bd_ctx* c, int B, int32_t* dev_tokens_out, int32_t* host
     BD_TRY(check_launch());
   }
   int32_t k = 0;
-  HIP_TRY(hipMemcpyAsync(&k, c->spec_k, 4, hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipStreamSynchronize(s));
-  if (k < 1 || k > B) {
-    snprintf(g_last_error, sizeof g_last_error, "speculative step returned an accept length of %d for a block of %d", (int)k, B);
-    return BD_E_HIP;
-  }
+  BD_TRY(read_accept_length(c, B, "speculative", &k));
   c->n += k;
   c->carry_valid = true;
   *host_n_accepted = k;
