@@ -86,6 +86,8 @@ def main():
                     help="instead of the benchmark: print the per-phase time line of one denoising forward (in-kernel "
                          "timestamps) at this prefix, as text")
     ap.add_argument("--flags", type=int, default=0, help="bd_config.flags of the context (alternative code paths, see include/bd.h)")
+    ap.add_argument("--shuffle-pages", action="store_true",
+                    help="hand the cache pages out in a shuffled order (the kernels then follow the page table)")
     ap.add_argument("--floors", action="store_true",
                     help="bound the layers kernel instead of benchmarking: its time with no weight requests (fixed cost of "
                          "hand-overs, barriers and arithmetic) and the time of its weight stream alone")
@@ -121,6 +123,9 @@ def main():
     blocks = args.warmup + args.steps
     ctx = binding.Context(shape, max_seq=args.prefix + (max(blocks, args.steps) + 1) * B, max_block=64,
                           weight_dtype=binding.BD_FP8_E4M3 if fp8 else binding.BD_BF16, flags=args.flags)
+    if args.shuffle_pages:
+        n_pages = -(-(args.prefix + (max(blocks, args.steps) + 1) * B) // 32)
+        ctx.bd_kv_page_order(np.random.default_rng(5).permutation(n_pages).astype(np.int32))
     t0 = time.time()
     ctx.load_model(w)
     print(f"[bench] weights uploaded in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)

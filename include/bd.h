@@ -171,6 +171,19 @@ int bd_quad_step(bd_ctx* ctx, int B, const int32_t* dev_draft, int32_t* dev_next
 int bd_crop(bd_ctx* ctx, int new_len);
 
 /* Committed context length, or a negative error. */
+/* Paged cache.  The cache of a context is a pool of max_seq/32 (rounded up) pages of 32 positions, each holding the keys
+ * and values of those positions for every layer and kv head; block i of the sequence (positions 32 i .. 32 i + 31) lives
+ * in whatever page the page list assigns to it, and every kernel follows that list.  Pages are taken from a free list
+ * when a call first touches a block (prefill, any forward: the new rows' keys and values land at cache_len ..) and go
+ * back to it when the context is cut (bd_crop, the crop inside a speculative or quadratic step, the reset of
+ * bd_prefill), last block first.  Results do not depend on which pages hold which blocks.
+ * bd_kv_page_order: the order in which free pages are handed out (host int32[n_pages], a permutation of 0 .. n_pages-1,
+ *   n_pages = ceil(max_seq / 32)); default ascending.  BD_E_STATE while any page is in use (call it before bd_prefill or
+ *   after bd_crop(ctx, 0)), BD_E_ARG for anything that is not such a permutation.
+ * bd_kv_pages: returns the number of blocks in use and writes the page of block i to host_out[i] for i < capacity. */
+int bd_kv_page_order(bd_ctx* ctx, const int32_t* host_order, int n_pages);
+int bd_kv_pages(const bd_ctx* ctx, int32_t* host_out, int capacity);
+
 int bd_cache_len(const bd_ctx* ctx);
 
 /* Synchronise the stream and report the device-side state: BD_E_HIP if a grid barrier of the forward

@@ -28,7 +28,7 @@ EXPORTS = [
     "bd_verify_block", "bd_decode_block", "bd_speculative_step", "bd_quad_draft", "bd_quad_step", "bd_crop", "bd_cache_len", "bd_status", "bd_debug_logits", "bd_read_logits", "bd_read_kv",
     "bd_read_carry", "bd_read_rows", "bd_forward_bytes", "bd_strerror", "bd_last_error",
     "bd_k_attention", "bd_k_attention_static", "bd_k_profile", "bd_k_profile_read", "bd_k_class_count", "bd_k_class_name",
-    "bd_k_class_bytes", "bd_k_trace", "bd_k_trace_read", "bd_k_stream_floor",
+    "bd_k_class_bytes", "bd_k_trace", "bd_k_trace_read", "bd_k_stream_floor", "bd_kv_page_order", "bd_kv_pages",
 ]
 
 
@@ -85,6 +85,8 @@ def lib() -> C.CDLL:
     L.bd_k_class_bytes.argtypes = [vp, i32]
     L.bd_k_class_bytes.restype = C.c_int64
     L.bd_k_trace.argtypes = [vp, i32]
+    L.bd_kv_page_order.argtypes = [vp, vp, i32]
+    L.bd_kv_pages.argtypes = [vp, vp, i32]
     L.bd_k_stream_floor.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     L.bd_k_trace_read.argtypes = [vp, vp, i32, C.POINTER(i32), C.POINTER(i32)]
     _lib = L
@@ -260,6 +262,19 @@ def _trace_methods():
     def bd_k_trace(self, enable: bool):
         _check(lib().bd_k_trace(self._h, int(enable)))
 
+    def bd_kv_page_order(self, order):
+        """Order in which free cache pages are handed out: a permutation of range(ceil(max_seq / 32))."""
+        o = np.ascontiguousarray(order, dtype=np.int32)
+        _check(lib().bd_kv_page_order(self._h, o.ctypes.data, int(o.size)))
+
+    def bd_kv_pages(self):
+        """Pages of the blocks in use, in sequence order."""
+        n = lib().bd_kv_pages(self._h, None, 0)
+        _check(min(n, 0))
+        out = np.zeros(max(n, 1), dtype=np.int32)
+        lib().bd_kv_pages(self._h, out.ctypes.data, n)
+        return out[:n]
+
     def bd_k_stream_floor(self, repeats: int = 10):
         """(milliseconds, bytes) of reading one forward's layer weights with no consumer, hand-over or barrier."""
         ms, nb = C.c_double(0), C.c_int64(0)
@@ -279,6 +294,8 @@ def _trace_methods():
 
     Context.bd_k_trace = bd_k_trace
     Context.bd_k_stream_floor = bd_k_stream_floor
+    Context.bd_kv_page_order = bd_kv_page_order
+    Context.bd_kv_pages = bd_kv_pages
     Context.bd_k_trace_read = bd_k_trace_read
 
 

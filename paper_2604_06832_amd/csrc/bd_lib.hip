@@ -48,6 +48,9 @@ struct bd_ctx {
   int device = 0, num_cus = 256;
   int H, QD, KVD, NQKV, F, V, D, L, G;
   int Mp_max, max_kb;
+  // paged cache: block kb of the sequence lives in page page_of[kb] (-1: none yet); pages come off the back of `free_pages`
+  int* kv_pages = nullptr; std::vector<int> page_of, free_pages; int blocks_in_use = 0;
+  int scattered = 0;               // blocks in use that do not sit in the page of their own number (0: the cache is contiguous)
   int rows_max = 0;                // most rows any forward can have: Mp_max, or the rows of a quadratic forward through the large-M kernels
   MegaPlan plan;
   // weights
@@ -250,6 +253,46 @@ int launch_forward_kernels(bd_ctx* c, int MT, MegaArgs& a, bool lm_only = false)
 constexpr int kQuadMaxB = 16;      // largest block of a quadratic step: B (B + 1) = 272 rows
 constexpr int kStreamRows = 32;    // rows of a forward the decode kernels stream the weights against (two token tiles)
 
+// ---- paged cache: the host owns the page list, the device holds a copy that the kernels index ---------------------
+// Pages for every block that holds a position below `upto`, taken off the free list in order; the device table follows
+// in stream order.
+int ensure_pages(bd_ctx* c, int upto) {
+  const int need = std::min(ceil_div(upto, 32), c->max_kb);
+  while (c->blocks_in_use < need) {
+    PageVals pv{};
+    const int kb0 = c->blocks_in_use;
+    int cnt = 0;
+    while (cnt < 16 && kb0 + cnt < need) {
+      if (c->free_pages.empty()) { set_last_error("paged cache: no free page for block %d", kb0 + cnt); return BD_E_CAPACITY; }
+      const int pg = c->free_pages.back();
+      c->free_pages.pop_back();
+      c->page_of[(size_t)(kb0 + cnt)] = pg;
+      c->scattered += pg != kb0 + cnt;
+      pv.v[cnt++] = pg;
+    }
+    hipLaunchKernelGGL(set_pages_kernel, dim3(1), dim3(64), 0, c->stream, c->kv_pages, kb0, cnt, pv);
+    BD_TRY(check_launch());
+    c->blocks_in_use += cnt;
+  }
+  return BD_OK;
+}
+
+// Truncate the page list to the blocks that hold positions below `len`: the others go back to the free list, last
+// block first (so that growing again hands them out in the same order).
+void release_pages(bd_ctx* c, int len) {
+  const int keep = ceil_div(len, 32);
+  while (c->blocks_in_use > keep) {
+    const int kb = --c->blocks_in_use;
+    c->scattered -= c->page_of[(size_t)kb] != kb;
+    c->free_pages.push_back(c->page_of[(size_t)kb]);
+    c->page_of[(size_t)kb] = -1;
+  }
+}
+
+// The table the kernels follow: none while every block in use sits in the page of its own number (the default hand-out
+// order on a single sequence: the cache is contiguous and the kernels skip the look-ups).
+const int* page_table(const bd_ctx* c) { return c->scattered ? c->kv_pages : nullptr; }
+
 // What every chunk through the large-M kernels shares: shapes, weights, cache and working buffers of the context.
 PfChunk chunk_args(bd_ctx* c) {
   PfChunk p{};
@@ -263,7 +306,7 @@ PfChunk chunk_args(bd_ctx* c) {
   p.gains = c->gains; p.wscale = c->wscale; p.wscale_layer = c->wscale_layer;
   for (int i = 0; i < 4; ++i) { p.wscale_off[i] = c->wscale_off[i]; p.w_off[i] = c->pf_off[i]; }
   p.w = c->pf_w; p.layer_elems = c->pf_layer_elems;
-  p.Kc = c->Kc; p.Vc = c->Vc; p.kv_layer_elems = c->kv_layer_elems;
+  p.Kc = c->Kc; p.Vc = c->Vc; p.kv_layer_elems = c->kv_layer_elems; p.pages = page_table(c);
   p.x = c->pf_x; p.xb = c->pf_xb; p.rs = c->pf_rs; p.rope = c->pf_rope; p.q = c->pf_q; p.ap = c->pf_ap; p.act = c->pf_act;
   p.part = c->pf_part;
   p.mode = BD_MODE_CAUSAL;
@@ -272,6 +315,7 @@ PfChunk chunk_args(bd_ctx* c) {
 
 // One chunk of `rows` prompt rows starting at prompt row `off` = cache position c->n through the large-M kernels.
 int prefill_chunk(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* dev_ids, int off, int rows) {
+  BD_TRY(ensure_pages(c, c->n + rows));
   PfChunk p = chunk_args(c);
   p.rows = rows; p.off = off;
   p.embeds = dev_embeds; p.n_embed = n_embed; p.ids = dev_ids;
@@ -329,6 +373,7 @@ int forward_large(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds,
 // Source of the rows: prompt rows [off, off+M) (embeds then ids), or block tokens with an optional mask.
 int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n_embed, const int32_t* ids, int off,
             int32_t* seed_tokens, uint8_t* seed_mask, const uint8_t* mask, bool skippable, int quad_B, bool lm_only, int row0) {
+  if (!lm_only) BD_TRY(ensure_pages(c, c->n + M));          // the new rows' keys and values land at [n, n + M)
   if (!lm_only && M > kStreamRows && c->pf_on && M <= std::max(c->Mp_max, c->rows_max))
     return forward_large(c, M, mode, want_lm, embeds, n_embed, ids, off, seed_tokens, seed_mask, mask, skippable, quad_B);
   // lm_only: the last residual version of the rows (bf16 copy and sums of squares) is already in place; only the final
@@ -361,6 +406,7 @@ int forward(bd_ctx* c, int M, int mode, bool want_lm, const float* embeds, int n
   a.fp8 = c->fp8 ? 1 : 0; a.wscale = c->wscale; a.wscale_layer = c->wscale_layer;
   for (int i = 0; i < 4; ++i) a.wscale_off[i] = c->wscale_off[i];
   a.rope = c->rope; a.Q = c->q; a.Kc = c->Kc; a.Vc = c->Vc; a.kv_layer_elems = c->kv_layer_elems; a.max_kb = c->max_kb;
+  a.kv_pages = page_table(c);
   a.ap = c->ap; a.ap_elems = c->ap_elems; a.act = c->act; a.act_elems = c->act_elems;
   a.wsD = c->wsD; a.wsD_layer_floats = c->wsD_layer_floats; a.cntD = c->counters;
   a.pO = c->pO; a.pm = c->pm; a.pl = c->pl; a.pO_layer_floats = c->pO_layer_floats; a.pml_layer_floats = c->pml_layer_floats;
@@ -573,6 +619,16 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
       A(c->pf_part, (size_t)kPfSplit * R * c->H * 4);
     }
   }
+  {
+    // page table of the cache: every block is a page; none is in use yet, and the free list hands them out in
+    // ascending order unless bd_kv_page_order says otherwise.  (The device copy starts as the identity: an entry of a
+    // block that is not in use is never followed, but it always names an existing page.)
+    A(c->kv_pages, (size_t)c->max_kb * 4);
+    c->page_of.assign((size_t)c->max_kb, -1);
+    c->free_pages.resize((size_t)c->max_kb);
+    for (int i = 0; i < c->max_kb; ++i) c->free_pages[(size_t)i] = c->max_kb - 1 - i;
+    hipLaunchKernelGGL(iota_kernel, dim3(ceil_div(c->max_kb, 256)), dim3(256), 0, c->stream, c->kv_pages, c->max_kb);
+  }
   A(c->st, sizeof(DevState));
   A(c->bar, (size_t)(1 + 2 * ceil_div(P.nwg, kBarGroup)) * 32 * 4);
   A(c->xbar, (size_t)8 * 32 * 4);
@@ -727,6 +783,7 @@ int bd_prefill(bd_ctx* c, const float* dev_embeds, int n_embed, const int32_t* d
   hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, s, c->st, 0, 1);
   BD_TRY(check_launch());
   c->n = 0; c->prefilled = false; c->carry_valid = false;
+  release_pages(c, 0);
   const int step = c->cfg.max_block;                   // (at most 32 with e4m3 weights, checked at creation)
   int off0 = 0;
   if (c->pf_on && total > kPfTokens) {
@@ -893,13 +950,14 @@ int bd_quad_step(bd_ctx* c, int B, const int32_t* dev_draft, int32_t* dev_next_d
     hipLaunchKernelGGL(finish_quad_kernel, dim3(1), dim3(64), 0, s, f, dev_next_draft);
     BD_TRY(check_launch());
     hipLaunchKernelGGL(quad_compact_kv_kernel, dim3(c->L * c->cfg.n_kv_heads), dim3(256), 0, s, c->Kc, c->Vc, c->kv_layer_elems,
-                       c->cfg.n_kv_heads, c->D, c->max_kb, c->st, c->spec_k, B);
+                       c->cfg.n_kv_heads, c->D, c->max_kb, c->st, c->spec_k, B, page_table(c));
     BD_TRY(check_launch());
   }
   int32_t k = 0;
   BD_TRY(read_accept_length(c, B, "quadratic", &k));
   c->n += k;
   c->carry_valid = true;
+  release_pages(c, c->n);                               // the rows beyond the accepted ones are gone: so are their pages
   *host_n_accepted = k;
   return BD_OK;
 }
@@ -936,6 +994,7 @@ int bd_speculative_step(bd_ctx* c, int B, int32_t* dev_tokens_out, int32_t* host
   BD_TRY(read_accept_length(c, B, "speculative", &k));
   c->n += k;
   c->carry_valid = true;
+  release_pages(c, c->n);                               // the rows beyond the accepted ones are gone: so are their pages
   *host_n_accepted = k;
   return BD_OK;
 }
@@ -948,7 +1007,27 @@ int bd_crop(bd_ctx* c, int new_len) {
   BD_TRY(check_launch());
   c->n = new_len;
   c->carry_valid = false;
+  release_pages(c, new_len);                            // the page list is cut where the context is
   return BD_OK;
+}
+
+int bd_kv_page_order(bd_ctx* c, const int32_t* host_order, int n_pages) {
+  if (c == nullptr || host_order == nullptr || n_pages != c->max_kb) return BD_E_ARG;
+  if (c->blocks_in_use != 0) return BD_E_STATE;
+  std::vector<char> seen((size_t)n_pages, 0);
+  for (int i = 0; i < n_pages; ++i) {
+    const int pg = host_order[i];
+    if (pg < 0 || pg >= n_pages || seen[(size_t)pg]) return BD_E_ARG;
+    seen[(size_t)pg] = 1;
+  }
+  for (int i = 0; i < n_pages; ++i) c->free_pages[(size_t)(n_pages - 1 - i)] = host_order[i];   // the back is handed out first
+  return BD_OK;
+}
+
+int bd_kv_pages(const bd_ctx* c, int32_t* host_out, int capacity) {
+  if (c == nullptr || (host_out == nullptr && capacity > 0) || capacity < 0) return BD_E_ARG;
+  for (int i = 0; i < c->blocks_in_use && i < capacity; ++i) host_out[i] = c->page_of[(size_t)i];
+  return c->blocks_in_use;
 }
 
 int bd_cache_len(const bd_ctx* c) { return c == nullptr ? BD_E_ARG : c->n; }
@@ -984,7 +1063,7 @@ int bd_read_kv(bd_ctx* c, int layer, int pos0, int count, float* dev_k_out, floa
   if (pos0 + count > c->cfg.max_seq) return BD_E_ARG;
   hipLaunchKernelGGL(read_kv_kernel, dim3(256), dim3(256), 0, c->stream, c->Kc + (size_t)layer * c->kv_layer_elems,
                      c->Vc + (size_t)layer * c->kv_layer_elems, c->cfg.n_kv_heads, c->D, c->max_kb, pos0, count,
-                     dev_k_out, dev_v_out, 1);
+                     dev_k_out, dev_v_out, 1, page_table(c));
   return check_launch();
 }
 

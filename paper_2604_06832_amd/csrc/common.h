@@ -60,6 +60,11 @@ __device__ inline size_t vp_index(int key, int d, int DT) {   // element index o
   return ((((size_t)kb * DT + (d >> 4)) * 64) + g * 16 + (d & 15)) * 8 + e;
 }
 
+// Paged cache: the 32-key blocks of a kv head are pages; `pages` maps the block a position falls in (position / 32) to the
+// page that holds it (the same page for every layer and kv head).  A null table is the identity.
+__device__ inline int page_of_block(const int* pages, int kb) { return pages != nullptr ? pages[kb] : kb; }
+__device__ inline int paged_key(const int* pages, int key) { return (page_of_block(pages, key >> 5) << 5) | (key & 31); }
+
 constexpr float kNegBig = -1.0e30f;
 
 // Merge two (max, argmax, sum of exp(. - max)) triples; equal maxima keep the lower index.

@@ -71,7 +71,7 @@ int launch_attention(hipStream_t s, const AttnShape& sh, const AttnBufs& b) {
   PfAttnArgs t{};
   t.q = b.q; t.Kc = b.Kc; t.Vc = b.Vc; t.max_kb = sh.max_kb; t.n0 = sh.n_prefix; t.Mc = sh.Mp; t.n_q = sh.n_q; t.n_kv = sh.n_kv;
   t.scale_log2e = 1.4426950408889634f / std::sqrt((float)sh.D);
-  t.out = b.ap; t.MTc = sh.MT; t.mode = sh.mode; t.Mvalid = sh.M; t.st = nullptr; t.skippable = 0;
+  t.out = b.ap; t.MTc = sh.MT; t.mode = sh.mode; t.Mvalid = sh.M; t.st = nullptr; t.skippable = 0; t.pages = nullptr;
   const int items = sh.n_q * sh.MT;
   if (sh.D == 128) hipLaunchKernelGGL((pf_attn_kernel<128, 8>), dim3(items), dim3(512), 0, s, t);
   else hipLaunchKernelGGL((pf_attn_kernel<64, 8>), dim3(items), dim3(512), 0, s, t);

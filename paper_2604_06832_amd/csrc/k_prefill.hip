@@ -86,7 +86,7 @@ int launch_prefill_chunk(hipStream_t s, const PfChunk& c) {
   g.MTc = MTc; g.Mvalid = rows; g.rs = c.rs; g.rope = c.rope; g.x = c.x; g.q = c.q; g.max_kb = c.max_kb; g.n0 = c.n0;
   g.act = c.act; g.H = c.H; g.QD = c.QD; g.KVD = c.KVD; g.D = c.D; g.n_q = c.n_q;
   g.SK = 1;
-  g.st = c.st; g.skippable = c.skippable;
+  g.st = c.st; g.skippable = c.skippable; g.pages = c.pages;
   int parts = 0;                                   // K splits of the last down projection still to be added to x
   auto norm = [&](const float* gain, const float* kparts, int n_kparts) -> int {
     if (skinny) hipLaunchKernelGGL(pf_norm_row_kernel, dim3(mc), dim3(kPfThreads), 0, s, c.x, c.H, c.rms_eps, c.xb, MTc, c.rs, gain, kparts, n_kparts, skip);
@@ -112,7 +112,7 @@ int launch_prefill_chunk(hipStream_t s, const PfChunk& c) {
       PfAttnArgs t{};
       t.q = c.q; t.Kc = g.Kc; t.Vc = g.Vc; t.max_kb = c.max_kb; t.n0 = c.n0; t.Mc = mc; t.n_q = c.n_q;
       t.n_kv = c.n_kv; t.scale_log2e = 1.4426950408889634f / std::sqrt((float)c.D); t.out = c.ap; t.MTc = MTc;
-      t.mode = c.mode; t.Mvalid = rows; t.st = c.st; t.skippable = c.skippable;
+      t.mode = c.mode; t.Mvalid = rows; t.st = c.st; t.skippable = c.skippable; t.pages = c.pages;
       const int items = t.n_q * (mc / 16);                    // one item per workgroup, its four wavefronts share the blocks
       const bool quad = c.mode >= 2;
       // (few rows leave most CUs without an item: eight wavefronts per item then halve each one's walk over the keys)

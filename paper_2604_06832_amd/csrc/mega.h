@@ -219,6 +219,7 @@ __device__ inline void store_xb(u16* xb, int token, int r, int n, const float* o
 // ---- one GEMM phase ------------------------------------------------------------------------------------------
 struct PhaseCtx {
   int layer, n;             // layer index, committed context length
+  int pg[3];                // pages of the blocks that hold positions n .. n+63 (the new rows' keys and values)
   f32x4* red;               // LDS [4][kT*MT][64]
   bf16x8* xstage;           // LDS, activation fragments: [4 wavefronts][XH][MT][64]
   int* s_flags;             // LDS scratch ints
@@ -247,7 +248,8 @@ __device__ inline void gemm_epilogue(const MegaArgs& a, const PhaseCtx& pc, cons
   if constexpr (PH == PH_QKV) {
     if (!live) return;
     const int D = DC ? DC : P.D, half = D >> 1;
-    const int key = pc.n + token;
+    const int rel = ((pc.n + token) >> 5) - (pc.n >> 5);    // which of the (at most three) blocks of the new rows
+    const int key = ((rel == 0 ? pc.pg[0] : rel == 1 ? pc.pg[1] : pc.pg[2]) << 5) | ((pc.n + token) & 31);   // in its page
     float2 csv[2];
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) {
@@ -652,12 +654,13 @@ __device__ inline void attention_phase(const MegaArgs& a, const PhaseCtx& pc, ch
     const int kb_end = min(n_kb, (chunk + 1) * chunk_len);
     for (int kb = chunk * chunk_len + wave; kb < kb_end; kb += kWavesPerWG) {
       bf16x8 kf[2][DS], vf[DT];
+      const int pb = page_of_block(a.kv_pages, __builtin_amdgcn_readfirstlane(kb));
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int ds = 0; ds < DS; ++ds) kf[t][ds] = Kh[(((size_t)kb * 2 + t) * DS + ds) * 64 + lane];
+        for (int ds = 0; ds < DS; ++ds) kf[t][ds] = Kh[(((size_t)pb * 2 + t) * DS + ds) * 64 + lane];
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) vf[dt] = Vh[((size_t)kb * DT + dt) * 64 + lane];
+      for (int dt = 0; dt < DT; ++dt) vf[dt] = Vh[((size_t)pb * DT + dt) * 64 + lane];
       const bool need_mask = (kb * 32 + 31) >= n;
       bf16x8 pf[JT];
 #pragma unroll
@@ -869,6 +872,7 @@ __global__ __launch_bounds__(kWGThreads, 1) void mega_kernel(MegaArgs a) {
 
   PhaseCtx pc;
   pc.n = a.st->n;
+  for (int i = 0; i < 3; ++i) pc.pg[i] = page_of_block(a.kv_pages, min((pc.n >> 5) + i, a.max_kb - 1));
   pc.xstage = reinterpret_cast<bf16x8*>(lds);
   pc.red = reinterpret_cast<f32x4*>(lds + kWavesPerWG * mega_xh<MT>() * MT * 1024);
   pc.s_flags = s_flags;
@@ -941,6 +945,7 @@ __global__ __launch_bounds__(kWGThreads, 1) void lm_kernel(MegaArgs a) {
   if (!s_flags[0]) return;
   PhaseCtx pc;
   pc.n = 0;
+  pc.pg[0] = pc.pg[1] = pc.pg[2] = 0;
   pc.layer = P.L;
   pc.xstage = reinterpret_cast<bf16x8*>(lds);
   pc.red = reinterpret_cast<f32x4*>(lds + kWavesPerWG * mega_xh<MT>() * MT * 1024);

@@ -41,15 +41,16 @@ __global__ void f32_to_bf16_kernel(const float* __restrict__ src, u16* __restric
 // rot_pairs: the K cache holds each head's dims in rotary-pair order (dim i at 2i, dim i + D/2 at 2i + 1).
 __global__ void read_kv_kernel(const u16* __restrict__ Kc, const u16* __restrict__ Vc, int n_kv, int D, int max_kb,
                                int pos0, int count, float* __restrict__ k_out, float* __restrict__ v_out,
-                               int rot_pairs) {
+                               int rot_pairs, const int* __restrict__ pages) {
   const size_t total = (size_t)count * n_kv * D;
   const size_t kv_head_elems = (size_t)max_kb * 32 * D;
   for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < total;
        idx += (size_t)gridDim.x * blockDim.x) {
     const int d = idx % D, h = (idx / D) % n_kv, p = (int)(idx / ((size_t)D * n_kv));
     const int dk = rot_pairs ? (d < D / 2 ? 2 * d : 2 * (d - D / 2) + 1) : d;
-    if (k_out) k_out[idx] = bf16_bits_to_f32(Kc[h * kv_head_elems + kp_index(pos0 + p, dk, D / 32)]);
-    if (v_out) v_out[idx] = bf16_bits_to_f32(Vc[h * kv_head_elems + vp_index(pos0 + p, d, D / 16)]);
+    const int key = paged_key(pages, pos0 + p);
+    if (k_out) k_out[idx] = bf16_bits_to_f32(Kc[h * kv_head_elems + kp_index(key, dk, D / 32)]);
+    if (v_out) v_out[idx] = bf16_bits_to_f32(Vc[h * kv_head_elems + vp_index(key, d, D / 16)]);
   }
 }
 
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(64) void finish_quad_kernel(FinishArgs a, int* next
 // first rows of groups 0..k-1, i.e. rows i*(B+1), and belong at positions n0 + i.  (Destinations 1..k-1 < B+1 never
 // coincide with a source, so all moves are independent.)  One workgroup per (layer, kv head).
 __global__ void quad_compact_kv_kernel(u16* Kc, u16* Vc, size_t kv_layer_elems, int n_kv, int D, int max_kb, const DevState* st,
-                                       const int* k_ptr, int B) {
+                                       const int* k_ptr, int B, const int* pages) {
   const int layer = blockIdx.x / n_kv, h = blockIdx.x % n_kv;
   const int k = *k_ptr;
   const int n0 = st->n - k;                       // the accept kernel has already advanced the length
@@ -237,9 +238,21 @@ __global__ void quad_compact_kv_kernel(u16* Kc, u16* Vc, size_t kv_layer_elems, 
   u16* vc = Vc + (size_t)layer * kv_layer_elems + (size_t)h * max_kb * 32 * D;
   for (int t = threadIdx.x; t < (k - 1) * D; t += blockDim.x) {
     const int i = 1 + t / D, d = t % D;
-    kc[kp_index(n0 + i, d, D / 32)] = kc[kp_index(n0 + i * (B + 1), d, D / 32)];
-    vc[vp_index(n0 + i, d, D / 16)] = vc[vp_index(n0 + i * (B + 1), d, D / 16)];
+    const int dst = paged_key(pages, n0 + i), src = paged_key(pages, n0 + i * (B + 1));
+    kc[kp_index(dst, d, D / 32)] = kc[kp_index(src, d, D / 32)];
+    vc[vp_index(dst, d, D / 16)] = vc[vp_index(src, d, D / 16)];
   }
+}
+
+// Entries [kb0, kb0 + count) of the page table (count <= 16: the values travel as kernel arguments, so the update is
+// an ordinary launch in stream order, with no host buffer that would have to stay alive).
+struct PageVals { int v[16]; };
+__global__ void iota_kernel(int* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = i;
+}
+__global__ void set_pages_kernel(int* pages, int kb0, int count, PageVals vals) {
+  if ((int)threadIdx.x < count) pages[kb0 + threadIdx.x] = vals.v[threadIdx.x];
 }
 
 // All positions of a block masked (the state before the draft pass of Alg. 1).

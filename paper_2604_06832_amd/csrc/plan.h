@@ -172,6 +172,7 @@ struct MegaArgs {
   const float* gains;         // [2L+1][H]: attn_norm l, ffn_norm l, ..., final_norm
   int skippable;              // this launch belongs to a step that does nothing once the block is complete (DevState::skip)
   int local_gu;               // the gate/up -> down hand-over stays inside each XCD (stream_fwd.h): plain stores, XCD barrier
+  const int* kv_pages;        // page of every 32-key block of the cache (null: contiguous)
   int no_weights;             // measurement only: the producers request nothing (the consumers multiply what the ring held)
   int attn_local;             // the attention phase stays inside each XCD (stream_fwd.h): partials in the XCD's L2, XCD barrier
   int n_xcd;                  // XCDs (8) when workgroup b runs on XCD b mod n_xcd, else 0

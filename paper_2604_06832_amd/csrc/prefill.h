@@ -39,7 +39,7 @@ __device__ inline void pf_epilogue(const PfGemmArgs& a, const f32x4 (&acc)[WN][T
         if (token >= a.Mvalid) continue;
         const int D = a.D, half = D >> 1;
         v *= a.rs[token];
-        const int key = a.n0 + token;
+        const int key = paged_key(a.pages, a.n0 + token);
 #pragma unroll
         for (int pr = 0; pr < 2; ++pr) {
           const int rp = r + 2 * pr;

@@ -26,6 +26,7 @@ struct PfGemmArgs {
   int max_kb, n0;         // key blocks per kv head; position of the chunk's first row
   u16* act;               // packed SwiGLU output (gate/up)
   int H, QD, KVD, D, n_q;
+  const int* pages;       // page of every 32-key block of the cache (null: contiguous)
   const DevState* st; int skippable;   // nothing to do once the block is complete (DevState::skip)
 };
 
@@ -38,6 +39,7 @@ struct PfAttnArgs {
   int MTc;
   int mode;               // visibility among the chunk's own rows: BD_MODE_* (bits 8.. = B of a quadratic forward)
   int Mvalid;             // rows of the chunk: keys n0 + Mvalid .. do not exist
+  const int* pages;       // page of every 32-key block of the cache (null: contiguous)
   const DevState* st; int skippable;   // nothing to do once the block is complete (DevState::skip)
 };
 
@@ -61,7 +63,7 @@ struct PfChunk {
   bool fp8, staged;
   const float* gains; const float* wscale; int wscale_layer; int wscale_off[4];
   const u16* w; size_t layer_elems; size_t w_off[4];
-  u16* Kc; u16* Vc; size_t kv_layer_elems;
+  u16* Kc; u16* Vc; size_t kv_layer_elems; const int* pages;
   float* x; u16* xb; float* rs; float2* rope; u16* q; u16* ap; u16* act; float* part;
 };
 

@@ -55,7 +55,7 @@ __global__ __launch_bounds__(64 * (NW > 4 ? NW : 4), NW > 4 ? 1 : 2) void pf_att
     KvBlock<D> b0;
     for (int j = 0; j < cnt; ++j) {
       const int kb = half + NW * j;
-      kv_load<D>(b0, Kh, Vh, kb, lane);
+      kv_load<D>(b0, Kh, Vh, kb, lane, a.pages);
       asm volatile("" ::: "memory");
       block(b0, kb);
     }

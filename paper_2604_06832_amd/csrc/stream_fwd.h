@@ -744,9 +744,11 @@ struct KvBlock {
   bf16x8 v[D / 16];
 };
 
+// Block kb of a kv head (the keys of positions 32 kb .. 32 kb + 31) out of the page that holds it.
 template <int D>
-__device__ inline void kv_load(KvBlock<D>& b, const bf16x8* Kh, const bf16x8* Vh, int kb, int lane) {
+__device__ inline void kv_load(KvBlock<D>& b, const bf16x8* Kh, const bf16x8* Vh, int kb_logical, int lane, const int* pages) {
   constexpr int DS = D / 32, DT = D / 16;
+  const int kb = page_of_block(pages, __builtin_amdgcn_readfirstlane(kb_logical));
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -864,16 +866,16 @@ __device__ inline void stream_attention_phase(const MegaArgs& a, FwdCtx& fc, Fwd
     const int kb0 = chunk * chunk_len + wave;
     // two register buffers, loads pinned one block ahead of their use
     KvBlock<D> b0, b1;
-    if (kb0 < kb_end) kv_load<D>(b0, Kh, Vh, kb0, lane);
+    if (kb0 < kb_end) kv_load<D>(b0, Kh, Vh, kb0, lane, a.kv_pages);
     asm volatile("" ::: "memory");
     for (int kb = kb0; kb < kb_end; kb += 2 * kWavesPerWG) {
       const int kb1 = kb + kWavesPerWG, kb2 = kb + 2 * kWavesPerWG;
-      if (kb1 < kb_end) kv_load<D>(b1, Kh, Vh, kb1, lane);
+      if (kb1 < kb_end) kv_load<D>(b1, Kh, Vh, kb1, lane, a.kv_pages);
       asm volatile("" ::: "memory");
       if (kb * 32 + 31 >= n) attn_block<D, true, QUAD>(b0, qf, O, mrun, lrun, kb, n, a.M, a.mode, row, g, c);
       else attn_block<D, false>(b0, qf, O, mrun, lrun, kb, n, a.M, a.mode, row, g, c);
       if (kb1 < kb_end) {
-        if (kb2 < kb_end) kv_load<D>(b0, Kh, Vh, kb2, lane);
+        if (kb2 < kb_end) kv_load<D>(b0, Kh, Vh, kb2, lane, a.kv_pages);
         asm volatile("" ::: "memory");
         if (kb1 * 32 + 31 >= n) attn_block<D, true, QUAD>(b1, qf, O, mrun, lrun, kb1, n, a.M, a.mode, row, g, c);
         else attn_block<D, false>(b1, qf, O, mrun, lrun, kb1, n, a.M, a.mode, row, g, c);
@@ -1066,16 +1068,16 @@ __device__ inline bool stream_attention_local(const MegaArgs& a, FwdCtx& fc, Fwd
     const int stride = kWavesPerWG * lp.NCH;
     const int kb0 = chunk + lp.NCH * wave;
     KvBlock<D> b0, b1;
-    if (kb0 < n_kb) kv_load<D>(b0, Kh, Vh, kb0, lane);
+    if (kb0 < n_kb) kv_load<D>(b0, Kh, Vh, kb0, lane, a.kv_pages);
     asm volatile("" ::: "memory");
     for (int kb = kb0; kb < n_kb; kb += 2 * stride) {
       const int kb1 = kb + stride, kb2 = kb + 2 * stride;
-      if (kb1 < n_kb) kv_load<D>(b1, Kh, Vh, kb1, lane);
+      if (kb1 < n_kb) kv_load<D>(b1, Kh, Vh, kb1, lane, a.kv_pages);
       asm volatile("" ::: "memory");
       if (kb * 32 + 31 >= n) attn_block<D, true, QUAD>(b0, qf, O, mrun, lrun, kb, n, a.M, a.mode, row, g, c);
       else attn_block<D, false>(b0, qf, O, mrun, lrun, kb, n, a.M, a.mode, row, g, c);
       if (kb1 < n_kb) {
-        if (kb2 < n_kb) kv_load<D>(b0, Kh, Vh, kb2, lane);
+        if (kb2 < n_kb) kv_load<D>(b0, Kh, Vh, kb2, lane, a.kv_pages);
         asm volatile("" ::: "memory");
         if (kb1 * 32 + 31 >= n) attn_block<D, true, QUAD>(b1, qf, O, mrun, lrun, kb1, n, a.M, a.mode, row, g, c);
         else attn_block<D, false>(b1, qf, O, mrun, lrun, kb1, n, a.M, a.mode, row, g, c);
@@ -1293,6 +1295,7 @@ __global__ __launch_bounds__(kFwdThreads, 1) void stream_fwd_kernel(MegaArgs a) 
   FwdCtx fc;
   fc.share = lds + kWavesPerWG * kSlots * 1024;
   fc.pc.n = a.st->n;
+  for (int i = 0; i < 3; ++i) fc.pc.pg[i] = page_of_block(a.kv_pages, min((fc.pc.n >> 5) + i, a.max_kb - 1));
   fc.pc.xstage = nullptr;
   fc.pc.red = reinterpret_cast<f32x4*>(fc.share);
   fc.red2 = fc.pc.red + kWavesPerWG * kT * MT * 64;

@@ -68,6 +68,8 @@ int main() {
   CHECK(bd_k_profile(nullptr, 1) == BD_E_ARG);
   CHECK(bd_k_trace(nullptr, 1) == BD_E_ARG);
   CHECK(bd_k_class_count() > 0 && bd_k_class_name(0) != nullptr && bd_k_class_name(99) == nullptr);
+  CHECK(bd_kv_page_order(nullptr, nullptr, 0) == BD_E_ARG);
+  CHECK(bd_kv_pages(nullptr, nullptr, 0) == BD_E_ARG);
   bd_destroy(nullptr);
 
   // creation proper: with a device the whole set-up and tear-down run (allocations, plan, packing tables); without one
@@ -78,6 +80,13 @@ int main() {
     CHECK(bd_cache_len(h) == 0);
     CHECK(bd_status(h) == BD_OK);
     CHECK(bd_crop(h, 0) == BD_E_STATE);                       // nothing prefilled yet
+    {
+      int32_t order[8] = {7, 6, 5, 4, 3, 2, 1, 0}, dup[8] = {0, 0, 1, 2, 3, 4, 5, 6}, out[8];
+      CHECK(bd_kv_page_order(h, order, 8) == BD_OK);          // max_seq 256 = 8 pages
+      CHECK(bd_kv_page_order(h, order, 7) == BD_E_ARG);
+      CHECK(bd_kv_page_order(h, dup, 8) == BD_E_ARG);
+      CHECK(bd_kv_pages(h, out, 8) == 0);                     // nothing in use before the first prefill
+    }
     CHECK(bd_prefill(h, nullptr, 0, nullptr, 0) == BD_E_ARG);
     float one[256];
     for (float& v : one) v = 1.f;

@@ -720,6 +720,121 @@ def test_large_m_forward_agrees_with_the_register_ring_kernel(B):
         assert err <= 2e-2 * scale, (i, err, scale)
 
 
+# ---- paged cache: results do not depend on which pages hold which blocks -----------------------------------------
+
+@pytest.mark.parametrize("flags", [0, binding.BD_FLAG_ATTENTION_KEY_SPLIT, binding.BD_FLAG_REGISTER_RING, binding.BD_FLAG_PREFILL_DECODE])
+def test_paged_cache_any_page_order_gives_the_same_bits(flags):
+    """Two contexts on the same model and prompt, one handing out its cache pages in ascending order (a contiguous
+    cache), one in a shuffled order: prompt pass, denoising steps, commit, verify + crop, a speculative step, quadratic
+    steps (30 and 72 rows), a 64-row forward and a last commit must agree bit for bit in logits, ids, accept lengths and
+    in the cache read back by position -- through the streaming kernel (attention inside the XCDs and by key split), the
+    register-ring kernel and the large-M kernels.  The page lists themselves must differ, shrink at every crop (the list
+    is cut where the context is) and hand the freed pages out again in the same order."""
+    _say(f"paged cache, shuffled vs ascending page order, flags={flags}")
+    shape = _wide(2, vocab=8192)
+    w = inputs.make_weights(shape, 6, "bf16", lm_head_scale=20.0, threads=8)
+    emb, ids = inputs.make_prompt(shape, 150, 57, seed=21)               # 207 rows: large-M prompt pass unless switched off
+    max_seq = 207 + 3 * 64 + 72 + 16
+    n_pages = -(-max_seq // 32)
+    order = np.random.default_rng(5).permutation(n_pages).astype(np.int32)
+    assert not np.array_equal(order, np.arange(n_pages))
+    runs = []
+    for shuffled in (False, True):
+        ctx = binding.Context(shape, max_seq=max_seq, max_block=64, flags=flags)
+        ctx.load_model(w, as_bf16_bits=True)
+        ctx.bd_debug_logits(True)
+        if shuffled:
+            ctx.bd_kv_page_order(order)
+        assert len(ctx.bd_kv_pages()) == 0
+        log, pages = [], []
+
+        def keep(*tensors):
+            log.extend(t.clone() if torch.is_tensor(t) else torch.tensor(t) for t in tensors)
+
+        ctx.bd_prefill(torch.from_numpy(emb).cuda(), torch.from_numpy(ids).cuda())
+        pages.append(ctx.bd_kv_pages().copy())
+        assert len(pages[-1]) == -(-207 // 32)
+        keep(ctx.bd_read_logits(1), *ctx.bd_read_kv(1, 0, 207))
+        tok, msk = fresh_block(shape, 32)
+        gt = torch.from_numpy(tok.astype(np.int32)).cuda()
+        gm = torch.from_numpy(msk.astype(np.uint8)).cuda()
+        while bool(gm.any().item()):
+            ctx.bd_denoise_step(gt, gm, 0.9, 4, None, None)
+            keep(ctx.bd_read_logits(32), gt, gm)
+        ctx.bd_commit_block(gt)                                            # 239
+        keep(ctx.bd_read_logits(32), *ctx.bd_read_kv(0, 200, 39))
+        pages.append(ctx.bd_kv_pages().copy())
+        # verify with commit, then crop into the middle of a block and to a block boundary
+        d = torch.arange(11, 11 + 16, dtype=torch.int32, device="cuda")
+        pred = torch.zeros(16, dtype=torch.int32, device="cuda")
+        nacc = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ctx.bd_verify_block(d, True, pred, nacc)                           # 255
+        keep(ctx.bd_read_logits(16), pred, nacc)
+        ctx.bd_crop(250)
+        assert len(ctx.bd_kv_pages()) == 8
+        ctx.bd_crop(224)
+        pages.append(ctx.bd_kv_pages().copy())
+        assert len(pages[-1]) == 7
+        ctx.bd_commit_block(torch.arange(3, 3 + 8, dtype=torch.int32, device="cuda"))   # 232: block 7 comes back
+        pages.append(ctx.bd_kv_pages().copy())
+        assert len(pages[-1]) == 8 and pages[-1][7] == pages[1][7]
+        out = torch.zeros(64, dtype=torch.int32, device="cuda")
+        k = ctx.bd_speculative_step(8, out)                                # 232 + k
+        keep(ctx.bd_read_logits(8), out[:k], k)
+        for B in (5, 7 if flags & binding.BD_FLAG_PREFILL_DECODE else 8):   # (72 rows need the large-M kernels)
+            dq = torch.zeros(B, dtype=torch.int32, device="cuda")
+            nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+            ctx.bd_quad_draft(B, dq)
+            k = ctx.bd_quad_step(B, dq, nx)
+            keep(ctx.bd_read_logits(B * (B + 1)), dq, nx, k)
+            assert len(ctx.bd_kv_pages()) == -(-ctx.bd_cache_len() // 32)   # the rows beyond the accepted ones gave their pages back
+        n = ctx.bd_cache_len()
+        tok, msk = fresh_block(shape, 64)
+        gt = torch.from_numpy(tok.astype(np.int32)).cuda()
+        gm = torch.from_numpy(msk.astype(np.uint8)).cuda()
+        ctx.bd_denoise_step(gt, gm, 0.9, 8, None, None)
+        keep(ctx.bd_read_logits(64), gt, gm)
+        ctx.bd_commit_block(torch.arange(40, 40 + 64, dtype=torch.int32, device="cuda"))
+        keep(ctx.bd_read_logits(64), *ctx.bd_read_kv(1, 0, n + 64), *ctx.bd_read_kv(0, n - 10, 74))
+        pages.append(ctx.bd_kv_pages().copy())
+        ctx.bd_status()
+        ctx.bd_crop(0)
+        assert len(ctx.bd_kv_pages()) == 0
+        ctx.close()
+        runs.append((log, pages))
+    (la, pa), (lb, pb) = runs
+    assert len(la) == len(lb)
+    for i, (x, y) in enumerate(zip(la, lb)):
+        assert torch.equal(x, y), f"output {i} depends on the page order"
+    for x, y in zip(pa, pb):
+        assert np.array_equal(x, np.arange(len(x)))                        # ascending order = the contiguous cache
+        assert np.array_equal(y, order[:len(y)]) and not np.array_equal(x, y)
+    note("count", what="outputs held bit-identical between page orders", n=len(la))
+
+
+def test_page_order_is_fixed_while_pages_are_in_use():
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, "bf16", threads=1)
+    ctx = binding.Context(shape, max_seq=96, max_block=16)
+    ctx.load_model(w, as_bf16_bits=True)
+    with pytest.raises(binding.BdError) as e:
+        ctx.bd_kv_page_order([0, 1])                                       # not the pool's size
+    assert e.value.code == binding.BD_E_ARG
+    with pytest.raises(binding.BdError):
+        ctx.bd_kv_page_order([0, 0, 1])                                    # not a permutation
+    ctx.bd_kv_page_order([2, 0, 1])
+    ctx.bd_prefill(None, torch.arange(40, dtype=torch.int32, device="cuda"))
+    assert list(ctx.bd_kv_pages()) == [2, 0]
+    with pytest.raises(binding.BdError) as e:
+        ctx.bd_kv_page_order([0, 1, 2])
+    assert e.value.code == binding.BD_E_STATE
+    ctx.bd_crop(0)
+    ctx.bd_kv_page_order([1, 2, 0])
+    ctx.bd_prefill(None, torch.arange(70, dtype=torch.int32, device="cuda"))
+    assert list(ctx.bd_kv_pages()) == [1, 2, 0]
+    ctx.close()
+
+
 # ---- configs[4]: e4m3 decoder weights with per-output-channel scales ---------------------------------------
 
 def test_fp8_tiny_block_decode():
