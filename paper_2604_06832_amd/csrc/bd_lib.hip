@@ -81,6 +81,7 @@ struct bd_ctx {
   float* pf_x = nullptr; u16* pf_xb = nullptr; float* pf_rs = nullptr; float2* pf_rope = nullptr;
   u16* pf_q = nullptr; u16* pf_ap = nullptr; u16* pf_act = nullptr;
   bool pf_staged = false;
+  float* pf_apart = nullptr;       // attention partials of forwards of at most 64 rows through the large-M kernels
   float* pf_part = nullptr;        // [kPfSplit][pf_rows][H] K splits of the down projection
   int32_t* spec_tokens = nullptr; uint8_t* spec_mask = nullptr; int32_t* spec_k = nullptr;   // bd_speculative_step, bd_decode_block, bd_quad_*
   int32_t* quad_ids = nullptr;     // rows of the quadratic forward
@@ -308,7 +309,7 @@ PfChunk chunk_args(bd_ctx* c) {
   p.w = c->pf_w; p.layer_elems = c->pf_layer_elems;
   p.Kc = c->Kc; p.Vc = c->Vc; p.kv_layer_elems = c->kv_layer_elems; p.pages = page_table(c);
   p.x = c->pf_x; p.xb = c->pf_xb; p.rs = c->pf_rs; p.rope = c->pf_rope; p.q = c->pf_q; p.ap = c->pf_ap; p.act = c->pf_act;
-  p.part = c->pf_part;
+  p.part = c->pf_part; p.apart = c->pf_apart;
   p.mode = BD_MODE_CAUSAL;
   return p;
 }
@@ -617,6 +618,7 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
       A(c->pf_ap, R * (size_t)ceil_div(c->QD, 32) * 32 * 2);
       A(c->pf_act, R * (size_t)ceil_div(c->F, 32) * 32 * 2);
       A(c->pf_part, (size_t)kPfSplit * R * c->H * 4);
+      A(c->pf_apart, (size_t)k.n_q_heads * 4 * kPfAttnChunks * ((size_t)(c->D / 16) * 256 + 128) * 4);
     }
   }
   {

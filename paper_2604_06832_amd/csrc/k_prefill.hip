@@ -115,12 +115,23 @@ int launch_prefill_chunk(hipStream_t s, const PfChunk& c) {
       t.mode = c.mode; t.Mvalid = rows; t.st = c.st; t.skippable = c.skippable; t.pages = c.pages;
       const int items = t.n_q * (mc / 16);                    // one item per workgroup, its four wavefronts share the blocks
       const bool quad = c.mode >= 2;
-      // (few rows leave most CUs without an item: eight wavefronts per item then halve each one's walk over the keys)
-      if (c.D == 128 && quad) hipLaunchKernelGGL((pf_attn_kernel<128, 4, true>), dim3(items), dim3(256), 0, s, t);
-      else if (c.D == 128 && skinny) hipLaunchKernelGGL((pf_attn_kernel<128, 8>), dim3(items), dim3(512), 0, s, t);
+      // (few rows: query tiles of a head share a workgroup, the keys are dealt to kPfAttnChunks workgroups, a second
+      // kernel sums the chunks)
+      const bool split = skinny && c.apart != nullptr;
+      if (split) {
+        t.n_chunks = kPfAttnChunks;
+        t.part = c.apart;
+        const int grid = t.n_kv * ceil_div(mc / 16, kPfAttnTiles) * (t.n_q / t.n_kv) * kPfAttnChunks;
+        if (c.D == 128 && quad) hipLaunchKernelGGL((pf_attn_split_kernel<128, kPfAttnTiles, true>), dim3(grid), dim3(256), 0, s, t);
+        else if (c.D == 128) hipLaunchKernelGGL((pf_attn_split_kernel<128, kPfAttnTiles>), dim3(grid), dim3(256), 0, s, t);
+        else if (quad) hipLaunchKernelGGL((pf_attn_split_kernel<64, kPfAttnTiles, true>), dim3(grid), dim3(256), 0, s, t);
+        else hipLaunchKernelGGL((pf_attn_split_kernel<64, kPfAttnTiles>), dim3(grid), dim3(256), 0, s, t);
+        BD_TRY(check_launch());
+        if (c.D == 128) hipLaunchKernelGGL((pf_attn_merge_kernel<128, kPfAttnChunks>), dim3(items * 2), dim3(256), 0, s, t);
+        else hipLaunchKernelGGL((pf_attn_merge_kernel<64, kPfAttnChunks>), dim3(items), dim3(256), 0, s, t);
+      } else if (c.D == 128 && quad) hipLaunchKernelGGL((pf_attn_kernel<128, 4, true>), dim3(items), dim3(256), 0, s, t);
       else if (c.D == 128) hipLaunchKernelGGL((pf_attn_kernel<128, 4>), dim3(items), dim3(256), 0, s, t);
       else if (quad) hipLaunchKernelGGL((pf_attn_kernel<64, 4, true>), dim3(items), dim3(256), 0, s, t);
-      else if (skinny) hipLaunchKernelGGL((pf_attn_kernel<64, 8>), dim3(items), dim3(512), 0, s, t);
       else hipLaunchKernelGGL((pf_attn_kernel<64, 4>), dim3(items), dim3(256), 0, s, t);
       BD_TRY(check_launch());
     }

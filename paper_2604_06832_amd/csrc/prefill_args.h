@@ -40,9 +40,19 @@ struct PfAttnArgs {
   int mode;               // visibility among the chunk's own rows: BD_MODE_* (bits 8.. = B of a quadratic forward)
   int Mvalid;             // rows of the chunk: keys n0 + Mvalid .. do not exist
   const int* pages;       // page of every 32-key block of the cache (null: contiguous)
+  int n_chunks;           // pf_attn_split_kernel: the key blocks of an item are dealt to this many workgroups (block kb to
+                          // chunk kb mod n_chunks), each leaving an unnormalised partial in `part`; pf_attn_merge_kernel finishes
+  float* part;            // [items][n_chunks] x (D/16 x 64 x 4 partial output + 64 maxima + 64 sums), fp32
   const DevState* st; int skippable;   // nothing to do once the block is complete (DevState::skip)
 };
-
+#ifndef BD_PF_ATTN_CHUNKS
+#define BD_PF_ATTN_CHUNKS 4
+#endif
+#ifndef BD_PF_ATTN_TILES
+#define BD_PF_ATTN_TILES 1
+#endif
+constexpr int kPfAttnChunks = BD_PF_ATTN_CHUNKS;   // key chunks per attention item in forwards of at most 64 rows
+constexpr int kPfAttnTiles = BD_PF_ATTN_TILES;     // query tiles of a head that share a workgroup (and its key/value loads) there
 
 // One chunk of rows through all layers (k_prefill.hip): plain pointers and sizes of the context.  The rows are prompt
 // rows (embeds / ids from row `off`), or, with `block` set, the tokens of a decode block (ids[0..rows), masked rows
@@ -65,6 +75,7 @@ struct PfChunk {
   const u16* w; size_t layer_elems; size_t w_off[4];
   u16* Kc; u16* Vc; size_t kv_layer_elems; const int* pages;
   float* x; u16* xb; float* rs; float2* rope; u16* q; u16* ap; u16* act; float* part;
+  float* apart;                   // attention partials of forwards of at most 64 rows
 };
 
 }  // namespace bd
