@@ -78,10 +78,11 @@ int launch_prefill_chunk(hipStream_t s, const PfChunk& c) {
   }
   hipLaunchKernelGGL(rope_table_kernel, dim3(mc), dim3(64), 0, s, c.rope, c.st, c.D / 2, c.rope_theta, c.quad_W);
   BD_TRY(check_launch());
-  // Up to 64 rows: the products are bound by how fast the weights arrive, not by the matrix cores.  Tiles of 32 rows x
+  // Up to 128 rows: the products are bound by how fast the weights arrive, not by the matrix cores.  Tiles of 32 rows x
   // 64 tokens put 2.5 to 8 times as many workgroups on the chip as the tiles above, each with a deep direct-to-LDS
-  // pipeline (84 to 96 KiB in flight per CU), and the two projections with few output rows split K over workgroups.
-  const bool skinny = MTc <= 4 && !c.staged;
+  // pipeline (84 to 132 KiB in flight per CU), and the two projections with few output rows split K over workgroups.
+  // (65 to 128 rows: two token groups per row group, the second of which finds the weights in its XCD's L2.)
+  const bool skinny = MTc <= 8 && !c.staged;
   PfGemmArgs g{};
   g.MTc = MTc; g.Mvalid = rows; g.rs = c.rs; g.rope = c.rope; g.x = c.x; g.q = c.q; g.max_kb = c.max_kb; g.n0 = c.n0;
   g.act = c.act; g.H = c.H; g.QD = c.QD; g.KVD = c.KVD; g.D = c.D; g.n_q = c.n_q;
@@ -117,7 +118,7 @@ int launch_prefill_chunk(hipStream_t s, const PfChunk& c) {
       const bool quad = c.mode >= 2;
       // (few rows: query tiles of a head share a workgroup, the keys are dealt to kPfAttnChunks workgroups, a second
       // kernel sums the chunks)
-      const bool split = skinny && c.apart != nullptr;
+      const bool split = skinny && MTc <= 4 && c.apart != nullptr;
       if (split) {
         t.n_chunks = kPfAttnChunks;
         t.part = c.apart;
