@@ -1,9 +1,10 @@
 /*
  * bd_kernels.h - kernel-level entry points of the block-denoising library.
  *
- * These expose block-causal attention on caller-provided tensors, per-kernel-class timing of a context and
- * the in-kernel phase trace, so that tests can check one operation against the oracle and the benchmark
- * can price one kernel against its roofline.  They are not part of the decode path.  Return codes as in
+ * These expose block-causal attention on caller-provided tensors (the attention kernel that forwards of more than
+ * 32 rows and the prompt pass run), per-kernel-class timing of a context, the in-kernel phase trace and the time of
+ * the weight stream alone, so that tests can check one operation against the oracle and the benchmark can price
+ * one kernel against its roofline.  The entry points themselves are not on the decode path.  Return codes as in
  * bd.h.
  */
 #ifndef BD_KERNELS_H_

@@ -39,3 +39,18 @@ def test_attention_first_causal_row_with_empty_prefix_sees_only_itself():
     got = got.cpu().numpy().reshape(6, 4, 64)
     for h in range(4):
         np.testing.assert_allclose(got[0, h], v[0, h // 2], atol=1e-2)
+
+
+def test_stream_floor_reads_the_layers_weight_stream():
+    """bd_k_stream_floor reads exactly the bytes of the decoder layers' weight stream (every wavefront its own share)
+    and reports a time that corresponds to a plausible memory rate."""
+    from paper_2604_06832_amd import inputs
+    shape = inputs.QWEN3B.with_layers(2)
+    ctx = binding.Context(shape, max_seq=256, max_block=32)
+    ms, nbytes = ctx.bd_k_stream_floor(5)
+    per_layer = shape.hidden * (shape.q_dim + 2 * shape.kv_dim) + shape.q_dim * shape.hidden + 3 * shape.hidden * shape.ffn
+    assert nbytes == 2 * 2 * per_layer, (nbytes, per_layer)
+    rate = nbytes / (ms * 1e-3) / 1e12
+    print(f"stream floor: {nbytes / 1e6:.1f} MB in {ms * 1e3:.1f} us = {rate:.2f} TB/s", flush=True)
+    assert 0.2 < rate < 8.0
+    ctx.close()
