@@ -58,6 +58,11 @@ int64_t bd_k_class_bytes(const bd_ctx* ctx, int kclass);
  * in milliseconds to *host_ms, the bytes read per launch to *host_bytes.  Synchronises the stream. */
 int bd_k_stream_floor(bd_ctx* ctx, int repeats, double* host_ms, int64_t* host_bytes);
 
+/* Test hook: raises the context's device-side error flag, as a forward kernel does when one of its bounded waits
+ * gives up.  Every later forward kernel then returns at once (no kernel waits for anything), bd_status and the calls
+ * that read a result back (bd_speculative_step, bd_quad_step) return BD_E_HIP, and the context stays unusable. */
+int bd_k_raise_device_error(bd_ctx* ctx);
+
 int bd_k_trace(bd_ctx* ctx, int enable);
 int bd_k_trace_read(bd_ctx* ctx, unsigned long long* host_out, int capacity, int* n_wg, int* per_wg);
 

@@ -28,7 +28,7 @@ EXPORTS = [
     "bd_verify_block", "bd_decode_block", "bd_speculative_step", "bd_quad_draft", "bd_quad_step", "bd_crop", "bd_cache_len", "bd_status", "bd_debug_logits", "bd_read_logits", "bd_read_kv",
     "bd_read_carry", "bd_read_rows", "bd_forward_bytes", "bd_strerror", "bd_last_error",
     "bd_k_attention", "bd_k_attention_static", "bd_k_profile", "bd_k_profile_read", "bd_k_class_count", "bd_k_class_name",
-    "bd_k_class_bytes", "bd_k_trace", "bd_k_trace_read", "bd_k_stream_floor", "bd_kv_page_order", "bd_kv_pages",
+    "bd_k_class_bytes", "bd_k_trace", "bd_k_trace_read", "bd_k_stream_floor", "bd_kv_page_order", "bd_kv_pages", "bd_k_raise_device_error",
 ]
 
 
@@ -87,6 +87,7 @@ def lib() -> C.CDLL:
     L.bd_k_trace.argtypes = [vp, i32]
     L.bd_kv_page_order.argtypes = [vp, vp, i32]
     L.bd_kv_pages.argtypes = [vp, vp, i32]
+    L.bd_k_raise_device_error.argtypes = [vp]
     L.bd_k_stream_floor.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     L.bd_k_trace_read.argtypes = [vp, vp, i32, C.POINTER(i32), C.POINTER(i32)]
     _lib = L
@@ -275,6 +276,9 @@ def _trace_methods():
         lib().bd_kv_pages(self._h, out.ctypes.data, n)
         return out[:n]
 
+    def bd_k_raise_device_error(self):
+        _check(lib().bd_k_raise_device_error(self._h))
+
     def bd_k_stream_floor(self, repeats: int = 10):
         """(milliseconds, bytes) of reading one forward's layer weights with no consumer, hand-over or barrier."""
         ms, nb = C.c_double(0), C.c_int64(0)
@@ -294,6 +298,7 @@ def _trace_methods():
 
     Context.bd_k_trace = bd_k_trace
     Context.bd_k_stream_floor = bd_k_stream_floor
+    Context.bd_k_raise_device_error = bd_k_raise_device_error
     Context.bd_kv_page_order = bd_kv_page_order
     Context.bd_kv_pages = bd_kv_pages
     Context.bd_k_trace_read = bd_k_trace_read

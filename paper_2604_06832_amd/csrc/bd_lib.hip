@@ -1161,6 +1161,12 @@ int bd_k_stream_floor(bd_ctx* c, int repeats, double* host_ms, int64_t* host_byt
   return BD_OK;
 }
 
+int bd_k_raise_device_error(bd_ctx* c) {
+  if (c == nullptr) return BD_E_ARG;
+  hipLaunchKernelGGL(raise_error_kernel, dim3(1), dim3(1), 0, c->stream, c->st);
+  return check_launch();
+}
+
 int bd_k_trace(bd_ctx* c, int enable) {
   if (c == nullptr) return BD_E_ARG;
   const size_t n = (size_t)c->plan.nwg * (10 * c->L + 4 + 64);

@@ -261,6 +261,9 @@ __global__ void fill_masked_kernel(int* tokens, uint8_t* mask, int B, int mask_i
   if (i < B) { tokens[i] = mask_id; mask[i] = (i == 0 && first_revealed) ? 0 : 1; }
   if (i == 0) { st->skip = 0; st->steps = 0; }
 }
+__global__ void raise_error_kernel(DevState* st) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) st->error = 1;
+}
 __global__ void read_steps_kernel(const DevState* st, int* out) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *out = st->steps;
 }

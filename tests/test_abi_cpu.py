@@ -82,6 +82,7 @@ def test_null_context_is_an_argument_error(L):
     assert L.bd_k_attention(None, None, None, None, 0, 4, 4, 2, 64, 0, None, 1, None) == binding.BD_E_ARG
     assert L.bd_k_attention_static(None, None, None, None, 0, 4, 4, 2, 64, 0, None) == binding.BD_E_ARG
     assert L.bd_kv_page_order(None, None, 0) == binding.BD_E_ARG
+    assert L.bd_k_raise_device_error(None) == binding.BD_E_ARG
     assert L.bd_kv_pages(None, None, 0) == binding.BD_E_ARG
     L.bd_destroy(None)
 

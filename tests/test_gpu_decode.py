@@ -996,6 +996,40 @@ def test_fp8_config_first_block_full_depth():
     p.close()
 
 
+def test_a_context_whose_kernels_gave_up_reports_it_and_never_hangs():
+    """What a timed-out barrier leaves behind, forced from the host: with the device-side error flag raised every forward
+    kernel returns at once, so nothing can wait for anything; bd_status, bd_speculative_step and bd_quad_step report
+    BD_E_HIP (the two steps must not hand back the accept length of an earlier call), and the host's view of the context
+    length stays where it was."""
+    shape = inputs.TINY
+    w = inputs.make_weights(shape, 0, "bf16", threads=1)
+    for max_seq in (96, 300):                                  # decode kernels only / with the large-M kernels
+        ctx = binding.Context(shape, max_seq=max_seq, max_block=16)
+        ctx.load_model(w, as_bf16_bits=True)
+        ctx.bd_prefill(None, torch.arange(40, dtype=torch.int32, device="cuda"))
+        out = torch.zeros(16, dtype=torch.int32, device="cuda")
+        assert 1 <= ctx.bd_speculative_step(4, out) <= 4       # a good step first: its accept length stays in the buffer
+        n = ctx.bd_cache_len()
+        ctx.bd_k_raise_device_error()
+        with pytest.raises(binding.BdError) as e:
+            ctx.bd_speculative_step(4, out)
+        assert e.value.code == binding.BD_E_HIP
+        assert ctx.bd_cache_len() == n
+        d = torch.zeros(3, dtype=torch.int32, device="cuda")
+        nx = torch.zeros(3, dtype=torch.int32, device="cuda")
+        with pytest.raises(binding.BdError) as e:
+            ctx.bd_quad_step(3, d, nx)
+        assert e.value.code == binding.BD_E_HIP
+        tok = torch.zeros(8, dtype=torch.int32, device="cuda")
+        msk = torch.ones(8, dtype=torch.uint8, device="cuda")
+        ctx.bd_denoise_step(tok, msk, 0.9, 0, None, None)      # enqueues; its kernels return at once
+        with pytest.raises(binding.BdError) as e:
+            ctx.bd_status()
+        assert e.value.code == binding.BD_E_HIP
+        assert ctx.bd_cache_len() == n
+        ctx.close()
+
+
 # ---- error paths that need a live context -------------------------------------------------------------------
 
 def test_call_order_and_capacity_errors():
