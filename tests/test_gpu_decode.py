@@ -968,6 +968,12 @@ def test_headline_config_first_block_full_depth():
     assert fwd == 8
     p.commit(tok)
     assert p.ctx.bd_forward_bytes() == 2 * shape.weight_elements() + 36864 * (1024 + 32)
+    # one denoising forward of 64 rows on top (the large-M kernels at full depth), and its commit
+    tok, msk = fresh_block(shape, 64)
+    tok, msk, _ = p.denoise_step(tok, msk, 0.9, fixed_k=4)
+    _say(f"  64-row denoise forward: {int((~msk).sum())}/64 revealed")
+    tok[msk] = 7
+    p.commit(tok)
     p.close()
 
 
