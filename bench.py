@@ -121,10 +121,13 @@ def main():
     print(f"[bench] weights generated in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
 
     blocks = args.warmup + args.steps
-    ctx = binding.Context(shape, max_seq=args.prefix + (max(blocks, args.steps) + 1) * B, max_block=64,
+    max_seq = args.prefix + (max(blocks, args.steps) + 1) * B
+    if args.quadratic > 0:        # eight iterations of at most qB accepted tokens, and the forward's qB (qB + 1) parked rows
+        max_seq = max(max_seq, args.prefix + 8 * args.quadratic + args.quadratic * (args.quadratic + 1))
+    ctx = binding.Context(shape, max_seq=max_seq, max_block=64,
                           weight_dtype=binding.BD_FP8_E4M3 if fp8 else binding.BD_BF16, flags=args.flags)
     if args.shuffle_pages:
-        n_pages = -(-(args.prefix + (max(blocks, args.steps) + 1) * B) // 32)
+        n_pages = -(-max_seq // 32)
         ctx.bd_kv_page_order(np.random.default_rng(5).permutation(n_pages).astype(np.int32))
     t0 = time.time()
     ctx.load_model(w)

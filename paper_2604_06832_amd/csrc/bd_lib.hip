@@ -76,13 +76,14 @@ struct bd_ctx {
   float* logits = nullptr; int logits_on = 0; int last_rows = 0; int last_had_logits = 0;
   int* row_cand = nullptr; float* row_conf = nullptr;
   // large-M prefill (prefill.h): tile-major copy of the decoder weights and the activations of one chunk
-  bool pf_on = false; int pf_rows = 0;
+  bool pf_on = false; int pf_rows = 0;   // large-M kernels in use; rows of a prompt chunk
+  int pf_cap = 0;                        // rows their working buffers hold: a prompt chunk, or the largest quadratic forward
   u16* pf_w = nullptr; size_t pf_layer_elems = 0; size_t pf_off[4] = {0, 0, 0, 0};
   float* pf_x = nullptr; u16* pf_xb = nullptr; float* pf_rs = nullptr; float2* pf_rope = nullptr;
   u16* pf_q = nullptr; u16* pf_ap = nullptr; u16* pf_act = nullptr;
   bool pf_staged = false;
   float* pf_apart = nullptr;       // attention partials of forwards of at most 64 rows through the large-M kernels
-  float* pf_part = nullptr;        // [kPfSplit][pf_rows][H] K splits of the down projection
+  float* pf_part = nullptr;        // [kPfSplit][pf_cap][H] K splits of the down projection
   int32_t* spec_tokens = nullptr; uint8_t* spec_mask = nullptr; int32_t* spec_k = nullptr;   // bd_speculative_step, bd_decode_block, bd_quad_*
   int32_t* quad_ids = nullptr;     // rows of the quadratic forward
   DevState* st = nullptr;
@@ -251,7 +252,7 @@ int launch_forward_kernels(bd_ctx* c, int MT, MegaArgs& a, bool lm_only = false)
   return BD_OK;
 }
 
-constexpr int kQuadMaxB = 16;      // largest block of a quadratic step: B (B + 1) = 272 rows
+constexpr int kQuadMaxB = 32;      // largest block of a quadratic step: B (B + 1) = 1056 rows
 constexpr int kStreamRows = 32;    // rows of a forward the decode kernels stream the weights against (two token tiles)
 
 // ---- paged cache: the host owns the page list, the device holds a copy that the kernels index ---------------------
@@ -532,7 +533,13 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
   // Large-M kernels for contexts whose cache can hold a chunk of 128 rows plus the prompt's last rows.
   c->pf_on = k.max_seq > kPfTokens && !(k.flags & BD_FLAG_PREFILL_DECODE);
   c->pf_rows = c->pf_on ? std::min(1024, (k.max_seq - 1) / kPfTokens * kPfTokens) : 0;
-  c->rows_max = c->pf_on ? std::max(c->Mp_max, std::min(c->pf_rows, kQuadMaxB * (kQuadMaxB + 1))) : c->Mp_max;
+  {
+    // the largest quadratic forward of this context: B (B + 1) rows for B = min(max_block, 32), if the cache can hold them
+    const int Bq = std::min(k.max_block, kQuadMaxB);
+    const int quad_rows = std::min(Bq * (Bq + 1), k.max_seq - 1);
+    c->pf_cap = c->pf_on ? std::max(c->pf_rows, ceil_div(quad_rows, 16) * 16) : 0;
+    c->rows_max = c->pf_on ? std::max(c->Mp_max, quad_rows) : c->Mp_max;
+  }
   c->loaded.assign(c->L + 1, 0u);
   c->kv_layer_elems = (size_t)k.n_kv_heads * c->max_kb * 32 * c->D;
   c->xcds = c->use_stream ? probe_xcds(c) : 0;
@@ -603,7 +610,7 @@ int bd_create(const bd_config* cfg, void* hip_stream, bd_ctx** out) {
     // decoder linears are widened into the bf16 copy, exactly; their row scales stay in the epilogue.)
     c->pf_staged = (k.flags & BD_FLAG_PREFILL_STAGED) != 0;     // register-staged GEMMs only (else: the fallback for K tails)
     if (c->pf_on) {
-      const size_t R = (size_t)c->pf_rows;
+      const size_t R = (size_t)c->pf_cap;
       const int NP[4] = {c->NQKV, c->H, 2 * c->F, c->H};
       const int KP[4] = {c->H, c->QD, c->H, c->F};
       size_t off = 0;
@@ -937,7 +944,7 @@ int bd_quad_step(bd_ctx* c, int B, const int32_t* dev_draft, int32_t* dev_next_d
   if (c == nullptr || B < 1 || dev_draft == nullptr || dev_next_draft == nullptr || host_n_accepted == nullptr) return BD_E_ARG;
   const int M = B * (B + 1);
   if (B > c->cfg.max_block || B > kQuadMaxB || c->fp8) return BD_E_ARG;   // (bf16 contexts only)
-  // B (B + 1) rows: within max_block through the decode kernels, beyond (up to 272) through the large-M kernels
+  // B (B + 1) rows: within max_block through the decode kernels, beyond (up to 1056) through the large-M kernels
   if (M > c->cfg.max_block && !(c->pf_on && M <= c->rows_max)) return BD_E_ARG;
   if (!c->prefilled) return BD_E_STATE;
   if (c->n + M > c->cfg.max_seq) return BD_E_CAPACITY;   // the forward parks its rows at [cache_len, cache_len + M)

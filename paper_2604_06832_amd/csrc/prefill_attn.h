@@ -52,9 +52,24 @@ __global__ __launch_bounds__(64 * (NW > 4 ? NW : 4), NW > 4 ? 1 : 2) void pf_att
       if (kb * 32 + 31 >= a.n0) attn_block<D, true, QUAD>(b, qf, O, mrun, lrun, kb, a.n0, a.Mvalid, a.mode, row, g, c);
       else attn_block<D, false>(b, qf, O, mrun, lrun, kb, a.n0, a.Mvalid, a.mode, row, g, c);
     };
+    // Quadratic forward: most blocks of the forward's own rows hold no key that any row of this tile sees (a row sees
+    // its own group, a group's first row the first rows of the groups before it); they would add exact zeros.
+    [[maybe_unused]] const int W = (a.mode >> 8) + 1;
+    [[maybe_unused]] const int r0 = qt * 16, r1 = min(qt * 16 + 15, a.Mvalid - 1);
+    [[maybe_unused]] const int g_lo = r0 / W, g_hi = r1 / W;
+    auto needed = [&](int kb) -> bool {
+      if constexpr (!QUAD) return true;
+      const int jb0 = kb * 32 - a.n0;                              // the block's first key, counted from the forward's first row
+      if (jb0 < 0) return true;                                    // keys of the prefix
+      if (jb0 < (g_hi + 1) * W && jb0 + 31 >= g_lo * W) return true;   // keys of a group of the tile's rows
+      if (g_hi * W < r0) return false;                             // no group's first row in the tile
+      const int first = (jb0 + W - 1) / W * W;                     // the first group-first key at or after jb0
+      return first <= jb0 + 31 && first <= g_hi * W;
+    };
     KvBlock<D> b0;
     for (int j = 0; j < cnt; ++j) {
       const int kb = half + NW * j;
+      if (!needed(kb)) continue;
       kv_load<D>(b0, Kh, Vh, kb, lane, a.pages);
       asm volatile("" ::: "memory");
       block(b0, kb);

@@ -381,13 +381,14 @@ def test_speculative_step_needs_a_carry():
 
 # ---- quadratic speculative decoding (Alg. 2): one forward per iteration -----------------------------------------
 
-@pytest.mark.parametrize("B", [1, 2, 3, 5, 7, 8, 16])
+@pytest.mark.parametrize("B", [1, 2, 3, 5, 7, 8, 16, 21, 32])
 def test_quadratic_step_against_the_oracle(B):
     """Draft, then iterations of the quadratic step, each held against the oracle's on the same state: logits of all
     B(B+1) rows, accept length, next draft, carry, and the cache (keys and values of the accepted first tokens moved
     into place).  B = 5 (30 rows) runs on the streaming kernel, B = 7 (56 rows) on the register-ring kernel (the context
-    is too small for the large-M kernels), B = 8 (72 rows) and B = 16 (272 rows) on the large-M kernels with the quadratic
-    mask and the per-row positions, the LM head in slices of 64 rows."""
+    is too small for the large-M kernels), B = 8 (72 rows), 16 (272), 21 (462: a ragged last tile) and 32 (1056 rows, the
+    largest block) on the large-M kernels with the quadratic mask and the per-row positions, the LM head in slices of
+    64 rows."""
     _say(f"quadratic step vs oracle, tiny config, B={B}")
     shape = inputs.TINY
     w = inputs.make_weights(shape, 0, "bf16", lm_head_scale=20.0, threads=1)
@@ -427,19 +428,21 @@ def test_quadratic_step_against_the_oracle(B):
         thr = bars(r["logits"], shape.n_layers)[1]
         W = B + 1
         firsts = top2_margin(r["logits"])[::W]
-        robust = firsts[:r["k"]].min() > thr and top2_margin(r["logits"])[(r["k"] - 1) * W:(r["k"] - 1) * W + B].min() > thr
-        if not robust:
+        if firsts[:r["k"]].min() <= thr:          # a near-tie among the rows that decide the accept length
             break
         assert k == r["k"], (it, k, r["k"])
-        assert np.array_equal(nxt.cpu().numpy(), r["next_draft"])
+        # the next draft, entry by entry where the oracle's row is not a near-tie (the first entry is the carry: held)
+        sure = top2_margin(r["logits"])[(r["k"] - 1) * W:(r["k"] - 1) * W + B] > thr
+        assert sure[0] and np.array_equal(nxt.cpu().numpy()[sure], r["next_draft"][sure])
+        note("count", what="next-draft entries held against the oracle's", n=int(sure.sum()))
         assert p.ctx.bd_cache_len() == p.o.n
         cand, _ = p.ctx.bd_read_carry()
         assert cand == int(np.argmax(p.o.carry))
         p.check_kv(max(0, p.o.n - k - 2), min(k + 2, p.o.n))
         compared += 1
         emitted += [int(t) for t in r["accepted"]]
-        d = r["next_draft"]
-        d_gpu.copy_(nxt)
+        d = r["next_draft"]                       # both sides go on from the oracle's draft
+        d_gpu.copy_(torch.from_numpy(np.asarray(d, np.int32)))
     note("count", what="quadratic iterations held against the oracle's", n=compared)
     assert compared >= 1 and len(emitted) >= 1, compared
     if draft_robust:
@@ -497,7 +500,7 @@ def test_quadratic_step_rejects_blocks_that_do_not_fit():
     ctx.close()
 
 
-@pytest.mark.parametrize("B", [5, 8, 16])
+@pytest.mark.parametrize("B", [5, 8, 16, 32])
 def test_quadratic_step_3b_shaped_two_layers(B):
     M = B * (B + 1)
     _say(f"quadratic step vs oracle, 3B-shaped x2 layers, B={B} ({M} rows)")
@@ -518,14 +521,14 @@ def test_quadratic_step_3b_shaped_two_layers(B):
         assert_logits_close(glog, r["logits"], n_layers=shape.n_layers)
         thr = bars(r["logits"], shape.n_layers)[1]
         W = B + 1
-        if top2_margin(r["logits"])[::W][:r["k"]].min() <= thr or \
-                top2_margin(r["logits"])[(r["k"] - 1) * W:(r["k"] - 1) * W + B].min() <= thr:
+        if top2_margin(r["logits"])[::W][:r["k"]].min() <= thr:
             break
-        assert k == r["k"] and np.array_equal(nxt.cpu().numpy(), r["next_draft"])
+        sure = top2_margin(r["logits"])[(r["k"] - 1) * W:(r["k"] - 1) * W + B] > thr
+        assert k == r["k"] and sure[0] and np.array_equal(nxt.cpu().numpy()[sure], r["next_draft"][sure])
         p.check_kv(p.o.n - k, k)
         compared += 1
-        d = r["next_draft"]
-        d_gpu.copy_(nxt)
+        d = r["next_draft"]                       # both sides go on from the oracle's draft
+        d_gpu.copy_(torch.from_numpy(np.asarray(d, np.int32)))
     note("count", what="quadratic iterations held against the oracle's (logits of every iteration run are held)", n=compared)
     p.close()
 
