@@ -152,7 +152,7 @@ int bd_speculative_step(bd_ctx* ctx, int B, int32_t* dev_tokens_out, int32_t* ho
 /* Quadratic speculative decoding (appendix "Details of Speculative Decoding", Alg. 2): B <= max_block and either
  * B*(B+1) <= max_block rows (decode kernels) or, on a context with max_seq > 128 (large-M kernels, quadratic mask and
  * per-row positions there), B <= 32 (the block of the paper's model: 1056 rows) and B*(B+1) < max_seq; BD_E_ARG
- * otherwise and for BD_FP8_E4M3 contexts.
+ * otherwise.  (A BD_FP8_E4M3 context without the large-M kernels, max_seq <= 128, takes at most 32 rows.)
  * bd_quad_draft: step 1, the first block's draft: B mask tokens after the context, one bidirectional forward without
  *   cache update; dev_draft_out[0] = the carry's argmax, dev_draft_out[i] = argmax of the row before position i.
  * bd_quad_step: one iteration: a single forward over the B groups [draft[i], MASK x B] (group i at positions

@@ -943,7 +943,7 @@ int bd_quad_draft(bd_ctx* c, int B, int32_t* dev_draft_out) {
 int bd_quad_step(bd_ctx* c, int B, const int32_t* dev_draft, int32_t* dev_next_draft, int32_t* host_n_accepted) {
   if (c == nullptr || B < 1 || dev_draft == nullptr || dev_next_draft == nullptr || host_n_accepted == nullptr) return BD_E_ARG;
   const int M = B * (B + 1);
-  if (B > c->cfg.max_block || B > kQuadMaxB || c->fp8) return BD_E_ARG;   // (bf16 contexts only)
+  if (B > c->cfg.max_block || B > kQuadMaxB) return BD_E_ARG;
   // B (B + 1) rows: within max_block through the decode kernels, beyond (up to 1056) through the large-M kernels
   if (M > c->cfg.max_block && !(c->pf_on && M <= c->rows_max)) return BD_E_ARG;
   if (!c->prefilled) return BD_E_STATE;

@@ -38,7 +38,7 @@ int launch_inst(hipStream_t s, const MegaArgs& a) {
 
 template <int MT, int D>
 int launch_d(hipStream_t s, bool fp8, bool quad, const MegaArgs& a) {
-  if (quad) return fp8 ? BD_E_ARG : launch_inst<MT, D, false, true>(s, a);   // quadratic mask (Alg. 2): bf16 weights only
+  if (quad) return fp8 ? launch_inst<MT, D, true, true>(s, a) : launch_inst<MT, D, false, true>(s, a);   // quadratic mask (Alg. 2)
   return fp8 ? launch_inst<MT, D, true, false>(s, a) : launch_inst<MT, D, false, false>(s, a);
 }
 }  // namespace

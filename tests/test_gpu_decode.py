@@ -877,7 +877,7 @@ def test_fp8_large_m_prefill(n_embed, n_ids):
 def test_fp8_whole_block_and_speculative_calls():
     """The calls that chain forwards on the device, on a context with e4m3 weights: a whole block per call equals the
     step-by-step loop bit for bit, a speculative iteration accepts between 1 and B tokens and leaves a valid carry, and
-    the quadratic step (bf16 contexts only) is refused."""
+    so does a quadratic one (held against the oracle in test_fp8_quadratic_step)."""
     _say("tiny config, e4m3 weights: bd_decode_block, bd_speculative_step, bd_quad_step")
     shape = inputs.TINY
     w = inputs.make_weights(shape, 2, "fp8", lm_head_scale=20.0, threads=1)
@@ -905,11 +905,51 @@ def test_fp8_whole_block_and_speculative_calls():
     k = a.bd_speculative_step(8, out)
     assert 1 <= k <= 8 and a.bd_cache_len() == 40 + B + k
     a.bd_read_carry()
-    with pytest.raises(binding.BdError):
-        a.bd_quad_step(3, out, tok)
+    n0 = a.bd_cache_len()
+    a.bd_quad_draft(3, out)
+    k = a.bd_quad_step(3, out, tok)
+    assert 1 <= k <= 3 and a.bd_cache_len() == n0 + k
+    a.bd_read_carry()
     a.bd_status()
     a.close()
     b.close()
+
+
+@pytest.mark.parametrize("shape_name,B", [("tiny", 3), ("tiny", 5), ("tiny", 8), ("wide", 5), ("wide", 16)])
+def test_fp8_quadratic_step(shape_name, B):
+    """Alg. 2 on e4m3 decoder linears: 12 and 30 rows on the streaming kernel, 72 and 272 rows on the large-M kernels
+    (widened weights, row scales in the epilogue); logits of every row, accept length, next draft and the moved cache
+    rows against the oracle's on the same state."""
+    M = B * (B + 1)
+    _say(f"quadratic step vs oracle, e4m3 weights, {shape_name}, B={B} ({M} rows)")
+    shape = inputs.TINY if shape_name == "tiny" else _wide(2, vocab=8192)
+    w = inputs.make_weights(shape, 2, "fp8", lm_head_scale=20.0, threads=1 if shape_name == "tiny" else 8)
+    emb, ids = inputs.make_prompt(shape, 100, 41, seed=13)
+    p = Pair(shape, w, max_seq=141 + 3 * B + M, max_block=32 if M <= 32 else 64)
+    p.prefill(emb, ids)
+    d_gpu = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nxt = torch.zeros(B, dtype=torch.int32, device="cuda")
+    p.ctx.bd_quad_draft(B, d_gpu)
+    d = d_gpu.cpu().numpy()                       # the oracle follows the device's draft: the step is what is compared
+    compared = 0
+    W = B + 1
+    for it in range(3):
+        r = p.o.quad_step(d)
+        k = p.ctx.bd_quad_step(B, d_gpu, nxt)
+        glog = p.ctx.bd_read_logits(M).cpu().numpy()
+        assert_logits_close(glog, r["logits"], frac=FP8_LOGIT_TOL, n_layers=shape.n_layers)
+        thr = bars(r["logits"], shape.n_layers)[1]
+        if top2_margin(r["logits"])[::W][:r["k"]].min() <= thr:
+            break
+        sure = top2_margin(r["logits"])[(r["k"] - 1) * W:(r["k"] - 1) * W + B] > thr
+        assert k == r["k"] and sure[0] and np.array_equal(nxt.cpu().numpy()[sure], r["next_draft"][sure])
+        assert p.ctx.bd_cache_len() == p.o.n
+        p.check_kv(p.o.n - k, k, frac=6e-2)
+        compared += 1
+        d = r["next_draft"]                       # both sides go on from the oracle's draft
+        d_gpu.copy_(torch.from_numpy(np.asarray(d, np.int32)))
+    note("count", what="quadratic iterations held against the oracle's (logits of every iteration run are held)", n=compared)
+    p.close()
 
 
 @pytest.mark.parametrize("B", [4, 16, 32, 33, 64])
